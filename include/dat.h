@@ -1,0 +1,187 @@
+/* dat.h -- C ABI of libdat: one worker's step of distributed adversarial training (DAT) on one
+ * AMD MI355X (gfx950).
+ *
+ * The calls follow Algorithm A1 of Liu et al., "Distributed Adversarial Training to Robustify
+ * Deep Neural Networks at Scale" (UAI 2022), worker block (steps 4-7):
+ *   dat_attack      step 5, Eq. (inner_max_alg): per-sample inner maximisation under an l-inf ball
+ *                   by K projected sign-gradient steps (K = 1: FGSM, K > 1: PGD; the unified
+ *                   update of Sec. "Methodologies", paragraph on inner maximisation);
+ *   dat_step        step 6, Eq. (stoch_grad_batch) with lambda = 0 and phi = cross-entropy:
+ *                   batch-mean gradient w.r.t. the parameters at the perturbed samples;
+ *   dat_quantize    step 7: randomized b-bit quantizer Q, Eqs. (rand_q) and (xi) of appendix
+ *                   "Additional details on gradient quantization";
+ *   dat_dequantize  the map back to fp32 that the aggregation of Eq. (grad_agg) applies.
+ *
+ * Conventions
+ *   - Every call returns a dat_status, never throws or aborts; on an argument error nothing
+ *     is launched and outputs are untouched.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The model object owns its parameters and workspace (allocated at
+ *     dat_model_create for `max_batch`), freed by dat_model_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work on it and return without synchronising unless a host output (`loss`,
+ *     `loss_per_step`) is requested; host outputs are written after an internal
+ *     hipStreamSynchronize.
+ *   - Images are NHWC fp32 with C = 3 and pixel values in [0,1]; eps, alpha, delta and the
+ *     [0,1] clip live in pixel space.  A model created with mean/std applies
+ *     (x - mean_c) * (1/std_c) as its first operation.
+ *   - Parameters and gradients are one flat fp32 vector in tensor-table order (op order; conv:
+ *     W[Cout][kh][kw][Cin] (then bias); batch-norm: gamma, beta; linear: W[out][in], b).
+ *   - A DAT_BF16 model stores conv/linear weights, activations and activation gradients in
+ *     bf16 and accumulates in fp32 on the matrix cores; a DAT_F32 model keeps everything in
+ *     fp32.  Batch-norm runs in train mode (batch statistics) in every pass.
+ *   - Calls on one model, or sharing one stream's buffers, must not overlap in time.
+ */
+#ifndef DAT_H
+#define DAT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dat_model dat_model;
+
+typedef enum {
+  DAT_OK = 0,
+  DAT_ERR_ARG = 1,         /* null pointer, negative size, bad enum, misaligned buffer */
+  DAT_ERR_SHAPE = 2,       /* batch larger than max_batch, unsupported image size       */
+  DAT_ERR_NOMEM = 3,       /* device or host allocation failed                           */
+  DAT_ERR_NONFINITE = 4,   /* a checked value was NaN or Inf                             */
+  DAT_ERR_HIP = 5,         /* a HIP runtime call failed (see dat_last_error)             */
+  DAT_ERR_UNSUPPORTED = 6  /* valid request that this build does not implement           */
+} dat_status;
+
+typedef enum {
+  DAT_ARCH_TINYCNN = 0,         /* conv3x3(3-16)+b+ReLU, conv3x3(16-32,s2)+b+ReLU, GAP, FC        */
+  DAT_ARCH_RESNET18_CIFAR = 1,  /* post-activation BasicBlocks [2,2,2,2], widths 64..512          */
+  DAT_ARCH_WRN34_10 = 2,        /* pre-activation wide blocks, widths 160/320/640                 */
+  DAT_ARCH_RESNET50 = 3,        /* Bottleneck [3,4,6,3], stride on the 3x3, 7x7 stem + max-pool   */
+  DAT_ARCH_TESTNET = 100        /* small net containing every op kind (for parity tests)          */
+} dat_arch;
+
+typedef enum { DAT_F32 = 0, DAT_BF16 = 1 } dat_dtype;
+
+typedef enum { DAT_INIT_ZERO = 0, DAT_INIT_UNIFORM = 1, DAT_INIT_GIVEN = 2 } dat_init_mode;
+
+/* Start point z_0 of the inner maximisation.  UNIFORM: i.i.d. U(-eps,eps) from Philox4x32-10
+ * (counter = flat element index / 4, stream 1, key = seed).  GIVEN: `delta0` (device,
+ * [B,H,W,3]) projected onto the eps-ball.  In all modes z_0 is then clipped to [-x, 1-x]. */
+typedef struct {
+  dat_init_mode mode;
+  uint64_t seed;
+  const float* delta0;
+} dat_init;
+
+/* ---- model ------------------------------------------------------------------------------ */
+
+/* Builds `arch` for H x W x 3 inputs and `num_classes` outputs, allocates parameters (zero)
+ * and a workspace for batches up to `max_batch` on the current device.  mean/stdv: host,
+ * 3 floats each, or both NULL for no normalisation. */
+dat_status dat_model_create(dat_arch arch, dat_dtype dtype, int max_batch, int H, int W,
+                            int num_classes, const float* mean, const float* stdv,
+                            dat_model** out);
+dat_status dat_model_destroy(dat_model* m);
+
+/* d = total parameter count, num_tensors = entries of the tensor table. */
+dat_status dat_model_num_params(const dat_model* m, int64_t* d, int* num_tensors);
+
+/* Host outputs: offsets[num_tensors+1] (element offsets into the flat vector), and optionally
+ * fan_in[num_tensors], kind[num_tensors] (0 conv W, 1 conv bias, 2 BN gamma, 3 BN beta,
+ * 4 linear W, 5 linear b).  The model also keeps a device copy of `offsets`, returned by
+ * dat_model_offsets_device (int64, num_tensors+1 entries, owned by the model). */
+dat_status dat_model_tensor_table(const dat_model* m, int64_t* offsets, int32_t* fan_in,
+                                  int32_t* kind);
+const int64_t* dat_model_offsets_device(const dat_model* m);
+
+/* Flat fp32 parameter vector, host memory, d elements.  set: uploads and (bf16 models) rounds
+ * conv/linear weights to nearest-even bf16 for the compute copy; synchronous. */
+dat_status dat_model_set_params(dat_model* m, const float* host_flat);
+dat_status dat_model_get_params(const dat_model* m, float* host_flat);
+
+/* ---- the worker step --------------------------------------------------------------------- */
+
+/* Inner maximisation (Alg. A1 step 5).  x, delta: device fp32 [B,H,W,3]; y: device int32 [B].
+ *   z_0 per `init`;  for k = 1..K:  G = grad_x sum_n CE(net(x + z_{k-1}), y)
+ *     z_k = clip(z_{k-1} + alpha*sign(G), -eps, eps), sign(0) = 0;  z_k = min(max(z_k, -x), 1-x)
+ *   delta = z_K (K = 0 returns z_0).  loss_per_step: optional host array of K+1 floats, mean CE
+ *   at z_0..z_K (costs one extra forward and a synchronisation). */
+dat_status dat_attack(dat_model* m, const float* x, const int32_t* y, int B, float eps,
+                      float alpha, int K, dat_init init, float* delta, float* loss_per_step,
+                      void* stream);
+
+/* Outer gradient (Alg. A1 step 6): grads[d] (device fp32, tensor-table order) =
+ * (1/B) sum_n grad_theta CE(net(x_adv_n), y_n).  x_adv: device fp32 [B,H,W,3] pixels (already
+ * perturbed).  loss: optional host float, mean CE. */
+dat_status dat_step(dat_model* m, const float* x_adv, const int32_t* y, int B, float* grads,
+                    float* loss, void* stream);
+
+/* One backward-to-input pass: gx[B,H,W,3] (device fp32) = grad_x sum_n CE(net(x), y); logits
+ * (optional, device fp32 [B,classes]).  The quantity whose sign drives dat_attack. */
+dat_status dat_input_grad(dat_model* m, const float* x, const int32_t* y, int B, float* gx,
+                          float* logits, float* loss, void* stream);
+
+/* The elementwise pieces of the attack on their own (also what dat_attack launches):
+ * dat_pgd_init writes z_0; dat_pgd_update applies one projected sign step in place.
+ * N = number of fp32 elements (B*H*W*3); all pointers device; buffers 16-byte aligned. */
+dat_status dat_pgd_init(const float* x, int64_t N, float eps, dat_init init, float* delta,
+                        void* stream);
+dat_status dat_pgd_update(const float* x, const float* G, float* delta, int64_t N, float eps,
+                          float alpha, void* stream);
+
+/* Plain SGD on the fp32 master parameters: theta <- theta - lr * grads (then the bf16 compute
+ * copy is refreshed).  The outer-minimisation oracle A(.) of Alg. A1 in its simplest form. */
+dat_status dat_sgd_update(dat_model* m, const float* grads, float lr, void* stream);
+
+/* ---- gradient quantizer (Alg. A1 step 7) ---------------------------------------------------
+ * Per tensor t of the table: scale_t = max_i |g_i|;  S = 2^(bits-1) - 1;
+ *   r = |g_i| * (S / scale_t);  l = floor(r);  code magnitude = l + [u_i < r - l] (capped at S),
+ *   u_i = 24-bit uniform from Philox4x32-10 (counter = i/4, stream 0, key = seed, word i mod 4,
+ *   i = flat element index);  the code carries the sign of g_i.  scale_t = 0 gives zero codes;
+ *   a non-finite scale_t is written to scales[t] and that tensor's codes are zero.
+ * Codes are `bits`-bit two's-complement fields packed little-endian (element i occupies bits
+ * [(i*bits) mod 8, ...) of byte i*bits/8).  bits in {2,4,8,16}.
+ *   grads: device fp32 [d], 16-byte aligned;  offsets_dev: device int64 [num_tensors+1];
+ *   q: device, dat_quantized_bytes(d,bits) bytes, 4-byte aligned;  scales: device fp32
+ *   [num_tensors].  Asynchronous on `stream`. */
+dat_status dat_quantize(const float* grads, const int64_t* offsets_dev, int num_tensors,
+                        int64_t d, int bits, uint64_t seed, uint8_t* q, float* scales,
+                        void* stream);
+
+/* grads_out[i] = code_i * (scale_t / S), device fp32 [d], 16-byte aligned. */
+dat_status dat_dequantize(const uint8_t* q, const float* scales, const int64_t* offsets_dev,
+                          int num_tensors, int64_t d, int bits, float* grads_out, void* stream);
+
+size_t dat_quantized_bytes(int64_t d, int bits);
+
+/* ---- convolution kernels on their own (bf16 storage, fp32 accumulate on MFMA) --------------
+ * The three contractions behind dat_attack / dat_step, exposed for per-shape parity tests and
+ * timing.  Tensors are device bf16 (uint16 bit patterns): x [B,H,W,Cin], w [Cout,k,k,Cin],
+ * y / dy [B,Ho,Wo,Cout], Ho = (H + 2*pad - k)/stride + 1; Cin and Cout multiples of 8.
+ *   forward:         y = conv(x, w)
+ *   backward_data:   dx = adjoint of forward w.r.t. x applied to dy
+ *   backward_weight: dw (device fp32 [Cout,k,k,Cin]) = adjoint w.r.t. w applied to dy */
+dat_status dat_conv_forward(const uint16_t* x, const uint16_t* w, uint16_t* y, int B, int H,
+                            int W, int Cin, int Cout, int k, int stride, int pad, void* stream);
+dat_status dat_conv_backward_data(const uint16_t* dy, const uint16_t* w, uint16_t* dx, int B,
+                                  int H, int W, int Cin, int Cout, int k, int stride, int pad,
+                                  void* stream);
+dat_status dat_conv_backward_weight(const uint16_t* x, const uint16_t* dy, float* dw, int B,
+                                    int H, int W, int Cin, int Cout, int k, int stride, int pad,
+                                    void* stream);
+
+/* ---- misc ---------------------------------------------------------------------------------- */
+const char* dat_status_string(dat_status s);
+/* Text of the last HIP error seen by this thread's calls ("" if none). */
+const char* dat_last_error(void);
+/* Fills out[n] (device) with the library's Philox uniforms for flat indices start..start+n-1:
+ * the stream the quantizer (stream_id 0) and the random init (stream_id 1) draw from. */
+dat_status dat_philox_uniform(uint64_t start, int64_t n, uint64_t seed, uint32_t stream_id,
+                              float* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAT_H */

@@ -206,7 +206,7 @@ def dequantize(codes, scales, offsets, S):
 
 def pack(codes, bits):
     codes = np.ascontiguousarray(codes, np.int32)
-    n = codes.size if bits == 8 else (codes.size + 1) // 2
+    n = (codes.size * bits + 7) // 8
     q = np.zeros(n, np.uint8)
     _pack(codes, codes.size, bits, q)
     return q

@@ -948,22 +948,31 @@ void orc_dequantize(const int32_t* codes, const float* scales, const int64_t* of
   }
 }
 
-// Wire packing: b = 8 -> one two's-complement byte per code; b = 4 -> two's-complement
-// nibbles, element 2j in the low nibble of byte j.
+// Wire packing: `bits`-bit two's-complement fields, little-endian: element i occupies bits
+// [(i*bits) mod 8, ...) of byte floor(i*bits/8) (for bits = 4: element 2j in the low nibble of
+// byte j; for bits = 16: low byte first).  bits in {2, 4, 8, 16}.
 void orc_pack(const int32_t* codes, int64_t d, int bits, uint8_t* q) {
-  if (bits == 8) { for (int64_t i = 0; i < d; ++i) q[i] = (uint8_t)(int8_t)codes[i]; return; }
-  for (int64_t j = 0; j < (d + 1) / 2; ++j) {
-    uint8_t lo = (uint8_t)(codes[2 * j] & 0xF);
-    uint8_t hi = (2 * j + 1 < d) ? (uint8_t)(codes[2 * j + 1] & 0xF) : 0;
-    q[j] = (uint8_t)(lo | (hi << 4));
+  int64_t nbytes = (d * bits + 7) / 8;
+  for (int64_t j = 0; j < nbytes; ++j) q[j] = 0;
+  for (int64_t i = 0; i < d; ++i) {
+    uint32_t field = (uint32_t)codes[i] & ((1u << bits) - 1u);
+    for (int b = 0; b < bits; ++b) {
+      int64_t pos = i * bits + b;
+      if ((field >> b) & 1u) q[pos / 8] |= (uint8_t)(1u << (pos % 8));
+    }
   }
 }
 
 void orc_unpack(const uint8_t* q, int64_t d, int bits, int32_t* codes) {
-  if (bits == 8) { for (int64_t i = 0; i < d; ++i) codes[i] = (int8_t)q[i]; return; }
   for (int64_t i = 0; i < d; ++i) {
-    int v = (q[i / 2] >> ((i & 1) * 4)) & 0xF;
-    codes[i] = v >= 8 ? v - 16 : v;
+    uint32_t field = 0;
+    for (int b = 0; b < bits; ++b) {
+      int64_t pos = i * bits + b;
+      if ((q[pos / 8] >> (pos % 8)) & 1u) field |= 1u << b;
+    }
+    int32_t v = (int32_t)field;
+    if (field & (1u << (bits - 1))) v -= (int32_t)(1u << bits);
+    codes[i] = v;
   }
 }
 

@@ -1,0 +1,257 @@
+"""ctypes binding of libdat.so with the same names as include/dat.h (without the dat_ prefix on
+methods of Model).  Raises if the library has not been built: there is no fallback path."""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdat.so")
+
+ARCH_TINYCNN, ARCH_RESNET18_CIFAR, ARCH_WRN34_10, ARCH_RESNET50, ARCH_TESTNET = 0, 1, 2, 3, 100
+F32, BF16 = 0, 1
+INIT_ZERO, INIT_UNIFORM, INIT_GIVEN = 0, 1, 2
+
+EXPORTS = [
+    "dat_model_create", "dat_model_destroy", "dat_model_num_params", "dat_model_tensor_table",
+    "dat_model_offsets_device", "dat_model_set_params", "dat_model_get_params", "dat_attack", "dat_step",
+    "dat_input_grad", "dat_pgd_init", "dat_pgd_update", "dat_sgd_update", "dat_quantize", "dat_dequantize",
+    "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
+    "dat_status_string", "dat_last_error", "dat_philox_uniform",
+]
+
+
+class DatError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        msg = _lib.dat_status_string(status).decode()
+        extra = _lib.dat_last_error().decode()
+        super().__init__("%s: %s (%d)%s" % (where, msg, self.status, (" -- " + extra) if extra and self.status == 5 else ""))
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libdat.so is not built: run `python -m paper_2206_06257_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no CPU fallback")
+    return C.CDLL(LIB_PATH)
+
+
+_lib = _load()
+
+
+class _Init(C.Structure):
+    _fields_ = [("mode", C.c_int), ("seed", C.c_uint64), ("delta0", C.c_void_p)]
+
+
+_vp, _i, _i64, _f, _u64 = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_uint64
+_lib.dat_status_string.restype = C.c_char_p
+_lib.dat_status_string.argtypes = [_i]
+_lib.dat_last_error.restype = C.c_char_p
+_lib.dat_model_create.argtypes = [_i, _i, _i, _i, _i, _i, _vp, _vp, C.POINTER(_vp)]
+_lib.dat_model_destroy.argtypes = [_vp]
+_lib.dat_model_num_params.argtypes = [_vp, C.POINTER(_i64), C.POINTER(_i)]
+_lib.dat_model_tensor_table.argtypes = [_vp, _vp, _vp, _vp]
+_lib.dat_model_offsets_device.restype = _vp
+_lib.dat_model_offsets_device.argtypes = [_vp]
+_lib.dat_model_set_params.argtypes = [_vp, _vp]
+_lib.dat_model_get_params.argtypes = [_vp, _vp]
+_lib.dat_attack.argtypes = [_vp, _vp, _vp, _i, _f, _f, _i, _Init, _vp, _vp, _vp]
+_lib.dat_step.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp]
+_lib.dat_input_grad.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp]
+_lib.dat_pgd_init.argtypes = [_vp, _i64, _f, _Init, _vp, _vp]
+_lib.dat_pgd_update.argtypes = [_vp, _vp, _vp, _i64, _f, _f, _vp]
+_lib.dat_sgd_update.argtypes = [_vp, _vp, _f, _vp]
+_lib.dat_quantize.argtypes = [_vp, _vp, _i, _i64, _i, _u64, _vp, _vp, _vp]
+_lib.dat_dequantize.argtypes = [_vp, _vp, _vp, _i, _i64, _i, _vp, _vp]
+_lib.dat_quantized_bytes.restype = C.c_size_t
+_lib.dat_quantized_bytes.argtypes = [_i64, _i]
+for _n in ("dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight"):
+    getattr(_lib, _n).argtypes = [_vp, _vp, _vp] + [_i] * 8 + [_vp]
+_lib.dat_philox_uniform.argtypes = [_u64, _i64, _u64, C.c_uint32, _vp, _vp]
+
+
+def _check(status, where):
+    if status != 0:
+        raise DatError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dev(t, dtype):
+    assert t.is_cuda and t.is_contiguous() and t.dtype == dtype, (t.device, t.dtype, dtype)
+    return t
+
+
+def _init(mode, seed, delta0):
+    return _Init(int(mode), int(seed) & 0xFFFFFFFFFFFFFFFF, None if delta0 is None else delta0.data_ptr())
+
+
+class Model:
+    """dat_model handle: one architecture with its device parameters and workspace."""
+
+    def __init__(self, arch, dtype, max_batch, H, W, num_classes, mean=None, std=None):
+        h = _vp()
+        m = None if mean is None else np.ascontiguousarray(mean, np.float32)
+        s = None if std is None else np.ascontiguousarray(std, np.float32)
+        _check(_lib.dat_model_create(arch, dtype, max_batch, H, W, num_classes,
+                                     None if m is None else m.ctypes.data, None if s is None else s.ctypes.data,
+                                     C.byref(h)), "dat_model_create")
+        self._h = h
+        self.arch, self.dtype, self.max_batch, self.H, self.W, self.classes = arch, dtype, max_batch, H, W, num_classes
+        d, nt = _i64(), _i()
+        _check(_lib.dat_model_num_params(h, C.byref(d), C.byref(nt)), "dat_model_num_params")
+        self.d, self.num_tensors = d.value, nt.value
+        self.offsets = np.zeros(self.num_tensors + 1, np.int64)
+        self.fan_in = np.zeros(self.num_tensors, np.int32)
+        self.kind = np.zeros(self.num_tensors, np.int32)
+        _check(_lib.dat_model_tensor_table(h, self.offsets.ctypes.data, self.fan_in.ctypes.data, self.kind.ctypes.data),
+               "dat_model_tensor_table")
+        self.offsets_device_ptr = _lib.dat_model_offsets_device(h)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib.dat_model_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def set_params(self, flat):
+        flat = np.ascontiguousarray(flat, np.float32)
+        assert flat.size == self.d
+        _check(_lib.dat_model_set_params(self._h, flat.ctypes.data), "dat_model_set_params")
+
+    def get_params(self):
+        out = np.zeros(self.d, np.float32)
+        _check(_lib.dat_model_get_params(self._h, out.ctypes.data), "dat_model_get_params")
+        return out
+
+    def attack(self, x, y, eps, alpha, K, init=INIT_ZERO, seed=0, delta0=None, delta=None, want_losses=False, stream=None):
+        _dev(x, torch.float32); _dev(y, torch.int32)
+        B = x.shape[0]
+        if delta is None:
+            delta = torch.empty_like(x)
+        losses = np.zeros(K + 1, np.float32) if want_losses else None
+        _check(_lib.dat_attack(self._h, _ptr(x), _ptr(y), B, eps, alpha, K, _init(init, seed, delta0), _ptr(delta),
+                               None if losses is None else losses.ctypes.data, _stream(stream)), "dat_attack")
+        return (delta, losses) if want_losses else delta
+
+    def step(self, x_adv, y, grads=None, want_loss=False, stream=None):
+        _dev(x_adv, torch.float32); _dev(y, torch.int32)
+        if grads is None:
+            grads = torch.empty(self.d, dtype=torch.float32, device=x_adv.device)
+        loss = C.c_float(0.0)
+        _check(_lib.dat_step(self._h, _ptr(x_adv), _ptr(y), x_adv.shape[0], _ptr(grads),
+                             C.byref(loss) if want_loss else None, _stream(stream)), "dat_step")
+        return (grads, loss.value) if want_loss else grads
+
+    def input_grad(self, x, y, want_logits=True, want_loss=True, stream=None):
+        _dev(x, torch.float32); _dev(y, torch.int32)
+        gx = torch.empty_like(x)
+        logits = torch.empty(x.shape[0], self.classes, dtype=torch.float32, device=x.device) if want_logits else None
+        loss = C.c_float(0.0)
+        _check(_lib.dat_input_grad(self._h, _ptr(x), _ptr(y), x.shape[0], _ptr(gx), _ptr(logits),
+                                   C.byref(loss) if want_loss else None, _stream(stream)), "dat_input_grad")
+        return gx, logits, (loss.value if want_loss else None)
+
+    def sgd_update(self, grads, lr, stream=None):
+        _check(_lib.dat_sgd_update(self._h, _ptr(_dev(grads, torch.float32)), lr, _stream(stream)), "dat_sgd_update")
+
+    def offsets_device(self):
+        """int64 device pointer to the tensor table (owned by the model)."""
+        return self.offsets_device_ptr
+
+
+def pgd_init(x, eps, init=INIT_ZERO, seed=0, delta0=None, delta=None, stream=None):
+    _dev(x, torch.float32)
+    if delta is None:
+        delta = torch.empty_like(x)
+    _check(_lib.dat_pgd_init(_ptr(x), x.numel(), eps, _init(init, seed, delta0), _ptr(delta), _stream(stream)), "dat_pgd_init")
+    return delta
+
+
+def pgd_update(x, G, delta, eps, alpha, stream=None):
+    _dev(x, torch.float32); _dev(G, torch.float32); _dev(delta, torch.float32)
+    _check(_lib.dat_pgd_update(_ptr(x), _ptr(G), _ptr(delta), x.numel(), eps, alpha, _stream(stream)), "dat_pgd_update")
+    return delta
+
+
+def quantized_bytes(d, bits):
+    return int(_lib.dat_quantized_bytes(d, bits))
+
+
+def quantize(grads, offsets_dev, bits, seed, q=None, scales=None, stream=None):
+    """offsets_dev: int64 CUDA tensor [T+1] or a raw device pointer with num_tensors given as (ptr, T)."""
+    _dev(grads, torch.float32)
+    if isinstance(offsets_dev, tuple):
+        optr, T = C.c_void_p(offsets_dev[0]), offsets_dev[1]
+    else:
+        _dev(offsets_dev, torch.int64)
+        optr, T = _ptr(offsets_dev), offsets_dev.numel() - 1
+    d = grads.numel()
+    if q is None:
+        q = torch.empty(max(quantized_bytes(d, bits), 1), dtype=torch.uint8, device=grads.device)
+    if scales is None:
+        scales = torch.empty(T, dtype=torch.float32, device=grads.device)
+    _check(_lib.dat_quantize(_ptr(grads), optr, T, d, bits, int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(q), _ptr(scales),
+                             _stream(stream)), "dat_quantize")
+    return q, scales
+
+
+def dequantize(q, scales, offsets_dev, d, bits, out=None, stream=None):
+    if isinstance(offsets_dev, tuple):
+        optr, T = C.c_void_p(offsets_dev[0]), offsets_dev[1]
+    else:
+        optr, T = _ptr(offsets_dev), offsets_dev.numel() - 1
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=q.device)
+    _check(_lib.dat_dequantize(_ptr(q), _ptr(scales), optr, T, d, bits, _ptr(out), _stream(stream)), "dat_dequantize")
+    return out
+
+
+def philox_uniform(start, n, seed, stream_id, device="cuda"):
+    out = torch.empty(n, dtype=torch.float32, device=device)
+    _check(_lib.dat_philox_uniform(start, n, seed, stream_id, _ptr(out), _stream(None)), "dat_philox_uniform")
+    return out
+
+
+def _conv_shapes(B, H, W, Cin, Cout, k, stride, pad):
+    return (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+
+
+def conv_forward(x, w, stride, pad, stream=None):
+    """x [B,H,W,Cin] bf16, w [Cout,k,k,Cin] bf16 -> y [B,Ho,Wo,Cout] bf16."""
+    _dev(x, torch.bfloat16); _dev(w, torch.bfloat16)
+    B, H, W, Cin = x.shape
+    Cout, k = w.shape[0], w.shape[1]
+    Ho, Wo = _conv_shapes(B, H, W, Cin, Cout, k, stride, pad)
+    y = torch.empty(B, Ho, Wo, Cout, dtype=torch.bfloat16, device=x.device)
+    _check(_lib.dat_conv_forward(_ptr(x), _ptr(w), _ptr(y), B, H, W, Cin, Cout, k, stride, pad, _stream(stream)), "dat_conv_forward")
+    return y
+
+
+def conv_backward_data(dy, w, in_hw, stride, pad, stream=None):
+    _dev(dy, torch.bfloat16); _dev(w, torch.bfloat16)
+    B = dy.shape[0]
+    Cout, k, Cin = w.shape[0], w.shape[1], w.shape[3]
+    H, W = in_hw
+    dx = torch.empty(B, H, W, Cin, dtype=torch.bfloat16, device=dy.device)
+    _check(_lib.dat_conv_backward_data(_ptr(dy), _ptr(w), _ptr(dx), B, H, W, Cin, Cout, k, stride, pad, _stream(stream)), "dat_conv_backward_data")
+    return dx
+
+
+def conv_backward_weight(x, dy, k, stride, pad, stream=None):
+    _dev(x, torch.bfloat16); _dev(dy, torch.bfloat16)
+    B, H, W, Cin = x.shape
+    Cout = dy.shape[3]
+    dw = torch.empty(Cout, k, k, Cin, dtype=torch.float32, device=x.device)
+    _check(_lib.dat_conv_backward_weight(_ptr(x), _ptr(dy), _ptr(dw), B, H, W, Cin, Cout, k, stride, pad, _stream(stream)), "dat_conv_backward_weight")
+    return dw

@@ -1,0 +1,522 @@
+// bf16 convolutions as implicit GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16,
+// fp32 accumulate): forward, backward-data and backward-weight of the conv layers that make
+// up dat_attack / dat_step.  Written for 64-wide wavefronts: a 256-thread workgroup is four
+// waves in a 2x2 arrangement, each wave owning a (TC/2 channels) x (TP/2 pixels) accumulator
+// block made of 32x32 MFMA tiles.
+//
+// Forward / backward-data (one kernel, `igemm_kernel`):
+//   D[c][p] = sum_k Wt[c][k] * X[p][k],  k = (r, s, ci) flattened, ci fastest.
+//   Wt rows are output channels ([Cout][k*k*Cin], K-contiguous); X[p][k] is the im2col view of
+//   the NHWC input, gathered on the fly: 8 consecutive k are 8 consecutive channels of one tap,
+//   i.e. one 16-byte vector.  Both operands are staged in LDS as [row][32 k] tiles with an XOR
+//   swizzle of the 16-byte slots (slot ^= (row>>1)&3) so that the 16-byte fragment reads of
+//   the 32 lanes sharing a k-slot hit distinct banks; tiles are double buffered and the next
+//   tile's global loads are issued before the current tile's MFMAs.
+//   Backward-data is the same contraction over the output gradient with the flipped,
+//   transposed filter ([Cin][k][k][Cout]), unit output stride, and an input "dilation" equal
+//   to the forward stride (taps that fall between samples contribute zero).
+//   The epilogue adds an optional residual (or the previously stored gradient) in fp32, rounds
+//   once to bf16, transposes through LDS and writes 16-byte channel vectors.
+//   Workgroups are numbered so that the channel tiles of one pixel tile land on the same XCD
+//   (ids congruent mod 8 share an L2), which keeps the gathered activations L2-resident.
+//
+// Backward-weight (`wgrad_kernel`): dW[co][(r,s,ci)] = sum_p dY[p][co] * X[p][(r,s,ci)], a
+// contraction over pixels, which are the strided dimension of both operands.  Each thread
+// loads an 8-pixel x 8-channel block as eight 16-byte vectors, transposes it in registers
+// (v_perm_b32) and stores pixel-contiguous rows to LDS, so the MFMA fragments are again
+// 16-byte reads.  The pixel range is split over gridDim.z; partial tiles go to a workspace
+// and a second kernel sums them in a fixed order (deterministic).
+#include "kernels.h"
+
+namespace dat {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kThreads = 256;
+constexpr int BK = 32;                 // k per LDS tile (two MFMA k-steps)
+
+union Frag { uint4 u; bf16x8 v; };
+
+__device__ __forceinline__ int swz(int row, int slot) { return row * 64 + ((slot ^ ((row >> 1) & 3)) << 4); }
+
+struct IgemmArgs {
+  const bf16_t* in;     // [B][Hin][Win][Cin]
+  const bf16_t* wt;     // [Cout][KH*KW*Cin]
+  const bf16_t* res;    // optional [M][Cout] added before rounding
+  bf16_t* out;          // [M][Cout], M = B*Hout*Wout
+  int B, Hin, Win, Cin, Hout, Wout, Cout;
+  int KH, KW, ostride, pad, dshift;   // input dilation = 1 << dshift
+  int M, Ktot, nct, npt;
+};
+
+template <int TC, int TP>
+__global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
+  constexpr int WC = TC / 2, WP = TP / 2;          // wave tile
+  constexpr int NI = WC / 32, NJ = WP / 32;        // MFMA tiles per wave
+  constexpr int VW = TC * 4 / kThreads, VX = TP * 4 / kThreads;   // 16-byte vectors per thread per tile
+  constexpr int TILE_BYTES = (TC + TP) * 64;
+  constexpr int STG_STRIDE = TC * 2 + 16;
+  constexpr int LDS_BYTES = (2 * TILE_BYTES > TP * STG_STRIDE) ? 2 * TILE_BYTES : TP * STG_STRIDE;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
+
+  // XCD-aware tile numbering
+  const int bid = blockIdx.x;
+  const int q = bid >> 3;
+  const int ct = q % a.nct;
+  const int pt = (q / a.nct) * 8 + (bid & 7);
+  if (pt >= a.npt) return;
+  const int c0 = ct * TC, m0 = pt * TP;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wc = wave & 1, wp = wave >> 1;
+  const int kvec = tid & 3, lrow = tid >> 2;       // this thread's slot in the global->LDS copy
+
+  // im2col row state for the activation vectors this thread fetches
+  int hb[VX], wb[VX]; int64_t nb[VX]; bool mv[VX];
+  const int HW = a.Hout * a.Wout;
+#pragma unroll
+  for (int i = 0; i < VX; ++i) {
+    const int m = m0 + lrow + 64 * i;
+    mv[i] = m < a.M;
+    const int mm = mv[i] ? m : 0;
+    const int n = mm / HW, rem = mm - n * HW;
+    const int ho = rem / a.Wout, wo = rem - ho * a.Wout;
+    hb[i] = ho * a.ostride - a.pad; wb[i] = wo * a.ostride - a.pad;
+    nb[i] = (int64_t)n * a.Hin * a.Win;
+  }
+  // (r, s, c) of this thread's k-slot, advanced by BK per tile
+  int kc, kr, ks;
+  {
+    const int k = kvec * 8;
+    const int tap = k / a.Cin;
+    kc = k - tap * a.Cin; kr = tap / a.KW; ks = tap - kr * a.KW;
+  }
+  const int dmask = (1 << a.dshift) - 1;
+  const int ntiles = (a.Ktot + BK - 1) / BK;
+
+  uint4 gw[VW], gx[VX];
+  auto fetch = [&](int kt) {
+    const int k = kt * BK + kvec * 8;
+    const bool kvalid = k < a.Ktot;
+#pragma unroll
+    for (int i = 0; i < VW; ++i) {
+      const int c = c0 + lrow + 64 * i;
+      gw[i] = (kvalid && c < a.Cout) ? *reinterpret_cast<const uint4*>(a.wt + (int64_t)c * a.Ktot + k) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < VX; ++i) {
+      const int ph = hb[i] + kr, pw = wb[i] + ks;
+      bool ok = kvalid && mv[i] && ph >= 0 && pw >= 0 && ((ph | pw) & dmask) == 0;
+      const int hi = ph >> a.dshift, wi = pw >> a.dshift;
+      ok = ok && hi < a.Hin && wi < a.Win;
+      gx[i] = ok ? *reinterpret_cast<const uint4*>(a.in + ((nb[i] + (int64_t)hi * a.Win + wi) * a.Cin + kc)) : make_uint4(0, 0, 0, 0);
+    }
+    // advance (r,s,c) to the next tile
+    kc += BK;
+    while (kc >= a.Cin) { kc -= a.Cin; if (++ks == a.KW) { ks = 0; ++kr; } }
+  };
+  auto stash = [&](int buf) {
+    unsigned char* wbase = lds + buf * TILE_BYTES;
+    unsigned char* xbase = wbase + TC * 64;
+#pragma unroll
+    for (int i = 0; i < VW; ++i) *reinterpret_cast<uint4*>(wbase + swz(lrow + 64 * i, kvec)) = gw[i];
+#pragma unroll
+    for (int i = 0; i < VX; ++i) *reinterpret_cast<uint4*>(xbase + swz(lrow + 64 * i, kvec)) = gx[i];
+  };
+
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < ntiles) fetch(kt + 1);
+    const unsigned char* wbase = lds + buf * TILE_BYTES;
+    const unsigned char* xbase = wbase + TC * 64;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      Frag fa[NI], fb[NJ];
+      const int slot = kk * 2 + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < NI; ++i) fa[i].u = *reinterpret_cast<const uint4*>(wbase + swz(wc * WC + i * 32 + (lane & 31), slot));
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) fb[j].u = *reinterpret_cast<const uint4*>(xbase + swz(wp * WP + j * 32 + (lane & 31), slot));
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < ntiles) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: (+res) -> bf16 -> LDS transpose -> 16-byte stores -------------------------
+  // accumulator element e of lane l in tile (i,j): channel = 8*(e/4) + 4*(l/32) + e%4, pixel = l%32
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int prow = wp * WP + j * 32 + (lane & 31);
+      const int m = m0 + prow;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int ch = wc * WC + i * 32 + 8 * g + 4 * (lane >> 5);
+        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        if (a.res && m < a.M && c0 + ch < a.Cout) {
+          const uint2 r = *reinterpret_cast<const uint2*>(a.res + (int64_t)m * a.Cout + c0 + ch);
+          v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xffff0000u);
+          v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xffff0000u);
+        }
+        uint2 pk;
+        pk.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+        pk.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+        *reinterpret_cast<uint2*>(lds + prow * STG_STRIDE + ch * 2) = pk;
+      }
+    }
+  __syncthreads();
+  constexpr int CV = TC / 8;                       // channel vectors per pixel row
+  constexpr int RPP = kThreads / CV;               // pixel rows per pass
+  const int cv = tid % CV, pr0 = tid / CV;
+#pragma unroll
+  for (int i = 0; i < TP / RPP; ++i) {
+    const int prow = pr0 + i * RPP;
+    const int m = m0 + prow, ch = c0 + cv * 8;
+    if (m < a.M && ch < a.Cout)
+      *reinterpret_cast<uint4*>(a.out + (int64_t)m * a.Cout + ch) = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
+  }
+}
+
+__global__ void widen_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = bf2f(src[i]);
+}
+
+int log2_exact(int v) { int s = 0; while ((1 << s) < v) ++s; return (1 << s) == v ? s : -1; }
+
+template <int TC, int TP>
+dat_status launch_igemm(IgemmArgs a, hipStream_t st) {
+  a.nct = (a.Cout + TC - 1) / TC;
+  a.npt = (a.M + TP - 1) / TP;
+  const int npt8 = (a.npt + 7) / 8 * 8;
+  hipLaunchKernelGGL((igemm_kernel<TC, TP>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
+  if (a.Cin % 8 != 0 || a.Cout % 8 != 0 || a.dshift < 0) return DAT_ERR_UNSUPPORTED;
+  if (a.Cout <= 64) return launch_igemm<64, 128>(a, st);
+  return launch_igemm<128, 128>(a, st);
+}
+
+// ---- weight layouts ---------------------------------------------------------------------------
+// master fp32 [Cout][k][k][cin_real] -> w [Cout][k][k][Cin] bf16 (zero padded channels) and
+// wT [Cin][k][k][Cout] bf16 with wT[ci][r][s][co] = w[co][k-1-r][k-1-s][ci].
+__global__ void weight_transform_kernel(const float* __restrict__ master, bf16_t* __restrict__ w, bf16_t* __restrict__ wT,
+                                        int Cout, int k, int cin_real, int Cin) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)Cout * k * k * Cin) return;
+  const int ci = (int)(i % Cin);
+  int64_t p = i / Cin;
+  const int s = (int)(p % k); p /= k;
+  const int r = (int)(p % k);
+  const int co = (int)(p / k);
+  const bf16_t v = ci < cin_real ? f2bf(master[(((int64_t)co * k + r) * k + s) * cin_real + ci]) : (bf16_t)0;
+  w[i] = v;
+  wT[(((int64_t)ci * k + (k - 1 - r)) * k + (k - 1 - s)) * Cout + co] = v;
+}
+
+// ---- backward-weight ----------------------------------------------------------------------------
+struct WgradArgs {
+  const bf16_t* x;      // [B][H][W][Cin]
+  const bf16_t* dy;     // [M][Cout], M = B*Ho*Wo
+  float* ws;            // [splits][Cout][Ktot]
+  int B, H, W, Cin, Ho, Wo, Cout, k, stride, pad;
+  int M, Ktot, pix_per_split;
+};
+
+__device__ __forceinline__ void transpose8x8(const uint4 in[8], uint4 out[8]) {
+  // in[q] = 8 channels of pixel q (dword d holds channels 2d, 2d+1); out[c] = 8 pixels of channel c
+  const uint32_t* pi = reinterpret_cast<const uint32_t*>(in);
+  uint32_t* po = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq) {
+      const uint32_t lo = pi[(2 * qq) * 4 + (c >> 1)], hi = pi[(2 * qq + 1) * 4 + (c >> 1)];
+      po[c * 4 + qq] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+    }
+}
+
+// LDS tile [row][64 pixels] bf16, rows 128 bytes; 16-byte slots swizzled by row.
+__device__ __forceinline__ int swz128(int row, int slot) { return row * 128 + ((slot ^ (row & 7)) << 4); }
+
+template <int TC, int TJ>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
+  constexpr int BP = 64;                           // pixels per LDS tile
+  constexpr int WC = TC / 2, WJ = TJ / 2;
+  constexpr int NI = WC / 32, NJ = WJ / 32;
+  constexpr int NBLK_A = (TC / 8) * (BP / 8), NBLK_B = (TJ / 8) * (BP / 8);
+  constexpr int PER_A = (NBLK_A + kThreads - 1) / kThreads, PER_B = (NBLK_B + kThreads - 1) / kThreads;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[(TC + TJ) * 128];
+  unsigned char* abase = lds;
+  unsigned char* bbase = lds + TC * 128;
+
+  const int c0 = blockIdx.x * TC, j0 = blockIdx.y * TJ;
+  const int split = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wc = wave & 1, wj = wave >> 1;
+  const int p_begin = split * a.pix_per_split;
+  const int p_end = min(a.M, p_begin + a.pix_per_split);
+  const int HW = a.Ho * a.Wo;
+
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // column (r,s,ci) decode for this thread's B blocks is loop invariant
+  int b_cv[PER_B], b_pg[PER_B], b_r[PER_B], b_s[PER_B], b_ci[PER_B]; bool b_ok[PER_B];
+#pragma unroll
+  for (int u = 0; u < PER_B; ++u) {
+    const int blk = tid + u * kThreads;
+    b_cv[u] = blk % (TJ / 8); b_pg[u] = blk / (TJ / 8);
+    const int j = j0 + b_cv[u] * 8;
+    b_ok[u] = blk < NBLK_B && j < a.Ktot;
+    const int jj = b_ok[u] ? j : 0;
+    const int tap = jj / a.Cin;
+    b_ci[u] = jj - tap * a.Cin; b_r[u] = tap / a.k; b_s[u] = tap - b_r[u] * a.k;
+  }
+
+  for (int p0 = p_begin; p0 < p_end; p0 += BP) {
+    // ---- global -> registers -> transpose -> LDS
+#pragma unroll
+    for (int u = 0; u < PER_A; ++u) {
+      const int blk = tid + u * kThreads;
+      if (blk < NBLK_A) {
+        const int cv = blk % (TC / 8), pg = blk / (TC / 8);
+        const int c = c0 + cv * 8;
+        uint4 in[8], out[8];
+#pragma unroll
+        for (int qd = 0; qd < 8; ++qd) {
+          const int p = p0 + pg * 8 + qd;
+          in[qd] = (p < p_end && c < a.Cout) ? *reinterpret_cast<const uint4*>(a.dy + (int64_t)p * a.Cout + c) : make_uint4(0, 0, 0, 0);
+        }
+        transpose8x8(in, out);
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) *reinterpret_cast<uint4*>(abase + swz128(cv * 8 + cc, pg)) = out[cc];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < PER_B; ++u) {
+      const int blk = tid + u * kThreads;
+      if (blk < NBLK_B) {
+        uint4 in[8], out[8];
+        int p = p0 + b_pg[u] * 8;
+        int n = p / HW, rem = p - n * HW;
+        int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+#pragma unroll
+        for (int qd = 0; qd < 8; ++qd) {
+          const int hi = ho * a.stride + b_r[u] - a.pad, wi = wo * a.stride + b_s[u] - a.pad;
+          const bool ok = b_ok[u] && (p + qd) < p_end && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
+          in[qd] = ok ? *reinterpret_cast<const uint4*>(a.x + (((int64_t)n * a.H + hi) * a.W + wi) * a.Cin + b_ci[u]) : make_uint4(0, 0, 0, 0);
+          if (++wo == a.Wo) { wo = 0; if (++ho == a.Ho) { ho = 0; ++n; } }
+        }
+        transpose8x8(in, out);
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) *reinterpret_cast<uint4*>(bbase + swz128(b_cv[u] * 8 + cc, b_pg[u])) = out[cc];
+      }
+    }
+    __syncthreads();
+    // ---- MFMA over the 64 pixels (4 k-steps of 16)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      Frag fa[NI], fb[NJ];
+      const int slot = kk * 2 + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < NI; ++i) fa[i].u = *reinterpret_cast<const uint4*>(abase + swz128(wc * WC + i * 32 + (lane & 31), slot));
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) fb[j].u = *reinterpret_cast<const uint4*>(bbase + swz128(wj * WJ + j * 32 + (lane & 31), slot));
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+  // ---- partial tile -> workspace[split][co][j]   (lane: column j = l%32, rows co = 8g+4h+e)
+  float* dst = a.ws + (int64_t)split * a.Cout * a.Ktot;
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int col = j0 + wj * WJ + j * 32 + (lane & 31);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int co = c0 + wc * WC + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (co < a.Cout && col < a.Ktot) dst[(int64_t)co * a.Ktot + col] = acc[i][j][e];
+      }
+    }
+}
+
+__global__ void wgrad_reduce_kernel(const float* __restrict__ ws, int splits, int64_t per_split, int Cin, int cin_real,
+                                    float scale, float* __restrict__ dw) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= per_split) return;
+  const int ci = (int)(i % Cin);
+  if (ci >= cin_real) return;
+  float s = 0.f;
+  for (int k = 0; k < splits; ++k) s += ws[(int64_t)k * per_split + i];
+  dw[(i / Cin) * cin_real + ci] = s * scale;
+}
+
+struct WgradPlan { int splits, pix_per_split, gx, gy; bool narrow; };
+
+WgradPlan plan_wgrad(const ConvGeom& g) {
+  WgradPlan p;
+  const int M = g.B * g.Ho * g.Wo, Ktot = g.k * g.k * g.Cin;
+  p.narrow = g.Cout <= 64;
+  const int TC = p.narrow ? 64 : 128;
+  p.gx = (g.Cout + TC - 1) / TC;
+  p.gy = (Ktot + 127) / 128;
+  const int tiles = p.gx * p.gy;
+  int splits = (2048 + tiles - 1) / tiles;
+  const int max_by_pixels = (M + 255) / 256;
+  if (splits > max_by_pixels) splits = max_by_pixels;
+  if (splits < 1) splits = 1;
+  if (splits > 512) splits = 512;
+  int pps = (M + splits - 1) / splits;
+  pps = (pps + 63) / 64 * 64;
+  p.pix_per_split = pps;
+  p.splits = (M + pps - 1) / pps;
+  return p;
+}
+
+}  // namespace
+
+size_t conv_mfma_wgrad_workspace(const ConvGeom& g) {
+  const WgradPlan p = plan_wgrad(g);
+  return (size_t)p.splits * g.Cout * g.k * g.k * g.Cin * sizeof(float);
+}
+
+dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, hipStream_t st) {
+  IgemmArgs a;
+  a.in = x; a.wt = w; a.res = res; a.out = y;
+  a.B = g.B; a.Hin = g.H; a.Win = g.W; a.Cin = g.Cin; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
+  a.KH = g.k; a.KW = g.k; a.ostride = g.stride; a.pad = g.pad; a.dshift = 0;
+  a.M = g.B * g.Ho * g.Wo; a.Ktot = g.k * g.k * g.Cin; a.nct = a.npt = 0;
+  return run_igemm(a, st);
+}
+
+dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, hipStream_t st) {
+  IgemmArgs a;
+  a.in = dy; a.wt = wT; a.res = accumulate ? dx : nullptr; a.out = dx;
+  a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H; a.Wout = g.W; a.Cout = g.Cin;
+  a.KH = g.k; a.KW = g.k; a.ostride = 1; a.pad = g.k - 1 - g.pad; a.dshift = log2_exact(g.stride);
+  a.M = g.B * g.H * g.W; a.Ktot = g.k * g.k * g.Cout; a.nct = a.npt = 0;
+  return run_igemm(a, st);
+}
+
+dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale,
+                                     void* ws, hipStream_t st) {
+  if (g.Cin % 8 != 0 || g.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
+  const WgradPlan p = plan_wgrad(g);
+  WgradArgs a;
+  a.x = x; a.dy = dy; a.ws = (float*)ws;
+  a.B = g.B; a.H = g.H; a.W = g.W; a.Cin = g.Cin; a.Ho = g.Ho; a.Wo = g.Wo; a.Cout = g.Cout;
+  a.k = g.k; a.stride = g.stride; a.pad = g.pad;
+  a.M = g.B * g.Ho * g.Wo; a.Ktot = g.k * g.k * g.Cin; a.pix_per_split = p.pix_per_split;
+  const dim3 grid((unsigned)p.gx, (unsigned)p.gy, (unsigned)p.splits);
+  if (p.narrow) hipLaunchKernelGGL((wgrad_kernel<64, 128>), grid, dim3(kThreads), 0, st, a);
+  else hipLaunchKernelGGL((wgrad_kernel<128, 128>), grid, dim3(kThreads), 0, st, a);
+  DAT_LAUNCH_CHECK();
+  const int64_t per_split = (int64_t)g.Cout * a.Ktot;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per_split + 255) / 256)), dim3(256), 0, st, (const float*)ws, p.splits,
+                     per_split, g.Cin, cin_real, scale, dw);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, int Cout, int k, int cin_real, int Cin, hipStream_t st) {
+  const int64_t n = (int64_t)Cout * k * k * Cin;
+  hipLaunchKernelGGL(weight_transform_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, master, w, wT, Cout, k, cin_real, Cin);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+}  // namespace dat
+
+// ---- C entry points for per-shape tests and timing -----------------------------------------------
+using namespace dat;
+
+static bool geom_from(int B, int H, int W, int Cin, int Cout, int k, int stride, int pad, ConvGeom* g) {
+  if (B < 1 || H < 1 || W < 1 || Cin < 8 || Cout < 8 || Cin % 8 || Cout % 8 || k < 1 || pad < 0 || pad >= k) return false;
+  if (stride != 1 && stride != 2) return false;
+  g->B = B; g->H = H; g->W = W; g->Cin = Cin; g->Cout = Cout; g->k = k; g->stride = stride; g->pad = pad;
+  g->Ho = (H + 2 * pad - k) / stride + 1; g->Wo = (W + 2 * pad - k) / stride + 1;
+  if (g->Ho < 1 || g->Wo < 1) return false;
+  if ((int64_t)B * H * W * Cin >= (1ll << 31) || (int64_t)B * g->Ho * g->Wo * Cout >= (1ll << 31)) return false;
+  return true;
+}
+
+extern "C" dat_status dat_conv_forward(const uint16_t* x, const uint16_t* w, uint16_t* y, int B, int H, int W, int Cin,
+                                       int Cout, int k, int stride, int pad, void* stream) {
+  ConvGeom g;
+  if (!x || !w || !y || !geom_from(B, H, W, Cin, Cout, k, stride, pad, &g)) return DAT_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return DAT_ERR_ARG;
+  return conv_mfma_forward(x, w, nullptr, y, g, (hipStream_t)stream);
+}
+
+extern "C" dat_status dat_conv_backward_data(const uint16_t* dy, const uint16_t* w, uint16_t* dx, int B, int H, int W,
+                                             int Cin, int Cout, int k, int stride, int pad, void* stream) {
+  ConvGeom g;
+  if (!dy || !w || !dx || !geom_from(B, H, W, Cin, Cout, k, stride, pad, &g)) return DAT_ERR_ARG;
+  if (!aligned(dy, 16) || !aligned(w, 16) || !aligned(dx, 16)) return DAT_ERR_ARG;
+  // build the flipped transpose of w on the fly (test/timing path; the model caches it)
+  hipStream_t st = (hipStream_t)stream;
+  const size_t n = (size_t)Cout * k * k * Cin;
+  float* wf = nullptr; bf16_t* w2 = nullptr; bf16_t* wT = nullptr;
+  if (hipMalloc((void**)&wf, n * 4) != hipSuccess || hipMalloc((void**)&w2, n * 2) != hipSuccess ||
+      hipMalloc((void**)&wT, n * 2) != hipSuccess) {
+    (void)hipGetLastError();
+    if (wf) (void)hipFree(wf);
+    if (w2) (void)hipFree(w2);
+    return DAT_ERR_NOMEM;
+  }
+  dat_status s = DAT_OK;
+  hipLaunchKernelGGL(widen_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, w, wf, (int64_t)n);
+  if (hipGetLastError() != hipSuccess) s = DAT_ERR_HIP;
+  if (s == DAT_OK) s = launch_weight_transform(wf, w2, wT, Cout, k, Cin, Cin, st);
+  if (s == DAT_OK) s = conv_mfma_backward_data(dy, wT, dx, g, false, st);
+  (void)hipStreamSynchronize(st);
+  (void)hipFree(wf); (void)hipFree(w2); (void)hipFree(wT);
+  return s;
+}
+
+extern "C" dat_status dat_conv_backward_weight(const uint16_t* x, const uint16_t* dy, float* dw, int B, int H, int W,
+                                               int Cin, int Cout, int k, int stride, int pad, void* stream) {
+  ConvGeom g;
+  if (!x || !dy || !dw || !geom_from(B, H, W, Cin, Cout, k, stride, pad, &g)) return DAT_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(dw, 16)) return DAT_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  void* ws = nullptr;
+  if (hipMalloc(&ws, conv_mfma_wgrad_workspace(g)) != hipSuccess) { (void)hipGetLastError(); return DAT_ERR_NOMEM; }
+  dat_status s = conv_mfma_backward_weight(x, dy, dw, Cin, g, 1.0f, ws, st);
+  (void)hipStreamSynchronize(st);
+  (void)hipFree(ws);
+  return s;
+}

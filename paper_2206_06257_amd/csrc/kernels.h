@@ -1,0 +1,91 @@
+// Internal launch interfaces between the translation units of libdat.
+#pragma once
+#include "common.h"
+
+namespace dat {
+
+// ---- attack elementwise kernels (pgd.hip) --------------------------------------------------
+struct NetInputDesc {
+  void* ptr;          // network input tensor, or nullptr
+  int bf16;           // 1: bf16 NHWC with channels padded to 8 (pad = 0); 0: fp32 NHWC, 3 channels
+  int normalize;
+  float mean[3], inv_std[3];
+};
+// z_0 (and optionally the network input at x + z_0) for `npix` pixels of 3 channels.
+dat_status launch_attack_init(const float* x, int64_t npix, float eps, dat_init init, float* delta,
+                              const NetInputDesc& in, hipStream_t st);
+// One projected sign step in place (and optionally the network input at the new point).
+dat_status launch_attack_update(const float* x, const float* G, float* delta, int64_t npix, float eps,
+                                float alpha, const NetInputDesc& in, hipStream_t st);
+// Network input from pixels alone (delta = nullptr) or from x + delta.
+dat_status launch_make_input(const float* x, const float* delta, int64_t npix, const NetInputDesc& in,
+                             hipStream_t st);
+
+}  // namespace dat
+
+namespace dat {
+
+// ---- tensors ---------------------------------------------------------------------------------
+// All activation tensors are NHWC with `rows` = B*H*W pixels of C contiguous channels, stored
+// as fp32 (dtype 0) or bf16 (dtype 1).  C is a multiple of 8.
+struct ConvGeom {
+  int B, H, W, Cin;      // input  [B,H,W,Cin]
+  int Ho, Wo, Cout;      // output [B,Ho,Wo,Cout]
+  int k, stride, pad;
+};
+
+// ---- fp32 direct convolutions (conv_direct.hip): the DAT_F32 path ------------------------------
+dat_status conv_direct_forward(const float* x, const float* w, const float* res, float* y, const ConvGeom& g, hipStream_t st);
+dat_status conv_direct_backward_data(const float* dy, const float* w, float* dx, const ConvGeom& g, bool accumulate, hipStream_t st);
+dat_status conv_direct_backward_weight(const float* x, const float* dy, float* dw, const ConvGeom& g, float scale, hipStream_t st);
+
+// ---- bf16 implicit-GEMM convolutions on MFMA (conv_mfma.hip): the DAT_BF16 path ----------------
+// w: [Cout][k][k][Cin] bf16.  wT: [Cin][k][k][Cout] bf16 with the taps flipped (see
+// launch_weight_transform), the operand of backward-data.
+dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, hipStream_t st);
+dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, hipStream_t st);
+// dw fp32 [Cout][k][k][Cin_real] (Cin_real <= g.Cin: padded input channels are dropped), scaled.
+// `ws` is a workspace of conv_mfma_wgrad_workspace(g) bytes.
+size_t conv_mfma_wgrad_workspace(const ConvGeom& g);
+dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale, void* ws, hipStream_t st);
+// master fp32 [Cout][k][k][cin_real] -> w bf16 [Cout][k][k][Cin] (zero padded) and wT.
+dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, int Cout, int k, int cin_real, int Cin, hipStream_t st);
+
+// ---- everything that is not a convolution (layers.hip) -----------------------------------------
+// Batch statistics of x[rows][C]: mean[C], rstd[C] = 1/sqrt(var + 1e-5) (biased variance).
+// `partial` holds bn_partial_floats(rows, C) floats.
+size_t bn_partial_floats(int64_t rows, int C);
+dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partial, float* mean, float* rstd, hipStream_t st);
+// out = act(gamma*((x-mean)*rstd) + beta [+ res])
+dat_status bnact_forward(const void* x, const void* res, void* out, int dtype, int64_t rows, int C, const float* mean,
+                         const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st);
+// dy = dout masked by (out > 0) if relu.  sums[0..C) = sum dy (= dbeta), sums[C..2C) = sum dy*xhat (= dgamma).
+// Then dx (+)= gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows); dres (+)= dy.
+// dgamma/dbeta (fp32, may be null) receive scale*sums.
+dat_status bnact_backward(const void* x, const void* out, const void* dout, void* dx, bool dx_accumulate, void* dres,
+                          bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
+                          const float* gamma, int relu, float* partial, float* sums, float* dgamma, float* dbeta,
+                          float scale, hipStream_t st);
+dat_status biasact_forward(const void* x, void* out, int dtype, int64_t rows, int C, const float* bias, int relu, hipStream_t st);
+dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx_accumulate, int dtype, int64_t rows, int C,
+                            int relu, float* partial, float* dbias, float scale, hipStream_t st);
+dat_status maxpool_forward(const void* x, void* out, int dtype, int B, int H, int W, int C, int Ho, int Wo, hipStream_t st);
+dat_status maxpool_backward(const void* x, const void* dout, void* dx, bool accumulate, int dtype, int B, int H, int W, int C,
+                            int Ho, int Wo, hipStream_t st);
+// pooled[B][C] fp32 = mean over the HW pixels;  backward: dx (+)= dpooled/HW.
+dat_status gap_forward(const void* x, float* pooled, int dtype, int B, int HW, int C, hipStream_t st);
+dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dtype, int B, int HW, int C, hipStream_t st);
+// logits[B][O] = f[B][I] . W[O][I]^T + b;  backward: df, and (if dW) dW = scale * dz^T f, db = scale * sum dz.
+dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, hipStream_t st);
+dat_status fc_backward(const float* f, const float* W, const float* dz, float* df, float* dW, float* db, int B, int I, int O,
+                       float scale, hipStream_t st);
+// Softmax cross-entropy: loss_n per sample, dz = (softmax - onehot) * gscale; loss_mean[0] = mean loss_n.
+dat_status ce_forward_backward(const float* logits, const int32_t* y, float* dz, float* loss_n, float* loss_mean, int B, int O,
+                               float gscale, hipStream_t st);
+// fp32 -> bf16 copy (linear weights) ; first-layer gradient [rows][Cpad] -> gx[rows][3] * inv_std.
+dat_status launch_round_bf16_values(const float* src, float* dst, int64_t n, hipStream_t st);
+dat_status launch_input_grad(const void* g0, int dtype, int Cpad, int64_t rows, float s0, float s1, float s2, float* gx, hipStream_t st);
+dat_status launch_sgd(float* theta, const float* g, float lr, int64_t n, hipStream_t st);
+dat_status launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+
+}  // namespace dat

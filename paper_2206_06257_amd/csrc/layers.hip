@@ -1,0 +1,633 @@
+// Non-convolution layers of the networks and their backward passes: train-mode batch
+// normalisation fused with residual add and ReLU, bias+ReLU, 3x3/2 max-pool, global average
+// pool, the linear classifier, and the softmax cross-entropy gradient.  All are HBM-streaming
+// kernels over NHWC tensors: a thread owns 8 consecutive channels of one pixel (one 16-byte
+// vector in bf16, two in fp32) so that a wavefront touches contiguous memory.
+//
+// Per-channel reductions (batch statistics, BN/bias gradients) are two-stage and
+// deterministic: slabs of rows are reduced in registers + LDS in a fixed order into a
+// [slab][channel] table, which one thread per channel then sums in fp64.
+#include "kernels.h"
+
+namespace dat {
+namespace {
+
+constexpr int kT = 256;
+constexpr int kMaxSlabs = 512;
+
+template <typename T> struct V8;
+template <> struct V8<float> {
+  static __device__ __forceinline__ void load(const float* p, float v[8]) {
+    const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float v[8]) {
+    reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+  }
+};
+template <> struct V8<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float v[8]) {
+    const uint4 a = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { v[2 * j] = __uint_as_float(w[j] << 16); v[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u); }
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float v[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = (uint32_t)f2bf(v[2 * j]) | ((uint32_t)f2bf(v[2 * j + 1]) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+__device__ __forceinline__ void load8f(const float* p, float v[8]) { V8<float>::load(p, v); }
+
+struct SlabPlan { int tpr, rpp, nslabs; int64_t rows_per_slab; };
+
+SlabPlan plan_slabs(int64_t rows, int C) {
+  SlabPlan p;
+  p.tpr = C / 8;
+  p.rpp = kT / p.tpr;
+  if (p.rpp < 1) p.rpp = 1;
+  int64_t want = (rows + (int64_t)p.rpp * 4 - 1) / ((int64_t)p.rpp * 4);
+  p.nslabs = (int)(want < 1 ? 1 : (want > kMaxSlabs ? kMaxSlabs : want));
+  p.rows_per_slab = (rows + p.nslabs - 1) / p.nslabs;
+  return p;
+}
+
+// ---- per-channel two-value reduction -------------------------------------------------------
+// MODE 0: (sum x, sum x^2)            -- batch statistics
+// MODE 1: (sum dy, sum dy*xhat)       -- BN backward, dy = dout masked by out > 0 when relu
+// MODE 2: (sum dy, 0)                 -- bias backward
+template <typename T, int MODE>
+__global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, const T* __restrict__ out,
+                                                       const T* __restrict__ dout, const float* __restrict__ mean,
+                                                       const float* __restrict__ rstd, int relu, int64_t rows, int C,
+                                                       int tpr, int rpp, int64_t rows_per_slab,
+                                                       float* __restrict__ partial) {
+  __shared__ float red[2][kT][8];
+  const int tid = threadIdx.x, rr = tid / tpr, cv = tid % tpr;
+  const bool active = rr < rpp;
+  const int c0 = cv * 8;
+  float a1[8], a2[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { a1[j] = 0.f; a2[j] = 0.f; }
+  float mu[8], rs[8];
+  if (MODE == 1 && active) { load8f(mean + c0, mu); load8f(rstd + c0, rs); }
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
+  const int64_t r1 = min(rows, r0 + rows_per_slab);
+  if (active) {
+    for (int64_t r = r0 + rr; r < r1; r += rpp) {
+      const int64_t o = r * C + c0;
+      if (MODE == 0) {
+        float v[8]; V8<T>::load(x + o, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { a1[j] += v[j]; a2[j] += v[j] * v[j]; }
+      } else {
+        float g[8]; V8<T>::load(dout + o, g);
+        if (relu) {
+          float ov[8]; V8<T>::load(out + o, ov);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) if (!(ov[j] > 0.f)) g[j] = 0.f;
+        }
+        if (MODE == 1) {
+          float v[8]; V8<T>::load(x + o, v);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { a1[j] += g[j]; a2[j] += g[j] * ((v[j] - mu[j]) * rs[j]); }
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) a1[j] += g[j];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { red[0][tid][j] = a1[j]; red[1][tid][j] = a2[j]; }
+  __syncthreads();
+  if (rr == 0) {
+    for (int q = 1; q < rpp; ++q) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { a1[j] += red[0][q * tpr + cv][j]; a2[j] += red[1][q * tpr + cv][j]; }
+    }
+    float* p = partial + (int64_t)blockIdx.x * 2 * C;
+    V8<float>::store(p + c0, a1);
+    V8<float>::store(p + C + c0, a2);
+  }
+}
+
+// MODE 0: mean / rstd.  MODE 1,2: sums[0..C) = s1, sums[C..2C) = s2 and optional scaled copies.
+template <int MODE>
+__global__ void colfinal_kernel(const float* __restrict__ partial, int nslabs, int C, int64_t rows,
+                                float* __restrict__ o1, float* __restrict__ o2, float* __restrict__ e1,
+                                float* __restrict__ e2, float scale) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  double s1 = 0.0, s2 = 0.0;
+  for (int s = 0; s < nslabs; ++s) { s1 += (double)partial[(int64_t)s * 2 * C + c]; s2 += (double)partial[(int64_t)s * 2 * C + C + c]; }
+  if (MODE == 0) {
+    const double m = s1 / (double)rows;
+    double var = s2 / (double)rows - m * m;
+    if (var < 0.0) var = 0.0;
+    o1[c] = (float)m;
+    o2[c] = (float)(1.0 / sqrt(var + 1e-5));
+  } else {
+    o1[c] = (float)s1;
+    if (o2) o2[c] = (float)s2;
+    if (e1) e1[c] = (float)(s1 * (double)scale);
+    if (e2) e2[c] = (float)(s2 * (double)scale);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, const T* __restrict__ res,
+                                                       T* __restrict__ out, int64_t nvec, int tpr,
+                                                       const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                       const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                       int relu) {
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= nvec) return;
+  const int c0 = (int)(v % tpr) * 8;
+  float xv[8], mu[8], rs[8], ga[8], be[8], o[8];
+  V8<T>::load(x + v * 8, xv);
+  load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(beta + c0, be);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = ga[j] * ((xv[j] - mu[j]) * rs[j]) + be[j];
+  if (res) {
+    float rv[8]; V8<T>::load(res + v * 8, rv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] += rv[j];
+  }
+  if (relu) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = o[j] > 0.f ? o[j] : 0.f;
+  }
+  V8<T>::store(out + v * 8, o);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ out,
+                                                             const T* __restrict__ dout, T* __restrict__ dx,
+                                                             int dx_acc, T* __restrict__ dres, int dres_acc,
+                                                             int64_t nvec, int tpr, float inv_rows,
+                                                             const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                             const float* __restrict__ gamma, const float* __restrict__ sums,
+                                                             int C, int relu) {
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= nvec) return;
+  const int c0 = (int)(v % tpr) * 8;
+  float g[8], xv[8], mu[8], rs[8], ga[8], s1[8], s2[8], r[8];
+  V8<T>::load(dout + v * 8, g);
+  if (relu) {
+    float ov[8]; V8<T>::load(out + v * 8, ov);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) if (!(ov[j] > 0.f)) g[j] = 0.f;
+  }
+  if (dres) {
+    if (dres_acc) {
+      float old[8]; V8<T>::load(dres + v * 8, old);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) r[j] = old[j] + g[j];
+      V8<T>::store(dres + v * 8, r);
+    } else {
+      V8<T>::store(dres + v * 8, g);
+    }
+  }
+  V8<T>::load(x + v * 8, xv);
+  load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(sums + c0, s1); load8f(sums + C + c0, s2);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float xh = (xv[j] - mu[j]) * rs[j];
+    r[j] = ga[j] * rs[j] * (g[j] - s1[j] * inv_rows - xh * s2[j] * inv_rows);
+  }
+  if (dx_acc) {
+    float old[8]; V8<T>::load(dx + v * 8, old);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] += old[j];
+  }
+  V8<T>::store(dx + v * 8, r);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kT) void biasact_fwd_kernel(const T* __restrict__ x, T* __restrict__ out, int64_t nvec,
+                                                         int tpr, const float* __restrict__ bias, int relu) {
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= nvec) return;
+  float xv[8], b[8];
+  V8<T>::load(x + v * 8, xv); load8f(bias + (int)(v % tpr) * 8, b);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { xv[j] += b[j]; if (relu && !(xv[j] > 0.f)) xv[j] = 0.f; }
+  V8<T>::store(out + v * 8, xv);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kT) void biasact_bwd_kernel(const T* __restrict__ out, const T* __restrict__ dout,
+                                                         T* __restrict__ dx, int acc, int64_t nvec, int relu) {
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= nvec) return;
+  float g[8];
+  V8<T>::load(dout + v * 8, g);
+  if (relu) {
+    float ov[8]; V8<T>::load(out + v * 8, ov);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) if (!(ov[j] > 0.f)) g[j] = 0.f;
+  }
+  if (acc) {
+    float old[8]; V8<T>::load(dx + v * 8, old);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) g[j] += old[j];
+  }
+  V8<T>::store(dx + v * 8, g);
+}
+
+// 3x3 window, stride 2, padding 1.
+template <typename T>
+__global__ __launch_bounds__(kT) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ out, int B, int H,
+                                                         int W, int C, int Ho, int Wo) {
+  const int tpr = C / 8;
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= (int64_t)B * Ho * Wo * tpr) return;
+  const int cv = (int)(v % tpr);
+  int64_t p = v / tpr;
+  const int wo = (int)(p % Wo); p /= Wo;
+  const int ho = (int)(p % Ho);
+  const int n = (int)(p / Ho);
+  float best[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) best[j] = -__builtin_inff();
+  for (int r = 0; r < 3; ++r) {
+    const int hi = ho * 2 + r - 1;
+    if (hi < 0 || hi >= H) continue;
+    for (int s = 0; s < 3; ++s) {
+      const int wi = wo * 2 + s - 1;
+      if (wi < 0 || wi >= W) continue;
+      float xv[8]; V8<T>::load(x + (((int64_t)n * H + hi) * W + wi) * C + cv * 8, xv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) if (xv[j] > best[j]) best[j] = xv[j];
+    }
+  }
+  V8<T>::store(out + v * 8, best);
+}
+
+// Gather form: an input pixel receives the gradient of every window whose FIRST maximum (in
+// row-major window order) it is; contributions are summed in fp32 and stored once.
+template <typename T>
+__global__ __launch_bounds__(kT) void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dout,
+                                                         T* __restrict__ dx, int acc, int B, int H, int W, int C,
+                                                         int Ho, int Wo) {
+  const int tpr = C / 8;
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= (int64_t)B * H * W * tpr) return;
+  const int cv = (int)(v % tpr);
+  int64_t p = v / tpr;
+  const int w = (int)(p % W); p /= W;
+  const int h = (int)(p % H);
+  const int n = (int)(p / H);
+  float sum[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) sum[j] = 0.f;
+  const int ho_lo = max(0, (h) / 2), ho_hi = min(Ho - 1, (h + 1) / 2);
+  const int wo_lo = max(0, (w) / 2), wo_hi = min(Wo - 1, (w + 1) / 2);
+  for (int ho = ho_lo; ho <= ho_hi; ++ho)
+    for (int wo = wo_lo; wo <= wo_hi; ++wo) {
+      // is (h,w) inside this window?  rows ho*2-1 .. ho*2+1
+      if (h < ho * 2 - 1 || h > ho * 2 + 1 || w < wo * 2 - 1 || w > wo * 2 + 1) continue;
+      float best[8]; int arg[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { best[j] = -__builtin_inff(); arg[j] = -1; }
+      for (int r = 0; r < 3; ++r) {
+        const int hi = ho * 2 + r - 1;
+        if (hi < 0 || hi >= H) continue;
+        for (int s = 0; s < 3; ++s) {
+          const int wi = wo * 2 + s - 1;
+          if (wi < 0 || wi >= W) continue;
+          float xv[8]; V8<T>::load(x + (((int64_t)n * H + hi) * W + wi) * C + cv * 8, xv);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) if (xv[j] > best[j]) { best[j] = xv[j]; arg[j] = hi * W + wi; }
+        }
+      }
+      float g[8]; V8<T>::load(dout + (((int64_t)n * Ho + ho) * Wo + wo) * C + cv * 8, g);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) if (arg[j] == h * W + w) sum[j] += g[j];
+    }
+  if (acc) {
+    float old[8]; V8<T>::load(dx + v * 8, old);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum[j] += old[j];
+  }
+  V8<T>::store(dx + v * 8, sum);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kT) void gap_fwd_kernel(const T* __restrict__ x, float* __restrict__ pooled, int B, int HW, int C) {
+  const int tpr = C / 8;
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= (int64_t)B * tpr) return;
+  const int cv = (int)(v % tpr), n = (int)(v / tpr);
+  float s[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) s[j] = 0.f;
+  for (int i = 0; i < HW; ++i) {
+    float xv[8]; V8<T>::load(x + ((int64_t)n * HW + i) * C + cv * 8, xv);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s[j] += xv[j];
+  }
+  const float inv = 1.0f / (float)HW;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) s[j] *= inv;
+  V8<float>::store(pooled + (int64_t)n * C + cv * 8, s);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kT) void gap_bwd_kernel(const float* __restrict__ dpooled, T* __restrict__ dx, int acc, int B,
+                                                     int HW, int C) {
+  const int tpr = C / 8;
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= (int64_t)B * HW * tpr) return;
+  const int cv = (int)(v % tpr);
+  const int n = (int)(v / ((int64_t)tpr * HW));
+  float g[8]; load8f(dpooled + (int64_t)n * C + cv * 8, g);
+  const float inv = 1.0f / (float)HW;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) g[j] *= inv;
+  if (acc) {
+    float old[8]; V8<T>::load(dx + v * 8, old);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) g[j] += old[j];
+  }
+  V8<T>::store(dx + v * 8, g);
+}
+
+// ---- linear classifier (fp32) --------------------------------------------------------------
+// one wavefront per output logit: lanes stride over the input features
+__global__ __launch_bounds__(kT) void fc_fwd_kernel(const float* __restrict__ f, const float* __restrict__ W,
+                                                    const float* __restrict__ b, float* __restrict__ z, int B, int I, int O) {
+  const int64_t wave = ((int64_t)blockIdx.x * kT + threadIdx.x) >> 6;
+  const int lane = threadIdx.x & 63;
+  if (wave >= (int64_t)B * O) return;
+  const int n = (int)(wave / O), o = (int)(wave % O);
+  float acc = 0.f;
+  for (int i = lane; i < I; i += 64) acc += f[(int64_t)n * I + i] * W[(int64_t)o * I + i];
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
+  if (lane == 0) z[(int64_t)n * O + o] = acc + b[o];
+}
+
+__global__ __launch_bounds__(kT) void fc_bwd_input_kernel(const float* __restrict__ W, const float* __restrict__ dz,
+                                                          float* __restrict__ df, int B, int I, int O) {
+  const int64_t t = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (t >= (int64_t)B * I) return;
+  const int n = (int)(t / I), i = (int)(t % I);
+  float acc = 0.f;
+  for (int o = 0; o < O; ++o) acc += dz[(int64_t)n * O + o] * W[(int64_t)o * I + i];
+  df[t] = acc;
+}
+
+__global__ __launch_bounds__(kT) void fc_bwd_weight_kernel(const float* __restrict__ f, const float* __restrict__ dz,
+                                                           float* __restrict__ dW, float* __restrict__ db, int B, int I,
+                                                           int O, float scale) {
+  const int64_t t = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (t >= (int64_t)O * I) return;
+  const int o = (int)(t / I), i = (int)(t % I);
+  float acc = 0.f, sb = 0.f;
+  for (int n = 0; n < B; ++n) { const float g = dz[(int64_t)n * O + o]; acc += g * f[(int64_t)n * I + i]; sb += g; }
+  dW[t] = acc * scale;
+  if (i == 0) db[o] = sb * scale;
+}
+
+// ---- softmax cross-entropy: one wavefront per sample ------------------------------------------
+__global__ __launch_bounds__(64) void ce_kernel(const float* __restrict__ z, const int32_t* __restrict__ y,
+                                                float* __restrict__ dz, float* __restrict__ loss_n, int B, int O, float gscale) {
+  const int n = blockIdx.x, lane = threadIdx.x;
+  const float* zn = z + (int64_t)n * O;
+  float mx = -__builtin_inff();
+  for (int c = lane; c < O; c += 64) mx = fmaxf(mx, zn[c]);
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s));
+  float se = 0.f;
+  for (int c = lane; c < O; c += 64) se += expf(zn[c] - mx);
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) se += __shfl_xor(se, s);
+  const float lse = mx + logf(se);
+  const int yn = y[n];
+  for (int c = lane; c < O; c += 64) dz[(int64_t)n * O + c] = (expf(zn[c] - lse) - (c == yn ? 1.f : 0.f)) * gscale;
+  if (lane == 0) loss_n[n] = lse - zn[yn];
+}
+
+__global__ void mean_kernel(const float* __restrict__ v, int n, float* __restrict__ out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += (double)v[i];
+    out[0] = (float)(s / n);
+  }
+}
+
+__global__ void round_bf16_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = bf2f(f2bf(src[i]));
+}
+
+template <typename T>
+__global__ void input_grad_kernel(const T* __restrict__ g0, int Cpad, int64_t rows, float s0, float s1, float s2,
+                                  float* __restrict__ gx) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * 3) return;
+  const int64_t r = i / 3; const int c = (int)(i % 3);
+  float v;
+  if (sizeof(T) == 2) v = bf2f(((const bf16_t*)g0)[r * Cpad + c]); else v = ((const float*)g0)[r * Cpad + c];
+  gx[i] = __fmul_rn(v, c == 0 ? s0 : (c == 1 ? s1 : s2));
+}
+
+__global__ void sgd_kernel(float* __restrict__ theta, const float* __restrict__ g, float lr, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) theta[i] = __fsub_rn(theta[i], __fmul_rn(lr, g[i]));
+}
+
+__global__ void zero_kernel(uint32_t* __restrict__ p, int64_t nwords) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nwords) p[i] = 0u;
+}
+
+inline unsigned nblk(int64_t n) { return (unsigned)((n + kT - 1) / kT); }
+
+template <typename T, int MODE>
+dat_status colreduce(const void* x, const void* out, const void* dout, const float* mean, const float* rstd, int relu,
+                     int64_t rows, int C, float* partial, hipStream_t st, SlabPlan& p) {
+  p = plan_slabs(rows, C);
+  hipLaunchKernelGGL((colreduce_kernel<T, MODE>), dim3(p.nslabs), dim3(kT), 0, st, (const T*)x, (const T*)out,
+                     (const T*)dout, mean, rstd, relu, rows, C, p.tpr, p.rpp, p.rows_per_slab, partial);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+}  // namespace
+
+size_t bn_partial_floats(int64_t rows, int C) { (void)rows; return (size_t)kMaxSlabs * 2 * C; }
+
+#define DAT_BY_DTYPE(dtype, CALL_F32, CALL_BF16) do { if ((dtype) == 0) { CALL_F32; } else { CALL_BF16; } } while (0)
+
+dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partial, float* mean, float* rstd, hipStream_t st) {
+  if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
+  SlabPlan p; dat_status s;
+  DAT_BY_DTYPE(dtype, s = (colreduce<float, 0>(x, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)),
+               s = (colreduce<bf16_t, 0>(x, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)));
+  if (s != DAT_OK) return s;
+  hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 63) / 64), dim3(64), 0, st, partial, p.nslabs, C, rows, mean, rstd,
+                     (float*)nullptr, (float*)nullptr, 1.0f);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status bnact_forward(const void* x, const void* res, void* out, int dtype, int64_t rows, int C, const float* mean,
+                         const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st) {
+  const int64_t nvec = rows * (C / 8);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(bnact_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (const float*)res, (float*)out, nvec, C / 8, mean, rstd, gamma, beta, relu),
+    hipLaunchKernelGGL(bnact_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)res, (bf16_t*)out, nvec, C / 8, mean, rstd, gamma, beta, relu));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status bnact_backward(const void* x, const void* out, const void* dout, void* dx, bool dx_accumulate, void* dres,
+                          bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
+                          const float* gamma, int relu, float* partial, float* sums, float* dgamma, float* dbeta,
+                          float scale, hipStream_t st) {
+  if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
+  SlabPlan p; dat_status s;
+  DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)),
+               s = (colreduce<bf16_t, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)));
+  if (s != DAT_OK) return s;
+  hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 63) / 64), dim3(64), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
+                     dbeta, dgamma, scale);
+  DAT_LAUNCH_CHECK();
+  const int64_t nvec = rows * (C / 8);
+  const float inv_rows = (float)(1.0 / (double)rows);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (const float*)out, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, nvec, C / 8, inv_rows, mean, rstd, gamma, sums, C, relu),
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, nvec, C / 8, inv_rows, mean, rstd, gamma, sums, C, relu));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status biasact_forward(const void* x, void* out, int dtype, int64_t rows, int C, const float* bias, int relu, hipStream_t st) {
+  const int64_t nvec = rows * (C / 8);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(biasact_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (float*)out, nvec, C / 8, bias, relu),
+    hipLaunchKernelGGL(biasact_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (bf16_t*)out, nvec, C / 8, bias, relu));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx_accumulate, int dtype, int64_t rows, int C,
+                            int relu, float* partial, float* dbias, float scale, hipStream_t st) {
+  if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
+  if (dbias) {
+    SlabPlan p; dat_status s;
+    DAT_BY_DTYPE(dtype, s = (colreduce<float, 2>(nullptr, out, dout, nullptr, nullptr, relu, rows, C, partial, st, p)),
+                 s = (colreduce<bf16_t, 2>(nullptr, out, dout, nullptr, nullptr, relu, rows, C, partial, st, p)));
+    if (s != DAT_OK) return s;
+    hipLaunchKernelGGL(colfinal_kernel<2>, dim3((C + 63) / 64), dim3(64), 0, st, partial, p.nslabs, C, rows, dbias,
+                       (float*)nullptr, dbias, (float*)nullptr, scale);
+    DAT_LAUNCH_CHECK();
+  }
+  const int64_t nvec = rows * (C / 8);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(biasact_bwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)out, (const float*)dout, (float*)dx, (int)dx_accumulate, nvec, relu),
+    hipLaunchKernelGGL(biasact_bwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)out, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, nvec, relu));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status maxpool_forward(const void* x, void* out, int dtype, int B, int H, int W, int C, int Ho, int Wo, hipStream_t st) {
+  const int64_t nvec = (int64_t)B * Ho * Wo * (C / 8);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(maxpool_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (float*)out, B, H, W, C, Ho, Wo),
+    hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (bf16_t*)out, B, H, W, C, Ho, Wo));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status maxpool_backward(const void* x, const void* dout, void* dx, bool accumulate, int dtype, int B, int H, int W, int C,
+                            int Ho, int Wo, hipStream_t st) {
+  const int64_t nvec = (int64_t)B * H * W * (C / 8);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(maxpool_bwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (const float*)dout, (float*)dx, (int)accumulate, B, H, W, C, Ho, Wo),
+    hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)dout, (bf16_t*)dx, (int)accumulate, B, H, W, C, Ho, Wo));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status gap_forward(const void* x, float* pooled, int dtype, int B, int HW, int C, hipStream_t st) {
+  const int64_t nvec = (int64_t)B * (C / 8);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(gap_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, pooled, B, HW, C),
+    hipLaunchKernelGGL(gap_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, pooled, B, HW, C));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dtype, int B, int HW, int C, hipStream_t st) {
+  const int64_t nvec = (int64_t)B * HW * (C / 8);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(gap_bwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, dpooled, (float*)dx, (int)accumulate, B, HW, C),
+    hipLaunchKernelGGL(gap_bwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, dpooled, (bf16_t*)dx, (int)accumulate, B, HW, C));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, hipStream_t st) {
+  hipLaunchKernelGGL(fc_fwd_kernel, dim3(nblk((int64_t)B * O * 64)), dim3(kT), 0, st, f, W, b, logits, B, I, O);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status fc_backward(const float* f, const float* W, const float* dz, float* df, float* dW, float* db, int B, int I, int O,
+                       float scale, hipStream_t st) {
+  hipLaunchKernelGGL(fc_bwd_input_kernel, dim3(nblk((int64_t)B * I)), dim3(kT), 0, st, W, dz, df, B, I, O);
+  DAT_LAUNCH_CHECK();
+  if (dW) {
+    hipLaunchKernelGGL(fc_bwd_weight_kernel, dim3(nblk((int64_t)O * I)), dim3(kT), 0, st, f, dz, dW, db, B, I, O, scale);
+    DAT_LAUNCH_CHECK();
+  }
+  return DAT_OK;
+}
+
+dat_status ce_forward_backward(const float* logits, const int32_t* y, float* dz, float* loss_n, float* loss_mean, int B, int O,
+                               float gscale, hipStream_t st) {
+  hipLaunchKernelGGL(ce_kernel, dim3(B), dim3(64), 0, st, logits, y, dz, loss_n, B, O, gscale);
+  DAT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(64), 0, st, loss_n, B, loss_mean);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status launch_round_bf16_values(const float* src, float* dst, int64_t n, hipStream_t st) {
+  if (n == 0) return DAT_OK;
+  hipLaunchKernelGGL(round_bf16_kernel, dim3(nblk(n)), dim3(kT), 0, st, src, dst, n);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status launch_input_grad(const void* g0, int dtype, int Cpad, int64_t rows, float s0, float s1, float s2, float* gx, hipStream_t st) {
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(input_grad_kernel<float>, dim3(nblk(rows * 3)), dim3(kT), 0, st, (const float*)g0, Cpad, rows, s0, s1, s2, gx),
+    hipLaunchKernelGGL(input_grad_kernel<bf16_t>, dim3(nblk(rows * 3)), dim3(kT), 0, st, (const bf16_t*)g0, Cpad, rows, s0, s1, s2, gx));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status launch_sgd(float* theta, const float* g, float lr, int64_t n, hipStream_t st) {
+  hipLaunchKernelGGL(sgd_kernel, dim3(nblk(n)), dim3(kT), 0, st, theta, g, lr, n);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+  const int64_t nwords = (int64_t)((bytes + 3) / 4);
+  if (nwords == 0) return DAT_OK;
+  hipLaunchKernelGGL(zero_kernel, dim3(nblk(nwords)), dim3(kT), 0, st, (uint32_t*)p, nwords);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+}  // namespace dat

@@ -1,0 +1,520 @@
+// Host side of libdat: the static layer graph of each architecture, its device memory, and
+// the three passes built from it -- forward, backward-to-input, backward-with-weight-gradients
+// -- plus the C entry points dat_attack / dat_step / dat_input_grad that sequence them
+// (Alg. A1, worker block, steps 5 and 6).  No arithmetic happens here: every step is a kernel
+// launch on the caller's stream.
+//
+// Gradient storage rule: every activation tensor has one gradient buffer in the model's
+// storage type.  Contributions arrive in reverse op order; the first one is stored, later
+// ones are added to the stored value (read-modify-write in the consumer's kernel).
+#include <stdlib.h>
+#include <string.h>
+#include <vector>
+#include "kernels.h"
+
+using namespace dat;
+
+namespace {
+
+enum OpKind { OP_CONV, OP_BIASACT, OP_BNACT, OP_MAXPOOL, OP_GAP, OP_FC };
+
+struct Shape { int H, W, C; int64_t numel() const { return (int64_t)H * W * C; } };
+
+struct Op {
+  OpKind kind;
+  int in = -1, out = -1, res = -1;
+  int k = 0, stride = 1, pad = 0, relu = 0;
+  int p0 = -1, p1 = -1;
+  int cin_real = 0;             // conv: channels of the parameter tensor (input may be padded)
+  bf16_t* w16 = nullptr;        // conv, bf16 model: [Cout][k][k][Cin_padded]
+  bf16_t* w16T = nullptr;       //   and the flipped transpose used by backward-data
+  float* mean = nullptr;        // BN batch statistics of the last forward
+  float* rstd = nullptr;
+};
+
+struct PTensor { int64_t off, numel; int fan_in, kind; };
+
+}  // namespace
+
+struct dat_model {
+  dat_arch arch; int dtype; int maxB; int H, W, classes;
+  int normalize = 0; float mean[3] = {0, 0, 0}, inv_std[3] = {1, 1, 1};
+  std::vector<Shape> tens;           // logical per-sample shapes (channels as stored)
+  std::vector<char> is_f32;          // pooled features and logits stay fp32 in every model
+  std::vector<Op> ops;
+  std::vector<PTensor> ptab;
+  int64_t d = 0;
+  std::vector<void*> allocs;
+  float* master = nullptr;           // fp32 parameters, the optimizer's copy
+  float* compute = nullptr;          // parameters as the kernels read them (bf16 model: linear W rounded)
+  int64_t* offsets_dev = nullptr;
+  std::vector<void*> act, grad;
+  std::vector<char> ghas;
+  float* partial = nullptr; float* sums = nullptr;
+  float* loss_n = nullptr; float* loss_steps = nullptr; int loss_cap = 0;
+  float* gx = nullptr;
+  void* wgrad_ws = nullptr; size_t wgrad_ws_bytes = 0;
+  float* host_stage = nullptr;       // pinned staging for loss values
+
+  int esize() const { return dtype == DAT_BF16 ? 2 : 4; }
+  int add_tensor(Shape s, bool f32 = false) { tens.push_back(s); is_f32.push_back(f32 ? 1 : 0); return (int)tens.size() - 1; }
+  int add_param(int64_t n, int fan_in, int kind) { ptab.push_back({d, n, fan_in, kind}); d += n; return (int)ptab.size() - 1; }
+
+  int conv(int in, int cout, int k, int stride, int pad, int res = -1) {
+    Shape s = tens[in];
+    Op op; op.kind = OP_CONV; op.in = in; op.res = res; op.k = k; op.stride = stride; op.pad = pad;
+    op.cin_real = (in == 0) ? 3 : s.C;
+    op.out = add_tensor({(s.H + 2 * pad - k) / stride + 1, (s.W + 2 * pad - k) / stride + 1, cout});
+    op.p0 = add_param((int64_t)cout * k * k * op.cin_real, op.cin_real * k * k, 0);
+    ops.push_back(op); return op.out;
+  }
+  int biasact(int in, int relu) {
+    Op op; op.kind = OP_BIASACT; op.in = in; op.relu = relu; op.out = add_tensor(tens[in]);
+    op.p0 = add_param(tens[in].C, 0, 1);
+    ops.push_back(op); return op.out;
+  }
+  int bnact(int in, int relu, int res = -1) {
+    Op op; op.kind = OP_BNACT; op.in = in; op.relu = relu; op.res = res; op.out = add_tensor(tens[in]);
+    op.p0 = add_param(tens[in].C, 0, 2); op.p1 = add_param(tens[in].C, 0, 3);
+    ops.push_back(op); return op.out;
+  }
+  int maxpool(int in) {
+    Shape s = tens[in];
+    Op op; op.kind = OP_MAXPOOL; op.in = in; op.k = 3; op.stride = 2; op.pad = 1;
+    op.out = add_tensor({(s.H - 1) / 2 + 1, (s.W - 1) / 2 + 1, s.C});
+    ops.push_back(op); return op.out;
+  }
+  int gap(int in) {
+    Op op; op.kind = OP_GAP; op.in = in; op.out = add_tensor({1, 1, tens[in].C}, true);
+    ops.push_back(op); return op.out;
+  }
+  int fc(int in, int nout) {
+    Op op; op.kind = OP_FC; op.in = in; op.out = add_tensor({1, 1, nout}, true);
+    op.p0 = add_param((int64_t)nout * tens[in].C, tens[in].C, 4); op.p1 = add_param(nout, 0, 5);
+    ops.push_back(op); return op.out;
+  }
+};
+
+namespace {
+
+// ---- architectures (Sec. "Experiment setup" names them; shapes are the standard ones) --------
+int basic_block(dat_model& m, int x, int cout, int stride) {
+  const int cin = m.tens[x].C;
+  int y = m.bnact(m.conv(x, cout, 3, stride, 1), 1);
+  y = m.conv(y, cout, 3, 1, 1);
+  int sc = x;
+  if (stride != 1 || cin != cout) sc = m.bnact(m.conv(x, cout, 1, stride, 0), 0);
+  return m.bnact(y, 1, sc);
+}
+
+int bottleneck(dat_model& m, int x, int width, int stride) {
+  const int cin = m.tens[x].C, cout = 4 * width;
+  int y = m.bnact(m.conv(x, width, 1, 1, 0), 1);
+  y = m.bnact(m.conv(y, width, 3, stride, 1), 1);
+  y = m.conv(y, cout, 1, 1, 0);
+  int sc = x;
+  if (stride != 1 || cin != cout) sc = m.bnact(m.conv(x, cout, 1, stride, 0), 0);
+  return m.bnact(y, 1, sc);
+}
+
+int wide_block(dat_model& m, int x, int cout, int stride) {
+  const int cin = m.tens[x].C;
+  const int o = m.bnact(x, 1);
+  const int y = m.bnact(m.conv(o, cout, 3, stride, 1), 1);
+  int sc = x;
+  if (stride != 1 || cin != cout) sc = m.conv(o, cout, 1, stride, 0);
+  return m.conv(y, cout, 3, 1, 1, sc);
+}
+
+bool build_graph(dat_model& m) {
+  int t = 0;
+  switch (m.arch) {
+    case DAT_ARCH_TINYCNN:
+      t = m.biasact(m.conv(t, 16, 3, 1, 1), 1);
+      t = m.biasact(m.conv(t, 32, 3, 2, 1), 1);
+      break;
+    case DAT_ARCH_RESNET18_CIFAR: {
+      t = m.bnact(m.conv(t, 64, 3, 1, 1), 1);
+      const int widths[4] = {64, 128, 256, 512};
+      for (int g = 0; g < 4; ++g)
+        for (int b = 0; b < 2; ++b) t = basic_block(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
+      break;
+    }
+    case DAT_ARCH_WRN34_10: {
+      t = m.conv(t, 16, 3, 1, 1);
+      const int widths[3] = {160, 320, 640};
+      for (int g = 0; g < 3; ++g)
+        for (int b = 0; b < 5; ++b) t = wide_block(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
+      t = m.bnact(t, 1);
+      break;
+    }
+    case DAT_ARCH_RESNET50: {
+      t = m.maxpool(m.bnact(m.conv(t, 64, 7, 2, 3), 1));
+      const int widths[4] = {64, 128, 256, 512}, depth[4] = {3, 4, 6, 3};
+      for (int g = 0; g < 4; ++g)
+        for (int b = 0; b < depth[g]; ++b) t = bottleneck(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
+      break;
+    }
+    case DAT_ARCH_TESTNET:
+      t = m.maxpool(m.bnact(m.conv(t, 8, 3, 1, 1), 1));
+      t = basic_block(m, t, 8, 1);
+      t = basic_block(m, t, 16, 2);
+      t = bottleneck(m, t, 8, 2);
+      t = wide_block(m, t, 16, 1);
+      t = wide_block(m, t, 16, 1);
+      t = m.bnact(t, 1);
+      break;
+    default:
+      return false;
+  }
+  m.fc(m.gap(t), m.classes);
+  return true;
+}
+
+template <typename T>
+dat_status dev_alloc(dat_model& m, T** p, size_t bytes) {
+  void* q = nullptr;
+  if (bytes == 0) bytes = 16;
+  hipError_t e = hipMalloc(&q, bytes);
+  if (e != hipSuccess) { (void)hipGetLastError(); return DAT_ERR_NOMEM; }
+  m.allocs.push_back(q);
+  *p = (T*)q;
+  return DAT_OK;
+}
+
+#define DAT_TRY(expr) do { dat_status s_ = (expr); if (s_ != DAT_OK) return s_; } while (0)
+
+ConvGeom geom_of(const dat_model& m, const Op& op, int B) {
+  const Shape si = m.tens[op.in], so = m.tens[op.out];
+  ConvGeom g;
+  g.B = B; g.H = si.H; g.W = si.W; g.Cin = si.C; g.Ho = so.H; g.Wo = so.W; g.Cout = so.C;
+  g.k = op.k; g.stride = op.stride; g.pad = op.pad;
+  return g;
+}
+
+dat_status allocate(dat_model& m) {
+  const int es = m.esize();
+  DAT_TRY(dev_alloc(m, &m.master, (size_t)m.d * 4));
+  if (m.dtype == DAT_BF16) DAT_TRY(dev_alloc(m, &m.compute, (size_t)m.d * 4)); else m.compute = m.master;
+  DAT_TRY(dev_alloc(m, &m.offsets_dev, (m.ptab.size() + 1) * 8));
+  std::vector<int64_t> off(m.ptab.size() + 1);
+  for (size_t i = 0; i < m.ptab.size(); ++i) off[i] = m.ptab[i].off;
+  off[m.ptab.size()] = m.d;
+  DAT_HIP(hipMemcpy(m.offsets_dev, off.data(), off.size() * 8, hipMemcpyHostToDevice));
+  m.act.assign(m.tens.size(), nullptr); m.grad.assign(m.tens.size(), nullptr); m.ghas.assign(m.tens.size(), 0);
+  int cmax = 8;
+  for (size_t t = 0; t < m.tens.size(); ++t) {
+    const size_t bytes = (size_t)m.maxB * m.tens[t].numel() * (m.is_f32[t] ? 4 : es);
+    DAT_TRY(dev_alloc(m, &m.act[t], bytes));
+    DAT_TRY(dev_alloc(m, &m.grad[t], bytes));
+    cmax = m.tens[t].C > cmax ? m.tens[t].C : cmax;
+  }
+  // the padded channels of a bf16 input tensor are written by the input kernels on every call
+  size_t ws = 0;
+  for (Op& op : m.ops) {
+    if (op.kind == OP_BNACT) {
+      DAT_TRY(dev_alloc(m, &op.mean, (size_t)m.tens[op.in].C * 4));
+      DAT_TRY(dev_alloc(m, &op.rstd, (size_t)m.tens[op.in].C * 4));
+    }
+    if (op.kind == OP_CONV && m.dtype == DAT_BF16) {
+      const size_t n = (size_t)m.tens[op.out].C * op.k * op.k * m.tens[op.in].C;
+      DAT_TRY(dev_alloc(m, &op.w16, n * 2));
+      DAT_TRY(dev_alloc(m, &op.w16T, n * 2));
+      const size_t need = conv_mfma_wgrad_workspace(geom_of(m, op, m.maxB));
+      ws = need > ws ? need : ws;
+    }
+  }
+  m.wgrad_ws_bytes = ws;
+  if (ws) DAT_TRY(dev_alloc(m, &m.wgrad_ws, ws));
+  DAT_TRY(dev_alloc(m, &m.partial, bn_partial_floats(0, cmax) * 4));
+  DAT_TRY(dev_alloc(m, &m.sums, (size_t)2 * cmax * 4));
+  DAT_TRY(dev_alloc(m, &m.loss_n, (size_t)m.maxB * 4));
+  m.loss_cap = 1024;
+  DAT_TRY(dev_alloc(m, &m.loss_steps, (size_t)m.loss_cap * 4));
+  DAT_TRY(dev_alloc(m, &m.gx, (size_t)m.maxB * m.H * m.W * 3 * 4));
+  if (hipHostMalloc((void**)&m.host_stage, (size_t)m.loss_cap * 4, hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    return DAT_ERR_NOMEM;
+  }
+  DAT_TRY(launch_fill_zero(m.master, (size_t)m.d * 4, nullptr));
+  if (m.compute != m.master) DAT_TRY(launch_fill_zero(m.compute, (size_t)m.d * 4, nullptr));
+  DAT_HIP(hipDeviceSynchronize());
+  return DAT_OK;
+}
+
+// Rebuilds what the kernels read from the fp32 master copy.
+dat_status refresh_compute(dat_model& m, hipStream_t st) {
+  if (m.dtype != DAT_BF16) return DAT_OK;
+  DAT_HIP(hipMemcpyAsync(m.compute, m.master, (size_t)m.d * 4, hipMemcpyDeviceToDevice, st));
+  for (Op& op : m.ops) {
+    if (op.kind == OP_CONV)
+      DAT_TRY(launch_weight_transform(m.master + m.ptab[op.p0].off, op.w16, op.w16T, m.tens[op.out].C, op.k, op.cin_real,
+                                      m.tens[op.in].C, st));
+    if (op.kind == OP_FC)
+      DAT_TRY(launch_round_bf16_values(m.master + m.ptab[op.p0].off, m.compute + m.ptab[op.p0].off, m.ptab[op.p0].numel, st));
+  }
+  return DAT_OK;
+}
+
+NetInputDesc input_desc(const dat_model& m) {
+  NetInputDesc d;
+  d.ptr = m.act[0]; d.bf16 = m.dtype == DAT_BF16; d.normalize = m.normalize;
+  for (int c = 0; c < 3; ++c) { d.mean[c] = m.mean[c]; d.inv_std[c] = m.inv_std[c]; }
+  return d;
+}
+
+dat_status forward(dat_model& m, int B, hipStream_t st) {
+  const int dt = m.dtype;
+  for (Op& op : m.ops) {
+    const Shape si = m.tens[op.in], so = m.tens[op.out];
+    const int64_t rows_in = (int64_t)B * si.H * si.W;
+    switch (op.kind) {
+      case OP_CONV: {
+        const ConvGeom g = geom_of(m, op, B);
+        const void* res = op.res >= 0 ? m.act[op.res] : nullptr;
+        if (dt == DAT_BF16) DAT_TRY(conv_mfma_forward((const bf16_t*)m.act[op.in], op.w16, (const bf16_t*)res, (bf16_t*)m.act[op.out], g, st));
+        else DAT_TRY(conv_direct_forward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, (const float*)res, (float*)m.act[op.out], g, st));
+        break;
+      }
+      case OP_BIASACT:
+        DAT_TRY(biasact_forward(m.act[op.in], m.act[op.out], dt, rows_in, si.C, m.compute + m.ptab[op.p0].off, op.relu, st));
+        break;
+      case OP_BNACT:
+        DAT_TRY(bn_stats(m.act[op.in], dt, rows_in, si.C, m.partial, op.mean, op.rstd, st));
+        DAT_TRY(bnact_forward(m.act[op.in], op.res >= 0 ? m.act[op.res] : nullptr, m.act[op.out], dt, rows_in, si.C, op.mean,
+                              op.rstd, m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off, op.relu, st));
+        break;
+      case OP_MAXPOOL:
+        DAT_TRY(maxpool_forward(m.act[op.in], m.act[op.out], dt, B, si.H, si.W, si.C, so.H, so.W, st));
+        break;
+      case OP_GAP:
+        DAT_TRY(gap_forward(m.act[op.in], (float*)m.act[op.out], dt, B, si.H * si.W, si.C, st));
+        break;
+      case OP_FC:
+        DAT_TRY(fc_forward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off,
+                           (float*)m.act[op.out], B, si.C, so.C, st));
+        break;
+    }
+  }
+  return DAT_OK;
+}
+
+// Loss and logit gradient; `loss_slot` indexes m.loss_steps.
+dat_status loss_grad(dat_model& m, const int32_t* y, int B, float gscale, int loss_slot, hipStream_t st) {
+  const int t = m.ops.back().out;
+  DAT_TRY(ce_forward_backward((const float*)m.act[t], y, (float*)m.grad[t], m.loss_n, m.loss_steps + loss_slot, B, m.classes, gscale, st));
+  std::fill(m.ghas.begin(), m.ghas.end(), 0);
+  m.ghas[t] = 1;
+  return DAT_OK;
+}
+
+// grads == nullptr: backward to the input only (attack); otherwise also parameter gradients.
+dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hipStream_t st) {
+  const int dt = m.dtype;
+  for (int i = (int)m.ops.size() - 1; i >= 0; --i) {
+    Op& op = m.ops[i];
+    const Shape si = m.tens[op.in], so = m.tens[op.out];
+    const int64_t rows_in = (int64_t)B * si.H * si.W, rows_out = (int64_t)B * so.H * so.W;
+    float* g0 = grads && op.p0 >= 0 ? grads + m.ptab[op.p0].off : nullptr;
+    float* g1 = grads && op.p1 >= 0 ? grads + m.ptab[op.p1].off : nullptr;
+    switch (op.kind) {
+      case OP_CONV: {
+        const ConvGeom g = geom_of(m, op, B);
+        if (op.res >= 0) {   // out = conv + res: the residual receives d out unchanged
+          DAT_TRY(biasact_backward(nullptr, m.grad[op.out], m.grad[op.res], m.ghas[op.res], dt, rows_out, so.C, 0, nullptr, nullptr, 1.0f, st));
+          m.ghas[op.res] = 1;
+        }
+        if (g0) {
+          if (dt == DAT_BF16) DAT_TRY(conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, st));
+          else DAT_TRY(conv_direct_backward_weight((const float*)m.act[op.in], (const float*)m.grad[op.out], g0, g, 1.0f, st));
+        }
+        if (op.in != 0 || need_input_grad) {
+          if (dt == DAT_BF16) DAT_TRY(conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
+          else DAT_TRY(conv_direct_backward_data((const float*)m.grad[op.out], m.compute + m.ptab[op.p0].off, (float*)m.grad[op.in], g, m.ghas[op.in], st));
+          m.ghas[op.in] = 1;
+        }
+        break;
+      }
+      case OP_BIASACT:
+        DAT_TRY(biasact_backward(m.act[op.out], m.grad[op.out], m.grad[op.in], m.ghas[op.in], dt, rows_in, si.C, op.relu, m.partial, g0, 1.0f, st));
+        m.ghas[op.in] = 1;
+        break;
+      case OP_BNACT: {
+        void* dres = op.res >= 0 ? m.grad[op.res] : nullptr;
+        const bool dres_acc = op.res >= 0 && m.ghas[op.res];
+        DAT_TRY(bnact_backward(m.act[op.in], m.act[op.out], m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
+                               si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, m.sums, g0, g1, 1.0f, st));
+        if (op.res >= 0) m.ghas[op.res] = 1;
+        m.ghas[op.in] = 1;
+        break;
+      }
+      case OP_MAXPOOL:
+        DAT_TRY(maxpool_backward(m.act[op.in], m.grad[op.out], m.grad[op.in], m.ghas[op.in], dt, B, si.H, si.W, si.C, so.H, so.W, st));
+        m.ghas[op.in] = 1;
+        break;
+      case OP_GAP:
+        DAT_TRY(gap_backward((const float*)m.grad[op.out], m.grad[op.in], m.ghas[op.in], dt, B, si.H * si.W, si.C, st));
+        m.ghas[op.in] = 1;
+        break;
+      case OP_FC:
+        DAT_TRY(fc_backward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, (const float*)m.grad[op.out],
+                            (float*)m.grad[op.in], g0, g1, B, si.C, so.C, 1.0f, st));
+        m.ghas[op.in] = 1;
+        break;
+    }
+  }
+  return DAT_OK;
+}
+
+dat_status pixel_grad(dat_model& m, int B, float* gx, hipStream_t st) {
+  const bool n = m.normalize;
+  return launch_input_grad(m.grad[0], m.dtype, m.tens[0].C, (int64_t)B * m.H * m.W, n ? m.inv_std[0] : 1.0f,
+                           n ? m.inv_std[1] : 1.0f, n ? m.inv_std[2] : 1.0f, gx, st);
+}
+
+dat_status fetch_losses(dat_model& m, int count, float* host_out, hipStream_t st) {
+  DAT_HIP(hipMemcpyAsync(m.host_stage, m.loss_steps, (size_t)count * 4, hipMemcpyDeviceToHost, st));
+  DAT_HIP(hipStreamSynchronize(st));
+  memcpy(host_out, m.host_stage, (size_t)count * 4);
+  return DAT_OK;
+}
+
+bool batch_ok(const dat_model* m, int B) { return B >= 1 && B <= m->maxB; }
+
+}  // namespace
+
+// =============================================================================================
+extern "C" dat_status dat_model_create(dat_arch arch, dat_dtype dtype, int max_batch, int H, int W, int num_classes,
+                                       const float* mean, const float* stdv, dat_model** out) {
+  if (!out || max_batch < 1 || H < 1 || W < 1 || num_classes < 1) return DAT_ERR_ARG;
+  if (dtype != DAT_F32 && dtype != DAT_BF16) return DAT_ERR_ARG;
+  if ((mean == nullptr) != (stdv == nullptr)) return DAT_ERR_ARG;
+  dat_model* m = new (std::nothrow) dat_model();
+  if (!m) return DAT_ERR_NOMEM;
+  m->arch = arch; m->dtype = dtype; m->maxB = max_batch; m->H = H; m->W = W; m->classes = num_classes;
+  if (mean) {
+    m->normalize = 1;
+    for (int c = 0; c < 3; ++c) {
+      if (!(stdv[c] > 0.0f)) { delete m; return DAT_ERR_ARG; }
+      m->mean[c] = mean[c]; m->inv_std[c] = 1.0f / stdv[c];
+    }
+  }
+  m->add_tensor({H, W, dtype == DAT_BF16 ? 8 : 3});
+  if (!build_graph(*m)) { delete m; return DAT_ERR_UNSUPPORTED; }
+  for (const Shape& s : m->tens)
+    if (s.H < 1 || s.W < 1) { delete m; return DAT_ERR_SHAPE; }
+  dat_status s = allocate(*m);
+  if (s != DAT_OK) { dat_model_destroy(m); return s; }
+  *out = m;
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_model_destroy(dat_model* m) {
+  if (!m) return DAT_ERR_ARG;
+  (void)hipDeviceSynchronize();
+  for (void* p : m->allocs) (void)hipFree(p);
+  if (m->host_stage) (void)hipHostFree(m->host_stage);
+  delete m;
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_model_num_params(const dat_model* m, int64_t* d, int* num_tensors) {
+  if (!m) return DAT_ERR_ARG;
+  if (d) *d = m->d;
+  if (num_tensors) *num_tensors = (int)m->ptab.size();
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_model_tensor_table(const dat_model* m, int64_t* offsets, int32_t* fan_in, int32_t* kind) {
+  if (!m || !offsets) return DAT_ERR_ARG;
+  for (size_t i = 0; i < m->ptab.size(); ++i) {
+    offsets[i] = m->ptab[i].off;
+    if (fan_in) fan_in[i] = m->ptab[i].fan_in;
+    if (kind) kind[i] = m->ptab[i].kind;
+  }
+  offsets[m->ptab.size()] = m->d;
+  return DAT_OK;
+}
+
+extern "C" const int64_t* dat_model_offsets_device(const dat_model* m) { return m ? m->offsets_dev : nullptr; }
+
+extern "C" dat_status dat_model_set_params(dat_model* m, const float* host_flat) {
+  if (!m || !host_flat) return DAT_ERR_ARG;
+  DAT_HIP(hipMemcpy(m->master, host_flat, (size_t)m->d * 4, hipMemcpyHostToDevice));
+  DAT_TRY(refresh_compute(*m, nullptr));
+  DAT_HIP(hipDeviceSynchronize());
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_model_get_params(const dat_model* m, float* host_flat) {
+  if (!m || !host_flat) return DAT_ERR_ARG;
+  DAT_HIP(hipDeviceSynchronize());
+  DAT_HIP(hipMemcpy(host_flat, m->master, (size_t)m->d * 4, hipMemcpyDeviceToHost));
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_attack(dat_model* m, const float* x, const int32_t* y, int B, float eps, float alpha, int K,
+                                 dat_init init, float* delta, float* loss_per_step, void* stream) {
+  if (!m || !x || !y || !delta || K < 0 || !(eps >= 0.0f) || !(alpha >= 0.0f)) return DAT_ERR_ARG;
+  if (init.mode != DAT_INIT_ZERO && init.mode != DAT_INIT_UNIFORM && init.mode != DAT_INIT_GIVEN) return DAT_ERR_ARG;
+  if (init.mode == DAT_INIT_GIVEN && !init.delta0) return DAT_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(delta, 16)) return DAT_ERR_ARG;
+  if (!batch_ok(m, B)) return DAT_ERR_SHAPE;
+  if (loss_per_step && K + 1 > m->loss_cap) return DAT_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t npix = (int64_t)B * m->H * m->W;
+  const NetInputDesc in = input_desc(*m);
+  DAT_TRY(launch_attack_init(x, npix, eps, init, delta, in, st));
+  for (int k = 0; k < K; ++k) {
+    DAT_TRY(forward(*m, B, st));
+    DAT_TRY(loss_grad(*m, y, B, 1.0f, loss_per_step ? k : 0, st));
+    DAT_TRY(backward(*m, B, nullptr, true, st));
+    DAT_TRY(pixel_grad(*m, B, m->gx, st));
+    DAT_TRY(launch_attack_update(x, m->gx, delta, npix, eps, alpha, in, st));
+  }
+  if (loss_per_step) {
+    DAT_TRY(forward(*m, B, st));
+    DAT_TRY(loss_grad(*m, y, B, 1.0f, K, st));
+    DAT_TRY(fetch_losses(*m, K + 1, loss_per_step, st));
+  }
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_step(dat_model* m, const float* x_adv, const int32_t* y, int B, float* grads, float* loss,
+                               void* stream) {
+  if (!m || !x_adv || !y || !grads) return DAT_ERR_ARG;
+  if (!aligned(x_adv, 16) || !aligned(grads, 16)) return DAT_ERR_ARG;
+  if (!batch_ok(m, B)) return DAT_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  DAT_TRY(launch_make_input(x_adv, nullptr, (int64_t)B * m->H * m->W, input_desc(*m), st));
+  DAT_TRY(forward(*m, B, st));
+  DAT_TRY(loss_grad(*m, y, B, 1.0f / (float)B, 0, st));
+  DAT_TRY(backward(*m, B, grads, false, st));
+  if (loss) DAT_TRY(fetch_losses(*m, 1, loss, st));
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_input_grad(dat_model* m, const float* x, const int32_t* y, int B, float* gx, float* logits,
+                                     float* loss, void* stream) {
+  if (!m || !x || !y || !gx) return DAT_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(gx, 16)) return DAT_ERR_ARG;
+  if (!batch_ok(m, B)) return DAT_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  DAT_TRY(launch_make_input(x, nullptr, (int64_t)B * m->H * m->W, input_desc(*m), st));
+  DAT_TRY(forward(*m, B, st));
+  if (logits)
+    DAT_HIP(hipMemcpyAsync(logits, m->act[m->ops.back().out], (size_t)B * m->classes * 4, hipMemcpyDeviceToDevice, st));
+  DAT_TRY(loss_grad(*m, y, B, 1.0f, 0, st));
+  DAT_TRY(backward(*m, B, nullptr, true, st));
+  DAT_TRY(pixel_grad(*m, B, gx, st));
+  if (loss) DAT_TRY(fetch_losses(*m, 1, loss, st));
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_sgd_update(dat_model* m, const float* grads, float lr, void* stream) {
+  if (!m || !grads) return DAT_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  DAT_TRY(launch_sgd(m->master, grads, lr, m->d, st));
+  DAT_TRY(refresh_compute(*m, st));
+  return DAT_OK;
+}

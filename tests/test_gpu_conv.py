@@ -1,0 +1,66 @@
+"""GPU parity of the three MFMA convolution kernels against the CPU reference's direct
+convolution, per layer shape (bf16 operands, fp32 accumulate): the inputs are bf16 values, so
+the exact result is the fp64 sum; the kernel may differ from it by fp32 accumulation error
+before its single rounding to bf16."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+# (B, H, W, Cin, Cout, k, stride, pad): the distinct kinds of layers in the four networks at
+# reduced spatial size, with ragged tiles (pixel counts and channel counts off the tile sizes)
+SHAPES = [
+    (2, 9, 7, 16, 24, 3, 1, 1),        # everything ragged
+    (3, 8, 8, 64, 64, 3, 1, 1),        # ResNet 3x3
+    (2, 8, 8, 64, 128, 3, 2, 1),       # strided 3x3
+    (2, 7, 7, 64, 256, 1, 1, 0),       # bottleneck expand
+    (2, 8, 8, 256, 64, 1, 1, 0),       # bottleneck reduce
+    (2, 8, 8, 128, 256, 1, 2, 0),      # projection shortcut
+    (2, 18, 14, 8, 64, 7, 2, 3),       # ImageNet stem (3 channels padded to 8)
+    (2, 8, 8, 8, 16, 3, 1, 1),         # CIFAR stem
+    (1, 6, 6, 160, 320, 3, 2, 1),      # wide-ResNet widths
+    (5, 12, 12, 32, 40, 3, 1, 1),      # several pixel tiles + ragged channel tile
+]
+
+
+@pytest.fixture(scope="module")
+def dat():
+    import paper_2206_06257_amd as dat
+    return dat
+
+
+def _bf16_values(rng, shape, scale=1.0):
+    t = torch.tensor(rng.standard_normal(shape) * scale, dtype=torch.float32).to(torch.bfloat16)
+    return t
+
+
+def _check(got_bf16, exact64, what):
+    got = got_bf16.float().cpu().numpy().astype(np.float64)
+    # one rounding to bf16 (2^-9 relative) plus fp32 accumulation noise on the largest terms
+    tol = 2.0 ** -8 * np.abs(exact64) + 1e-5 * np.abs(exact64).max()
+    bad = np.abs(got - exact64) > tol
+    assert not bad.any(), (what, int(bad.sum()), float(np.abs(got - exact64).max()))
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_conv_forward_backward_parity(dat, shape):
+    B, H, W, Ci, Co, k, st, pad = shape
+    rng = np.random.default_rng(hash(shape) % (2 ** 31))
+    x = _bf16_values(rng, (B, H, W, Ci))
+    w = _bf16_values(rng, (Co, k, k, Ci), 1.0 / np.sqrt(Ci * k * k))
+    x64, w64 = x.double().numpy(), w.double().numpy()
+    y64 = oracle.conv_forward(x64, w64, st, pad)
+    y = dat.conv_forward(x.cuda(), w.cuda(), st, pad)
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == y64.shape
+    _check(y, y64, "forward")
+    dy = _bf16_values(rng, y64.shape)
+    dx64, dw64 = oracle.conv_backward(x64, w64, dy.double().numpy(), st, pad)
+    dx = dat.conv_backward_data(dy.cuda(), w.cuda(), (H, W), st, pad)
+    _check(dx, dx64, "backward_data")
+    dw = dat.conv_backward_weight(x.cuda(), dy.cuda(), k, st, pad).cpu().numpy().astype(np.float64)
+    err = np.abs(dw - dw64).max() / np.abs(dw64).max()
+    assert err < 2e-5, ("backward_weight", err)

