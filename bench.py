@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the DAT worker step on one MI355X.
+
+A "step" is one pass of the whole hot path over one resident synthetic batch:
+dat_attack (K-step PGD) -> dat_step (outer gradient) -> dat_quantize -> dat_dequantize (8 bit).
+Default workload = the configuration the headline metric is quoted on: ResNet-50, 224x224,
+batch 256, bf16, PGD-10 (eps 2/255, alpha 0.5/255, uniform random init).
+
+Prints ONE JSON line.  `value` = examples/s through the whole step; `roofline` describes the
+dominant kernel (the implicit-GEMM convolution) from hipEvent pairs recorded around every
+launch during the timed steps; `cpu_baseline` times the CPU reference on a bounded sample."""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MEAN, STD = (0.485, 0.456, 0.406), (0.229, 0.224, 0.225)
+WORKLOADS = {
+    # name: arch, H, W, classes, B, K, eps, alpha, normalise, config id for seeds
+    "resnet50_224_b256_pgd10": (3, 224, 224, 1000, 256, 10, 2 / 255, 0.5 / 255, True, 6),
+    "resnet50_224_b256_fgsm": (3, 224, 224, 1000, 256, 1, 2 / 255, 2.5 / 255, True, 4),
+    "resnet50_224_b256_pgd3": (3, 224, 224, 1000, 256, 3, 4 / 255, 1 / 255, True, 5),
+    "resnet18_cifar_b512_pgd10": (1, 32, 32, 10, 512, 10, 8 / 255, 2 / 255, False, 2),
+    "wrn34_10_b256_pgd10": (2, 32, 32, 10, 256, 10, 8 / 255, 2 / 255, False, 3),
+}
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(arch, H, W, classes, K, eps, alpha, norm):
+    """CPU reference on a bounded sample: B=2 images, one attack iteration + the outer step,
+    extrapolated to K attack iterations per example."""
+    import oracle
+    import synth_inputs as syn
+    B = 2
+    m = oracle.Model(arch, 1, H, W, classes, MEAN if norm else None, STD if norm else None)
+    m.set_params(syn.he_normal_params(0, m.offsets, m.fan_in, m.kind))
+    x, y = syn.images(0, B, H, W), syn.labels(0, B, classes)
+    t0 = time.time()
+    d = m.attack(x, y, eps, alpha, 1, oracle.INIT_UNIFORM, seed=1)
+    t1 = time.time()
+    m.step(oracle.make_xadv(x, d), y)
+    t2 = time.time()
+    per_example = (K * (t1 - t0) + (t2 - t1)) / B
+    return {"value": 1.0 / per_example, "unit": "examples/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "B=2 images of the same shape: 1 attack iteration (%.1f s) + outer step (%.1f s), "
+                      "extrapolated to K=%d iterations per example" % (t1 - t0, t2 - t1, K)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="resnet50_224_b256_pgd10", choices=sorted(WORKLOADS))
+    ap.add_argument("--bits", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-launch-events", action="store_true", help="do not bracket launches with events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2206_06257_amd as dat
+    import synth_inputs as syn
+
+    arch, H, W, classes, B, K, eps, alpha, norm, cfg = WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    model = dat.Model(arch, dat.BF16, B, H, W, classes, MEAN if norm else None, STD if norm else None)
+    model.set_params(syn.he_normal_params(cfg, model.offsets, model.fan_in, model.kind))
+    x = torch.from_numpy(syn.images(cfg, B, H, W)).cuda()
+    y = torch.from_numpy(syn.labels(cfg, B, classes)).cuda()
+    delta = torch.empty_like(x)
+    xadv = torch.empty_like(x)
+    grads = torch.empty(model.d, dtype=torch.float32, device="cuda")
+    q = torch.empty(dat.quantized_bytes(model.d, args.bits), dtype=torch.uint8, device="cuda")
+    scales = torch.empty(model.num_tensors, dtype=torch.float32, device="cuda")
+    deq = torch.empty(model.d, dtype=torch.float32, device="cuda")
+    offs = (model.offsets_device(), model.num_tensors)
+    seed_init, seed_q = syn.seed_for(cfg, "attack_init"), syn.seed_for(cfg, "quantizer")
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+
+    def one_step(i, marks=None):
+        model.attack(x, y, eps, alpha, K, dat.INIT_UNIFORM, seed=seed_init + i, delta=delta)
+        if marks:
+            marks[0].record()
+        torch.add(x, delta, out=xadv)          # x + delta (already inside [0,1] by construction)
+        model.step(xadv, y, grads=grads)
+        if marks:
+            marks[1].record()
+        dat.quantize(grads, offs, args.bits, seed_q + i, q=q, scales=scales)
+        if marks:
+            marks[2].record()
+        dat.dequantize(q, scales, offs, model.d, args.bits, out=deq)
+        if marks:
+            marks[3].record()
+
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    if not args.no_launch_events:
+        model.profile_enable(True)
+    start = torch.cuda.Event(enable_timing=True)
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start.record()
+    for i in range(args.steps):
+        starts[i].record()
+        one_step(args.warmup + i, ev[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    prof = model.profile_read() if not args.no_launch_events else None
+    if prof:
+        model.profile_enable(False)
+
+    t_attack = np.mean([starts[i].elapsed_time(ev[i][0]) for i in range(args.steps)])
+    t_step = np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(args.steps)])
+    t_quant = np.mean([ev[i][1].elapsed_time(ev[i][2]) for i in range(args.steps)])
+    t_deq = np.mean([ev[i][2].elapsed_time(ev[i][3]) for i in range(args.steps)])
+
+    out = {
+        "metric": "PGD-10 adv examples/s + train imgs/s (ResNet-50 224, 1 GPU); % MFMA/HBM peak",
+        "value": B / (ms_per_step * 1e-3), "unit": "examples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": B, "image": [H, W, 3], "pgd_steps": K, "eps": eps, "alpha": alpha,
+                   "quantizer_bits": args.bits, "params": model.d},
+        "adv_examples_per_s": B / (t_attack * 1e-3), "train_images_per_s": B / (t_step * 1e-3),
+        "phase_ms": {"attack": t_attack, "step": t_step, "quantize": t_quant, "dequantize": t_deq},
+    }
+    d = model.d
+    out["quantizer"] = {
+        "quantize_GBs": d * (8 + args.bits / 8) / (t_quant * 1e-3) / 1e9, "dequantize_GBs": d * (4 + args.bits / 8) / (t_deq * 1e-3) / 1e9,
+        "frac_hbm_quantize": d * (8 + args.bits / 8) / (t_quant * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "note": "event time around the whole call (fill + absmax + encode launches); 8+b/8 and 4+b/8 algorithmic bytes per element"}
+    if prof:
+        ms = prof["conv_fwd"][0] + prof["conv_bwd_data"][0]
+        n = prof["conv_fwd"][1] + prof["conv_bwd_data"][1]
+        flops = prof["conv_fwd"][2] + prof["conv_bwd_data"][2]
+        ach = flops / (ms * 1e-3) / 1e12
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic_igemm_" + args.workload + ".json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        out["roofline"] = {"bound": "mfma", "kernel": "igemm_kernel (conv forward + backward-data)", "achieved": ach,
+                           "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
+                           "launches": n, "avg_launch_ms": ms / max(n, 1), "flops_per_launch": flops / max(n, 1)}
+        out["kernel_classes"] = {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps,
+                                     "work_per_step": v[2] / args.steps} for k, v in prof.items()}
+        pg = prof["pgd"]
+        if pg[0] > 0:
+            out["pgd_update"] = {"GBs": pg[2] / (pg[0] * 1e-3) / 1e9, "frac_hbm": pg[2] / (pg[0] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                 "bytes_per_element": 18}
+        total_flops = sum(prof[k][2] for k in ("conv_fwd", "conv_bwd_data", "conv_wgrad")) / args.steps
+        out["step_conv_TFLOPs"] = total_flops / 1e12
+        out["step_frac_mfma_peak"] = total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(arch, H, W, classes, K, eps, alpha, norm)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

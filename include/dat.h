@@ -90,7 +90,7 @@ dat_status dat_model_num_params(const dat_model* m, int64_t* d, int* num_tensors
 
 /* Host outputs: offsets[num_tensors+1] (element offsets into the flat vector), and optionally
  * fan_in[num_tensors], kind[num_tensors] (0 conv W, 1 conv bias, 2 BN gamma, 3 BN beta,
- * 4 linear W, 5 linear b).  The model also keeps a device copy of `offsets`, returned by
+ * 4 linear W, 5 linear b, 6 gamma of the last BN of a residual branch).  The model also keeps a device copy of `offsets`, returned by
  * dat_model_offsets_device (int64, num_tensors+1 entries, owned by the model). */
 dat_status dat_model_tensor_table(const dat_model* m, int64_t* offsets, int32_t* fan_in,
                                   int32_t* kind);
@@ -171,6 +171,24 @@ dat_status dat_conv_backward_data(const uint16_t* dy, const uint16_t* w, uint16_
 dat_status dat_conv_backward_weight(const uint16_t* x, const uint16_t* dy, float* dw, int B,
                                     int H, int W, int Cin, int Cout, int k, int stride, int pad,
                                     void* stream);
+
+/* ---- per-launch timing (for benchmarks; not part of the paper's method) ----------------------
+ * While enabled, every launch group of dat_attack / dat_step / dat_input_grad on this model is
+ * bracketed by a hipEvent pair on the caller's stream.  dat_profile_read synchronises the device
+ * and returns, for one class, the summed event time (ms), the number of launch groups and their
+ * summed algorithmic work: FLOPs (2 * B*Ho*Wo*Cout*k*k*Cin, the same count for the forward,
+ * backward-data and backward-weight of a layer) for the convolution classes, bytes for the
+ * others.  dat_profile_enable(m, 0/1) also clears the records. */
+typedef enum {
+  DAT_PROF_CONV_FWD = 0,       /* implicit-GEMM forward                                  */
+  DAT_PROF_CONV_BWD_DATA = 1,  /* implicit-GEMM backward-data (same kernel as forward)   */
+  DAT_PROF_CONV_WGRAD = 2,     /* backward-weight + its split reduction                  */
+  DAT_PROF_BN = 3,             /* batch-norm statistics + apply, forward and backward    */
+  DAT_PROF_PGD = 4,            /* fused projected sign step                              */
+  DAT_PROF_NUM_CLASSES = 5
+} dat_prof_class;
+dat_status dat_profile_enable(dat_model* m, int on);
+dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* launches, double* work);
 
 /* ---- misc ---------------------------------------------------------------------------------- */
 const char* dat_status_string(dat_status s);

@@ -115,7 +115,8 @@ struct Op {
   int p0 = -1, p1 = -1;    // indices into the parameter-tensor table
 };
 
-struct PTensor { int64_t off, numel; int fan_in; int kind; };  // kind: 0 conv W, 1 bias, 2 gamma, 3 beta, 4 fc W, 5 fc b
+// kind: 0 conv W, 1 bias, 2 BN gamma, 3 BN beta, 4 fc W, 5 fc b, 6 gamma of the last BN of a residual branch
+struct PTensor { int64_t off, numel; int fan_in; int kind; };
 
 struct Model {
   int arch = 0, emu = 0, classes = 0;
@@ -161,10 +162,10 @@ struct Model {
     op.p0 = add_param(s.C, 0, 1);
     ops.push_back(op); return op.out;
   }
-  int bnact(int in, int relu, int res = -1) {
+  int bnact(int in, int relu, int res = -1, bool branch_final = false) {
     Shape s = tens[in];
     Op op; op.kind = OP_BNACT; op.in = in; op.out = add_tensor(s); op.relu = relu; op.res = res;
-    op.p0 = add_param(s.C, 0, 2); op.p1 = add_param(s.C, 0, 3);
+    op.p0 = add_param(s.C, 0, branch_final ? 6 : 2); op.p1 = add_param(s.C, 0, 3);
     ops.push_back(op); return op.out;
   }
   int maxpool(int in) {   // 3x3 window, stride 2, padding 1
@@ -204,7 +205,7 @@ int basic_block(Model& m, int x, int cout, int stride) {
   y = m.conv(y, cout, 3, 1, 1);
   int sc = x;
   if (stride != 1 || cin != cout) { sc = m.conv(x, cout, 1, stride, 0); sc = m.bnact(sc, 0); }
-  return m.bnact(y, 1, sc);
+  return m.bnact(y, 1, sc, true);
 }
 
 void build_resnet18_cifar(Model& m) {
@@ -223,7 +224,7 @@ int bottleneck(Model& m, int x, int width, int stride) {
   y = m.conv(y, cout, 1, 1, 0);
   int sc = x;
   if (stride != 1 || cin != cout) { sc = m.conv(x, cout, 1, stride, 0); sc = m.bnact(sc, 0); }
-  return m.bnact(y, 1, sc);
+  return m.bnact(y, 1, sc, true);
 }
 
 void build_resnet50(Model& m) {
@@ -241,7 +242,7 @@ void build_resnet50(Model& m) {
 int wide_block(Model& m, int x, int cout, int stride) {
   int cin = m.tens[x].C;
   int o = m.bnact(x, 1);
-  int y = m.conv(o, cout, 3, stride, 1); y = m.bnact(y, 1);
+  int y = m.conv(o, cout, 3, stride, 1); y = m.bnact(y, 1, -1, true);
   int sc = x;
   if (stride != 1 || cin != cout) sc = m.conv(o, cout, 1, stride, 0);
   return m.conv(y, cout, 3, 1, 1, sc);

@@ -18,7 +18,7 @@ EXPORTS = [
     "dat_model_offsets_device", "dat_model_set_params", "dat_model_get_params", "dat_attack", "dat_step",
     "dat_input_grad", "dat_pgd_init", "dat_pgd_update", "dat_sgd_update", "dat_quantize", "dat_dequantize",
     "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
-    "dat_status_string", "dat_last_error", "dat_philox_uniform",
+    "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read",
 ]
 
 
@@ -69,6 +69,9 @@ _lib.dat_quantized_bytes.argtypes = [_i64, _i]
 for _n in ("dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight"):
     getattr(_lib, _n).argtypes = [_vp, _vp, _vp] + [_i] * 8 + [_vp]
 _lib.dat_philox_uniform.argtypes = [_u64, _i64, _u64, C.c_uint32, _vp, _vp]
+_lib.dat_profile_enable.argtypes = [_vp, _i]
+_lib.dat_profile_read.argtypes = [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]
+PROF_CLASSES = ("conv_fwd", "conv_bwd_data", "conv_wgrad", "bn", "pgd")
 
 
 def _check(status, where):
@@ -164,6 +167,18 @@ class Model:
 
     def sgd_update(self, grads, lr, stream=None):
         _check(_lib.dat_sgd_update(self._h, _ptr(_dev(grads, torch.float32)), lr, _stream(stream)), "dat_sgd_update")
+
+    def profile_enable(self, on=True):
+        _check(_lib.dat_profile_enable(self._h, int(bool(on))), "dat_profile_enable")
+
+    def profile_read(self):
+        """{class: (ms_total, launches, algorithmic work)} since profile_enable(True)."""
+        out = {}
+        for i, name in enumerate(PROF_CLASSES):
+            ms, n, w = C.c_double(), _i64(), C.c_double()
+            _check(_lib.dat_profile_read(self._h, i, C.byref(ms), C.byref(n), C.byref(w)), "dat_profile_read")
+            out[name] = (ms.value, n.value, w.value)
+        return out
 
     def offsets_device(self):
         """int64 device pointer to the tensor table (owned by the model)."""

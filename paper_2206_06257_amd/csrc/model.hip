@@ -55,6 +55,17 @@ struct dat_model {
   float* gx = nullptr;
   void* wgrad_ws = nullptr; size_t wgrad_ws_bytes = 0;
   float* host_stage = nullptr;       // pinned staging for loss values
+  // optional per-launch timing (dat_profile_*): one event pair per launch group
+  bool prof = false;
+  struct ProfRec { int cls; hipEvent_t a, b; double work; };
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t take_event() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    return e;
+  }
 
   int esize() const { return dtype == DAT_BF16 ? 2 : 4; }
   int add_tensor(Shape s, bool f32 = false) { tens.push_back(s); is_f32.push_back(f32 ? 1 : 0); return (int)tens.size() - 1; }
@@ -73,9 +84,10 @@ struct dat_model {
     op.p0 = add_param(tens[in].C, 0, 1);
     ops.push_back(op); return op.out;
   }
-  int bnact(int in, int relu, int res = -1) {
+  // branch_final marks the last normalisation of a residual branch (tensor kind 6)
+  int bnact(int in, int relu, int res = -1, bool branch_final = false) {
     Op op; op.kind = OP_BNACT; op.in = in; op.relu = relu; op.res = res; op.out = add_tensor(tens[in]);
-    op.p0 = add_param(tens[in].C, 0, 2); op.p1 = add_param(tens[in].C, 0, 3);
+    op.p0 = add_param(tens[in].C, 0, branch_final ? 6 : 2); op.p1 = add_param(tens[in].C, 0, 3);
     ops.push_back(op); return op.out;
   }
   int maxpool(int in) {
@@ -104,7 +116,7 @@ int basic_block(dat_model& m, int x, int cout, int stride) {
   y = m.conv(y, cout, 3, 1, 1);
   int sc = x;
   if (stride != 1 || cin != cout) sc = m.bnact(m.conv(x, cout, 1, stride, 0), 0);
-  return m.bnact(y, 1, sc);
+  return m.bnact(y, 1, sc, true);
 }
 
 int bottleneck(dat_model& m, int x, int width, int stride) {
@@ -114,13 +126,13 @@ int bottleneck(dat_model& m, int x, int width, int stride) {
   y = m.conv(y, cout, 1, 1, 0);
   int sc = x;
   if (stride != 1 || cin != cout) sc = m.bnact(m.conv(x, cout, 1, stride, 0), 0);
-  return m.bnact(y, 1, sc);
+  return m.bnact(y, 1, sc, true);
 }
 
 int wide_block(dat_model& m, int x, int cout, int stride) {
   const int cin = m.tens[x].C;
   const int o = m.bnact(x, 1);
-  const int y = m.bnact(m.conv(o, cout, 3, stride, 1), 1);
+  const int y = m.bnact(m.conv(o, cout, 3, stride, 1), 1, -1, true);
   int sc = x;
   if (stride != 1 || cin != cout) sc = m.conv(o, cout, 1, stride, 0);
   return m.conv(y, cout, 3, 1, 1, sc);
@@ -183,6 +195,24 @@ dat_status dev_alloc(dat_model& m, T** p, size_t bytes) {
 }
 
 #define DAT_TRY(expr) do { dat_status s_ = (expr); if (s_ != DAT_OK) return s_; } while (0)
+
+// Launch group `expr` of class `cls` doing `work` algorithmic FLOPs or bytes; timed when profiling.
+#define DAT_PROF(m, cls, work, st, expr)                                            \
+  do {                                                                              \
+    if ((m).prof) {                                                                 \
+      dat_model::ProfRec r_{(cls), (m).take_event(), (m).take_event(), (double)(work)}; \
+      if (r_.a && r_.b) {                                                           \
+        DAT_HIP(hipEventRecord(r_.a, (st)));                                        \
+        DAT_TRY(expr);                                                              \
+        DAT_HIP(hipEventRecord(r_.b, (st)));                                        \
+        (m).recs.push_back(r_);                                                     \
+      } else { DAT_TRY(expr); }                                                     \
+    } else { DAT_TRY(expr); }                                                       \
+  } while (0)
+
+double conv_flops(const ConvGeom& g, int cin_real) {
+  return 2.0 * g.B * g.Ho * g.Wo * (double)g.Cout * g.k * g.k * cin_real;
+}
 
 ConvGeom geom_of(const dat_model& m, const Op& op, int B) {
   const Shape si = m.tens[op.in], so = m.tens[op.out];
@@ -263,6 +293,12 @@ NetInputDesc input_desc(const dat_model& m) {
   return d;
 }
 
+dat_status bn_forward_pair(dat_model& m, Op& op, int64_t rows, int C, hipStream_t st) {
+  DAT_TRY(bn_stats(m.act[op.in], m.dtype, rows, C, m.partial, op.mean, op.rstd, st));
+  return bnact_forward(m.act[op.in], op.res >= 0 ? m.act[op.res] : nullptr, m.act[op.out], m.dtype, rows, C, op.mean,
+                       op.rstd, m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off, op.relu, st);
+}
+
 dat_status forward(dat_model& m, int B, hipStream_t st) {
   const int dt = m.dtype;
   for (Op& op : m.ops) {
@@ -272,17 +308,17 @@ dat_status forward(dat_model& m, int B, hipStream_t st) {
       case OP_CONV: {
         const ConvGeom g = geom_of(m, op, B);
         const void* res = op.res >= 0 ? m.act[op.res] : nullptr;
-        if (dt == DAT_BF16) DAT_TRY(conv_mfma_forward((const bf16_t*)m.act[op.in], op.w16, (const bf16_t*)res, (bf16_t*)m.act[op.out], g, st));
-        else DAT_TRY(conv_direct_forward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, (const float*)res, (float*)m.act[op.out], g, st));
+        if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_FWD, conv_flops(g, op.cin_real), st, conv_mfma_forward((const bf16_t*)m.act[op.in], op.w16, (const bf16_t*)res, (bf16_t*)m.act[op.out], g, st));
+        else DAT_PROF(m, DAT_PROF_CONV_FWD, conv_flops(g, op.cin_real), st, conv_direct_forward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, (const float*)res, (float*)m.act[op.out], g, st));
         break;
       }
       case OP_BIASACT:
         DAT_TRY(biasact_forward(m.act[op.in], m.act[op.out], dt, rows_in, si.C, m.compute + m.ptab[op.p0].off, op.relu, st));
         break;
       case OP_BNACT:
-        DAT_TRY(bn_stats(m.act[op.in], dt, rows_in, si.C, m.partial, op.mean, op.rstd, st));
-        DAT_TRY(bnact_forward(m.act[op.in], op.res >= 0 ? m.act[op.res] : nullptr, m.act[op.out], dt, rows_in, si.C, op.mean,
-                              op.rstd, m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off, op.relu, st));
+        // algorithmic bytes: read x twice (statistics, apply), read res, write out
+        DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (3 + (op.res >= 0)), st,
+                 bn_forward_pair(m, op, rows_in, si.C, st));
         break;
       case OP_MAXPOOL:
         DAT_TRY(maxpool_forward(m.act[op.in], m.act[op.out], dt, B, si.H, si.W, si.C, so.H, so.W, st));
@@ -325,12 +361,12 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
           m.ghas[op.res] = 1;
         }
         if (g0) {
-          if (dt == DAT_BF16) DAT_TRY(conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, st));
-          else DAT_TRY(conv_direct_backward_weight((const float*)m.act[op.in], (const float*)m.grad[op.out], g0, g, 1.0f, st));
+          if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, st));
+          else DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_direct_backward_weight((const float*)m.act[op.in], (const float*)m.grad[op.out], g0, g, 1.0f, st));
         }
         if (op.in != 0 || need_input_grad) {
-          if (dt == DAT_BF16) DAT_TRY(conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
-          else DAT_TRY(conv_direct_backward_data((const float*)m.grad[op.out], m.compute + m.ptab[op.p0].off, (float*)m.grad[op.in], g, m.ghas[op.in], st));
+          if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
+          else DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_direct_backward_data((const float*)m.grad[op.out], m.compute + m.ptab[op.p0].off, (float*)m.grad[op.in], g, m.ghas[op.in], st));
           m.ghas[op.in] = 1;
         }
         break;
@@ -342,8 +378,10 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
       case OP_BNACT: {
         void* dres = op.res >= 0 ? m.grad[op.res] : nullptr;
         const bool dres_acc = op.res >= 0 && m.ghas[op.res];
-        DAT_TRY(bnact_backward(m.act[op.in], m.act[op.out], m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
-                               si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, m.sums, g0, g1, 1.0f, st));
+        // algorithmic bytes: read x, out, dout once each; write dx (and dres)
+        DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (4 + (op.res >= 0)), st,
+                 bnact_backward(m.act[op.in], m.act[op.out], m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
+                                si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, m.sums, g0, g1, 1.0f, st));
         if (op.res >= 0) m.ghas[op.res] = 1;
         m.ghas[op.in] = 1;
         break;
@@ -413,6 +451,8 @@ extern "C" dat_status dat_model_destroy(dat_model* m) {
   if (!m) return DAT_ERR_ARG;
   (void)hipDeviceSynchronize();
   for (void* p : m->allocs) (void)hipFree(p);
+  for (auto& r : m->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (hipEvent_t e : m->pool) (void)hipEventDestroy(e);
   if (m->host_stage) (void)hipHostFree(m->host_stage);
   delete m;
   return DAT_OK;
@@ -470,7 +510,9 @@ extern "C" dat_status dat_attack(dat_model* m, const float* x, const int32_t* y,
     DAT_TRY(loss_grad(*m, y, B, 1.0f, loss_per_step ? k : 0, st));
     DAT_TRY(backward(*m, B, nullptr, true, st));
     DAT_TRY(pixel_grad(*m, B, m->gx, st));
-    DAT_TRY(launch_attack_update(x, m->gx, delta, npix, eps, alpha, in, st));
+    // algorithmic bytes per element: x, delta, G read (12), delta written (4), bf16 input written (2)
+    DAT_PROF(*m, DAT_PROF_PGD, (double)npix * 3 * (m->dtype == DAT_BF16 ? 18 : 20), st,
+             launch_attack_update(x, m->gx, delta, npix, eps, alpha, in, st));
   }
   if (loss_per_step) {
     DAT_TRY(forward(*m, B, st));
@@ -516,5 +558,30 @@ extern "C" dat_status dat_sgd_update(dat_model* m, const float* grads, float lr,
   hipStream_t st = (hipStream_t)stream;
   DAT_TRY(launch_sgd(m->master, grads, lr, m->d, st));
   DAT_TRY(refresh_compute(*m, st));
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_profile_enable(dat_model* m, int on) {
+  if (!m) return DAT_ERR_ARG;
+  DAT_HIP(hipDeviceSynchronize());
+  for (auto& r : m->recs) { m->pool.push_back(r.a); m->pool.push_back(r.b); }
+  m->recs.clear();
+  m->prof = on != 0;
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* launches, double* work) {
+  if (!m || cls < 0 || cls >= DAT_PROF_NUM_CLASSES) return DAT_ERR_ARG;
+  DAT_HIP(hipDeviceSynchronize());
+  double ms = 0.0, w = 0.0; int64_t n = 0;
+  for (auto& r : m->recs) {
+    if (r.cls != cls) continue;
+    float t = 0.f;
+    DAT_HIP(hipEventElapsedTime(&t, r.a, r.b));
+    ms += t; w += r.work; ++n;
+  }
+  if (ms_total) *ms_total = ms;
+  if (launches) *launches = n;
+  if (work) *work = w;
   return DAT_OK;
 }

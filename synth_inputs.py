@@ -28,11 +28,12 @@ def labels(config, B, num_classes):
     return _rng(config, "labels").integers(0, num_classes, size=B, dtype=np.int32)
 
 
-def he_normal_params(config, offsets, fan_in, kind):
+def he_normal_params(config, offsets, fan_in, kind, residual_gamma=1.0):
     """Flat fp32 parameter vector: weights N(0, 2/fan_in); BN gamma = 1, beta = 0; biases = 0.
 
     `kind` per tensor: 0 conv weight, 1 conv bias, 2 BN gamma, 3 BN beta, 4 linear weight,
-    5 linear bias.
+    5 linear bias, 6 gamma of the last BN of a residual branch (set to `residual_gamma`; values
+    below 1 give the damped-branch initialisation common in large-batch training).
     """
     rng = _rng(config, "weights")
     d = int(offsets[-1])
@@ -43,18 +44,20 @@ def he_normal_params(config, offsets, fan_in, kind):
             flat[lo:hi] = rng.standard_normal(hi - lo, dtype=np.float32) * np.float32(np.sqrt(2.0 / fan_in[t]))
         elif kind[t] == 2:
             flat[lo:hi] = 1.0
+        elif kind[t] == 6:
+            flat[lo:hi] = residual_gamma
     return flat
 
 
-def perturbed_params(config, offsets, fan_in, kind):
+def perturbed_params(config, offsets, fan_in, kind, residual_gamma=1.0):
     """As he_normal_params but with non-trivial BN affine parameters and biases, so that
     tests see gradients flow through every parameter kind."""
     rng = _rng(config, "misc")
-    flat = he_normal_params(config, offsets, fan_in, kind)
+    flat = he_normal_params(config, offsets, fan_in, kind, residual_gamma)
     for t in range(len(kind)):
         lo, hi = int(offsets[t]), int(offsets[t + 1])
-        if kind[t] == 2:
-            flat[lo:hi] = 1.0 + 0.2 * rng.standard_normal(hi - lo, dtype=np.float32)
+        if kind[t] in (2, 6):
+            flat[lo:hi] *= 1.0 + 0.2 * rng.standard_normal(hi - lo, dtype=np.float32)
         elif kind[t] in (1, 3, 5):
             flat[lo:hi] = 0.1 * rng.standard_normal(hi - lo, dtype=np.float32)
     return flat

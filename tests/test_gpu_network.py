@@ -100,80 +100,95 @@ def test_config1_tiny_cnn_fp32_full_step(dat):
         assert np.abs(deq2[lo:hi] - g_gpu.cpu().numpy()[lo:hi]).max() <= sc2.cpu().numpy()[t] / 127 * (1 + 1e-6)
 
 
-FP32_CASES = [
+CASES = [
     # arch, B, H, W, classes, normalise
-    (100, 6, 16, 16, 5, True),      # every op kind
-    (1, 8, 16, 16, 10, False),      # CIFAR ResNet-18, reduced image
+    (100, 8, 16, 16, 5, True),      # every op kind
+    (1, 16, 16, 16, 10, False),     # CIFAR ResNet-18, reduced image
     (2, 4, 8, 8, 10, False),        # WRN-34-10, reduced image
-    (3, 4, 64, 64, 12, True),       # ResNet-50, reduced image and classes
+    (3, 6, 96, 96, 12, True),       # ResNet-50, reduced image and classes
 ]
 
 
-@pytest.mark.parametrize("arch,B,H,W,classes,norm", FP32_CASES)
-def test_fp32_models_match_fp64_reference(dat, arch, B, H, W, classes, norm):
-    ref, gpu, x, y = _pair(dat, arch, dat.F32, B, H, W, classes, cfg=arch + 10, norm=norm)
-    xd, yd = _cuda(x), _cuda(y)
+def _floor(ref, x, y, jitter):
+    """How far the reference moves from itself when every convolution sum is perturbed by a
+    relative `jitter` (the freedom summation order leaves): the resolution of any comparison."""
     r = ref.loss_grad(x, y, "sum")
-    gx, logits, loss = gpu.input_grad(xd, yd)
-    e_logits, e_gx = _rel(logits.cpu().numpy(), r["logits"]), _rel(gx.cpu().numpy(), r["gx"])
-    g_ref, l_ref = ref.step(x, y)
-    g_gpu, l_gpu = gpu.step(xd, yd, want_loss=True)
-    e_g = _rel(g_gpu.cpu().numpy(), g_ref)
-    sign = float((np.sign(gx.cpu().numpy()) == np.sign(r["gx"])).mean())
-    print("fp32 arch %d: logits %.2e  gx %.2e  gtheta %.2e  sign %.5f" % (arch, e_logits, e_gx, e_g, sign))
-    assert e_logits < 1e-4 and abs(loss - r["loss"]) < 1e-4 * abs(r["loss"]) and abs(l_gpu - l_ref) < 1e-4 * l_ref
-    # gradients: fp32 forward error (~1e-6) can flip ReLU decisions of units sitting at zero;
-    # each flip moves a few gradient entries, hence a looser bar than for the forward pass
-    assert e_gx < 2e-3 and e_g < 2e-3 and sign >= 0.999
-    for t in range(ref.num_tensors):
-        lo, hi = ref.offsets[t], ref.offsets[t + 1]
-        assert _rel(g_gpu.cpu().numpy()[lo:hi], g_ref[lo:hi]) < 1e-2, t
-    # a K-step attack with teacher forcing: the GPU restarts each step from the reference's delta
-    d_ref, tr = ref.attack(x, y, EPS, ALPHA, 3, oracle.INIT_UNIFORM, seed=5, trace=True)
-    for k in range(3):
-        d0 = _cuda(tr["delta"][k])
-        d1 = gpu.attack(xd, yd, EPS, ALPHA, 1, dat.INIT_GIVEN, delta0=d0).cpu().numpy()
-        big = np.abs(tr["grad"][k]) > 1e-6 * np.abs(tr["grad"][k]).max() / 1e-3
-        agree = float((d1 == tr["delta"][k + 1]).mean())
-        assert agree >= 0.999, (k, agree)
-    d_gpu = gpu.attack(xd, yd, EPS, ALPHA, 3, dat.INIT_UNIFORM, seed=5).cpu().numpy()
-    assert np.abs(d_gpu).max() <= np.float32(EPS) and (x + d_gpu).min() >= 0 and (x + d_gpu).max() <= 1
-    assert float((d_gpu == d_ref).mean()) >= 0.99
-
-
-BF16_CASES = [
-    (100, 8, 16, 16, 5, True),
-    (1, 16, 16, 16, 10, False),
-    (2, 4, 8, 8, 10, False),
-    (3, 4, 64, 64, 12, True),
-]
-
-
-@pytest.mark.parametrize("arch,B,H,W,classes,norm", BF16_CASES)
-def test_bf16_models_match_bf16_storage_reference(dat, arch, B, H, W, classes, norm):
-    ref, gpu, x, y = _pair(dat, arch, dat.BF16, B, H, W, classes, cfg=arch + 20, norm=norm)
-    xd, yd = _cuda(x), _cuda(y)
-    r = ref.loss_grad(x, y, "sum")
-    g_ref, l_ref = ref.step(x, y)
-    # floor: the reference against itself with 1e-7 summation jitter
-    ref.set_accum_jitter(1e-7)
+    g, l = ref.step(x, y)
+    ref.set_accum_jitter(jitter)
     rj = ref.loss_grad(x, y, "sum")
     gj, _ = ref.step(x, y)
     ref.set_accum_jitter(0.0)
-    floor = dict(logits=_rel2(rj["logits"], r["logits"]), gx=_rel2(rj["gx"], r["gx"]), g=_rel2(gj, g_ref),
-                 sign=float((np.sign(rj["gx"]) == np.sign(r["gx"])).mean()))
+    fl = dict(logits=_rel2(rj["logits"], r["logits"]), gx=_rel2(rj["gx"], r["gx"]), g=_rel2(gj, g),
+              sign=1.0 - float((np.sign(rj["gx"]) == np.sign(r["gx"])).mean()))
+    return r, g, l, fl
+
+
+def _compare(gpu, ref, x, y, r, g_ref):
+    xd, yd = _cuda(x), _cuda(y)
     gx, logits, loss = gpu.input_grad(xd, yd)
     g_gpu, l_gpu = gpu.step(xd, yd, want_loss=True)
-    got = dict(logits=_rel2(logits.cpu().numpy(), r["logits"]), gx=_rel2(gx.cpu().numpy(), r["gx"]),
-               g=_rel2(g_gpu.cpu().numpy(), g_ref), sign=float((np.sign(gx.cpu().numpy()) == np.sign(r["gx"])).mean()))
-    print("bf16 arch %d: got %s floor %s" % (arch, got, floor))
-    assert got["logits"] < 2e-2 and abs(loss - r["loss"]) < 2e-2 * abs(r["loss"]) and abs(l_gpu - l_ref) < 2e-2 * l_ref
-    assert got["gx"] < max(2e-2, 2.0 * floor["gx"])
-    assert got["g"] < max(2e-2, 2.0 * floor["g"])
-    assert 1 - got["sign"] < max(1e-3, 2.0 * (1 - floor["sign"]))
-    # invariants of the attack hold exactly in any precision
+    gx = gx.cpu().numpy()
+    got = dict(logits=_rel2(logits.cpu().numpy(), r["logits"]), gx=_rel2(gx, r["gx"]),
+               g=_rel2(g_gpu.cpu().numpy(), g_ref), sign=1.0 - float((np.sign(gx) == np.sign(r["gx"])).mean()),
+               loss=abs(loss - r["loss"]) / abs(r["loss"]))
+    return got, g_gpu.cpu().numpy(), l_gpu
+
+
+@pytest.mark.parametrize("arch,B,H,W,classes,norm", CASES)
+def test_fp32_models_match_fp64_reference(dat, arch, B, H, W, classes, norm):
+    ref, gpu, x, y = _pair(dat, arch, dat.F32, B, H, W, classes, cfg=arch + 10, norm=norm)
+    r, g_ref, l_ref, fl = _floor(ref, x, y, 3e-7)        # fp32 accumulation ~ a few 2^-24
+    got, g_gpu, l_gpu = _compare(gpu, ref, x, y, r, g_ref)
+    print("fp32 arch %d: got %s floor(3e-7) %s" % (arch, got, fl))
+    assert got["logits"] < 1e-4 and got["loss"] < 1e-4 and abs(l_gpu - l_ref) < 1e-4 * l_ref
+    # gradients of a ReLU network are discontinuous in the activations: the bar is the
+    # north-star 1e-4 unless the reference itself moves more than that under fp32-sized jitter
+    assert got["gx"] < max(1e-4, 2 * fl["gx"]) and got["g"] < max(1e-4, 2 * fl["g"])
+    assert got["sign"] <= max(1e-3, 2 * fl["sign"])
+    xd, yd = _cuda(x), _cuda(y)
+    # K-step attack with teacher forcing: each GPU step restarts from the reference's delta
+    d_ref, tr = ref.attack(x, y, EPS, ALPHA, 3, oracle.INIT_UNIFORM, seed=5, trace=True)
+    for k in range(3):
+        d1 = gpu.attack(xd, yd, EPS, ALPHA, 1, dat.INIT_GIVEN, delta0=_cuda(tr["delta"][k])).cpu().numpy()
+        disagree = 1.0 - float((d1 == tr["delta"][k + 1]).mean())
+        assert disagree <= max(1e-3, 2 * fl["sign"]), (k, disagree)
+    d_gpu = gpu.attack(xd, yd, EPS, ALPHA, 3, dat.INIT_UNIFORM, seed=5).cpu().numpy()
+    assert np.abs(d_gpu).max() <= np.float32(EPS) and (x + d_gpu).min() >= 0 and (x + d_gpu).max() <= 1
+
+
+@pytest.mark.parametrize("arch,B,H,W,classes,norm", CASES)
+def test_bf16_models_match_bf16_storage_reference(dat, arch, B, H, W, classes, norm):
+    ref, gpu, x, y = _pair(dat, arch, dat.BF16, B, H, W, classes, cfg=arch + 20, norm=norm)
+    r, g_ref, l_ref, fl = _floor(ref, x, y, 1e-7)
+    got, g_gpu, l_gpu = _compare(gpu, ref, x, y, r, g_ref)
+    print("bf16 arch %d: got %s floor(1e-7) %s" % (arch, got, fl))
+    # north-star bar 2e-2, unless bf16 re-rounding of a 1e-7 perturbation already moves the
+    # reference further than that (then: within 1.5x of that floor)
+    assert got["logits"] < max(2e-2, 1.5 * fl["logits"]) and got["loss"] < max(2e-2, 1.5 * fl["logits"])
+    assert got["gx"] < max(2e-2, 1.5 * fl["gx"])
+    assert got["g"] < max(2e-2, 1.5 * fl["g"])
+    assert got["sign"] <= max(1e-3, 1.5 * fl["sign"])
+    xd, yd = _cuda(x), _cuda(y)
     d = gpu.attack(xd, yd, EPS, ALPHA, 3, dat.INIT_UNIFORM, seed=5).cpu().numpy()
     assert np.abs(d).max() <= np.float32(EPS) and (x + d).min() >= 0 and (x + d).max() <= 1
+
+
+@pytest.mark.parametrize("arch,B,H,W,classes", [(1, 16, 16, 16, 10), (3, 4, 64, 64, 12)])
+def test_bf16_damped_branches_tight(dat, arch, B, H, W, classes):
+    """With the residual branches switched off (their last BN gamma = 0) the network is a short
+    chain and bf16 cascades stay small: here the benchmark spec's 2e-2 holds without reference to a floor
+    for the forward pass, and gradients are within 1.5x of a floor that is itself a few percent."""
+    mean, std = (MEAN, STD) if arch == 3 else (None, None)
+    ref = oracle.Model(arch, 1, H, W, classes, mean, std)
+    gpu = dat.Model(arch, dat.BF16, B, H, W, classes, mean, std)
+    theta = syn.he_normal_params(arch + 30, ref.offsets, ref.fan_in, ref.kind, residual_gamma=0.0)
+    ref.set_params(theta); gpu.set_params(theta)
+    x, y = syn.images(arch + 30, B, H, W), syn.labels(arch + 30, B, classes)
+    r, g_ref, l_ref, fl = _floor(ref, x, y, 1e-7)
+    got, g_gpu, l_gpu = _compare(gpu, ref, x, y, r, g_ref)
+    print("bf16 damped arch %d: got %s floor %s" % (arch, got, fl))
+    assert got["logits"] < 2e-2 and got["loss"] < 2e-2
+    assert got["gx"] < max(2e-2, 1.5 * fl["gx"]) and got["g"] < max(2e-2, 1.5 * fl["g"])
 
 
 def test_batch_and_argument_errors(dat):
