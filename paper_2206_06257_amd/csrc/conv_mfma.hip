@@ -46,16 +46,27 @@ struct IgemmArgs {
   const bf16_t* wt;     // [Cout][KH*KW*Cin]
   const bf16_t* res;    // optional [M][Cout] added before rounding
   bf16_t* out;          // [M][Cout], M = B*Hout*Wout
-  int B, Hin, Win, Cin, Hout, Wout, Cout;
-  int KH, KW, ostride, pad, dshift;   // input dilation = 1 << dshift
+  int B, Hin, Win, Cin, Hout, Wout, Cout;   // Hout x Wout = grid of output pixels this launch computes
+  int KH, KW, ostride, pad_h, pad_w;
+  // output pixel (n, a, b) is stored at row (n*outH + a*ostep + oh0)*outW + b*ostep + ow0 of `out`
+  int outH, outW, ostep, oh0, ow0;
   int M, Ktot, nct, npt;
 };
 
-template <int TC, int TP>
+__device__ __forceinline__ int64_t out_row(const IgemmArgs& a, int m) {
+  if (a.ostep == 1 && a.outH == a.Hout && a.outW == a.Wout) return m;
+  const int HW = a.Hout * a.Wout;
+  const int n = m / HW, rem = m - n * HW;
+  const int ya = rem / a.Wout, xb = rem - ya * a.Wout;
+  return ((int64_t)n * a.outH + ya * a.ostep + a.oh0) * a.outW + xb * a.ostep + a.ow0;
+}
+
+template <int TC, int TP, int WGC>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
-  constexpr int WC = TC / 2, WP = TP / 2;          // wave tile
+  constexpr int WGP = 4 / WGC;                     // waves along channels x waves along pixels
+  constexpr int WC = TC / WGC, WP = TP / WGP;      // wave tile
   constexpr int NI = WC / 32, NJ = WP / 32;        // MFMA tiles per wave
-  constexpr int VW = TC * 4 / kThreads, VX = TP * 4 / kThreads;   // 16-byte vectors per thread per tile
+  constexpr int VW = (TC * 4 + kThreads - 1) / kThreads, VX = TP * 4 / kThreads;   // 16-byte vectors per thread per tile
   constexpr int TILE_BYTES = (TC + TP) * 64;
   constexpr int STG_STRIDE = TC * 2 + 16;
   constexpr int LDS_BYTES = (2 * TILE_BYTES > TP * STG_STRIDE) ? 2 * TILE_BYTES : TP * STG_STRIDE;
@@ -70,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   const int c0 = ct * TC, m0 = pt * TP;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wc = wave & 1, wp = wave >> 1;
+  const int wc = wave % WGC, wp = wave / WGC;
   const int kvec = tid & 3, lrow = tid >> 2;       // this thread's slot in the global->LDS copy
 
   // im2col row state for the activation vectors this thread fetches
@@ -83,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     const int mm = mv[i] ? m : 0;
     const int n = mm / HW, rem = mm - n * HW;
     const int ho = rem / a.Wout, wo = rem - ho * a.Wout;
-    hb[i] = ho * a.ostride - a.pad; wb[i] = wo * a.ostride - a.pad;
+    hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * a.ostride - a.pad_w;
     nb[i] = (int64_t)n * a.Hin * a.Win;
   }
   // (r, s, c) of this thread's k-slot, advanced by BK per tile
@@ -93,7 +104,6 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     const int tap = k / a.Cin;
     kc = k - tap * a.Cin; kr = tap / a.KW; ks = tap - kr * a.KW;
   }
-  const int dmask = (1 << a.dshift) - 1;
   const int ntiles = (a.Ktot + BK - 1) / BK;
 
   uint4 gw[VW], gx[VX];
@@ -103,14 +113,12 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
 #pragma unroll
     for (int i = 0; i < VW; ++i) {
       const int c = c0 + lrow + 64 * i;
-      gw[i] = (kvalid && c < a.Cout) ? *reinterpret_cast<const uint4*>(a.wt + (int64_t)c * a.Ktot + k) : make_uint4(0, 0, 0, 0);
+      gw[i] = (kvalid && lrow + 64 * i < TC && c < a.Cout) ? *reinterpret_cast<const uint4*>(a.wt + (int64_t)c * a.Ktot + k) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < VX; ++i) {
-      const int ph = hb[i] + kr, pw = wb[i] + ks;
-      bool ok = kvalid && mv[i] && ph >= 0 && pw >= 0 && ((ph | pw) & dmask) == 0;
-      const int hi = ph >> a.dshift, wi = pw >> a.dshift;
-      ok = ok && hi < a.Hin && wi < a.Win;
+      const int hi = hb[i] + kr, wi = wb[i] + ks;
+      const bool ok = kvalid && mv[i] && hi >= 0 && wi >= 0 && hi < a.Hin && wi < a.Win;
       gx[i] = ok ? *reinterpret_cast<const uint4*>(a.in + ((nb[i] + (int64_t)hi * a.Win + wi) * a.Cin + kc)) : make_uint4(0, 0, 0, 0);
     }
     // advance (r,s,c) to the next tile
@@ -121,7 +129,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     unsigned char* wbase = lds + buf * TILE_BYTES;
     unsigned char* xbase = wbase + TC * 64;
 #pragma unroll
-    for (int i = 0; i < VW; ++i) *reinterpret_cast<uint4*>(wbase + swz(lrow + 64 * i, kvec)) = gw[i];
+    for (int i = 0; i < VW; ++i) if (lrow + 64 * i < TC) *reinterpret_cast<uint4*>(wbase + swz(lrow + 64 * i, kvec)) = gw[i];
 #pragma unroll
     for (int i = 0; i < VX; ++i) *reinterpret_cast<uint4*>(xbase + swz(lrow + 64 * i, kvec)) = gx[i];
   };
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
         const int ch = wc * WC + i * 32 + 8 * g + 4 * (lane >> 5);
         float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
         if (a.res && m < a.M && c0 + ch < a.Cout) {
-          const uint2 r = *reinterpret_cast<const uint2*>(a.res + (int64_t)m * a.Cout + c0 + ch);
+          const uint2 r = *reinterpret_cast<const uint2*>(a.res + out_row(a, m) * a.Cout + c0 + ch);
           v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xffff0000u);
           v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xffff0000u);
         }
@@ -192,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     const int prow = pr0 + i * RPP;
     const int m = m0 + prow, ch = c0 + cv * 8;
     if (m < a.M && ch < a.Cout)
-      *reinterpret_cast<uint4*>(a.out + (int64_t)m * a.Cout + ch) = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
+      *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
   }
 }
 
@@ -201,29 +209,46 @@ __global__ void widen_kernel(const bf16_t* __restrict__ src, float* __restrict__
   if (i < n) dst[i] = bf2f(src[i]);
 }
 
-int log2_exact(int v) { int s = 0; while ((1 << s) < v) ++s; return (1 << s) == v ? s : -1; }
-
-template <int TC, int TP>
+template <int TC, int TP, int WGC>
 dat_status launch_igemm(IgemmArgs a, hipStream_t st) {
   a.nct = (a.Cout + TC - 1) / TC;
   a.npt = (a.M + TP - 1) / TP;
+  if (a.npt == 0) return DAT_OK;
   const int npt8 = (a.npt + 7) / 8 * 8;
-  hipLaunchKernelGGL((igemm_kernel<TC, TP>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
 
 dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
-  if (a.Cin % 8 != 0 || a.Cout % 8 != 0 || a.dshift < 0) return DAT_ERR_UNSUPPORTED;
-  if (a.Cout <= 64) return launch_igemm<64, 128>(a, st);
-  return launch_igemm<128, 128>(a, st);
+  if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
+  if (a.Cout <= 32) return launch_igemm<32, 128, 1>(a, st);
+  if (a.Cout <= 64) return launch_igemm<64, 128, 2>(a, st);
+  return launch_igemm<128, 128, 2>(a, st);
 }
 
 // ---- weight layouts ---------------------------------------------------------------------------
-// master fp32 [Cout][k][k][cin_real] -> w [Cout][k][k][Cin] bf16 (zero padded channels) and
-// wT [Cin][k][k][Cout] bf16 with wT[ci][r][s][co] = w[co][k-1-r][k-1-s][ci].
+// master fp32 [Cout][k][k][cin_real] -> w [Cout][k][k][Cin] bf16 (zero padded channels) and the
+// backward-data operand wT.
+//   stride 1: wT [Cin][k][k][Cout], wT[ci][r'][s'][co] = w[co][k-1-r'][k-1-s'][ci].
+//   stride 2: the input pixels split into four parity classes (h%2, w%2); class (ph,pw) only sees
+//     the taps r = rf + 2i, s = sf + 2j with rf = (ph+pad)%2, sf = (pw+pad)%2, and is a dense
+//     stride-1 convolution of dY with that nr x ns sub-filter.  wT holds the four flipped
+//     sub-filters back to back: class q = 2*ph+pw at offset Cin*Cout*(taps of earlier classes),
+//     laid out [Cin][nr][ns][Cout].
+struct ParityClass { int rf, nr, pad; };
+__host__ __device__ inline ParityClass parity_class(int p, int k, int pad) {
+  ParityClass c;
+  c.rf = (p + pad) & 1;
+  c.nr = (k - c.rf + 1) / 2;
+  if (c.rf >= k) c.nr = 0;
+  const int off = (p + pad - c.rf) / 2;
+  c.pad = c.nr - 1 - off;
+  return c;
+}
+
 __global__ void weight_transform_kernel(const float* __restrict__ master, bf16_t* __restrict__ w, bf16_t* __restrict__ wT,
-                                        int Cout, int k, int cin_real, int Cin) {
+                                        int Cout, int k, int cin_real, int Cin, int stride, int pad) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)Cout * k * k * Cin) return;
   const int ci = (int)(i % Cin);
@@ -233,7 +258,18 @@ __global__ void weight_transform_kernel(const float* __restrict__ master, bf16_t
   const int co = (int)(p / k);
   const bf16_t v = ci < cin_real ? f2bf(master[(((int64_t)co * k + r) * k + s) * cin_real + ci]) : (bf16_t)0;
   w[i] = v;
-  wT[(((int64_t)ci * k + (k - 1 - r)) * k + (k - 1 - s)) * Cout + co] = v;
+  if (stride == 1) {
+    wT[(((int64_t)ci * k + (k - 1 - r)) * k + (k - 1 - s)) * Cout + co] = v;
+  } else {
+    // the class whose first tap has the parity of r (resp. s)
+    const int ph = (r + pad) & 1, pw = (s + pad) & 1;      // (ph+pad)%2 == r%2  <=>  ph == (r+pad)%2
+    int64_t base = 0;
+    for (int q = 0; q < 2 * ph + pw; ++q)
+      base += (int64_t)parity_class(q >> 1, k, pad).nr * parity_class(q & 1, k, pad).nr;
+    const ParityClass ch = parity_class(ph, k, pad), cw = parity_class(pw, k, pad);
+    const int ii = (r - ch.rf) / 2, jj = (s - cw.rf) / 2;
+    wT[base * Cin * Cout + (((int64_t)ci * ch.nr + (ch.nr - 1 - ii)) * cw.nr + (cw.nr - 1 - jj)) * Cout + co] = v;
+  }
 }
 
 // ---- backward-weight ----------------------------------------------------------------------------
@@ -417,18 +453,38 @@ dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res
   IgemmArgs a;
   a.in = x; a.wt = w; a.res = res; a.out = y;
   a.B = g.B; a.Hin = g.H; a.Win = g.W; a.Cin = g.Cin; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
-  a.KH = g.k; a.KW = g.k; a.ostride = g.stride; a.pad = g.pad; a.dshift = 0;
+  a.KH = g.k; a.KW = g.k; a.ostride = g.stride; a.pad_h = a.pad_w = g.pad;
+  a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
   a.M = g.B * g.Ho * g.Wo; a.Ktot = g.k * g.k * g.Cin; a.nct = a.npt = 0;
   return run_igemm(a, st);
 }
 
 dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, hipStream_t st) {
   IgemmArgs a;
-  a.in = dy; a.wt = wT; a.res = accumulate ? dx : nullptr; a.out = dx;
-  a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H; a.Wout = g.W; a.Cout = g.Cin;
-  a.KH = g.k; a.KW = g.k; a.ostride = 1; a.pad = g.k - 1 - g.pad; a.dshift = log2_exact(g.stride);
-  a.M = g.B * g.H * g.W; a.Ktot = g.k * g.k * g.Cout; a.nct = a.npt = 0;
-  return run_igemm(a, st);
+  a.in = dy; a.res = accumulate ? dx : nullptr; a.out = dx;
+  a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Cout = g.Cin;
+  a.ostride = 1; a.outH = g.H; a.outW = g.W; a.nct = a.npt = 0;
+  if (g.stride == 1) {
+    a.wt = wT; a.Hout = g.H; a.Wout = g.W; a.KH = a.KW = g.k; a.pad_h = a.pad_w = g.k - 1 - g.pad;
+    a.ostep = 1; a.oh0 = a.ow0 = 0;
+    a.M = g.B * g.H * g.W; a.Ktot = g.k * g.k * g.Cout;
+    return run_igemm(a, st);
+  }
+  if (g.stride != 2) return DAT_ERR_UNSUPPORTED;
+  int64_t base = 0;
+  for (int q = 0; q < 4; ++q) {
+    const int ph = q >> 1, pw = q & 1;
+    const ParityClass ch = parity_class(ph, g.k, g.pad), cw = parity_class(pw, g.k, g.pad);
+    a.wt = wT + base * g.Cin * g.Cout;
+    a.Hout = (g.H - ph + 1) / 2; a.Wout = (g.W - pw + 1) / 2;
+    a.KH = ch.nr; a.KW = cw.nr; a.pad_h = ch.pad; a.pad_w = cw.pad;
+    a.ostep = 2; a.oh0 = ph; a.ow0 = pw;
+    a.M = g.B * a.Hout * a.Wout; a.Ktot = ch.nr * cw.nr * g.Cout;
+    if (a.Ktot == 0) a.KH = a.KW = 1;   // class without taps: the launch only writes zeros (or keeps the stored gradient)
+    if (a.M > 0) { dat_status s = run_igemm(a, st); if (s != DAT_OK) return s; }
+    base += (int64_t)ch.nr * cw.nr;
+  }
+  return DAT_OK;
 }
 
 dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale,
@@ -451,9 +507,10 @@ dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* d
   return DAT_OK;
 }
 
-dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, int Cout, int k, int cin_real, int Cin, hipStream_t st) {
+dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, int Cout, int k, int cin_real, int Cin, int stride,
+                                   int pad, hipStream_t st) {
   const int64_t n = (int64_t)Cout * k * k * Cin;
-  hipLaunchKernelGGL(weight_transform_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, master, w, wT, Cout, k, cin_real, Cin);
+  hipLaunchKernelGGL(weight_transform_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, master, w, wT, Cout, k, cin_real, Cin, stride, pad);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -500,7 +557,7 @@ extern "C" dat_status dat_conv_backward_data(const uint16_t* dy, const uint16_t*
   dat_status s = DAT_OK;
   hipLaunchKernelGGL(widen_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, w, wf, (int64_t)n);
   if (hipGetLastError() != hipSuccess) s = DAT_ERR_HIP;
-  if (s == DAT_OK) s = launch_weight_transform(wf, w2, wT, Cout, k, Cin, Cin, st);
+  if (s == DAT_OK) s = launch_weight_transform(wf, w2, wT, Cout, k, Cin, Cin, stride, pad, st);
   if (s == DAT_OK) s = conv_mfma_backward_data(dy, wT, dx, g, false, st);
   (void)hipStreamSynchronize(st);
   (void)hipFree(wf); (void)hipFree(w2); (void)hipFree(wT);

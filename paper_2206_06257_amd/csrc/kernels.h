@@ -40,8 +40,8 @@ dat_status conv_direct_backward_data(const float* dy, const float* w, float* dx,
 dat_status conv_direct_backward_weight(const float* x, const float* dy, float* dw, const ConvGeom& g, float scale, hipStream_t st);
 
 // ---- bf16 implicit-GEMM convolutions on MFMA (conv_mfma.hip): the DAT_BF16 path ----------------
-// w: [Cout][k][k][Cin] bf16.  wT: [Cin][k][k][Cout] bf16 with the taps flipped (see
-// launch_weight_transform), the operand of backward-data.
+// w: [Cout][k][k][Cin] bf16.  wT: the backward-data operand built by launch_weight_transform
+// (flipped transpose for stride 1, four parity-class sub-filters for stride 2).
 dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, hipStream_t st);
 dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, hipStream_t st);
 // dw fp32 [Cout][k][k][Cin_real] (Cin_real <= g.Cin: padded input channels are dropped), scaled.
@@ -49,7 +49,7 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
 size_t conv_mfma_wgrad_workspace(const ConvGeom& g);
 dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale, void* ws, hipStream_t st);
 // master fp32 [Cout][k][k][cin_real] -> w bf16 [Cout][k][k][Cin] (zero padded) and wT.
-dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, int Cout, int k, int cin_real, int Cin, hipStream_t st);
+dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, int Cout, int k, int cin_real, int Cin, int stride, int pad, hipStream_t st);
 
 // ---- everything that is not a convolution (layers.hip) -----------------------------------------
 // Batch statistics of x[rows][C]: mean[C], rstd[C] = 1/sqrt(var + 1e-5) (biased variance).

@@ -13,7 +13,8 @@ namespace dat {
 namespace {
 
 constexpr int kT = 256;
-constexpr int kMaxSlabs = 512;
+constexpr int kMaxSlabs = 1024;      // slabs of a per-channel reduction
+constexpr int kMaxApplySlabs = 8192;  // slabs of an elementwise pass
 
 template <typename T> struct V8;
 template <> struct V8<float> {
@@ -45,14 +46,19 @@ __device__ __forceinline__ void load8f(const float* p, float v[8]) { V8<float>::
 
 struct SlabPlan { int tpr, rpp, nslabs; int64_t rows_per_slab; };
 
-SlabPlan plan_slabs(int64_t rows, int C) {
+// Row slabs for the streaming kernels: a workgroup owns `rows_per_slab` consecutive rows; thread
+// (rr, cv) = (tid / tpr, tid % tpr) walks rows rr, rr+rpp, ... of the slab for channel vector cv,
+// so per-channel parameters stay in registers.  Enough slabs to fill 256 CUs several times over.
+SlabPlan plan_slabs(int64_t rows, int C, int max_slabs) {
   SlabPlan p;
   p.tpr = C / 8;
   p.rpp = kT / p.tpr;
   if (p.rpp < 1) p.rpp = 1;
-  int64_t want = (rows + (int64_t)p.rpp * 4 - 1) / ((int64_t)p.rpp * 4);
-  p.nslabs = (int)(want < 1 ? 1 : (want > kMaxSlabs ? kMaxSlabs : want));
+  int64_t want = (rows + (int64_t)p.rpp * 8 - 1) / ((int64_t)p.rpp * 8);
+  p.nslabs = (int)(want < 1 ? 1 : (want > max_slabs ? max_slabs : want));
   p.rows_per_slab = (rows + p.nslabs - 1) / p.nslabs;
+  p.rows_per_slab = (p.rows_per_slab + p.rpp - 1) / p.rpp * p.rpp;
+  p.nslabs = (int)((rows + p.rows_per_slab - 1) / p.rows_per_slab);
   return p;
 }
 
@@ -78,26 +84,38 @@ __global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, 
   const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
   const int64_t r1 = min(rows, r0 + rows_per_slab);
   if (active) {
-    for (int64_t r = r0 + rr; r < r1; r += rpp) {
-      const int64_t o = r * C + c0;
-      if (MODE == 0) {
-        float v[8]; V8<T>::load(x + o, v);
+    constexpr int U = 4;
+    for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
+      float xv[U][8], gv[U][8], ov[U][8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { a1[j] += v[j]; a2[j] += v[j] * v[j]; }
-      } else {
-        float g[8]; V8<T>::load(dout + o, g);
-        if (relu) {
-          float ov[8]; V8<T>::load(out + o, ov);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) if (!(ov[j] > 0.f)) g[j] = 0.f;
+      for (int u = 0; u < U; ++u) {
+        const int64_t r = rb + (int64_t)u * rpp;
+        const int64_t o = r * C + c0;
+        if (r < r1) {
+          if (MODE == 0 || MODE == 1) V8<T>::load(x + o, xv[u]);
+          if (MODE != 0) { V8<T>::load(dout + o, gv[u]); if (relu) V8<T>::load(out + o, ov[u]); }
         }
-        if (MODE == 1) {
-          float v[8]; V8<T>::load(x + o, v);
+      }
 #pragma unroll
-          for (int j = 0; j < 8; ++j) { a1[j] += g[j]; a2[j] += g[j] * ((v[j] - mu[j]) * rs[j]); }
-        } else {
+      for (int u = 0; u < U; ++u) {
+        const int64_t r = rb + (int64_t)u * rpp;
+        if (r < r1) {
+          if (MODE == 0) {
 #pragma unroll
-          for (int j = 0; j < 8; ++j) a1[j] += g[j];
+            for (int j = 0; j < 8; ++j) { a1[j] += xv[u][j]; a2[j] += xv[u][j] * xv[u][j]; }
+          } else {
+            if (relu) {
+#pragma unroll
+              for (int j = 0; j < 8; ++j) if (!(ov[u][j] > 0.f)) gv[u][j] = 0.f;
+            }
+            if (MODE == 1) {
+#pragma unroll
+              for (int j = 0; j < 8; ++j) { a1[j] += gv[u][j]; a2[j] += gv[u][j] * ((xv[u][j] - mu[j]) * rs[j]); }
+            } else {
+#pragma unroll
+              for (int j = 0; j < 8; ++j) a1[j] += gv[u][j];
+            }
+          }
         }
       }
     }
@@ -117,14 +135,23 @@ __global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, 
 }
 
 // MODE 0: mean / rstd.  MODE 1,2: sums[0..C) = s1, sums[C..2C) = s2 and optional scaled copies.
+// A workgroup owns 16 channels; 16 thread groups each sum every 16th slab in fp64, then the 16
+// group results are added in a fixed order.
 template <int MODE>
-__global__ void colfinal_kernel(const float* __restrict__ partial, int nslabs, int C, int64_t rows,
-                                float* __restrict__ o1, float* __restrict__ o2, float* __restrict__ e1,
-                                float* __restrict__ e2, float scale) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= C) return;
+__global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ partial, int nslabs, int C, int64_t rows,
+                                                      float* __restrict__ o1, float* __restrict__ o2, float* __restrict__ e1,
+                                                      float* __restrict__ e2, float scale) {
+  __shared__ double sh[2][16][16];
+  const int cl = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl;
   double s1 = 0.0, s2 = 0.0;
-  for (int s = 0; s < nslabs; ++s) { s1 += (double)partial[(int64_t)s * 2 * C + c]; s2 += (double)partial[(int64_t)s * 2 * C + C + c]; }
+  if (c < C)
+    for (int s = grp; s < nslabs; s += 16) { s1 += (double)partial[(int64_t)s * 2 * C + c]; s2 += (double)partial[(int64_t)s * 2 * C + C + c]; }
+  sh[0][grp][cl] = s1; sh[1][grp][cl] = s2;
+  __syncthreads();
+  if (grp != 0 || c >= C) return;
+  s1 = 0.0; s2 = 0.0;
+  for (int g = 0; g < 16; ++g) { s1 += sh[0][g][cl]; s2 += sh[1][g][cl]; }
   if (MODE == 0) {
     const double m = s1 / (double)rows;
     double var = s2 / (double)rows - m * m;
@@ -141,71 +168,98 @@ __global__ void colfinal_kernel(const float* __restrict__ partial, int nslabs, i
 
 template <typename T>
 __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, const T* __restrict__ res,
-                                                       T* __restrict__ out, int64_t nvec, int tpr,
+                                                       T* __restrict__ out, int64_t rows, int C, int tpr, int rpp,
+                                                       int64_t rows_per_slab,
                                                        const float* __restrict__ mean, const float* __restrict__ rstd,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        int relu) {
-  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
-  if (v >= nvec) return;
-  const int c0 = (int)(v % tpr) * 8;
-  float xv[8], mu[8], rs[8], ga[8], be[8], o[8];
-  V8<T>::load(x + v * 8, xv);
+  const int tid = threadIdx.x, rr = tid / tpr, cv = tid % tpr;
+  if (rr >= rpp) return;
+  const int c0 = cv * 8;
+  float mu[8], rs[8], ga[8], be[8];
   load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(beta + c0, be);
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
+  const int64_t r1 = min(rows, r0 + rows_per_slab);
+  constexpr int U = 4;
+  for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
+    float xv[U][8], rv[U][8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) o[j] = ga[j] * ((xv[j] - mu[j]) * rs[j]) + be[j];
-  if (res) {
-    float rv[8]; V8<T>::load(res + v * 8, rv);
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = rb + (int64_t)u * rpp;
+      if (r < r1) { V8<T>::load(x + r * C + c0, xv[u]); if (res) V8<T>::load(res + r * C + c0, rv[u]); }
+    }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] += rv[j];
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = rb + (int64_t)u * rpp;
+      if (r < r1) {
+        float o[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          o[j] = ga[j] * ((xv[u][j] - mu[j]) * rs[j]) + be[j];
+          if (res) o[j] += rv[u][j];
+          if (relu) o[j] = o[j] > 0.f ? o[j] : 0.f;
+        }
+        V8<T>::store(out + r * C + c0, o);
+      }
+    }
   }
-  if (relu) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = o[j] > 0.f ? o[j] : 0.f;
-  }
-  V8<T>::store(out + v * 8, o);
 }
 
 template <typename T>
 __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ out,
                                                              const T* __restrict__ dout, T* __restrict__ dx,
                                                              int dx_acc, T* __restrict__ dres, int dres_acc,
-                                                             int64_t nvec, int tpr, float inv_rows,
+                                                             int64_t rows, int C, int tpr, int rpp, int64_t rows_per_slab,
+                                                             float inv_rows,
                                                              const float* __restrict__ mean, const float* __restrict__ rstd,
                                                              const float* __restrict__ gamma, const float* __restrict__ sums,
-                                                             int C, int relu) {
-  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
-  if (v >= nvec) return;
-  const int c0 = (int)(v % tpr) * 8;
-  float g[8], xv[8], mu[8], rs[8], ga[8], s1[8], s2[8], r[8];
-  V8<T>::load(dout + v * 8, g);
-  if (relu) {
-    float ov[8]; V8<T>::load(out + v * 8, ov);
+                                                             int relu) {
+  const int tid = threadIdx.x, rr = tid / tpr, cv = tid % tpr;
+  if (rr >= rpp) return;
+  const int c0 = cv * 8;
+  float mu[8], rs[8], ga[8], s1[8], s2[8];
+  load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(sums + c0, s1); load8f(sums + C + c0, s2);
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
+  const int64_t r1 = min(rows, r0 + rows_per_slab);
+  constexpr int U = 2;
+  for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
+    float g[U][8], xv[U][8], ov[U][8], od[U][8], orr[U][8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) if (!(ov[j] > 0.f)) g[j] = 0.f;
-  }
-  if (dres) {
-    if (dres_acc) {
-      float old[8]; V8<T>::load(dres + v * 8, old);
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = rb + (int64_t)u * rpp;
+      if (r < r1) {
+        const int64_t o = r * C + c0;
+        V8<T>::load(dout + o, g[u]); V8<T>::load(x + o, xv[u]);
+        if (relu) V8<T>::load(out + o, ov[u]);
+        if (dx_acc) V8<T>::load(dx + o, od[u]);
+        if (dres && dres_acc) V8<T>::load(dres + o, orr[u]);
+      }
+    }
 #pragma unroll
-      for (int j = 0; j < 8; ++j) r[j] = old[j] + g[j];
-      V8<T>::store(dres + v * 8, r);
-    } else {
-      V8<T>::store(dres + v * 8, g);
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = rb + (int64_t)u * rpp;
+      if (r < r1) {
+        const int64_t o = r * C + c0;
+        float q[8];
+        if (relu) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) if (!(ov[u][j] > 0.f)) g[u][j] = 0.f;
+        }
+        if (dres) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) q[j] = dres_acc ? orr[u][j] + g[u][j] : g[u][j];
+          V8<T>::store(dres + o, q);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float xh = (xv[u][j] - mu[j]) * rs[j];
+          q[j] = ga[j] * rs[j] * (g[u][j] - s1[j] * inv_rows - xh * s2[j] * inv_rows);
+          if (dx_acc) q[j] += od[u][j];
+        }
+        V8<T>::store(dx + o, q);
+      }
     }
   }
-  V8<T>::load(x + v * 8, xv);
-  load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(sums + c0, s1); load8f(sums + C + c0, s2);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float xh = (xv[j] - mu[j]) * rs[j];
-    r[j] = ga[j] * rs[j] * (g[j] - s1[j] * inv_rows - xh * s2[j] * inv_rows);
-  }
-  if (dx_acc) {
-    float old[8]; V8<T>::load(dx + v * 8, old);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) r[j] += old[j];
-  }
-  V8<T>::store(dx + v * 8, r);
 }
 
 template <typename T>
@@ -453,7 +507,7 @@ inline unsigned nblk(int64_t n) { return (unsigned)((n + kT - 1) / kT); }
 template <typename T, int MODE>
 dat_status colreduce(const void* x, const void* out, const void* dout, const float* mean, const float* rstd, int relu,
                      int64_t rows, int C, float* partial, hipStream_t st, SlabPlan& p) {
-  p = plan_slabs(rows, C);
+  p = plan_slabs(rows, C, kMaxSlabs);
   hipLaunchKernelGGL((colreduce_kernel<T, MODE>), dim3(p.nslabs), dim3(kT), 0, st, (const T*)x, (const T*)out,
                      (const T*)dout, mean, rstd, relu, rows, C, p.tpr, p.rpp, p.rows_per_slab, partial);
   DAT_LAUNCH_CHECK();
@@ -472,7 +526,7 @@ dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partia
   DAT_BY_DTYPE(dtype, s = (colreduce<float, 0>(x, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)),
                s = (colreduce<bf16_t, 0>(x, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)));
   if (s != DAT_OK) return s;
-  hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 63) / 64), dim3(64), 0, st, partial, p.nslabs, C, rows, mean, rstd,
+  hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 15) / 16), dim3(kT), 0, st, partial, p.nslabs, C, rows, mean, rstd,
                      (float*)nullptr, (float*)nullptr, 1.0f);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
@@ -480,10 +534,11 @@ dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partia
 
 dat_status bnact_forward(const void* x, const void* res, void* out, int dtype, int64_t rows, int C, const float* mean,
                          const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st) {
-  const int64_t nvec = rows * (C / 8);
+  if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
+  const SlabPlan p = plan_slabs(rows, C, kMaxApplySlabs);
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (const float*)res, (float*)out, nvec, C / 8, mean, rstd, gamma, beta, relu),
-    hipLaunchKernelGGL(bnact_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)res, (bf16_t*)out, nvec, C / 8, mean, rstd, gamma, beta, relu));
+    hipLaunchKernelGGL(bnact_fwd_kernel<float>, dim3(p.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)res, (float*)out, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu),
+    hipLaunchKernelGGL(bnact_fwd_kernel<bf16_t>, dim3(p.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)res, (bf16_t*)out, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -497,14 +552,14 @@ dat_status bnact_backward(const void* x, const void* out, const void* dout, void
   DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)),
                s = (colreduce<bf16_t, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)));
   if (s != DAT_OK) return s;
-  hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 63) / 64), dim3(64), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
+  hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 15) / 16), dim3(kT), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
                      dbeta, dgamma, scale);
   DAT_LAUNCH_CHECK();
-  const int64_t nvec = rows * (C / 8);
   const float inv_rows = (float)(1.0 / (double)rows);
+  const SlabPlan q = plan_slabs(rows, C, kMaxApplySlabs);
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (const float*)out, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, nvec, C / 8, inv_rows, mean, rstd, gamma, sums, C, relu),
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, nvec, C / 8, inv_rows, mean, rstd, gamma, sums, C, relu));
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, inv_rows, mean, rstd, gamma, sums, relu),
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, inv_rows, mean, rstd, gamma, sums, relu));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -526,7 +581,7 @@ dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx
     DAT_BY_DTYPE(dtype, s = (colreduce<float, 2>(nullptr, out, dout, nullptr, nullptr, relu, rows, C, partial, st, p)),
                  s = (colreduce<bf16_t, 2>(nullptr, out, dout, nullptr, nullptr, relu, rows, C, partial, st, p)));
     if (s != DAT_OK) return s;
-    hipLaunchKernelGGL(colfinal_kernel<2>, dim3((C + 63) / 64), dim3(64), 0, st, partial, p.nslabs, C, rows, dbias,
+    hipLaunchKernelGGL(colfinal_kernel<2>, dim3((C + 15) / 16), dim3(kT), 0, st, partial, p.nslabs, C, rows, dbias,
                        (float*)nullptr, dbias, (float*)nullptr, scale);
     DAT_LAUNCH_CHECK();
   }

@@ -279,7 +279,7 @@ dat_status refresh_compute(dat_model& m, hipStream_t st) {
   for (Op& op : m.ops) {
     if (op.kind == OP_CONV)
       DAT_TRY(launch_weight_transform(m.master + m.ptab[op.p0].off, op.w16, op.w16T, m.tens[op.out].C, op.k, op.cin_real,
-                                      m.tens[op.in].C, st));
+                                      m.tens[op.in].C, op.stride, op.pad, st));
     if (op.kind == OP_FC)
       DAT_TRY(launch_round_bf16_values(m.master + m.ptab[op.p0].off, m.compute + m.ptab[op.p0].off, m.ptab[op.p0].numel, st));
   }

@@ -23,6 +23,10 @@ SHAPES = [
     (2, 8, 8, 8, 16, 3, 1, 1),         # CIFAR stem
     (1, 6, 6, 160, 320, 3, 2, 1),      # wide-ResNet widths
     (5, 12, 12, 32, 40, 3, 1, 1),      # several pixel tiles + ragged channel tile
+    (2, 9, 7, 16, 32, 3, 2, 1),        # stride 2 on odd sizes (parity classes of unequal size)
+    (2, 15, 13, 8, 64, 7, 2, 3),       # stem on odd sizes
+    (2, 7, 9, 64, 128, 1, 2, 0),       # 1x1 stride 2: three parity classes receive zeros
+    (3, 16, 16, 128, 128, 3, 1, 1),    # full 128x128 tiles
 ]
 
 
