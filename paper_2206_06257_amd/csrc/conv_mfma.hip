@@ -37,9 +37,19 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kThreads = 256;
 constexpr int BK = 32;                 // k per LDS tile (two MFMA k-steps)
 
-union Frag { uint4 u; bf16x8 v; };
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte vector (stays in registers)
+union Frag { u32x4 u; bf16x8 v; };
 
-__device__ __forceinline__ int swz(int row, int slot) { return row * 64 + ((slot ^ ((row >> 1) & 3)) << 4); }
+// 16-byte slot permutation of a [row][4 slots] tile with 64-byte rows.  Chosen so that both any 8
+// consecutive rows (one 128-byte bank sweep) and any 16 consecutive rows (a 256-byte sweep) reading
+// the same logical slot touch distinct 16-byte bank groups.
+__device__ __forceinline__ int swz(int row, int slot) {
+  const int f = (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1);
+  return row * 64 + ((slot ^ f) << 4);
+}
+
+// Out-of-range and padding vectors are read from this zero page instead of being masked.
+__device__ __attribute__((aligned(16))) uint32_t g_zero_page[4] = {0u, 0u, 0u, 0u};
 
 struct IgemmArgs {
   const bf16_t* in;     // [B][Hin][Win][Cin]
@@ -61,7 +71,7 @@ __device__ __forceinline__ int64_t out_row(const IgemmArgs& a, int m) {
   return ((int64_t)n * a.outH + ya * a.ostep + a.oh0) * a.outW + xb * a.ostep + a.ow0;
 }
 
-template <int TC, int TP, int WGC>
+template <int TC, int TP, int WGC, int PF, bool FAST>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   constexpr int WGP = 4 / WGC;                     // waves along channels x waves along pixels
   constexpr int WC = TC / WGC, WP = TP / WGP;      // wave tile
@@ -84,8 +94,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   const int wc = wave % WGC, wp = wave / WGC;
   const int kvec = tid & 3, lrow = tid >> 2;       // this thread's slot in the global->LDS copy
 
-  // im2col row state for the activation vectors this thread fetches
-  int hb[VX], wb[VX]; int64_t nb[VX]; bool mv[VX];
+  // im2col row state for the activation vectors this thread fetches (32-bit element offsets)
+  int hb[VX], wb[VX], nb[VX]; bool mv[VX];
   const int HW = a.Hout * a.Wout;
 #pragma unroll
   for (int i = 0; i < VX; ++i) {
@@ -95,44 +105,96 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     const int n = mm / HW, rem = mm - n * HW;
     const int ho = rem / a.Wout, wo = rem - ho * a.Wout;
     hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * a.ostride - a.pad_w;
-    nb[i] = (int64_t)n * a.Hin * a.Win;
+    nb[i] = n * a.Hin * a.Win;
   }
-  // (r, s, c) of this thread's k-slot, advanced by BK per tile
-  int kc, kr, ks;
+  const int ntiles = (a.Ktot + BK - 1) / BK;
+  const u32x4* zero_page = reinterpret_cast<const u32x4*>(g_zero_page);
+
+  // Weight rows of this thread: offset of (row, k = kvec*8) and row validity; advances by BK per tile.
+  int woff[VW]; bool wrow[VW];
+#pragma unroll
+  for (int i = 0; i < VW; ++i) {
+    const int c = c0 + lrow + 64 * i;
+    wrow[i] = (lrow + 64 * i < TC) & (c < a.Cout);
+    woff[i] = (wrow[i] ? c : 0) * a.Ktot + kvec * 8;
+  }
+  // Activation state.  FAST (Cin % 32 == 0): a k-tile never straddles a filter tap, so the tap
+  // (r,s), the bounds test and the pixel offset change only every Cin/32 tiles (a uniform branch);
+  // in between the offset just advances by 32 channels.  Otherwise every vector decodes its own tap.
+  int xoff[VX]; bool xok[VX];
+  int kc0 = 0, kr = 0, ks = 0;                      // FAST: channel offset of the tile, current tap
+  int kc, gr, gs;                                   // generic: this thread's channel / tap
   {
     const int k = kvec * 8;
     const int tap = k / a.Cin;
-    kc = k - tap * a.Cin; kr = tap / a.KW; ks = tap - kr * a.KW;
+    kc = k - tap * a.Cin; gr = tap / a.KW; gs = tap - gr * a.KW;
   }
-  const int ntiles = (a.Ktot + BK - 1) / BK;
-
-  uint4 gw[VW], gx[VX];
-  auto fetch = [&](int kt) {
-    const int k = kt * BK + kvec * 8;
-    const bool kvalid = k < a.Ktot;
-#pragma unroll
-    for (int i = 0; i < VW; ++i) {
-      const int c = c0 + lrow + 64 * i;
-      gw[i] = (kvalid && lrow + 64 * i < TC && c < a.Cout) ? *reinterpret_cast<const uint4*>(a.wt + (int64_t)c * a.Ktot + k) : make_uint4(0, 0, 0, 0);
-    }
+  auto retap = [&](int r, int s_, int cofs) {
 #pragma unroll
     for (int i = 0; i < VX; ++i) {
-      const int hi = hb[i] + kr, wi = wb[i] + ks;
-      const bool ok = kvalid && mv[i] && hi >= 0 && wi >= 0 && hi < a.Hin && wi < a.Win;
-      gx[i] = ok ? *reinterpret_cast<const uint4*>(a.in + ((nb[i] + (int64_t)hi * a.Win + wi) * a.Cin + kc)) : make_uint4(0, 0, 0, 0);
+      const int hi = hb[i] + r, wi = wb[i] + s_;
+      xok[i] = mv[i] & (hi >= 0) & (wi >= 0) & (hi < a.Hin) & (wi < a.Win);
+      xoff[i] = (nb[i] + hi * a.Win + wi) * a.Cin + cofs;
     }
-    // advance (r,s,c) to the next tile
-    kc += BK;
-    while (kc >= a.Cin) { kc -= a.Cin; if (++ks == a.KW) { ks = 0; ++kr; } }
   };
-  auto stash = [&](int buf) {
-    unsigned char* wbase = lds + buf * TILE_BYTES;
-    unsigned char* xbase = wbase + TC * 64;
+
+  // Global loads run PF tiles ahead of the MFMAs: tile t+1 sits in LDS (other buffer) while tiles
+  // t+2 .. t+1+PF are in flight into PF register sets.  Every step issues the same number of
+  // unconditional loads (invalid vectors read the zero page), so nothing waits on a load early.
+  struct RegSet { u32x4 w[VW]; u32x4 x[VX]; };
+  RegSet rs[PF];
+  int kf = 0;                                      // next tile to fetch
+  auto fetch = [&](RegSet& r) {
+    const bool tile_ok = kf < ntiles;
 #pragma unroll
-    for (int i = 0; i < VW; ++i) if (lrow + 64 * i < TC) *reinterpret_cast<uint4*>(wbase + swz(lrow + 64 * i, kvec)) = gw[i];
+    for (int i = 0; i < VW; ++i) {
+      const bool ok = tile_ok & wrow[i] & (FAST || kf * BK + kvec * 8 < a.Ktot);
+      const u32x4* p = ok ? reinterpret_cast<const u32x4*>(a.wt + woff[i]) : zero_page;
+      r.w[i] = *p;
+      woff[i] += BK;
+    }
+    if (FAST) {
+      if (kc0 == 0) retap(kr, ks, kvec * 8);       // uniform: first tile of a tap
 #pragma unroll
-    for (int i = 0; i < VX; ++i) *reinterpret_cast<uint4*>(xbase + swz(lrow + 64 * i, kvec)) = gx[i];
+      for (int i = 0; i < VX; ++i) {
+        const u32x4* p = (tile_ok & xok[i]) ? reinterpret_cast<const u32x4*>(a.in + xoff[i]) : zero_page;
+        r.x[i] = *p;
+        xoff[i] += BK;
+      }
+      kc0 += BK;
+      if (kc0 == a.Cin) { kc0 = 0; if (++ks == a.KW) { ks = 0; ++kr; } }
+    } else {
+      retap(gr, gs, kc);
+      const bool kvalid = tile_ok & (kf * BK + kvec * 8 < a.Ktot);
+#pragma unroll
+      for (int i = 0; i < VX; ++i) {
+        const u32x4* p = (kvalid & xok[i]) ? reinterpret_cast<const u32x4*>(a.in + xoff[i]) : zero_page;
+        r.x[i] = *p;
+      }
+      kc += BK;
+      while (kc >= a.Cin) { kc -= a.Cin; if (++gs == a.KW) { gs = 0; ++gr; } }
+    }
+    ++kf;
   };
+  const int st_w = swz(lrow, kvec), st_x = TC * 64 + swz(lrow, kvec);   // rows lrow + 64*i share the swizzle (64 % 16 == 0)
+  auto stash = [&](int buf, const RegSet& r) {
+    unsigned char* base = lds + buf * TILE_BYTES;
+#pragma unroll
+    for (int i = 0; i < VW; ++i)
+      if (lrow + 64 * i < TC) *reinterpret_cast<u32x4*>(base + st_w + i * 4096) = r.w[i];
+#pragma unroll
+    for (int i = 0; i < VX; ++i) *reinterpret_cast<u32x4*>(base + st_x + i * 4096) = r.x[i];
+  };
+  // fragment read offsets (bytes inside a tile) for kk = 0, 1
+  int fa_off[2][NI], fb_off[2][NJ];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    const int slot = kk * 2 + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) fa_off[kk][i] = swz(wc * WC + i * 32 + (lane & 31), slot);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) fb_off[kk][j] = TC * 64 + swz(wp * WP + j * 32 + (lane & 31), slot);
+  }
 
   f32x16 acc[NI][NJ];
 #pragma unroll
@@ -142,46 +204,59 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  fetch(0);
-  stash(0);
+  fetch(rs[0]);
+  stash(0, rs[0]);
+#pragma unroll
+  for (int p = 0; p < PF; ++p) fetch(rs[p]);
   __syncthreads();
-  for (int kt = 0; kt < ntiles; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < ntiles) fetch(kt + 1);
-    const unsigned char* wbase = lds + buf * TILE_BYTES;
-    const unsigned char* xbase = wbase + TC * 64;
+  auto step = [&](int t, RegSet& r) {
+    const unsigned char* base = lds + (t & 1) * TILE_BYTES;
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
       Frag fa[NI], fb[NJ];
-      const int slot = kk * 2 + (lane >> 5);
 #pragma unroll
-      for (int i = 0; i < NI; ++i) fa[i].u = *reinterpret_cast<const uint4*>(wbase + swz(wc * WC + i * 32 + (lane & 31), slot));
+      for (int i = 0; i < NI; ++i) fa[i].u = *reinterpret_cast<const u32x4*>(base + fa_off[kk][i]);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) fb[j].u = *reinterpret_cast<const uint4*>(xbase + swz(wp * WP + j * 32 + (lane & 31), slot));
+      for (int j = 0; j < NJ; ++j) fb[j].u = *reinterpret_cast<const u32x4*>(base + fb_off[kk][j]);
 #pragma unroll
       for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < ntiles) stash(buf ^ 1);
+    stash((t + 1) & 1, r);     // this register set holds tile t+1 (all zero past the end)
+    fetch(r);                  // ... and now receives tile t+1+PF
     __syncthreads();
+  };
+  // main loop: whole groups of PF steps, no conditionals, so that the number of loads in flight
+  // is the same on every path; then at most PF-1 guarded tail steps
+  int kt = 0;
+  for (; kt + PF <= ntiles; kt += PF) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) step(kt + u, rs[u]);
   }
+#pragma unroll
+  for (int u = 0; u < PF - 1; ++u)
+    if (kt + u < ntiles) step(kt + u, rs[u]);
 
   // ---- epilogue: (+res) -> bf16 -> LDS transpose -> 16-byte stores -------------------------
-  // accumulator element e of lane l in tile (i,j): channel = 8*(e/4) + 4*(l/32) + e%4, pixel = l%32
+  // accumulator element e of lane l in tile (i,j): channel = 8*(e/4) + 4*(l/32) + e%4, pixel = l%32.
+  // All four waves stage their block at once (one barrier), then every thread streams 16-byte
+  // channel vectors of whole pixel rows to global memory.
 #pragma unroll
   for (int i = 0; i < NI; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int prow = wp * WP + j * 32 + (lane & 31);
       const int m = m0 + prow;
+      int64_t orow = 0;
+      if (a.res && m < a.M) orow = out_row(a, m);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int ch = wc * WC + i * 32 + 8 * g + 4 * (lane >> 5);
         float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
         if (a.res && m < a.M && c0 + ch < a.Cout) {
-          const uint2 r = *reinterpret_cast<const uint2*>(a.res + out_row(a, m) * a.Cout + c0 + ch);
+          const uint2 r = *reinterpret_cast<const uint2*>(a.res + orow * a.Cout + c0 + ch);
           v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xffff0000u);
           v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xffff0000u);
         }
@@ -193,11 +268,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     }
   __syncthreads();
   constexpr int CV = TC / 8;                       // channel vectors per pixel row
-  constexpr int RPP = kThreads / CV;               // pixel rows per pass
+  constexpr int RPP = kThreads / CV;               // pixel rows per store sweep
   const int cv = tid % CV, pr0 = tid / CV;
 #pragma unroll
-  for (int i = 0; i < TP / RPP; ++i) {
-    const int prow = pr0 + i * RPP;
+  for (int prow = pr0; prow < TP; prow += RPP) {
     const int m = m0 + prow, ch = c0 + cv * 8;
     if (m < a.M && ch < a.Cout)
       *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
@@ -209,22 +283,29 @@ __global__ void widen_kernel(const bf16_t* __restrict__ src, float* __restrict__
   if (i < n) dst[i] = bf2f(src[i]);
 }
 
-template <int TC, int TP, int WGC>
+template <int TC, int TP, int WGC, int PF>
 dat_status launch_igemm(IgemmArgs a, hipStream_t st) {
+  // 32-bit element offsets inside the kernel
+  if ((int64_t)a.B * a.Hin * a.Win * a.Cin >= (1ll << 31) || (int64_t)a.Cout * a.Ktot >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;
   a.nct = (a.Cout + TC - 1) / TC;
   a.npt = (a.M + TP - 1) / TP;
   if (a.npt == 0) return DAT_OK;
   const int npt8 = (a.npt + 7) / 8 * 8;
-  hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
+  if (a.Cin % 32 == 0 && a.Ktot > 0)
+    hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC, PF, true>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC, PF, false>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
 
 dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
   if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
-  if (a.Cout <= 32) return launch_igemm<32, 128, 1>(a, st);
-  if (a.Cout <= 64) return launch_igemm<64, 128, 2>(a, st);
-  return launch_igemm<128, 128, 2>(a, st);
+  // short contractions (1x1 layers with few input channels) gain nothing from deep prefetch
+  const bool shallow = (a.Ktot + BK - 1) / BK <= 4;
+  if (a.Cout <= 32) return shallow ? launch_igemm<32, 128, 1, 1>(a, st) : launch_igemm<32, 128, 1, 3>(a, st);
+  if (a.Cout <= 64) return shallow ? launch_igemm<64, 128, 2, 1>(a, st) : launch_igemm<64, 128, 2, 3>(a, st);
+  return shallow ? launch_igemm<128, 128, 2, 1>(a, st) : launch_igemm<128, 128, 2, 3>(a, st);
 }
 
 // ---- weight layouts ---------------------------------------------------------------------------
@@ -383,9 +464,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
       Frag fa[NI], fb[NJ];
       const int slot = kk * 2 + (lane >> 5);
 #pragma unroll
-      for (int i = 0; i < NI; ++i) fa[i].u = *reinterpret_cast<const uint4*>(abase + swz128(wc * WC + i * 32 + (lane & 31), slot));
+      for (int i = 0; i < NI; ++i) fa[i].u = *reinterpret_cast<const u32x4*>(abase + swz128(wc * WC + i * 32 + (lane & 31), slot));
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) fb[j].u = *reinterpret_cast<const uint4*>(bbase + swz128(wj * WJ + j * 32 + (lane & 31), slot));
+      for (int j = 0; j < NJ; ++j) fb[j].u = *reinterpret_cast<const u32x4*>(bbase + swz128(wj * WJ + j * 32 + (lane & 31), slot));
 #pragma unroll
       for (int i = 0; i < NI; ++i)
 #pragma unroll

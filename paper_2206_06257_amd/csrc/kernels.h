@@ -69,8 +69,9 @@ dat_status bnact_backward(const void* x, const void* out, const void* dout, void
 dat_status biasact_forward(const void* x, void* out, int dtype, int64_t rows, int C, const float* bias, int relu, hipStream_t st);
 dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx_accumulate, int dtype, int64_t rows, int C,
                             int relu, float* partial, float* dbias, float scale, hipStream_t st);
-dat_status maxpool_forward(const void* x, void* out, int dtype, int B, int H, int W, int C, int Ho, int Wo, hipStream_t st);
-dat_status maxpool_backward(const void* x, const void* dout, void* dx, bool accumulate, int dtype, int B, int H, int W, int C,
+// arg: one byte per output element, the window position (3*r+s) of the first maximum.
+dat_status maxpool_forward(const void* x, void* out, uint8_t* arg, int dtype, int B, int H, int W, int C, int Ho, int Wo, hipStream_t st);
+dat_status maxpool_backward(const uint8_t* arg, const void* dout, void* dx, bool accumulate, int dtype, int B, int H, int W, int C,
                             int Ho, int Wo, hipStream_t st);
 // pooled[B][C] fp32 = mean over the HW pixels;  backward: dx (+)= dpooled/HW.
 dat_status gap_forward(const void* x, float* pooled, int dtype, int B, int HW, int C, hipStream_t st);

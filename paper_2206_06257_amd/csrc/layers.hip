@@ -135,23 +135,32 @@ __global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, 
 }
 
 // MODE 0: mean / rstd.  MODE 1,2: sums[0..C) = s1, sums[C..2C) = s2 and optional scaled copies.
-// A workgroup owns 16 channels; 16 thread groups each sum every 16th slab in fp64, then the 16
-// group results are added in a fixed order.
+// A workgroup owns 8 channels; 32 thread groups each sum every 32nd slab in fp64 (four loads in
+// flight), then the 32 group results are added in a fixed order.
 template <int MODE>
 __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ partial, int nslabs, int C, int64_t rows,
                                                       float* __restrict__ o1, float* __restrict__ o2, float* __restrict__ e1,
                                                       float* __restrict__ e2, float scale) {
-  __shared__ double sh[2][16][16];
-  const int cl = threadIdx.x & 15, grp = threadIdx.x >> 4;
-  const int c = blockIdx.x * 16 + cl;
+  __shared__ double sh[2][32][8];
+  const int cl = threadIdx.x & 7, grp = threadIdx.x >> 3;
+  const int c = blockIdx.x * 8 + cl;
   double s1 = 0.0, s2 = 0.0;
-  if (c < C)
-    for (int s = grp; s < nslabs; s += 16) { s1 += (double)partial[(int64_t)s * 2 * C + c]; s2 += (double)partial[(int64_t)s * 2 * C + C + c]; }
+  if (c < C) {
+    int s = grp;
+    for (; s + 96 < nslabs; s += 128) {
+      float a[4], b[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { a[u] = partial[(int64_t)(s + 32 * u) * 2 * C + c]; b[u] = partial[(int64_t)(s + 32 * u) * 2 * C + C + c]; }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { s1 += (double)a[u]; s2 += (double)b[u]; }
+    }
+    for (; s < nslabs; s += 32) { s1 += (double)partial[(int64_t)s * 2 * C + c]; s2 += (double)partial[(int64_t)s * 2 * C + C + c]; }
+  }
   sh[0][grp][cl] = s1; sh[1][grp][cl] = s2;
   __syncthreads();
   if (grp != 0 || c >= C) return;
   s1 = 0.0; s2 = 0.0;
-  for (int g = 0; g < 16; ++g) { s1 += sh[0][g][cl]; s2 += sh[1][g][cl]; }
+  for (int g = 0; g < 32; ++g) { s1 += sh[0][g][cl]; s2 += sh[1][g][cl]; }
   if (MODE == 0) {
     const double m = s1 / (double)rows;
     double var = s2 / (double)rows - m * m;
@@ -294,10 +303,11 @@ __global__ __launch_bounds__(kT) void biasact_bwd_kernel(const T* __restrict__ o
   V8<T>::store(dx + v * 8, g);
 }
 
-// 3x3 window, stride 2, padding 1.
+// 3x3 window, stride 2, padding 1.  The forward pass also records, per output element, which of
+// the nine window positions (3*r+s) holds the FIRST maximum in row-major order.
 template <typename T>
-__global__ __launch_bounds__(kT) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ out, int B, int H,
-                                                         int W, int C, int Ho, int Wo) {
+__global__ __launch_bounds__(kT) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ out,
+                                                         uint8_t* __restrict__ arg, int B, int H, int W, int C, int Ho, int Wo) {
   const int tpr = C / 8;
   const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (v >= (int64_t)B * Ho * Wo * tpr) return;
@@ -306,9 +316,9 @@ __global__ __launch_bounds__(kT) void maxpool_fwd_kernel(const T* __restrict__ x
   const int wo = (int)(p % Wo); p /= Wo;
   const int ho = (int)(p % Ho);
   const int n = (int)(p / Ho);
-  float best[8];
+  float best[8]; uint32_t pos[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) best[j] = -__builtin_inff();
+  for (int j = 0; j < 8; ++j) { best[j] = -__builtin_inff(); pos[j] = 0; }
   for (int r = 0; r < 3; ++r) {
     const int hi = ho * 2 + r - 1;
     if (hi < 0 || hi >= H) continue;
@@ -317,16 +327,20 @@ __global__ __launch_bounds__(kT) void maxpool_fwd_kernel(const T* __restrict__ x
       if (wi < 0 || wi >= W) continue;
       float xv[8]; V8<T>::load(x + (((int64_t)n * H + hi) * W + wi) * C + cv * 8, xv);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) if (xv[j] > best[j]) best[j] = xv[j];
+      for (int j = 0; j < 8; ++j) if (xv[j] > best[j]) { best[j] = xv[j]; pos[j] = 3 * r + s; }
     }
   }
   V8<T>::store(out + v * 8, best);
+  uint2 pk;
+  pk.x = pos[0] | (pos[1] << 8) | (pos[2] << 16) | (pos[3] << 24);
+  pk.y = pos[4] | (pos[5] << 8) | (pos[6] << 16) | (pos[7] << 24);
+  *reinterpret_cast<uint2*>(arg + v * 8) = pk;
 }
 
-// Gather form: an input pixel receives the gradient of every window whose FIRST maximum (in
-// row-major window order) it is; contributions are summed in fp32 and stored once.
+// Gather form: an input pixel receives the gradient of every window (at most four) whose recorded
+// arg-max position it is; contributions are summed in fp32 and stored once.
 template <typename T>
-__global__ __launch_bounds__(kT) void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dout,
+__global__ __launch_bounds__(kT) void maxpool_bwd_kernel(const uint8_t* __restrict__ arg, const T* __restrict__ dout,
                                                          T* __restrict__ dx, int acc, int B, int H, int W, int C,
                                                          int Ho, int Wo) {
   const int tpr = C / 8;
@@ -340,29 +354,21 @@ __global__ __launch_bounds__(kT) void maxpool_bwd_kernel(const T* __restrict__ x
   float sum[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) sum[j] = 0.f;
-  const int ho_lo = max(0, (h) / 2), ho_hi = min(Ho - 1, (h + 1) / 2);
-  const int wo_lo = max(0, (w) / 2), wo_hi = min(Wo - 1, (w + 1) / 2);
+  const int ho_lo = h / 2, ho_hi = min(Ho - 1, (h + 1) / 2);
+  const int wo_lo = w / 2, wo_hi = min(Wo - 1, (w + 1) / 2);
   for (int ho = ho_lo; ho <= ho_hi; ++ho)
     for (int wo = wo_lo; wo <= wo_hi; ++wo) {
-      // is (h,w) inside this window?  rows ho*2-1 .. ho*2+1
-      if (h < ho * 2 - 1 || h > ho * 2 + 1 || w < wo * 2 - 1 || w > wo * 2 + 1) continue;
-      float best[8]; int arg[8];
+      const int r = h - (ho * 2 - 1), s = w - (wo * 2 - 1);
+      if (r < 0 || r > 2 || s < 0 || s > 2) continue;
+      const uint32_t me = 3 * r + s;
+      const int64_t o = (((int64_t)n * Ho + ho) * Wo + wo) * C + cv * 8;
+      const uint2 pk = *reinterpret_cast<const uint2*>(arg + o);
+      float g[8]; V8<T>::load(dout + o, g);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { best[j] = -__builtin_inff(); arg[j] = -1; }
-      for (int r = 0; r < 3; ++r) {
-        const int hi = ho * 2 + r - 1;
-        if (hi < 0 || hi >= H) continue;
-        for (int s = 0; s < 3; ++s) {
-          const int wi = wo * 2 + s - 1;
-          if (wi < 0 || wi >= W) continue;
-          float xv[8]; V8<T>::load(x + (((int64_t)n * H + hi) * W + wi) * C + cv * 8, xv);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) if (xv[j] > best[j]) { best[j] = xv[j]; arg[j] = hi * W + wi; }
-        }
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t pj = ((j < 4 ? pk.x : pk.y) >> (8 * (j & 3))) & 0xffu;
+        if (pj == me) sum[j] += g[j];
       }
-      float g[8]; V8<T>::load(dout + (((int64_t)n * Ho + ho) * Wo + wo) * C + cv * 8, g);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) if (arg[j] == h * W + w) sum[j] += g[j];
     }
   if (acc) {
     float old[8]; V8<T>::load(dx + v * 8, old);
@@ -526,7 +532,7 @@ dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partia
   DAT_BY_DTYPE(dtype, s = (colreduce<float, 0>(x, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)),
                s = (colreduce<bf16_t, 0>(x, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)));
   if (s != DAT_OK) return s;
-  hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 15) / 16), dim3(kT), 0, st, partial, p.nslabs, C, rows, mean, rstd,
+  hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, mean, rstd,
                      (float*)nullptr, (float*)nullptr, 1.0f);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
@@ -552,7 +558,7 @@ dat_status bnact_backward(const void* x, const void* out, const void* dout, void
   DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)),
                s = (colreduce<bf16_t, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)));
   if (s != DAT_OK) return s;
-  hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 15) / 16), dim3(kT), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
+  hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
                      dbeta, dgamma, scale);
   DAT_LAUNCH_CHECK();
   const float inv_rows = (float)(1.0 / (double)rows);
@@ -581,7 +587,7 @@ dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx
     DAT_BY_DTYPE(dtype, s = (colreduce<float, 2>(nullptr, out, dout, nullptr, nullptr, relu, rows, C, partial, st, p)),
                  s = (colreduce<bf16_t, 2>(nullptr, out, dout, nullptr, nullptr, relu, rows, C, partial, st, p)));
     if (s != DAT_OK) return s;
-    hipLaunchKernelGGL(colfinal_kernel<2>, dim3((C + 15) / 16), dim3(kT), 0, st, partial, p.nslabs, C, rows, dbias,
+    hipLaunchKernelGGL(colfinal_kernel<2>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, dbias,
                        (float*)nullptr, dbias, (float*)nullptr, scale);
     DAT_LAUNCH_CHECK();
   }
@@ -593,21 +599,21 @@ dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx
   return DAT_OK;
 }
 
-dat_status maxpool_forward(const void* x, void* out, int dtype, int B, int H, int W, int C, int Ho, int Wo, hipStream_t st) {
+dat_status maxpool_forward(const void* x, void* out, uint8_t* arg, int dtype, int B, int H, int W, int C, int Ho, int Wo, hipStream_t st) {
   const int64_t nvec = (int64_t)B * Ho * Wo * (C / 8);
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(maxpool_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (float*)out, B, H, W, C, Ho, Wo),
-    hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (bf16_t*)out, B, H, W, C, Ho, Wo));
+    hipLaunchKernelGGL(maxpool_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (float*)out, arg, B, H, W, C, Ho, Wo),
+    hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (bf16_t*)out, arg, B, H, W, C, Ho, Wo));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
 
-dat_status maxpool_backward(const void* x, const void* dout, void* dx, bool accumulate, int dtype, int B, int H, int W, int C,
+dat_status maxpool_backward(const uint8_t* arg, const void* dout, void* dx, bool accumulate, int dtype, int B, int H, int W, int C,
                             int Ho, int Wo, hipStream_t st) {
   const int64_t nvec = (int64_t)B * H * W * (C / 8);
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(maxpool_bwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (const float*)dout, (float*)dx, (int)accumulate, B, H, W, C, Ho, Wo),
-    hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)dout, (bf16_t*)dx, (int)accumulate, B, H, W, C, Ho, Wo));
+    hipLaunchKernelGGL(maxpool_bwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, arg, (const float*)dout, (float*)dx, (int)accumulate, B, H, W, C, Ho, Wo),
+    hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, arg, (const bf16_t*)dout, (bf16_t*)dx, (int)accumulate, B, H, W, C, Ho, Wo));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }

@@ -29,6 +29,7 @@ struct Op {
   bf16_t* w16 = nullptr;        // conv, bf16 model: [Cout][k][k][Cin_padded]
   bf16_t* w16T = nullptr;       //   and the flipped transpose used by backward-data
   float* mean = nullptr;        // BN batch statistics of the last forward
+  uint8_t* argmax = nullptr;    // max-pool: window position of the maximum, per output element
   float* rstd = nullptr;
 };
 
@@ -246,6 +247,7 @@ dat_status allocate(dat_model& m) {
       DAT_TRY(dev_alloc(m, &op.mean, (size_t)m.tens[op.in].C * 4));
       DAT_TRY(dev_alloc(m, &op.rstd, (size_t)m.tens[op.in].C * 4));
     }
+    if (op.kind == OP_MAXPOOL) DAT_TRY(dev_alloc(m, &op.argmax, (size_t)m.maxB * m.tens[op.out].numel()));
     if (op.kind == OP_CONV && m.dtype == DAT_BF16) {
       const size_t n = (size_t)m.tens[op.out].C * op.k * op.k * m.tens[op.in].C;
       DAT_TRY(dev_alloc(m, &op.w16, n * 2));
@@ -321,7 +323,7 @@ dat_status forward(dat_model& m, int B, hipStream_t st) {
                  bn_forward_pair(m, op, rows_in, si.C, st));
         break;
       case OP_MAXPOOL:
-        DAT_TRY(maxpool_forward(m.act[op.in], m.act[op.out], dt, B, si.H, si.W, si.C, so.H, so.W, st));
+        DAT_TRY(maxpool_forward(m.act[op.in], m.act[op.out], op.argmax, dt, B, si.H, si.W, si.C, so.H, so.W, st));
         break;
       case OP_GAP:
         DAT_TRY(gap_forward(m.act[op.in], (float*)m.act[op.out], dt, B, si.H * si.W, si.C, st));
@@ -387,7 +389,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         break;
       }
       case OP_MAXPOOL:
-        DAT_TRY(maxpool_backward(m.act[op.in], m.grad[op.out], m.grad[op.in], m.ghas[op.in], dt, B, si.H, si.W, si.C, so.H, so.W, st));
+        DAT_TRY(maxpool_backward(op.argmax, m.grad[op.out], m.grad[op.in], m.ghas[op.in], dt, B, si.H, si.W, si.C, so.H, so.W, st));
         m.ghas[op.in] = 1;
         break;
       case OP_GAP:
