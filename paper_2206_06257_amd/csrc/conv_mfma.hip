@@ -35,17 +35,23 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kThreads = 256;
-constexpr int BK = 32;                 // k per LDS tile (two MFMA k-steps)
+
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte vector (stays in registers)
 union Frag { u32x4 u; bf16x8 v; };
 
-// 16-byte slot permutation of a [row][4 slots] tile with 64-byte rows.  Chosen so that both any 8
-// consecutive rows (one 128-byte bank sweep) and any 16 consecutive rows (a 256-byte sweep) reading
-// the same logical slot touch distinct 16-byte bank groups.
-__device__ __forceinline__ int swz(int row, int slot) {
+// 16-byte slot permutation of a [row][NS slots] LDS tile (NS = 4: 64-byte rows, NS = 8: 128-byte
+// rows).  Chosen so that the lanes of a fragment read (consecutive rows, same logical slot) touch
+// distinct 16-byte bank groups both within any 8 consecutive rows x 128 bytes and within any 16
+// consecutive rows x 256 bytes (LDS bank sweeps of 32 and of 64 banks).  Uses row bits 0..3 only.
+template <int NS> __device__ __forceinline__ int swz(int row, int slot);
+template <> __device__ __forceinline__ int swz<4>(int row, int slot) {
   const int f = (((row >> 2) & 1) << 1) | (((row >> 1) ^ (row >> 3)) & 1);
   return row * 64 + ((slot ^ f) << 4);
+}
+template <> __device__ __forceinline__ int swz<8>(int row, int slot) {
+  const int f = (row & 7) ^ ((row >> 3) & 1);
+  return row * 128 + ((slot ^ f) << 4);
 }
 
 // Out-of-range and padding vectors are read from this zero page instead of being masked.
@@ -61,6 +67,11 @@ struct IgemmArgs {
   // output pixel (n, a, b) is stored at row (n*outH + a*ostep + oh0)*outW + b*ostep + ow0 of `out`
   int outH, outW, ostep, oh0, ow0;
   int M, Ktot, nct, npt;
+  // Optional per-channel sums (sum v, sum v^2) of the stored (bf16-rounded) outputs -- the batch
+  // statistics of the normalisation that follows -- one [2][Cout] slab per pixel tile at
+  // stat_partial + (stat_slab0 + pixel_tile) * 2 * Cout.
+  int stat_mode, stat_slab0;
+  float* stat_partial;
 };
 
 __device__ __forceinline__ int64_t out_row(const IgemmArgs& a, int m) {
@@ -71,13 +82,17 @@ __device__ __forceinline__ int64_t out_row(const IgemmArgs& a, int m) {
   return ((int64_t)n * a.outH + ya * a.ostep + a.oh0) * a.outW + xb * a.ostep + a.ow0;
 }
 
-template <int TC, int TP, int WGC, int PF, bool FAST>
+template <int TC, int TP, int WGC, int PF, bool FAST, int BKT>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   constexpr int WGP = 4 / WGC;                     // waves along channels x waves along pixels
   constexpr int WC = TC / WGC, WP = TP / WGP;      // wave tile
   constexpr int NI = WC / 32, NJ = WP / 32;        // MFMA tiles per wave
-  constexpr int VW = (TC * 4 + kThreads - 1) / kThreads, VX = TP * 4 / kThreads;   // 16-byte vectors per thread per tile
-  constexpr int TILE_BYTES = (TC + TP) * 64;
+  constexpr int NS = BKT / 8;                      // 16-byte slots per tile row
+  constexpr int RB = BKT * 2;                      // bytes per tile row
+  constexpr int RPG = kThreads / NS;               // tile rows covered by one load per thread
+  constexpr int KS = BKT / 16;                     // MFMA k-steps per tile
+  constexpr int VW = (TC * NS + kThreads - 1) / kThreads, VX = TP * NS / kThreads;   // 16-byte vectors per thread per tile
+  constexpr int TILE_BYTES = (TC + TP) * RB;
   constexpr int STG_STRIDE = TC * 2 + 16;
   constexpr int LDS_BYTES = (2 * TILE_BYTES > TP * STG_STRIDE) ? 2 * TILE_BYTES : TP * STG_STRIDE;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
@@ -92,14 +107,14 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wc = wave % WGC, wp = wave / WGC;
-  const int kvec = tid & 3, lrow = tid >> 2;       // this thread's slot in the global->LDS copy
+  const int kvec = tid % NS, lrow = tid / NS;      // this thread's slot in the global->LDS copy
 
   // im2col row state for the activation vectors this thread fetches (32-bit element offsets)
   int hb[VX], wb[VX], nb[VX]; bool mv[VX];
   const int HW = a.Hout * a.Wout;
 #pragma unroll
   for (int i = 0; i < VX; ++i) {
-    const int m = m0 + lrow + 64 * i;
+    const int m = m0 + lrow + RPG * i;
     mv[i] = m < a.M;
     const int mm = mv[i] ? m : 0;
     const int n = mm / HW, rem = mm - n * HW;
@@ -107,15 +122,15 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * a.ostride - a.pad_w;
     nb[i] = n * a.Hin * a.Win;
   }
-  const int ntiles = (a.Ktot + BK - 1) / BK;
+  const int ntiles = (a.Ktot + BKT - 1) / BKT;
   const u32x4* zero_page = reinterpret_cast<const u32x4*>(g_zero_page);
 
   // Weight rows of this thread: offset of (row, k = kvec*8) and row validity; advances by BK per tile.
   int woff[VW]; bool wrow[VW];
 #pragma unroll
   for (int i = 0; i < VW; ++i) {
-    const int c = c0 + lrow + 64 * i;
-    wrow[i] = (lrow + 64 * i < TC) & (c < a.Cout);
+    const int c = c0 + lrow + RPG * i;
+    wrow[i] = (lrow + RPG * i < TC) & (c < a.Cout);
     woff[i] = (wrow[i] ? c : 0) * a.Ktot + kvec * 8;
   }
   // Activation state.  FAST (Cin % 32 == 0): a k-tile never straddles a filter tap, so the tap
@@ -148,10 +163,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
     const bool tile_ok = kf < ntiles;
 #pragma unroll
     for (int i = 0; i < VW; ++i) {
-      const bool ok = tile_ok & wrow[i] & (FAST || kf * BK + kvec * 8 < a.Ktot);
+      const bool ok = tile_ok & wrow[i] & (FAST || kf * BKT + kvec * 8 < a.Ktot);
       const u32x4* p = ok ? reinterpret_cast<const u32x4*>(a.wt + woff[i]) : zero_page;
       r.w[i] = *p;
-      woff[i] += BK;
+      woff[i] += BKT;
     }
     if (FAST) {
       if (kc0 == 0) retap(kr, ks, kvec * 8);       // uniform: first tile of a tap
@@ -159,41 +174,41 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
       for (int i = 0; i < VX; ++i) {
         const u32x4* p = (tile_ok & xok[i]) ? reinterpret_cast<const u32x4*>(a.in + xoff[i]) : zero_page;
         r.x[i] = *p;
-        xoff[i] += BK;
+        xoff[i] += BKT;
       }
-      kc0 += BK;
+      kc0 += BKT;
       if (kc0 == a.Cin) { kc0 = 0; if (++ks == a.KW) { ks = 0; ++kr; } }
     } else {
       retap(gr, gs, kc);
-      const bool kvalid = tile_ok & (kf * BK + kvec * 8 < a.Ktot);
+      const bool kvalid = tile_ok & (kf * BKT + kvec * 8 < a.Ktot);
 #pragma unroll
       for (int i = 0; i < VX; ++i) {
         const u32x4* p = (kvalid & xok[i]) ? reinterpret_cast<const u32x4*>(a.in + xoff[i]) : zero_page;
         r.x[i] = *p;
       }
-      kc += BK;
+      kc += BKT;
       while (kc >= a.Cin) { kc -= a.Cin; if (++gs == a.KW) { gs = 0; ++gr; } }
     }
     ++kf;
   };
-  const int st_w = swz(lrow, kvec), st_x = TC * 64 + swz(lrow, kvec);   // rows lrow + 64*i share the swizzle (64 % 16 == 0)
+  const int st_w = swz<NS>(lrow, kvec), st_x = TC * RB + swz<NS>(lrow, kvec);   // rows lrow + RPG*i share the swizzle (RPG % 16 == 0)
   auto stash = [&](int buf, const RegSet& r) {
     unsigned char* base = lds + buf * TILE_BYTES;
 #pragma unroll
     for (int i = 0; i < VW; ++i)
-      if (lrow + 64 * i < TC) *reinterpret_cast<u32x4*>(base + st_w + i * 4096) = r.w[i];
+      if (lrow + RPG * i < TC) *reinterpret_cast<u32x4*>(base + st_w + i * (RPG * RB)) = r.w[i];
 #pragma unroll
-    for (int i = 0; i < VX; ++i) *reinterpret_cast<u32x4*>(base + st_x + i * 4096) = r.x[i];
+    for (int i = 0; i < VX; ++i) *reinterpret_cast<u32x4*>(base + st_x + i * (RPG * RB)) = r.x[i];
   };
-  // fragment read offsets (bytes inside a tile) for kk = 0, 1
-  int fa_off[2][NI], fb_off[2][NJ];
+  // fragment read offsets (bytes inside a tile) per MFMA k-step
+  int fa_off[KS][NI], fb_off[KS][NJ];
 #pragma unroll
-  for (int kk = 0; kk < 2; ++kk) {
+  for (int kk = 0; kk < KS; ++kk) {
     const int slot = kk * 2 + (lane >> 5);
 #pragma unroll
-    for (int i = 0; i < NI; ++i) fa_off[kk][i] = swz(wc * WC + i * 32 + (lane & 31), slot);
+    for (int i = 0; i < NI; ++i) fa_off[kk][i] = swz<NS>(wc * WC + i * 32 + (lane & 31), slot);
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) fb_off[kk][j] = TC * 64 + swz(wp * WP + j * 32 + (lane & 31), slot);
+    for (int j = 0; j < NJ; ++j) fb_off[kk][j] = TC * RB + swz<NS>(wp * WP + j * 32 + (lane & 31), slot);
   }
 
   f32x16 acc[NI][NJ];
@@ -212,7 +227,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   auto step = [&](int t, RegSet& r) {
     const unsigned char* base = lds + (t & 1) * TILE_BYTES;
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
+    for (int kk = 0; kk < KS; ++kk) {
       Frag fa[NI], fb[NJ];
 #pragma unroll
       for (int i = 0; i < NI; ++i) fa[i].u = *reinterpret_cast<const u32x4*>(base + fa_off[kk][i]);
@@ -270,11 +285,39 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   constexpr int CV = TC / 8;                       // channel vectors per pixel row
   constexpr int RPP = kThreads / CV;               // pixel rows per store sweep
   const int cv = tid % CV, pr0 = tid / CV;
+  const int ch = c0 + cv * 8;
+  float s1[8], s2[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { s1[j] = 0.f; s2[j] = 0.f; }
 #pragma unroll
   for (int prow = pr0; prow < TP; prow += RPP) {
-    const int m = m0 + prow, ch = c0 + cv * 8;
-    if (m < a.M && ch < a.Cout)
-      *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
+    const int m = m0 + prow;
+    if (m < a.M && ch < a.Cout) {
+      const uint4 pk = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
+      *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = pk;
+      if (a.stat_mode) {
+        const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float v0 = __uint_as_float(w[j] << 16), v1 = __uint_as_float(w[j] & 0xffff0000u);
+          s1[2 * j] += v0; s2[2 * j] += v0 * v0; s1[2 * j + 1] += v1; s2[2 * j + 1] += v1 * v1;
+        }
+      }
+    }
+  }
+  if (a.stat_mode) {
+    // fold the RPP row groups in a fixed order through LDS, one slab per pixel tile
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(lds);     // [RPP][2][TC]
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { red[(pr0 * 2 + 0) * TC + cv * 8 + j] = s1[j]; red[(pr0 * 2 + 1) * TC + cv * 8 + j] = s2[j]; }
+    __syncthreads();
+    if (tid < 2 * TC) {
+      const int which = tid / TC, c = tid % TC;
+      float t = 0.f;
+      for (int g = 0; g < RPP; ++g) t += red[(g * 2 + which) * TC + c];
+      if (c0 + c < a.Cout) a.stat_partial[((int64_t)(a.stat_slab0 + pt) * 2 + which) * a.Cout + c0 + c] = t;
+    }
   }
 }
 
@@ -283,7 +326,7 @@ __global__ void widen_kernel(const bf16_t* __restrict__ src, float* __restrict__
   if (i < n) dst[i] = bf2f(src[i]);
 }
 
-template <int TC, int TP, int WGC, int PF>
+template <int TC, int TP, int WGC, int PF, int BKT>
 dat_status launch_igemm(IgemmArgs a, hipStream_t st) {
   // 32-bit element offsets inside the kernel
   if ((int64_t)a.B * a.Hin * a.Win * a.Cin >= (1ll << 31) || (int64_t)a.Cout * a.Ktot >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;
@@ -291,21 +334,28 @@ dat_status launch_igemm(IgemmArgs a, hipStream_t st) {
   a.npt = (a.M + TP - 1) / TP;
   if (a.npt == 0) return DAT_OK;
   const int npt8 = (a.npt + 7) / 8 * 8;
-  if (a.Cin % 32 == 0 && a.Ktot > 0)
-    hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC, PF, true>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
+  if (a.Cin % BKT == 0 && a.Ktot > 0)
+    hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC, PF, true, BKT>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
   else
-    hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC, PF, false>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC, PF, false, BKT>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
 
+template <int TC, int TP, int WGC>
+dat_status pick_depth(const IgemmArgs& a, hipStream_t st) {
+  // short contractions (1x1 layers with few input channels) gain nothing from deep prefetch;
+  // long ones use 64-wide k-tiles (half the barriers per MFMA) when a tile cannot straddle a tap
+  if (a.Ktot <= 128) return launch_igemm<TC, TP, WGC, 1, 32>(a, st);
+  if (a.Cin % 64 == 0) return launch_igemm<TC, TP, WGC, 2, 64>(a, st);
+  return launch_igemm<TC, TP, WGC, 3, 32>(a, st);
+}
+
 dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
   if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
-  // short contractions (1x1 layers with few input channels) gain nothing from deep prefetch
-  const bool shallow = (a.Ktot + BK - 1) / BK <= 4;
-  if (a.Cout <= 32) return shallow ? launch_igemm<32, 128, 1, 1>(a, st) : launch_igemm<32, 128, 1, 3>(a, st);
-  if (a.Cout <= 64) return shallow ? launch_igemm<64, 128, 2, 1>(a, st) : launch_igemm<64, 128, 2, 3>(a, st);
-  return shallow ? launch_igemm<128, 128, 2, 1>(a, st) : launch_igemm<128, 128, 2, 3>(a, st);
+  if (a.Cout <= 32) return pick_depth<32, 128, 1>(a, st);
+  if (a.Cout <= 64) return pick_depth<64, 128, 2>(a, st);
+  return pick_depth<128, 128, 2>(a, st);
 }
 
 // ---- weight layouts ---------------------------------------------------------------------------
@@ -376,7 +426,7 @@ __device__ __forceinline__ void transpose8x8(const uint4 in[8], uint4 out[8]) {
 }
 
 // LDS tile [row][64 pixels] bf16, rows 128 bytes; 16-byte slots swizzled by row.
-__device__ __forceinline__ int swz128(int row, int slot) { return row * 128 + ((slot ^ (row & 7)) << 4); }
+__device__ __forceinline__ int swz128(int row, int slot) { return swz<8>(row, slot); }
 
 template <int TC, int TJ>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
@@ -530,17 +580,32 @@ size_t conv_mfma_wgrad_workspace(const ConvGeom& g) {
   return (size_t)p.splits * g.Cout * g.k * g.k * g.Cin * sizeof(float);
 }
 
-dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, hipStream_t st) {
+static void set_stats(IgemmArgs& a, const ConvStats* s, int slab0) {
+  a.stat_mode = 0; a.stat_slab0 = slab0; a.stat_partial = nullptr;
+  if (!s || !s->mode) return;
+  a.stat_mode = 1; a.stat_partial = s->partial;
+}
+
+constexpr int kPixelTile = 128;   // TP of every configuration run_igemm selects
+
+int conv_stat_slabs(int64_t rows, int stride) {
+  // stride 2 backward-data runs four launches over the parity classes: at most 3 extra partial tiles
+  return (int)((rows + kPixelTile - 1) / kPixelTile) + (stride == 2 ? 4 : 0);
+}
+
+dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
   a.in = x; a.wt = w; a.res = res; a.out = y;
   a.B = g.B; a.Hin = g.H; a.Win = g.W; a.Cin = g.Cin; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
   a.KH = g.k; a.KW = g.k; a.ostride = g.stride; a.pad_h = a.pad_w = g.pad;
   a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
   a.M = g.B * g.Ho * g.Wo; a.Ktot = g.k * g.k * g.Cin; a.nct = a.npt = 0;
+  set_stats(a, stats, 0);
+  if (stats) stats->nslabs = (a.M + kPixelTile - 1) / kPixelTile;
   return run_igemm(a, st);
 }
 
-dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, hipStream_t st) {
+dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
   a.in = dy; a.res = accumulate ? dx : nullptr; a.out = dx;
   a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Cout = g.Cin;
@@ -549,10 +614,13 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
     a.wt = wT; a.Hout = g.H; a.Wout = g.W; a.KH = a.KW = g.k; a.pad_h = a.pad_w = g.k - 1 - g.pad;
     a.ostep = 1; a.oh0 = a.ow0 = 0;
     a.M = g.B * g.H * g.W; a.Ktot = g.k * g.k * g.Cout;
+    set_stats(a, stats, 0);
+    if (stats) stats->nslabs = (a.M + kPixelTile - 1) / kPixelTile;
     return run_igemm(a, st);
   }
   if (g.stride != 2) return DAT_ERR_UNSUPPORTED;
   int64_t base = 0;
+  int slab0 = 0;
   for (int q = 0; q < 4; ++q) {
     const int ph = q >> 1, pw = q & 1;
     const ParityClass ch = parity_class(ph, g.k, g.pad), cw = parity_class(pw, g.k, g.pad);
@@ -562,9 +630,12 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
     a.ostep = 2; a.oh0 = ph; a.ow0 = pw;
     a.M = g.B * a.Hout * a.Wout; a.Ktot = ch.nr * cw.nr * g.Cout;
     if (a.Ktot == 0) a.KH = a.KW = 1;   // class without taps: the launch only writes zeros (or keeps the stored gradient)
+    set_stats(a, stats, slab0);
     if (a.M > 0) { dat_status s = run_igemm(a, st); if (s != DAT_OK) return s; }
+    slab0 += (a.M + kPixelTile - 1) / kPixelTile;
     base += (int64_t)ch.nr * cw.nr;
   }
+  if (stats) stats->nslabs = slab0;
   return DAT_OK;
 }
 
@@ -616,7 +687,7 @@ extern "C" dat_status dat_conv_forward(const uint16_t* x, const uint16_t* w, uin
   ConvGeom g;
   if (!x || !w || !y || !geom_from(B, H, W, Cin, Cout, k, stride, pad, &g)) return DAT_ERR_ARG;
   if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return DAT_ERR_ARG;
-  return conv_mfma_forward(x, w, nullptr, y, g, (hipStream_t)stream);
+  return conv_mfma_forward(x, w, nullptr, y, g, nullptr, (hipStream_t)stream);
 }
 
 extern "C" dat_status dat_conv_backward_data(const uint16_t* dy, const uint16_t* w, uint16_t* dx, int B, int H, int W,
@@ -639,7 +710,7 @@ extern "C" dat_status dat_conv_backward_data(const uint16_t* dy, const uint16_t*
   hipLaunchKernelGGL(widen_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, w, wf, (int64_t)n);
   if (hipGetLastError() != hipSuccess) s = DAT_ERR_HIP;
   if (s == DAT_OK) s = launch_weight_transform(wf, w2, wT, Cout, k, Cin, Cin, stride, pad, st);
-  if (s == DAT_OK) s = conv_mfma_backward_data(dy, wT, dx, g, false, st);
+  if (s == DAT_OK) s = conv_mfma_backward_data(dy, wT, dx, g, false, nullptr, st);
   (void)hipStreamSynchronize(st);
   (void)hipFree(wf); (void)hipFree(w2); (void)hipFree(wT);
   return s;

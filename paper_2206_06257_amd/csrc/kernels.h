@@ -42,8 +42,18 @@ dat_status conv_direct_backward_weight(const float* x, const float* dy, float* d
 // ---- bf16 implicit-GEMM convolutions on MFMA (conv_mfma.hip): the DAT_BF16 path ----------------
 // w: [Cout][k][k][Cin] bf16.  wT: the backward-data operand built by launch_weight_transform
 // (flipped transpose for stride 1, four parity-class sub-filters for stride 2).
-dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, hipStream_t st);
-dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, hipStream_t st);
+// Optional fused batch statistics: with mode 1 the forward (or backward-data) epilogue also writes
+// per-channel (sum v, sum v^2) of everything it stores, as `nslabs` slabs of [2][C] floats in
+// `partial` (C = channels of the stored tensor); conv_stat_slabs gives an upper bound for sizing.
+// Reduce them with bn_finalize_slabs.
+struct ConvStats {
+  int mode;
+  float* partial;
+  int nslabs;            // out
+};
+int conv_stat_slabs(int64_t rows, int stride);
+dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st);
+dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st);
 // dw fp32 [Cout][k][k][Cin_real] (Cin_real <= g.Cin: padded input channels are dropped), scaled.
 // `ws` is a workspace of conv_mfma_wgrad_workspace(g) bytes.
 size_t conv_mfma_wgrad_workspace(const ConvGeom& g);
@@ -56,16 +66,25 @@ dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, i
 // `partial` holds bn_partial_floats(rows, C) floats.
 size_t bn_partial_floats(int64_t rows, int C);
 dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partial, float* mean, float* rstd, hipStream_t st);
+// Reduces `nslabs` slabs of [2][C] partial sums (from a convolution epilogue) in a fixed order.
+//   mode 1: mean[C], rstd[C] from (sum x, sum x^2) over `rows` rows  (o1 = mean, o2 = rstd)
+//   mode 2: sums[0..C) = sum dy, sums[C..2C) = sum dy*xhat (o1 = sums, o2 = sums + C), and
+//           dbeta = scale*sum dy, dgamma = scale*sum dy*xhat when the pointers are non-null.
+// `partial` must have room for fold_floats(nslabs, C) more floats after the slabs.
+size_t fold_floats(int nslabs, int C);
+dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
+                             float* dgamma, float scale, hipStream_t st);
 // out = act(gamma*((x-mean)*rstd) + beta [+ res])
 dat_status bnact_forward(const void* x, const void* res, void* out, int dtype, int64_t rows, int C, const float* mean,
                          const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st);
 // dy = dout masked by (out > 0) if relu.  sums[0..C) = sum dy (= dbeta), sums[C..2C) = sum dy*xhat (= dgamma).
 // Then dx (+)= gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows); dres (+)= dy.
 // dgamma/dbeta (fp32, may be null) receive scale*sums.
+// sums_ready: `sums` already holds the two sums (and dgamma/dbeta were written): only apply.
 dat_status bnact_backward(const void* x, const void* out, const void* dout, void* dx, bool dx_accumulate, void* dres,
                           bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
-                          const float* gamma, int relu, float* partial, float* sums, float* dgamma, float* dbeta,
-                          float scale, hipStream_t st);
+                          const float* gamma, int relu, float* partial, float* sums, bool sums_ready, float* dgamma,
+                          float* dbeta, float scale, hipStream_t st);
 dat_status biasact_forward(const void* x, void* out, int dtype, int64_t rows, int C, const float* bias, int relu, hipStream_t st);
 dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx_accumulate, int dtype, int64_t rows, int C,
                             int relu, float* partial, float* dbias, float scale, hipStream_t st);

@@ -175,6 +175,16 @@ __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ 
   }
 }
 
+// Sums groups of 32 consecutive slabs (fixed order): [S][W] -> [ceil(S/32)][W], W = 2*C columns.
+__global__ __launch_bounds__(kT) void slab_fold_kernel(const float* __restrict__ in, int S, int W, float* __restrict__ out) {
+  const int col = blockIdx.y * kT + threadIdx.x;
+  if (col >= W) return;
+  const int s0 = blockIdx.x * 32, s1 = min(S, s0 + 32);
+  float t = 0.f;
+  for (int s = s0; s < s1; ++s) t += in[(int64_t)s * W + col];
+  out[(int64_t)blockIdx.x * W + col] = t;
+}
+
 template <typename T>
 __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, const T* __restrict__ res,
                                                        T* __restrict__ out, int64_t rows, int C, int tpr, int rpp,
@@ -524,6 +534,26 @@ dat_status colreduce(const void* x, const void* out, const void* dout, const flo
 
 size_t bn_partial_floats(int64_t rows, int C) { (void)rows; return (size_t)kMaxSlabs * 2 * C; }
 
+size_t fold_floats(int nslabs, int C) { return nslabs > 512 ? (size_t)((nslabs + 31) / 32) * 2 * C : 0; }
+
+dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
+                             float* dgamma, float scale, hipStream_t st) {
+  const float* src = partial;
+  if (nslabs > 512) {   // two-level: keep the final per-channel loop short
+    float* folded = partial + (size_t)nslabs * 2 * C;
+    const int S2 = (nslabs + 31) / 32;
+    hipLaunchKernelGGL(slab_fold_kernel, dim3(S2, (2 * C + kT - 1) / kT), dim3(kT), 0, st, partial, nslabs, 2 * C, folded);
+    DAT_LAUNCH_CHECK();
+    src = folded; nslabs = S2;
+  }
+  if (mode == 1)
+    hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, (float*)nullptr, (float*)nullptr, 1.0f);
+  else
+    hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, dbeta, dgamma, scale);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
 #define DAT_BY_DTYPE(dtype, CALL_F32, CALL_BF16) do { if ((dtype) == 0) { CALL_F32; } else { CALL_BF16; } } while (0)
 
 dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partial, float* mean, float* rstd, hipStream_t st) {
@@ -551,16 +581,18 @@ dat_status bnact_forward(const void* x, const void* res, void* out, int dtype, i
 
 dat_status bnact_backward(const void* x, const void* out, const void* dout, void* dx, bool dx_accumulate, void* dres,
                           bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
-                          const float* gamma, int relu, float* partial, float* sums, float* dgamma, float* dbeta,
-                          float scale, hipStream_t st) {
+                          const float* gamma, int relu, float* partial, float* sums, bool sums_ready, float* dgamma,
+                          float* dbeta, float scale, hipStream_t st) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
-  SlabPlan p; dat_status s;
-  DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)),
-               s = (colreduce<bf16_t, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)));
-  if (s != DAT_OK) return s;
-  hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
-                     dbeta, dgamma, scale);
-  DAT_LAUNCH_CHECK();
+  if (!sums_ready) {
+    SlabPlan p; dat_status s;
+    DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)),
+                 s = (colreduce<bf16_t, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)));
+    if (s != DAT_OK) return s;
+    hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
+                       dbeta, dgamma, scale);
+    DAT_LAUNCH_CHECK();
+  }
   const float inv_rows = (float)(1.0 / (double)rows);
   const SlabPlan q = plan_slabs(rows, C, kMaxApplySlabs);
   DAT_BY_DTYPE(dtype,

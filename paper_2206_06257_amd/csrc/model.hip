@@ -9,6 +9,7 @@
 // ones are added to the stored value (read-modify-write in the consumer's kernel).
 #include <stdlib.h>
 #include <string.h>
+#include <algorithm>
 #include <vector>
 #include "kernels.h"
 
@@ -31,6 +32,10 @@ struct Op {
   float* mean = nullptr;        // BN batch statistics of the last forward
   uint8_t* argmax = nullptr;    // max-pool: window position of the maximum, per output element
   float* rstd = nullptr;
+  float* sums = nullptr;        // BN backward: [2][C] sums (sum dy, sum dy*xhat)
+  bool sums_ready = false;      //   ... already produced by the convolution that completed d(out)
+  bool stats_from_conv = false; // BN forward: mean/rstd come from the producing convolution's epilogue
+  int fwd_bn = -1;              // conv: BN op normalising this conv's output (statistics fused into the epilogue)
 };
 
 struct PTensor { int64_t off, numel; int fan_in, kind; };
@@ -181,6 +186,25 @@ bool build_graph(dat_model& m) {
       return false;
   }
   m.fc(m.gap(t), m.classes);
+  // Fusion links (bf16 models): which BN normalises a conv's output (its batch statistics come from
+  // the conv epilogue).
+  if (m.dtype == DAT_BF16) {
+    const int nt = (int)m.tens.size();
+    std::vector<int> producer(nt, -1), first_consumer(nt, -1);
+    for (int i = 0; i < (int)m.ops.size(); ++i) {
+      producer[m.ops[i].out] = i;
+      if (first_consumer[m.ops[i].in] < 0) first_consumer[m.ops[i].in] = i;
+      if (m.ops[i].res >= 0 && first_consumer[m.ops[i].res] < 0) first_consumer[m.ops[i].res] = i;
+    }
+    for (int i = 0; i < (int)m.ops.size(); ++i) {
+      Op& op = m.ops[i];
+      if (op.kind == OP_BNACT && producer[op.in] >= 0 && m.ops[producer[op.in]].kind == OP_CONV &&
+          m.ops[producer[op.in]].fwd_bn < 0) {
+        m.ops[producer[op.in]].fwd_bn = i;
+        op.stats_from_conv = true;
+      }
+    }
+  }
   return true;
 }
 
@@ -246,6 +270,7 @@ dat_status allocate(dat_model& m) {
     if (op.kind == OP_BNACT) {
       DAT_TRY(dev_alloc(m, &op.mean, (size_t)m.tens[op.in].C * 4));
       DAT_TRY(dev_alloc(m, &op.rstd, (size_t)m.tens[op.in].C * 4));
+      DAT_TRY(dev_alloc(m, &op.sums, (size_t)m.tens[op.in].C * 8));
     }
     if (op.kind == OP_MAXPOOL) DAT_TRY(dev_alloc(m, &op.argmax, (size_t)m.maxB * m.tens[op.out].numel()));
     if (op.kind == OP_CONV && m.dtype == DAT_BF16) {
@@ -258,7 +283,15 @@ dat_status allocate(dat_model& m) {
   }
   m.wgrad_ws_bytes = ws;
   if (ws) DAT_TRY(dev_alloc(m, &m.wgrad_ws, ws));
-  DAT_TRY(dev_alloc(m, &m.partial, bn_partial_floats(0, cmax) * 4));
+  size_t partial_floats = bn_partial_floats(0, cmax);
+  for (const Op& op : m.ops) {
+    if (op.kind != OP_CONV || m.dtype != DAT_BF16) continue;
+    const Shape si = m.tens[op.in], so = m.tens[op.out];
+    const int sf = conv_stat_slabs((int64_t)m.maxB * so.H * so.W, 1), sb = conv_stat_slabs((int64_t)m.maxB * si.H * si.W, op.stride);
+    const size_t need_f = (size_t)sf * 2 * so.C + fold_floats(sf, so.C), need_b = (size_t)sb * 2 * si.C + fold_floats(sb, si.C);
+    partial_floats = std::max(partial_floats, std::max(need_f, need_b));
+  }
+  DAT_TRY(dev_alloc(m, &m.partial, partial_floats * 4));
   DAT_TRY(dev_alloc(m, &m.sums, (size_t)2 * cmax * 4));
   DAT_TRY(dev_alloc(m, &m.loss_n, (size_t)m.maxB * 4));
   m.loss_cap = 1024;
@@ -296,7 +329,7 @@ NetInputDesc input_desc(const dat_model& m) {
 }
 
 dat_status bn_forward_pair(dat_model& m, Op& op, int64_t rows, int C, hipStream_t st) {
-  DAT_TRY(bn_stats(m.act[op.in], m.dtype, rows, C, m.partial, op.mean, op.rstd, st));
+  if (!op.stats_from_conv) DAT_TRY(bn_stats(m.act[op.in], m.dtype, rows, C, m.partial, op.mean, op.rstd, st));
   return bnact_forward(m.act[op.in], op.res >= 0 ? m.act[op.res] : nullptr, m.act[op.out], m.dtype, rows, C, op.mean,
                        op.rstd, m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off, op.relu, st);
 }
@@ -310,7 +343,15 @@ dat_status forward(dat_model& m, int B, hipStream_t st) {
       case OP_CONV: {
         const ConvGeom g = geom_of(m, op, B);
         const void* res = op.res >= 0 ? m.act[op.res] : nullptr;
-        if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_FWD, conv_flops(g, op.cin_real), st, conv_mfma_forward((const bf16_t*)m.act[op.in], op.w16, (const bf16_t*)res, (bf16_t*)m.act[op.out], g, st));
+        if (dt == DAT_BF16) {
+          ConvStats cs{};
+          cs.mode = op.fwd_bn >= 0 ? 1 : 0; cs.partial = m.partial;
+          DAT_PROF(m, DAT_PROF_CONV_FWD, conv_flops(g, op.cin_real), st, conv_mfma_forward((const bf16_t*)m.act[op.in], op.w16, (const bf16_t*)res, (bf16_t*)m.act[op.out], g, &cs, st));
+          if (cs.mode) {   // batch statistics of the normalisation that follows, from the epilogue's partial sums
+            Op& bn = m.ops[op.fwd_bn];
+            DAT_PROF(m, DAT_PROF_BN, 0.0, st, bn_finalize_slabs(m.partial, cs.nslabs, so.C, (int64_t)B * so.H * so.W, 1, bn.mean, bn.rstd, nullptr, nullptr, 1.0f, st));
+          }
+        }
         else DAT_PROF(m, DAT_PROF_CONV_FWD, conv_flops(g, op.cin_real), st, conv_direct_forward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, (const float*)res, (float*)m.act[op.out], g, st));
         break;
       }
@@ -319,7 +360,7 @@ dat_status forward(dat_model& m, int B, hipStream_t st) {
         break;
       case OP_BNACT:
         // algorithmic bytes: read x twice (statistics, apply), read res, write out
-        DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (3 + (op.res >= 0)), st,
+        DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (3 - (int)op.stats_from_conv + (op.res >= 0)), st,
                  bn_forward_pair(m, op, rows_in, si.C, st));
         break;
       case OP_MAXPOOL:
@@ -367,7 +408,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
           else DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_direct_backward_weight((const float*)m.act[op.in], (const float*)m.grad[op.out], g0, g, 1.0f, st));
         }
         if (op.in != 0 || need_input_grad) {
-          if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
+          if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], nullptr, st));
           else DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_direct_backward_data((const float*)m.grad[op.out], m.compute + m.ptab[op.p0].off, (float*)m.grad[op.in], g, m.ghas[op.in], st));
           m.ghas[op.in] = 1;
         }
@@ -383,7 +424,8 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         // algorithmic bytes: read x, out, dout once each; write dx (and dres)
         DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (4 + (op.res >= 0)), st,
                  bnact_backward(m.act[op.in], m.act[op.out], m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
-                                si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, m.sums, g0, g1, 1.0f, st));
+                                si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.sums_ready, g0, g1, 1.0f, st));
+        op.sums_ready = false;
         if (op.res >= 0) m.ghas[op.res] = 1;
         m.ghas[op.in] = 1;
         break;
