@@ -39,41 +39,70 @@ __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
 __global__ __launch_bounds__(kThreads) void absmax_kernel(const float* __restrict__ g,
                                                           const int64_t* __restrict__ off, int T,
                                                           int64_t d, uint32_t* __restrict__ scale_bits) {
+  // A workgroup owns 16 K consecutive elements, hence a run of consecutive tensors starting at
+  // `tfirst`.  Per-tensor maxima are first combined in LDS (slot = tensor - tfirst) and only the
+  // touched slots go to global memory: one global atomic per workgroup and tensor.  Thousands of
+  // atomics on one L2 address would otherwise dominate the kernel.
+  constexpr int kIterA = 2 * kIter;                // groups per thread
+  constexpr int kSlots = 128;
+  __shared__ uint32_t s_max[kSlots];
+  __shared__ int s_tfirst;
   const int64_t ngroups = (d + 3) >> 2;
-  int64_t grp = (int64_t)blockIdx.x * (kThreads * kIter) + threadIdx.x;
-  if (grp >= ngroups) return;
-  int t = find_tensor(off, T, grp << 2);
+  const int64_t grp0 = (int64_t)blockIdx.x * (kThreads * kIterA);
+  if (threadIdx.x == 0) s_tfirst = find_tensor(off, T, min(grp0 << 2, d - 1));
+  if (threadIdx.x < kSlots) s_max[threadIdx.x] = 0u;
+  __syncthreads();
+  const int tfirst = s_tfirst;
+  int t = tfirst;
   int64_t next = off[t + 1];
   uint32_t m = 0;
-  for (int it = 0; it < kIter; ++it, grp += kThreads) {
-    if (grp >= ngroups) break;
-    const int64_t i0 = grp << 2;
-    if (i0 + 3 < d && i0 + 3 < next) {
-      const float4 v = *reinterpret_cast<const float4*>(g + i0);
-      uint32_t a = __float_as_uint(v.x) & 0x7fffffffu, b = __float_as_uint(v.y) & 0x7fffffffu;
-      uint32_t c = __float_as_uint(v.z) & 0x7fffffffu, e = __float_as_uint(v.w) & 0x7fffffffu;
-      m = max(max(m, max(a, b)), max(c, e));
-    } else {
-      for (int j = 0; j < 4; ++j) {
-        const int64_t i = i0 + j;
-        if (i >= d) break;
-        while (i >= next) {
-          if (m) atomicMax(scale_bits + t, m);
-          m = 0; ++t; next = off[t + 1];
+  auto flush = [&]() {
+    if (m) {
+      const int slot = t - tfirst;
+      if (slot < kSlots) atomicMax(&s_max[slot], m); else atomicMax(scale_bits + t, m);
+    }
+    m = 0;
+  };
+  int64_t grp = grp0 + threadIdx.x;
+  for (int it = 0; it < kIterA; it += 4) {
+    // four groups per trip (16 elements, 4 KiB apart) so that four loads are in flight; the fast
+    // path needs all of them inside the current tensor
+    const int64_t ifirst = grp << 2, ilast = ((grp + 3 * kThreads) << 2) + 3;
+    if (ifirst < next && ilast < d && ilast < next) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(g + ((grp + u * kThreads) << 2));
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t a = __float_as_uint(v[u].x) & 0x7fffffffu, b = __float_as_uint(v[u].y) & 0x7fffffffu;
+        const uint32_t c = __float_as_uint(v[u].z) & 0x7fffffffu, e = __float_as_uint(v[u].w) & 0x7fffffffu;
+        m = max(max(m, max(a, b)), max(c, e));
+      }
+      grp += 4 * kThreads;
+      continue;
+    }
+    for (int u = 0; u < 4; ++u, grp += kThreads) {
+      if (grp >= ngroups) break;
+      const int64_t i0 = grp << 2;
+      while (i0 >= next) { flush(); ++t; next = off[t + 1]; }
+      if (i0 + 3 < d && i0 + 3 < next) {           // whole group inside the tensor
+        const float4 v = *reinterpret_cast<const float4*>(g + i0);
+        const uint32_t a = __float_as_uint(v.x) & 0x7fffffffu, b = __float_as_uint(v.y) & 0x7fffffffu;
+        const uint32_t c = __float_as_uint(v.z) & 0x7fffffffu, e = __float_as_uint(v.w) & 0x7fffffffu;
+        m = max(max(m, max(a, b)), max(c, e));
+      } else {
+        for (int j = 0; j < 4; ++j) {
+          const int64_t i = i0 + j;
+          if (i >= d) break;
+          while (i >= next) { flush(); ++t; next = off[t + 1]; }
+          m = max(m, __float_as_uint(g[i]) & 0x7fffffffu);
         }
-        m = max(m, __float_as_uint(g[i]) & 0x7fffffffu);
       }
     }
   }
-  // one atomic per wave when the whole wave ended in the same tensor
-  const int t0 = __builtin_amdgcn_readfirstlane(t);
-  if (__all(t == t0)) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, s));
-    if ((threadIdx.x & 63) == 0 && m) atomicMax(scale_bits + t0, m);
-  } else if (m) {
-    atomicMax(scale_bits + t, m);
-  }
+  flush();
+  __syncthreads();
+  if (threadIdx.x < kSlots && s_max[threadIdx.x]) atomicMax(scale_bits + tfirst + threadIdx.x, s_max[threadIdx.x]);
 }
 
 // ---- encoder / decoder ------------------------------------------------------------------
@@ -250,7 +279,7 @@ extern "C" dat_status dat_quantize(const float* grads, const int64_t* offsets_de
                      reinterpret_cast<uint32_t*>(scales), num_tensors, 0u);
   DAT_LAUNCH_CHECK();
   if (d == 0) return DAT_OK;
-  hipLaunchKernelGGL(absmax_kernel, dim3(blocks_for((d + 3) / 4)), dim3(kThreads), 0, st, grads,
+  hipLaunchKernelGGL(absmax_kernel, dim3((blocks_for((d + 3) / 4) + 1) / 2), dim3(kThreads), 0, st, grads,
                      offsets_dev, num_tensors, d, reinterpret_cast<uint32_t*>(scales));
   DAT_LAUNCH_CHECK();
 #define DAT_Q_LAUNCH(B)                                                                          \
