@@ -68,6 +68,8 @@ _uniform = _sig("orc_uniform", None, C.c_uint64, C.c_int64, C.c_uint64, C.c_uint
 _rbf16 = _sig("orc_round_bf16", C.c_double, C.c_double)
 _conv_f = _sig("orc_conv_forward", None, _f64p, _f64p, _f64p, *([C.c_int] * 8))
 _conv_b = _sig("orc_conv_backward", None, _f64p, _f64p, _f64p, _f64p, _f64p, *([C.c_int] * 8))
+_pts = [_sig(n, None, _f32p, _f32p, *([C.c_int] * 8), _i64p, C.c_int, _f64p)
+        for n in ("orc_conv_forward_points", "orc_conv_bwd_data_points", "orc_conv_bwd_weight_points")]
 _threads = _sig("orc_threads", C.c_int)
 
 
@@ -259,6 +261,33 @@ def conv_backward(x, w, dout, stride, pad):
     dw = np.zeros_like(w)
     _conv_b(x, w, dout, din, dw, B, H, W, Ci, Co, k, stride, pad)
     return din, dw
+
+
+def _points(which, a, b, geom, idx):
+    a = np.ascontiguousarray(a, np.float32)
+    b = np.ascontiguousarray(b, np.float32)
+    idx = np.ascontiguousarray(idx, np.int64)
+    out = np.zeros(idx.size, np.float64)
+    _pts[which](a.reshape(-1), b.reshape(-1), *geom, idx, idx.size, out)
+    return out
+
+
+def conv_forward_points(x, w, stride, pad, idx):
+    """Selected elements (flat indices into y[B,Ho,Wo,Co]) of conv(x, w), from the definition."""
+    B, H, W, Ci = x.shape
+    return _points(0, x, w, (B, H, W, Ci, w.shape[0], w.shape[1], stride, pad), idx)
+
+
+def conv_backward_data_points(dy, w, in_hw, stride, pad, idx):
+    """Selected elements (flat indices into dx[B,H,W,Ci]) of the adjoint w.r.t. the input."""
+    B = dy.shape[0]
+    return _points(1, dy, w, (B, in_hw[0], in_hw[1], w.shape[3], w.shape[0], w.shape[1], stride, pad), idx)
+
+
+def conv_backward_weight_points(x, dy, k, stride, pad, idx):
+    """Selected elements (flat indices into dw[Co,k,k,Ci]) of the adjoint w.r.t. the weights."""
+    B, H, W, Ci = x.shape
+    return _points(2, x, dy, (B, H, W, Ci, dy.shape[3], k, stride, pad), idx)
 
 
 def threads():

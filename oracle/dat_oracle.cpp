@@ -1015,6 +1015,70 @@ void orc_conv_backward(const double* in, const double* W, const double* dout, do
   std::copy(m.gtheta.begin(), m.gtheta.end(), dW);
 }
 
+// Single output elements of the three convolution contractions, straight from the definitions
+// (fp32 inputs, fp64 sums), for spot checks on tensors too large to convolve whole.
+//   forward:  idx = flat index into y[B][Ho][Wo][Co]
+//   bwd data: idx = flat index into dx[B][H][W][Ci]
+//   bwd weight: idx = flat index into dw[Co][k][k][Ci]
+void orc_conv_forward_points(const float* x, const float* w, int B, int H, int Wd, int Ci, int Co, int k,
+                             int stride, int pad, const int64_t* idx, int n, double* out) {
+  const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (Wd + 2 * pad - k) / stride + 1;
+  (void)B;
+  for (int q = 0; q < n; ++q) {
+    int64_t p = idx[q];
+    const int co = (int)(p % Co); p /= Co;
+    const int wo = (int)(p % Wo); p /= Wo;
+    const int ho = (int)(p % Ho); const int64_t b = p / Ho;
+    double acc = 0.0;
+    for (int r = 0; r < k; ++r) for (int s = 0; s < k; ++s) {
+      const int hi = ho * stride + r - pad, wi = wo * stride + s - pad;
+      if (hi < 0 || hi >= H || wi < 0 || wi >= Wd) continue;
+      for (int ci = 0; ci < Ci; ++ci)
+        acc += (double)x[((b * H + hi) * Wd + wi) * Ci + ci] * (double)w[(((int64_t)co * k + r) * k + s) * Ci + ci];
+    }
+    out[q] = acc;
+  }
+}
+
+void orc_conv_bwd_data_points(const float* dy, const float* w, int B, int H, int Wd, int Ci, int Co, int k,
+                              int stride, int pad, const int64_t* idx, int n, double* out) {
+  const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (Wd + 2 * pad - k) / stride + 1;
+  (void)B;
+  for (int q = 0; q < n; ++q) {
+    int64_t p = idx[q];
+    const int ci = (int)(p % Ci); p /= Ci;
+    const int wi = (int)(p % Wd); p /= Wd;
+    const int hi = (int)(p % H); const int64_t b = p / H;
+    double acc = 0.0;
+    for (int ho = 0; ho < Ho; ++ho) for (int wo = 0; wo < Wo; ++wo) {
+      const int r = hi - ho * stride + pad, s = wi - wo * stride + pad;   // tap that connects (ho,wo) to (hi,wi)
+      if (r < 0 || r >= k || s < 0 || s >= k) continue;
+      for (int co = 0; co < Co; ++co)
+        acc += (double)dy[((b * Ho + ho) * Wo + wo) * Co + co] * (double)w[(((int64_t)co * k + r) * k + s) * Ci + ci];
+    }
+    out[q] = acc;
+  }
+}
+
+void orc_conv_bwd_weight_points(const float* x, const float* dy, int B, int H, int Wd, int Ci, int Co, int k,
+                                int stride, int pad, const int64_t* idx, int n, double* out) {
+  const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (Wd + 2 * pad - k) / stride + 1;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int q = 0; q < n; ++q) {
+    int64_t p = idx[q];
+    const int ci = (int)(p % Ci); p /= Ci;
+    const int s = (int)(p % k); p /= k;
+    const int r = (int)(p % k); const int co = (int)(p / k);
+    double acc = 0.0;
+    for (int64_t b = 0; b < B; ++b) for (int ho = 0; ho < Ho; ++ho) for (int wo = 0; wo < Wo; ++wo) {
+      const int hi = ho * stride + r - pad, wi = wo * stride + s - pad;
+      if (hi < 0 || hi >= H || wi < 0 || wi >= Wd) continue;
+      acc += (double)dy[((b * Ho + ho) * Wo + wo) * Co + co] * (double)x[((b * H + hi) * Wd + wi) * Ci + ci];
+    }
+    out[q] = acc;
+  }
+}
+
 int orc_threads() {
 #ifdef _OPENMP
   return omp_get_max_threads();

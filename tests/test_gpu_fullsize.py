@@ -1,0 +1,143 @@
+"""Parity at the full benchmark sizes (ResNet-50, 224x224, batch 256, bf16), in the launch
+configuration bench.py times.  The whole-network reference would take the CPU hours here, so:
+  * the three convolution kernels are spot-checked at full layer shapes against single outputs the
+    reference computes one by one from the definition;
+  * the quantizer and the PGD update are compared bit for bit on the full 25.56 M / 38.5 M vectors;
+  * dat_attack / dat_step are checked through properties that hold at any size: the l-inf ball and
+    image box exactly, determinism, the batch-norm scale invariance <W, dL/dW> = 0 of every
+    convolution that feeds a batch-norm, sum_c dL/db_c = 0 of the classifier bias, loss growth."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as syn
+
+pytestmark = pytest.mark.gpu
+MEAN, STD = (0.485, 0.456, 0.406), (0.229, 0.224, 0.225)
+B = 256
+
+# full-size layers of ResNet-50 at batch 256 (H, Cin, Cout, k, stride, pad)
+LAYERS = [
+    (224, 8, 64, 7, 2, 3),       # stem (3 channels padded to 8)
+    (56, 64, 64, 3, 1, 1),       # layer1 3x3
+    (56, 256, 64, 1, 1, 0),      # layer1 reduce
+    (56, 128, 128, 3, 2, 1),     # layer2 strided 3x3
+    (28, 128, 512, 1, 1, 0),     # layer2 expand
+    (28, 512, 1024, 1, 2, 0),    # layer3 projection shortcut
+    (14, 256, 256, 3, 1, 1),     # layer3 3x3
+    (7, 2048, 512, 1, 1, 0),     # layer4 reduce
+    (7, 512, 512, 3, 1, 1),      # layer4 3x3
+]
+
+
+@pytest.fixture(scope="module")
+def dat():
+    import paper_2206_06257_amd as dat
+    return dat
+
+
+def _sample(rng, n, total, extra=()):
+    idx = np.unique(np.concatenate([rng.integers(0, total, size=n), np.array(extra, np.int64)]))
+    return idx.astype(np.int64)
+
+
+@pytest.mark.parametrize("layer", LAYERS)
+def test_conv_kernels_at_full_layer_shapes(dat, layer):
+    H, Ci, Co, k, st, pad = layer
+    g = torch.Generator(device="cuda"); g.manual_seed(H * 1000 + Ci)
+    x = torch.randn(B, H, H, Ci, device="cuda", generator=g).to(torch.bfloat16)
+    w = (torch.randn(Co, k, k, Ci, device="cuda", generator=g) / np.sqrt(Ci * k * k)).to(torch.bfloat16)
+    y = dat.conv_forward(x, w, st, pad)
+    Ho = y.shape[1]
+    dy = torch.randn(B, Ho, Ho, Co, device="cuda", generator=g).to(torch.bfloat16)
+    dx = dat.conv_backward_data(dy, w, (H, H), st, pad)
+    dw = dat.conv_backward_weight(x, dy, k, st, pad)
+    torch.cuda.synchronize()
+    xh, wh, dyh = x.float().cpu().numpy(), w.float().cpu().numpy(), dy.float().cpu().numpy()
+    rng = np.random.default_rng(H + Ci)
+    # samples include the tensor's first and last elements and borders (padding paths, last tiles)
+    iy = _sample(rng, 300, y.numel(), (0, y.numel() - 1, Co * Ho - 1))
+    want = oracle.conv_forward_points(xh, wh, st, pad, iy)
+    got = y.reshape(-1)[torch.from_numpy(iy).cuda()].float().cpu().numpy()
+    scale = np.abs(want).max()
+    assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-5 * scale), np.abs(got - want).max()
+    ix = _sample(rng, 200, dx.numel(), (0, dx.numel() - 1, Ci * H + 1))
+    want = oracle.conv_backward_data_points(dyh, wh, (H, H), st, pad, ix)
+    got = dx.reshape(-1)[torch.from_numpy(ix).cuda()].float().cpu().numpy()
+    scale = max(np.abs(want).max(), 1e-30)
+    assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-5 * scale), np.abs(got - want).max()
+    iw = _sample(rng, 24, dw.numel(), (0, dw.numel() - 1))
+    want = oracle.conv_backward_weight_points(xh, dyh, k, st, pad, iw)
+    got = dw.reshape(-1)[torch.from_numpy(iw).cuda()].cpu().numpy()
+    # fp32 accumulation over B*Ho*Wo (up to 3.2 M) bf16 products
+    assert np.abs(got - want).max() <= 3e-5 * np.abs(want).max() + 1e-3 * np.sqrt(B * Ho * Ho) * 2.0 ** -24 * 16, np.abs(got - want).max()
+
+
+def test_quantizer_full_gradient_bit_exact(dat):
+    """Config 5: b = 8 and b = 4 on the full 25.56 M-element gradient, 161 tensors."""
+    ref = oracle.Model(oracle.ARCH_RESNET50, 1, 224, 224, 1000, MEAN, STD)
+    g = syn.stress_gradient(5, ref.offsets)
+    gd = torch.from_numpy(g).cuda()
+    od = torch.from_numpy(ref.offsets).cuda()
+    seed = syn.seed_for(5, "quantizer")
+    for bits in (8, 4):
+        S = oracle.levels(bits)
+        codes, scales = oracle.quantize(g, ref.offsets, S, seed)
+        q, sc = dat.quantize(gd, od, bits, seed)
+        assert np.array_equal(sc.cpu().numpy(), scales)
+        assert np.array_equal(q.cpu().numpy(), oracle.pack(codes, bits))
+        out = dat.dequantize(q, sc, od, g.size, bits).cpu().numpy()
+        assert np.array_equal(out, oracle.dequantize(codes, scales, ref.offsets, S))
+
+
+def test_pgd_update_full_batch_bit_exact(dat):
+    eps, alpha = 2 / 255, 0.5 / 255
+    x = syn.images(6, B, 224, 224)
+    xd = torch.from_numpy(x).cuda()
+    seed = syn.seed_for(6, "attack_init")
+    d0 = dat.pgd_init(xd, eps, oracle.INIT_UNIFORM, seed)
+    want0 = oracle.init_delta(x, eps, oracle.INIT_UNIFORM, seed)
+    assert np.array_equal(d0.cpu().numpy(), want0)
+    G = np.random.default_rng(3).standard_normal(x.shape).astype(np.float32)
+    got = dat.pgd_update(xd, torch.from_numpy(G).cuda(), d0, eps, alpha).cpu().numpy()
+    assert np.array_equal(got, oracle.pgd_update(x, G, want0, eps, alpha))
+
+
+def test_attack_and_step_properties_at_full_size(dat):
+    eps, alpha, K = 4 / 255, 1 / 255, 3                      # config 5
+    model = dat.Model(dat.ARCH_RESNET50, dat.BF16, B, 224, 224, 1000, MEAN, STD)
+    theta = syn.he_normal_params(5, model.offsets, model.fan_in, model.kind)
+    model.set_params(theta)
+    x = syn.images(5, B, 224, 224)
+    y = syn.labels(5, B, 1000)
+    xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    seed = syn.seed_for(5, "attack_init")
+    delta, losses = model.attack(xd, yd, eps, alpha, K, dat.INIT_UNIFORM, seed=seed, want_losses=True)
+    d = delta.cpu().numpy()
+    assert np.abs(d).max() <= np.float32(eps)                 # exact, fp32
+    assert (x + d).min() >= 0.0 and (x + d).max() <= 1.0
+    assert np.isfinite(losses).all() and losses[-1] > losses[0]
+    # every step moves each coordinate by at most alpha from the clipped start
+    d0 = oracle.init_delta(x, eps, oracle.INIT_UNIFORM, seed)
+    assert np.abs(d - d0).max() <= K * np.float32(alpha) * (1 + 1e-6)
+    # determinism: same inputs, same bits
+    d2 = model.attack(xd, yd, eps, alpha, K, dat.INIT_UNIFORM, seed=seed).cpu().numpy()
+    assert np.array_equal(d, d2)
+    xadv = torch.from_numpy(oracle.make_xadv(x, d)).cuda()
+    g, loss = model.step(xadv, yd, want_loss=True)
+    g = g.cpu().numpy()
+    assert np.isfinite(g).all() and abs(loss - losses[-1]) < 2e-2 * abs(loss)
+    off, kind = model.offsets, model.kind
+    # classifier bias: sum_c dL/db_c = mean_n sum_c (softmax - onehot) = 0
+    tb = int(np.where(kind == 5)[0][0])
+    gb = g[off[tb]:off[tb + 1]]
+    assert abs(gb.sum()) < 1e-5 and np.abs(gb).max() > 1e-5
+    # every conv is followed by train-mode BN: the loss does not change when W is scaled, so
+    # <W, dL/dW> = 0 up to bf16 rounding of the stored tensors
+    worst = 0.0
+    for t in np.where(kind == 0)[0]:
+        wv, gv = theta[off[t]:off[t + 1]].astype(np.float64), g[off[t]:off[t + 1]].astype(np.float64)
+        worst = max(worst, abs(wv @ gv) / (np.linalg.norm(wv) * np.linalg.norm(gv) + 1e-300))
+    assert worst < 0.05, worst
+    model.close()

@@ -147,3 +147,18 @@ def test_bf16_storage_mode_rounds_and_stays_close():
     # the input gradient is a stored bf16 tensor times 1/std-free scale: on the bf16 grid
     g = torch.tensor(b["gx"])
     assert torch.equal(g, g.to(torch.bfloat16).to(torch.float32))
+
+
+def test_point_evaluators_agree_with_whole_tensor_convolution():
+    rng = np.random.default_rng(9)
+    for (k, stride, pad, H, W) in [(3, 1, 1, 6, 5), (3, 2, 1, 7, 8), (7, 2, 3, 12, 10), (1, 2, 0, 5, 5)]:
+        B, Ci, Co = 2, 3, 4
+        x = rng.standard_normal((B, H, W, Ci)).astype(np.float32)
+        w = rng.standard_normal((Co, k, k, Ci)).astype(np.float32)
+        y = oracle.conv_forward(x, w, stride, pad)
+        dy = rng.standard_normal(y.shape).astype(np.float32)
+        dx, dw = oracle.conv_backward(x, w, dy, stride, pad)
+        for full, pts in ((y, oracle.conv_forward_points(x, w, stride, pad, np.arange(y.size))),
+                          (dx, oracle.conv_backward_data_points(dy, w, (H, W), stride, pad, np.arange(dx.size))),
+                          (dw, oracle.conv_backward_weight_points(x, dy, k, stride, pad, np.arange(dw.size)))):
+            assert np.abs(full.reshape(-1) - pts).max() < 1e-12
