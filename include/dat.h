@@ -156,6 +156,28 @@ dat_status dat_dequantize(const uint8_t* q, const float* scales, const int64_t* 
 
 size_t dat_quantized_bytes(int64_t d, int bits);
 
+/* ---- after the worker block (next steps of Alg. A1) ----------------------------------------------
+ * dat_aggregate: the server's Eq. (grad_agg), g_hat = (1/M) sum_i Q(g^(i)), from M workers' packed
+ * codes and per-tensor scales (as written by dat_quantize, same `bits` and tensor table):
+ *   out[e] = (sum over i = 0..M-1, in this order, of code_i[e] * (scale_i[t] / S)) / M   in fp32, one
+ *   rounding per operation.  q, scales: HOST arrays of M DEVICE pointers (M <= DAT_MAX_WORKERS);
+ *   out: device fp32 [d].  A second, server-side quantization is dat_quantize applied to `out`.
+ * dat_lamb_update: the outer-minimisation oracle A(.) on the model's fp32 master parameters, the
+ *   layer-wise adaptive learning rate of Eq. (3) ("layer" = tensor of the table):
+ *     theta_i <- theta_i - eta * tau(||theta_i||_2) / ||u_i||_2 * u_i,  tau(x) = min(max(x, c_l), c_u)
+ *   with u = g + wd*theta (use_adam = 0) or the LAMB direction of Alg. A2 (use_adam = 1):
+ *     m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;  u = (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + zeta) + wd*theta,
+ *   t = 1, 2, ... the step number.  The moments live in the model (allocated on first use, zero).
+ *   A layer with ||u_i|| = 0 is left unchanged.  grads: device fp32 [d].  The bf16 compute copies
+ *   of the weights are refreshed afterwards. */
+#define DAT_MAX_WORKERS 32
+dat_status dat_aggregate(const uint8_t* const* q, const float* const* scales, int M,
+                         const int64_t* offsets_dev, int num_tensors, int64_t d, int bits, float* out,
+                         void* stream);
+dat_status dat_lamb_update(dat_model* m, const float* grads, int use_adam, float eta, float beta1,
+                           float beta2, float zeta, float weight_decay, float c_l, float c_u, int t,
+                           void* stream);
+
 /* ---- convolution kernels on their own (bf16 storage, fp32 accumulate on MFMA) --------------
  * The three contractions behind dat_attack / dat_step, exposed for per-shape parity tests and
  * timing.  Tensors are device bf16 (uint16 bit patterns): x [B,H,W,Cin], w [Cout,k,k,Cin],

@@ -70,6 +70,8 @@ _conv_f = _sig("orc_conv_forward", None, _f64p, _f64p, _f64p, *([C.c_int] * 8))
 _conv_b = _sig("orc_conv_backward", None, _f64p, _f64p, _f64p, _f64p, _f64p, *([C.c_int] * 8))
 _pts = [_sig(n, None, _f32p, _f32p, *([C.c_int] * 8), _i64p, C.c_int, _f64p)
         for n in ("orc_conv_forward_points", "orc_conv_bwd_data_points", "orc_conv_bwd_weight_points")]
+_lamb = _sig("orc_lamb_update", None, _f32p, _f32p, _f32p, _f32p, _i64p, C.c_int, C.c_int, *([C.c_double] * 7), C.c_int)
+_aggregate = _sig("orc_aggregate", None, C.c_void_p, C.c_void_p, C.c_int, _i64p, C.c_int, C.c_int, _f32p)
 _threads = _sig("orc_threads", C.c_int)
 
 
@@ -288,6 +290,27 @@ def conv_backward_weight_points(x, dy, k, stride, pad, idx):
     """Selected elements (flat indices into dw[Co,k,k,Ci]) of the adjoint w.r.t. the weights."""
     B, H, W, Ci = x.shape
     return _points(2, x, dy, (B, H, W, Ci, dy.shape[3], k, stride, pad), idx)
+
+
+def lamb_update(theta, m, v, g, offsets, use_adam, eta, b1=0.9, b2=0.999, zeta=1e-6, wd=0.0, c_l=0.0, c_u=10.0, t=1):
+    """In-place on copies: returns (theta, m, v) after one LALR/LAMB step (Eq. (3), Alg. A2)."""
+    theta = np.array(theta, np.float32, copy=True); m = np.array(m, np.float32, copy=True); v = np.array(v, np.float32, copy=True)
+    g = np.ascontiguousarray(g, np.float32); offsets = np.ascontiguousarray(offsets, np.int64)
+    _lamb(theta, m, v, g, offsets, offsets.size - 1, int(use_adam), eta, b1, b2, zeta, wd, c_l, c_u, t)
+    return theta, m, v
+
+
+def aggregate(codes_list, scales_list, offsets, S):
+    """g_hat = (1/M) sum_i dequantize(codes_i, scales_i)  (Eq. (grad_agg))."""
+    M = len(codes_list)
+    codes_list = [np.ascontiguousarray(c, np.int32) for c in codes_list]
+    scales_list = [np.ascontiguousarray(s, np.float32) for s in scales_list]
+    offsets = np.ascontiguousarray(offsets, np.int64)
+    cp = (C.c_void_p * M)(*[c.ctypes.data for c in codes_list])
+    sp = (C.c_void_p * M)(*[s.ctypes.data for s in scales_list])
+    out = np.zeros(codes_list[0].size, np.float32)
+    _aggregate(cp, sp, M, offsets, offsets.size - 1, S, out)
+    return out
 
 
 def threads():

@@ -977,6 +977,61 @@ void orc_unpack(const uint8_t* q, int64_t d, int bits, int32_t* codes) {
   }
 }
 
+// ----------------------------------------------------------------------------------------
+// Outer-minimisation oracle A(.): layer-wise adaptive learning rate, Eq. (3), with the descent
+// direction u of LAMB, Alg. A2 (use_adam = 1), or u = g (use_adam = 0).  "Layer" = one tensor
+// of the table.  Per element (Alg. A2): m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+// u = (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + zeta) [+ wd*theta: decoupled weight decay as in the
+// cited LAMB; wd = 0 gives the listing as printed].  Per layer i (Eq. (3)):
+//   theta_i <- theta_i - eta * tau(||theta_i||_2) / ||u_i||_2 * u_i,  tau(x) = min(max(x, c_l), c_u);
+// a layer with ||u_i|| = 0 is left unchanged.  fp64 arithmetic on fp32 state.
+void orc_lamb_update(float* theta, float* m, float* v, const float* g, const int64_t* offsets, int num_tensors,
+                     int use_adam, double eta, double b1, double b2, double zeta, double wd, double c_l, double c_u,
+                     int t) {
+  const double bc1 = 1.0 - std::pow(b1, t), bc2 = 1.0 - std::pow(b2, t);
+  for (int i = 0; i < num_tensors; ++i) {
+    const int64_t lo = offsets[i], hi = offsets[i + 1];
+    std::vector<double> u((size_t)(hi - lo));
+    double nth = 0.0, nu = 0.0;
+    for (int64_t e = lo; e < hi; ++e) {
+      double ue;
+      if (use_adam) {
+        const double mm = b1 * (double)m[e] + (1.0 - b1) * (double)g[e];
+        const double vv = b2 * (double)v[e] + (1.0 - b2) * (double)g[e] * (double)g[e];
+        m[e] = (float)mm; v[e] = (float)vv;
+        ue = ((double)m[e] / bc1) / (std::sqrt((double)v[e] / bc2) + zeta);
+      } else {
+        ue = (double)g[e];
+      }
+      ue += wd * (double)theta[e];
+      u[(size_t)(e - lo)] = ue;
+      nth += (double)theta[e] * (double)theta[e];
+      nu += ue * ue;
+    }
+    nth = std::sqrt(nth); nu = std::sqrt(nu);
+    if (!(nu > 0.0)) continue;
+    const double tau = std::min(std::max(nth, c_l), c_u);
+    const double rate = eta * tau / nu;
+    for (int64_t e = lo; e < hi; ++e) theta[e] = (float)((double)theta[e] - rate * u[(size_t)(e - lo)]);
+  }
+}
+
+// Server block, Eq. (grad_agg): g_hat = (1/M) sum_i Q(g^(i)), from M workers' codes and scales.
+// fp32, one rounding per operation, workers added in index order:  acc = acc + code*step_i; out = acc / M.
+void orc_aggregate(const int32_t* const* codes, const float* const* scales, int M, const int64_t* offsets,
+                   int num_tensors, int S, float* out) {
+  for (int t = 0; t < num_tensors; ++t)
+    for (int64_t e = offsets[t]; e < offsets[t + 1]; ++e) {
+      float acc = 0.0f;
+      for (int i = 0; i < M; ++i) {
+        const float step = scales[i][t] / (float)S;
+        const float term = (float)codes[i][e] * step;
+        acc = acc + term;
+      }
+      out[e] = acc / (float)M;
+    }
+}
+
 void orc_philox(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
   U4 c; std::memcpy(c.v, ctr, 16);
   U4 r = philox4x32_10(c, key[0], key[1]);

@@ -18,7 +18,7 @@ EXPORTS = [
     "dat_model_offsets_device", "dat_model_set_params", "dat_model_get_params", "dat_attack", "dat_step",
     "dat_input_grad", "dat_pgd_init", "dat_pgd_update", "dat_sgd_update", "dat_quantize", "dat_dequantize",
     "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
-    "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read",
+    "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read", "dat_aggregate", "dat_lamb_update",
 ]
 
 
@@ -69,6 +69,8 @@ _lib.dat_quantized_bytes.argtypes = [_i64, _i]
 for _n in ("dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight"):
     getattr(_lib, _n).argtypes = [_vp, _vp, _vp] + [_i] * 8 + [_vp]
 _lib.dat_philox_uniform.argtypes = [_u64, _i64, _u64, C.c_uint32, _vp, _vp]
+_lib.dat_aggregate.argtypes = [_vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp]
+_lib.dat_lamb_update.argtypes = [_vp, _vp, _i, _f, _f, _f, _f, _f, _f, _f, _i, _vp]
 _lib.dat_profile_enable.argtypes = [_vp, _i]
 _lib.dat_profile_read.argtypes = [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]
 PROF_CLASSES = ("conv_fwd", "conv_bwd_data", "conv_wgrad", "bn", "pgd")
@@ -168,6 +170,11 @@ class Model:
     def sgd_update(self, grads, lr, stream=None):
         _check(_lib.dat_sgd_update(self._h, _ptr(_dev(grads, torch.float32)), lr, _stream(stream)), "dat_sgd_update")
 
+    def lamb_update(self, grads, eta, use_adam=True, beta1=0.9, beta2=0.999, zeta=1e-6, weight_decay=0.0, c_l=0.0, c_u=10.0,
+                    t=1, stream=None):
+        _check(_lib.dat_lamb_update(self._h, _ptr(_dev(grads, torch.float32)), int(bool(use_adam)), eta, beta1, beta2, zeta,
+                                    weight_decay, c_l, c_u, int(t), _stream(stream)), "dat_lamb_update")
+
     def profile_enable(self, on=True):
         _check(_lib.dat_profile_enable(self._h, int(bool(on))), "dat_profile_enable")
 
@@ -229,6 +236,21 @@ def dequantize(q, scales, offsets_dev, d, bits, out=None, stream=None):
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=q.device)
     _check(_lib.dat_dequantize(_ptr(q), _ptr(scales), optr, T, d, bits, _ptr(out), _stream(stream)), "dat_dequantize")
+    return out
+
+
+def aggregate(q_list, scales_list, offsets_dev, d, bits, out=None, stream=None):
+    """g_hat = (1/M) sum_i dequantize(q_i, scales_i): Eq. (grad_agg) for M workers' quantized gradients."""
+    M = len(q_list)
+    if isinstance(offsets_dev, tuple):
+        optr, T = C.c_void_p(offsets_dev[0]), offsets_dev[1]
+    else:
+        optr, T = _ptr(offsets_dev), offsets_dev.numel() - 1
+    qp = (C.c_void_p * M)(*[t.data_ptr() for t in q_list])
+    sp = (C.c_void_p * M)(*[t.data_ptr() for t in scales_list])
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=q_list[0].device)
+    _check(_lib.dat_aggregate(qp, sp, M, optr, T, d, bits, _ptr(out), _stream(stream)), "dat_aggregate")
     return out
 
 

@@ -109,3 +109,26 @@ dat_status launch_sgd(float* theta, const float* g, float lr, int64_t n, hipStre
 dat_status launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 
 }  // namespace dat
+
+namespace dat {
+
+// ---- optimizer and aggregation (optim.hip) -------------------------------------------------------
+struct LambParams {
+  int use_adam;
+  float eta, b1, b2, zeta, wd, c_l, c_u;
+  float inv_bc1, inv_bc2;      // 1/(1-b1^t), 1/(1-b2^t)
+};
+// One LALR/LAMB step on the flat fp32 vectors; `norms` is a scratch of 2*T doubles.
+dat_status launch_lamb(float* theta, const float* g, float* m, float* v, float* u, const int64_t* off, int T, int64_t d,
+                       const LambParams& hp, double* norms, hipStream_t st);
+
+struct AggregateArgs {
+  const uint8_t* q[DAT_MAX_WORKERS];
+  const float* scales[DAT_MAX_WORKERS];
+  int M, T;
+  const int64_t* offsets;
+  int64_t d;
+  float* out;
+};
+
+}  // namespace dat

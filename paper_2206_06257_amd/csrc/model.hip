@@ -10,6 +10,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include <algorithm>
+#include <math.h>
 #include <vector>
 #include "kernels.h"
 
@@ -61,6 +62,7 @@ struct dat_model {
   float* gx = nullptr;
   void* wgrad_ws = nullptr; size_t wgrad_ws_bytes = 0;
   float* host_stage = nullptr;       // pinned staging for loss values
+  float* opt_m = nullptr; float* opt_v = nullptr; float* opt_u = nullptr; double* opt_norms = nullptr;   // LAMB state
   // optional per-launch timing (dat_profile_*): one event pair per launch group
   bool prof = false;
   struct ProfRec { int cls; hipEvent_t a, b; double work; };
@@ -627,5 +629,29 @@ extern "C" dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, 
   if (ms_total) *ms_total = ms;
   if (launches) *launches = n;
   if (work) *work = w;
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_lamb_update(dat_model* m, const float* grads, int use_adam, float eta, float beta1, float beta2,
+                                      float zeta, float weight_decay, float c_l, float c_u, int t, void* stream) {
+  if (!m || !grads || t < 1 || !(eta >= 0.0f) || !(c_u >= c_l)) return DAT_ERR_ARG;
+  if (use_adam && (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f))) return DAT_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  if (!m->opt_u) {
+    DAT_TRY(dev_alloc(*m, &m->opt_m, (size_t)m->d * 4));
+    DAT_TRY(dev_alloc(*m, &m->opt_v, (size_t)m->d * 4));
+    DAT_TRY(dev_alloc(*m, &m->opt_u, (size_t)m->d * 4));
+    DAT_TRY(dev_alloc(*m, &m->opt_norms, m->ptab.size() * 2 * sizeof(double)));
+    DAT_TRY(launch_fill_zero(m->opt_m, (size_t)m->d * 4, st));
+    DAT_TRY(launch_fill_zero(m->opt_v, (size_t)m->d * 4, st));
+  }
+  LambParams hp;
+  hp.use_adam = use_adam ? 1 : 0; hp.eta = eta; hp.b1 = beta1; hp.b2 = beta2; hp.zeta = zeta; hp.wd = weight_decay;
+  hp.c_l = c_l; hp.c_u = c_u;
+  hp.inv_bc1 = use_adam ? (float)(1.0 / (1.0 - pow((double)beta1, t))) : 1.0f;
+  hp.inv_bc2 = use_adam ? (float)(1.0 / (1.0 - pow((double)beta2, t))) : 1.0f;
+  DAT_TRY(launch_lamb(m->master, grads, m->opt_m, m->opt_v, m->opt_u, m->offsets_dev, (int)m->ptab.size(), m->d, hp,
+                      m->opt_norms, st));
+  DAT_TRY(refresh_compute(*m, st));
   return DAT_OK;
 }
