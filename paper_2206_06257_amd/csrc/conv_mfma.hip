@@ -97,17 +97,15 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   constexpr int LDS_BYTES = (2 * TILE_BYTES > TP * STG_STRIDE) ? 2 * TILE_BYTES : TP * STG_STRIDE;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
 
-  // XCD-aware tile numbering: workgroup ids congruent mod 8 run on the same XCD (one L2 each).
-  // Each XCD gets one contiguous eighth of the pixel tiles, and all channel tiles of a pixel tile,
-  // so that the rows shared by neighbouring tiles (filter halos) and by the channel tiles are
-  // fetched into one L2 only.
+  // XCD-aware tile numbering: workgroup ids congruent mod 8 run on the same XCD (one L2 each), so
+  // all channel tiles of a pixel tile get ids 8 apart and share the gathered activations in one L2.
+  // Pixel tiles advance through the tensor in dispatch order, which lets the next kernel start from
+  // the most recently written rows.
   const int bid = blockIdx.x;
   const int q = bid >> 3;
   const int ct = q % a.nct;
-  const int per_xcd = (a.npt + 7) >> 3;
-  const int pidx = q / a.nct;
-  const int pt = (bid & 7) * per_xcd + pidx;
-  if (pidx >= per_xcd || pt >= a.npt) return;
+  const int pt = (q / a.nct) * 8 + (bid & 7);
+  if (pt >= a.npt) return;
   const int c0 = ct * TC, m0 = pt * TP;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

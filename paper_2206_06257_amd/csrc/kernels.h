@@ -75,13 +75,14 @@ size_t fold_floats(int nslabs, int C);
 dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
                              float* dgamma, float scale, hipStream_t st);
 // out = act(gamma*((x-mean)*rstd) + beta [+ res])
-dat_status bnact_forward(const void* x, const void* res, void* out, int dtype, int64_t rows, int C, const float* mean,
+// mask (optional, rows*C/8 bytes): bit j of byte e/8 = (out[e] > 0), what the backward pass needs of `out`.
+dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mask, int dtype, int64_t rows, int C, const float* mean,
                          const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st);
 // dy = dout masked by (out > 0) if relu.  sums[0..C) = sum dy (= dbeta), sums[C..2C) = sum dy*xhat (= dgamma).
 // Then dx (+)= gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows); dres (+)= dy.
 // dgamma/dbeta (fp32, may be null) receive scale*sums.
 // sums_ready: `sums` already holds the two sums (and dgamma/dbeta were written): only apply.
-dat_status bnact_backward(const void* x, const void* out, const void* dout, void* dx, bool dx_accumulate, void* dres,
+dat_status bnact_backward(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
                           bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
                           const float* gamma, int relu, float* partial, float* sums, bool sums_ready, float* dgamma,
                           float* dbeta, float scale, hipStream_t st);

@@ -68,6 +68,7 @@ SlabPlan plan_slabs(int64_t rows, int C, int max_slabs) {
 // MODE 2: (sum dy, 0)                 -- bias backward
 template <typename T, int MODE>
 __global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, const T* __restrict__ out,
+                                                       const uint8_t* __restrict__ mask,
                                                        const T* __restrict__ dout, const float* __restrict__ mean,
                                                        const float* __restrict__ rstd, int relu, int64_t rows, int C,
                                                        int tpr, int rpp, int64_t rows_per_slab,
@@ -87,13 +88,18 @@ __global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, 
     constexpr int U = 4;
     for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
       float xv[U][8], gv[U][8], ov[U][8];
+      uint32_t mk[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int64_t r = rb + (int64_t)u * rpp;
         const int64_t o = r * C + c0;
+        mk[u] = 0xffu;
         if (r < r1) {
           if (MODE == 0 || MODE == 1) V8<T>::load(x + o, xv[u]);
-          if (MODE != 0) { V8<T>::load(dout + o, gv[u]); if (relu) V8<T>::load(out + o, ov[u]); }
+          if (MODE != 0) {
+            V8<T>::load(dout + o, gv[u]);
+            if (relu) { if (mask) mk[u] = mask[o >> 3]; else V8<T>::load(out + o, ov[u]); }
+          }
         }
       }
 #pragma unroll
@@ -105,8 +111,13 @@ __global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, 
             for (int j = 0; j < 8; ++j) { a1[j] += xv[u][j]; a2[j] += xv[u][j] * xv[u][j]; }
           } else {
             if (relu) {
+              if (mask) {
 #pragma unroll
-              for (int j = 0; j < 8; ++j) if (!(ov[u][j] > 0.f)) gv[u][j] = 0.f;
+                for (int j = 0; j < 8; ++j) if (!((mk[u] >> j) & 1u)) gv[u][j] = 0.f;
+              } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) if (!(ov[u][j] > 0.f)) gv[u][j] = 0.f;
+              }
             }
             if (MODE == 1) {
 #pragma unroll
@@ -187,7 +198,7 @@ __global__ __launch_bounds__(kT) void slab_fold_kernel(const float* __restrict__
 
 template <typename T>
 __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, const T* __restrict__ res,
-                                                       T* __restrict__ out, int64_t rows, int C, int tpr, int rpp,
+                                                       T* __restrict__ out, uint8_t* __restrict__ mask, int64_t rows, int C, int tpr, int rpp,
                                                        int64_t rows_per_slab,
                                                        const float* __restrict__ mean, const float* __restrict__ rstd,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
@@ -197,7 +208,9 @@ __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, 
   const int c0 = cv * 8;
   float mu[8], rs[8], ga[8], be[8];
   load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(beta + c0, be);
-  const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
+  // slabs are walked from the end of the tensor: the rows the producing kernel wrote (or the
+  // preceding reduction read) last are still in the 256 MB memory-side cache
+  const int64_t r0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * rows_per_slab;
   const int64_t r1 = min(rows, r0 + rows_per_slab);
   constexpr int U = 4;
   for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
@@ -212,13 +225,18 @@ __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, 
       const int64_t r = rb + (int64_t)u * rpp;
       if (r < r1) {
         float o[8];
+        uint32_t bits = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           o[j] = ga[j] * ((xv[u][j] - mu[j]) * rs[j]) + be[j];
           if (res) o[j] += rv[u][j];
           if (relu) o[j] = o[j] > 0.f ? o[j] : 0.f;
+          bits |= (o[j] > 0.f ? 1u : 0u) << j;
         }
         V8<T>::store(out + r * C + c0, o);
+        // one bit per element: out > 0 (what the backward pass needs of `out`); a positive fp32
+        // value never rounds to zero in the storage type, so this equals the sign of the stored value
+        if (mask) mask[(r * C + c0) >> 3] = (uint8_t)bits;
       }
     }
   }
@@ -226,6 +244,7 @@ __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, 
 
 template <typename T>
 __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ out,
+                                                             const uint8_t* __restrict__ mask,
                                                              const T* __restrict__ dout, T* __restrict__ dx,
                                                              int dx_acc, T* __restrict__ dres, int dres_acc,
                                                              int64_t rows, int C, int tpr, int rpp, int64_t rows_per_slab,
@@ -238,18 +257,22 @@ __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict
   const int c0 = cv * 8;
   float mu[8], rs[8], ga[8], s1[8], s2[8];
   load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(sums + c0, s1); load8f(sums + C + c0, s2);
-  const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
+  // slabs are walked from the end of the tensor: the rows the producing kernel wrote (or the
+  // preceding reduction read) last are still in the 256 MB memory-side cache
+  const int64_t r0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * rows_per_slab;
   const int64_t r1 = min(rows, r0 + rows_per_slab);
   constexpr int U = 2;
   for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
     float g[U][8], xv[U][8], ov[U][8], od[U][8], orr[U][8];
+    uint32_t mk[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = rb + (int64_t)u * rpp;
+      mk[u] = 0xffu;
       if (r < r1) {
         const int64_t o = r * C + c0;
         V8<T>::load(dout + o, g[u]); V8<T>::load(x + o, xv[u]);
-        if (relu) V8<T>::load(out + o, ov[u]);
+        if (relu) { if (mask) mk[u] = mask[o >> 3]; else V8<T>::load(out + o, ov[u]); }
         if (dx_acc) V8<T>::load(dx + o, od[u]);
         if (dres && dres_acc) V8<T>::load(dres + o, orr[u]);
       }
@@ -261,8 +284,13 @@ __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict
         const int64_t o = r * C + c0;
         float q[8];
         if (relu) {
+          if (mask) {
 #pragma unroll
-          for (int j = 0; j < 8; ++j) if (!(ov[u][j] > 0.f)) g[u][j] = 0.f;
+            for (int j = 0; j < 8; ++j) if (!((mk[u] >> j) & 1u)) g[u][j] = 0.f;
+          } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) if (!(ov[u][j] > 0.f)) g[u][j] = 0.f;
+          }
         }
         if (dres) {
 #pragma unroll
@@ -521,10 +549,10 @@ __global__ void zero_kernel(uint32_t* __restrict__ p, int64_t nwords) {
 inline unsigned nblk(int64_t n) { return (unsigned)((n + kT - 1) / kT); }
 
 template <typename T, int MODE>
-dat_status colreduce(const void* x, const void* out, const void* dout, const float* mean, const float* rstd, int relu,
+dat_status colreduce(const void* x, const void* out, const uint8_t* mask, const void* dout, const float* mean, const float* rstd, int relu,
                      int64_t rows, int C, float* partial, hipStream_t st, SlabPlan& p) {
   p = plan_slabs(rows, C, kMaxSlabs);
-  hipLaunchKernelGGL((colreduce_kernel<T, MODE>), dim3(p.nslabs), dim3(kT), 0, st, (const T*)x, (const T*)out,
+  hipLaunchKernelGGL((colreduce_kernel<T, MODE>), dim3(p.nslabs), dim3(kT), 0, st, (const T*)x, (const T*)out, mask,
                      (const T*)dout, mean, rstd, relu, rows, C, p.tpr, p.rpp, p.rows_per_slab, partial);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
@@ -559,8 +587,8 @@ dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, in
 dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partial, float* mean, float* rstd, hipStream_t st) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
   SlabPlan p; dat_status s;
-  DAT_BY_DTYPE(dtype, s = (colreduce<float, 0>(x, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)),
-               s = (colreduce<bf16_t, 0>(x, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)));
+  DAT_BY_DTYPE(dtype, s = (colreduce<float, 0>(x, nullptr, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)),
+               s = (colreduce<bf16_t, 0>(x, nullptr, nullptr, nullptr, nullptr, nullptr, 0, rows, C, partial, st, p)));
   if (s != DAT_OK) return s;
   hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, mean, rstd,
                      (float*)nullptr, (float*)nullptr, 1.0f);
@@ -568,26 +596,26 @@ dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partia
   return DAT_OK;
 }
 
-dat_status bnact_forward(const void* x, const void* res, void* out, int dtype, int64_t rows, int C, const float* mean,
+dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mask, int dtype, int64_t rows, int C, const float* mean,
                          const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
   const SlabPlan p = plan_slabs(rows, C, kMaxApplySlabs);
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_fwd_kernel<float>, dim3(p.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)res, (float*)out, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu),
-    hipLaunchKernelGGL(bnact_fwd_kernel<bf16_t>, dim3(p.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)res, (bf16_t*)out, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu));
+    hipLaunchKernelGGL(bnact_fwd_kernel<float>, dim3(p.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)res, (float*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu),
+    hipLaunchKernelGGL(bnact_fwd_kernel<bf16_t>, dim3(p.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)res, (bf16_t*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
 
-dat_status bnact_backward(const void* x, const void* out, const void* dout, void* dx, bool dx_accumulate, void* dres,
+dat_status bnact_backward(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
                           bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
                           const float* gamma, int relu, float* partial, float* sums, bool sums_ready, float* dgamma,
                           float* dbeta, float scale, hipStream_t st) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
   if (!sums_ready) {
     SlabPlan p; dat_status s;
-    DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)),
-                 s = (colreduce<bf16_t, 1>(x, out, dout, mean, rstd, relu, rows, C, partial, st, p)));
+    DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, mask, dout, mean, rstd, relu, rows, C, partial, st, p)),
+                 s = (colreduce<bf16_t, 1>(x, out, mask, dout, mean, rstd, relu, rows, C, partial, st, p)));
     if (s != DAT_OK) return s;
     hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
                        dbeta, dgamma, scale);
@@ -596,8 +624,8 @@ dat_status bnact_backward(const void* x, const void* out, const void* dout, void
   const float inv_rows = (float)(1.0 / (double)rows);
   const SlabPlan q = plan_slabs(rows, C, kMaxApplySlabs);
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, inv_rows, mean, rstd, gamma, sums, relu),
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, inv_rows, mean, rstd, gamma, sums, relu));
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, mask, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, inv_rows, mean, rstd, gamma, sums, relu),
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, mask, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, inv_rows, mean, rstd, gamma, sums, relu));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -616,8 +644,8 @@ dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
   if (dbias) {
     SlabPlan p; dat_status s;
-    DAT_BY_DTYPE(dtype, s = (colreduce<float, 2>(nullptr, out, dout, nullptr, nullptr, relu, rows, C, partial, st, p)),
-                 s = (colreduce<bf16_t, 2>(nullptr, out, dout, nullptr, nullptr, relu, rows, C, partial, st, p)));
+    DAT_BY_DTYPE(dtype, s = (colreduce<float, 2>(nullptr, out, nullptr, dout, nullptr, nullptr, relu, rows, C, partial, st, p)),
+                 s = (colreduce<bf16_t, 2>(nullptr, out, nullptr, dout, nullptr, nullptr, relu, rows, C, partial, st, p)));
     if (s != DAT_OK) return s;
     hipLaunchKernelGGL(colfinal_kernel<2>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, dbias,
                        (float*)nullptr, dbias, (float*)nullptr, scale);

@@ -33,6 +33,7 @@ struct Op {
   float* mean = nullptr;        // BN batch statistics of the last forward
   uint8_t* argmax = nullptr;    // max-pool: window position of the maximum, per output element
   float* rstd = nullptr;
+  uint8_t* mask = nullptr;      // BN with ReLU: one bit per output element (out > 0), read by the backward pass
   float* sums = nullptr;        // BN backward: [2][C] sums (sum dy, sum dy*xhat)
   bool sums_ready = false;      //   ... already produced by the convolution that completed d(out)
   bool stats_from_conv = false; // BN forward: mean/rstd come from the producing convolution's epilogue
@@ -273,6 +274,7 @@ dat_status allocate(dat_model& m) {
       DAT_TRY(dev_alloc(m, &op.mean, (size_t)m.tens[op.in].C * 4));
       DAT_TRY(dev_alloc(m, &op.rstd, (size_t)m.tens[op.in].C * 4));
       DAT_TRY(dev_alloc(m, &op.sums, (size_t)m.tens[op.in].C * 8));
+      if (op.relu) DAT_TRY(dev_alloc(m, &op.mask, (size_t)m.maxB * m.tens[op.in].numel() / 8));
     }
     if (op.kind == OP_MAXPOOL) DAT_TRY(dev_alloc(m, &op.argmax, (size_t)m.maxB * m.tens[op.out].numel()));
     if (op.kind == OP_CONV && m.dtype == DAT_BF16) {
@@ -332,7 +334,7 @@ NetInputDesc input_desc(const dat_model& m) {
 
 dat_status bn_forward_pair(dat_model& m, Op& op, int64_t rows, int C, hipStream_t st) {
   if (!op.stats_from_conv) DAT_TRY(bn_stats(m.act[op.in], m.dtype, rows, C, m.partial, op.mean, op.rstd, st));
-  return bnact_forward(m.act[op.in], op.res >= 0 ? m.act[op.res] : nullptr, m.act[op.out], m.dtype, rows, C, op.mean,
+  return bnact_forward(m.act[op.in], op.res >= 0 ? m.act[op.res] : nullptr, m.act[op.out], op.mask, m.dtype, rows, C, op.mean,
                        op.rstd, m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off, op.relu, st);
 }
 
@@ -425,7 +427,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         const bool dres_acc = op.res >= 0 && m.ghas[op.res];
         // algorithmic bytes: read x, out, dout once each; write dx (and dres)
         DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (4 + (op.res >= 0)), st,
-                 bnact_backward(m.act[op.in], m.act[op.out], m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
+                 bnact_backward(m.act[op.in], m.act[op.out], op.mask, m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
                                 si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.sums_ready, g0, g1, 1.0f, st));
         op.sums_ready = false;
         if (op.res >= 0) m.ghas[op.res] = 1;
