@@ -457,40 +457,52 @@ __global__ __launch_bounds__(kT) void gap_bwd_kernel(const float* __restrict__ d
 }
 
 // ---- linear classifier (fp32) --------------------------------------------------------------
-// one wavefront per output logit: lanes stride over the input features
-__global__ __launch_bounds__(kT) void fc_fwd_kernel(const float* __restrict__ f, const float* __restrict__ W,
-                                                    const float* __restrict__ b, float* __restrict__ z, int B, int I, int O) {
-  const int64_t wave = ((int64_t)blockIdx.x * kT + threadIdx.x) >> 6;
-  const int lane = threadIdx.x & 63;
-  if (wave >= (int64_t)B * O) return;
-  const int n = (int)(wave / O), o = (int)(wave % O);
-  float acc = 0.f;
-  for (int i = lane; i < I; i += 64) acc += f[(int64_t)n * I + i] * W[(int64_t)o * I + i];
+// One small tiled SGEMM serves the three products of the layer:
+//   C[m][n] = scale * sum_k A(m,k) * B(k,n) (+ bias[n]),  A(m,k) = A[m*sAm + k*sAk],  B(k,n) = B[k*sBk + n*sBn].
+// 32x32 output tile per workgroup, 32-deep k tiles staged in LDS (padded rows), each thread four
+// outputs.  The matrices are a few MB; the point is only not to be latency-bound.
+__global__ __launch_bounds__(kT) void sgemm_kernel(const float* __restrict__ A, const float* __restrict__ Bm,
+                                                   const float* __restrict__ bias, float* __restrict__ Cm, int M, int N,
+                                                   int K, int64_t sAm, int64_t sAk, int64_t sBk, int64_t sBn, float scale) {
+  __shared__ float As[32][33], Bs[32][33];           // As[m][k], Bs[n][k]
+  const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
+  const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < K; k0 += 32) {
 #pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
-  if (lane == 0) z[(int64_t)n * O + o] = acc + b[o];
+    for (int j = 0; j < 4; ++j) {
+      const int idx = tid + 256 * j;
+      // walk the unit-stride dimension with consecutive threads
+      const int am = sAk == 1 ? idx >> 5 : idx & 31, ak = sAk == 1 ? idx & 31 : idx >> 5;
+      As[am][ak] = (m0 + am < M && k0 + ak < K) ? A[(int64_t)(m0 + am) * sAm + (int64_t)(k0 + ak) * sAk] : 0.f;
+      const int bn = sBk == 1 ? idx >> 5 : idx & 31, bk = sBk == 1 ? idx & 31 : idx >> 5;
+      Bs[bn][bk] = (n0 + bn < N && k0 + bk < K) ? Bm[(int64_t)(k0 + bk) * sBk + (int64_t)(n0 + bn) * sBn] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+      const float bv = Bs[tx][k];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[r] += As[ty + 8 * r][k] * bv;
+    }
+    __syncthreads();
+  }
+  const int n = n0 + tx;
+  if (n < N) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int m = m0 + ty + 8 * r;
+      if (m < M) Cm[(int64_t)m * N + n] = acc[r] * scale + (bias ? bias[n] : 0.f);
+    }
+  }
 }
 
-__global__ __launch_bounds__(kT) void fc_bwd_input_kernel(const float* __restrict__ W, const float* __restrict__ dz,
-                                                          float* __restrict__ df, int B, int I, int O) {
-  const int64_t t = (int64_t)blockIdx.x * kT + threadIdx.x;
-  if (t >= (int64_t)B * I) return;
-  const int n = (int)(t / I), i = (int)(t % I);
-  float acc = 0.f;
-  for (int o = 0; o < O; ++o) acc += dz[(int64_t)n * O + o] * W[(int64_t)o * I + i];
-  df[t] = acc;
-}
-
-__global__ __launch_bounds__(kT) void fc_bwd_weight_kernel(const float* __restrict__ f, const float* __restrict__ dz,
-                                                           float* __restrict__ dW, float* __restrict__ db, int B, int I,
-                                                           int O, float scale) {
-  const int64_t t = (int64_t)blockIdx.x * kT + threadIdx.x;
-  if (t >= (int64_t)O * I) return;
-  const int o = (int)(t / I), i = (int)(t % I);
-  float acc = 0.f, sb = 0.f;
-  for (int n = 0; n < B; ++n) { const float g = dz[(int64_t)n * O + o]; acc += g * f[(int64_t)n * I + i]; sb += g; }
-  dW[t] = acc * scale;
-  if (i == 0) db[o] = sb * scale;
+__global__ void fc_bias_grad_kernel(const float* __restrict__ dz, float* __restrict__ db, int B, int O, float scale) {
+  const int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= O) return;
+  float s = 0.f;
+  for (int n = 0; n < B; ++n) s += dz[(int64_t)n * O + o];
+  db[o] = s * scale;
 }
 
 // ---- softmax cross-entropy: one wavefront per sample ------------------------------------------
@@ -696,18 +708,29 @@ dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dty
   return DAT_OK;
 }
 
-dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, hipStream_t st) {
-  hipLaunchKernelGGL(fc_fwd_kernel, dim3(nblk((int64_t)B * O * 64)), dim3(kT), 0, st, f, W, b, logits, B, I, O);
+static dat_status sgemm(const float* A, const float* Bm, const float* bias, float* Cm, int M, int N, int K, int64_t sAm,
+                        int64_t sAk, int64_t sBk, int64_t sBn, float scale, hipStream_t st) {
+  hipLaunchKernelGGL(sgemm_kernel, dim3((N + 31) / 32, (M + 31) / 32), dim3(kT), 0, st, A, Bm, bias, Cm, M, N, K, sAm, sAk, sBk,
+                     sBn, scale);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
 
+dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, hipStream_t st) {
+  // logits[n][o] = sum_i f[n][i] * W[o][i] + b[o]
+  return sgemm(f, W, b, logits, B, O, I, I, 1, 1, I, 1.0f, st);
+}
+
 dat_status fc_backward(const float* f, const float* W, const float* dz, float* df, float* dW, float* db, int B, int I, int O,
                        float scale, hipStream_t st) {
-  hipLaunchKernelGGL(fc_bwd_input_kernel, dim3(nblk((int64_t)B * I)), dim3(kT), 0, st, W, dz, df, B, I, O);
-  DAT_LAUNCH_CHECK();
+  // df[n][i] = sum_o dz[n][o] * W[o][i]
+  dat_status s = sgemm(dz, W, nullptr, df, B, I, O, O, 1, I, 1, 1.0f, st);
+  if (s != DAT_OK) return s;
   if (dW) {
-    hipLaunchKernelGGL(fc_bwd_weight_kernel, dim3(nblk((int64_t)O * I)), dim3(kT), 0, st, f, dz, dW, db, B, I, O, scale);
+    // dW[o][i] = scale * sum_n dz[n][o] * f[n][i];  db[o] = scale * sum_n dz[n][o]
+    s = sgemm(dz, f, nullptr, dW, O, I, B, 1, O, I, 1, scale, st);
+    if (s != DAT_OK) return s;
+    hipLaunchKernelGGL(fc_bias_grad_kernel, dim3((O + 255) / 256), dim3(256), 0, st, dz, db, B, O, scale);
     DAT_LAUNCH_CHECK();
   }
   return DAT_OK;
