@@ -123,21 +123,27 @@ def main():
     for i in range(args.warmup):
         one_step(i)
     torch.cuda.synchronize()
-    if not args.no_launch_events:
-        model.profile_enable(True)
-    start = torch.cuda.Event(enable_timing=True)
+    # ---- timed region: exactly `steps` steps, nothing else on the stream
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    start.record()
     for i in range(args.steps):
         starts[i].record()
         one_step(args.warmup + i, ev[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    prof = model.profile_read() if not args.no_launch_events else None
-    if prof:
+    # ---- the same steps once more with a hipEvent pair around every launch (per-kernel-class times
+    # for the roofline); kept out of the timed region because ~2700 event pairs per step cost ~7 %
+    prof = None
+    if not args.no_launch_events:
+        model.profile_enable(True)
+        tp0 = time.perf_counter()
+        for i in range(args.steps):
+            one_step(args.warmup + args.steps + i)
+        torch.cuda.synchronize()
+        ms_per_step_events = (time.perf_counter() - tp0) * 1e3 / args.steps
+        prof = model.profile_read()
         model.profile_enable(False)
 
     t_attack = np.mean([starts[i].elapsed_time(ev[i][0]) for i in range(args.steps)])
@@ -179,6 +185,7 @@ def main():
             out["pgd_update"] = {"GBs": pg[2] / (pg[0] * 1e-3) / 1e9, "frac_hbm": pg[2] / (pg[0] * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                  "bytes_per_element": 18}
         total_flops = sum(prof[k][2] for k in ("conv_fwd", "conv_bwd_data", "conv_wgrad")) / args.steps
+        out["roofline"]["measured_over"] = "%d further steps of the same work with a hipEvent pair around every launch (%.1f ms/step with events)" % (args.steps, ms_per_step_events)
         out["step_conv_TFLOPs"] = total_flops / 1e12
         out["step_frac_mfma_peak"] = total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
     if not args.no_cpu_baseline:

@@ -26,6 +26,7 @@
 // (v_perm_b32) and stores pixel-contiguous rows to LDS, so the MFMA fragments are again
 // 16-byte reads.  The pixel range is split over gridDim.z; partial tiles go to a workspace
 // and a second kernel sums them in a fixed order (deterministic).
+#include <atomic>
 #include "kernels.h"
 
 namespace dat {
@@ -354,7 +355,10 @@ dat_status pick_depth(const IgemmArgs& a, hipStream_t st) {
   return launch_igemm<TC, TP, WGC, 3, 32>(a, st);
 }
 
+std::atomic<int64_t> g_launches{0};
+
 dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
+  g_launches.fetch_add(1, std::memory_order_relaxed);
   if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
   if (a.Cout <= 32) return pick_depth<32, 128, 1>(a, st);
   if (a.Cout <= 64) return pick_depth<64, 128, 2>(a, st);
@@ -404,6 +408,49 @@ __global__ void weight_transform_kernel(const float* __restrict__ master, bf16_t
     const int ii = (r - ch.rf) / 2, jj = (s - cw.rf) / 2;
     wT[base * Cin * Cout + (((int64_t)ci * ch.nr + (ch.nr - 1 - ii)) * cw.nr + (cw.nr - 1 - jj)) * Cout + co] = v;
   }
+}
+
+// ---- 7x7 stride-2 pad-3 stem as a 4x4 stride-1 convolution over 2x2 pixel blocks -----------------
+// With 3 (padded to 8) input channels the stem wastes most of a 32-row MFMA tile in backward-data
+// and needs a per-vector tap decode in forward.  Storing the network input as 2x2 pixel blocks,
+//   x2[n][i][j][(ph*2+pw)*8 + c] = x[n][2i+ph][2j+pw][c]      (H, W even),
+// turns it into a dense layer with 32 input channels:
+//   forward:       y[ho][wo][co]  = sum_{a,b<4} sum_v  x2[ho-2+a][wo-2+b][v] * Vf[co][a][b][v]
+//                  Vf[co][a][b][(ph,pw,c)] = W[co][2a+ph-1][2b+pw-1][c]
+//   backward-data: dx2[i][j][v]   = sum_{a,b<4} sum_co dy[i-1+a][j-1+b][co] * Vb[v][a][b][co]
+//                  Vb[(ph,pw,c)][a][b][co] = W[co][5+ph-2a][5+pw-2b][c]
+// (filter taps outside 0..6 and channels c >= 3 are zero: 49 of the 64 window/parity pairs are
+// used), one launch each, all four pixel parities of the input gradient at once.
+__global__ void stem_weight_transform_kernel(const float* __restrict__ master, bf16_t* __restrict__ vf, bf16_t* __restrict__ vb,
+                                             int Cout, int cin_real) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= Cout * 16 * 32) return;
+  {   // vf[co][a][b][v]
+    const int v = i & 31, b = (i >> 5) & 3, a = (i >> 7) & 3, co = i >> 9;
+    const int ph = v >> 4, pw = (v >> 3) & 1, c = v & 7;
+    const int r = 2 * a + ph - 1, s = 2 * b + pw - 1;
+    const bool ok = c < cin_real && r >= 0 && r < 7 && s >= 0 && s < 7;
+    vf[i] = ok ? f2bf(master[((co * 7 + r) * 7 + s) * cin_real + c]) : (bf16_t)0;
+  }
+  {   // vb[v][a][b][co]
+    const int co = i % Cout; int t = i / Cout;
+    const int b = t & 3, a = (t >> 2) & 3, v = t >> 4;
+    const int ph = v >> 4, pw = (v >> 3) & 1, c = v & 7;
+    const int r = 5 + ph - 2 * a, s = 5 + pw - 2 * b;
+    const bool ok = c < cin_real && r >= 0 && r < 7 && s >= 0 && s < 7;
+    vb[i] = ok ? f2bf(master[((co * 7 + r) * 7 + s) * cin_real + c]) : (bf16_t)0;
+  }
+}
+
+// dW[co][r][s][c] = dVf[co][a][b][(ph,pw,c)] with r = 2a+ph-1, s = 2b+pw-1
+__global__ void stem_wgrad_gather_kernel(const float* __restrict__ dv, float* __restrict__ dw, int Cout, int cin_real) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= Cout * 49 * cin_real) return;
+  const int c = i % cin_real; int t = i / cin_real;
+  const int s = t % 7; t /= 7;
+  const int r = t % 7; const int co = t / 7;
+  const int ph = (r + 1) & 1, a = (r + 1) >> 1, pw = (s + 1) & 1, b = (s + 1) >> 1;
+  dw[i] = dv[((co * 4 + a) * 4 + b) * 32 + (ph * 2 + pw) * 8 + c];
 }
 
 // ---- backward-weight ----------------------------------------------------------------------------
@@ -589,6 +636,8 @@ static void set_stats(IgemmArgs& a, const ConvStats* s, int slab0) {
   a.stat_mode = 1; a.stat_partial = s->partial;
 }
 
+int64_t conv_mfma_launch_count() { return g_launches.load(std::memory_order_relaxed); }
+
 constexpr int kPixelTile = 128;   // TP of every configuration run_igemm selects
 
 int conv_stat_slabs(int64_t rows, int stride) {
@@ -642,6 +691,47 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
   return DAT_OK;
 }
 
+// ---- stem on 2x2 pixel blocks ---------------------------------------------------------------------
+bool conv_mfma_stem_blocked_ok(const ConvGeom& g, int cin_real) {
+  return g.k == 7 && g.stride == 2 && g.pad == 3 && g.Cin == 8 && cin_real <= 8 && g.H % 2 == 0 && g.W % 2 == 0 && g.Cout % 8 == 0;
+}
+
+ConvGeom conv_mfma_stem_blocked_geom(const ConvGeom& g) {
+  ConvGeom q = g;
+  q.H = g.H / 2; q.W = g.W / 2; q.Cin = 32; q.k = 4; q.stride = 1; q.pad = 2;   // Ho, Wo, Cout unchanged
+  return q;
+}
+
+dat_status launch_stem_weight_transform(const float* master, bf16_t* vf, bf16_t* vb, int Cout, int cin_real, hipStream_t st) {
+  const int n = Cout * 16 * 32;
+  hipLaunchKernelGGL(stem_weight_transform_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, master, vf, vb, Cout, cin_real);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
+  IgemmArgs a;
+  a.in = x2; a.wt = vf; a.res = nullptr; a.out = y;
+  a.B = g.B; a.Hin = g.H / 2; a.Win = g.W / 2; a.Cin = 32; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
+  a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 2;
+  a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
+  a.M = g.B * g.Ho * g.Wo; a.Ktot = 16 * 32; a.nct = a.npt = 0;
+  set_stats(a, stats, 0);
+  if (stats) stats->nslabs = (a.M + kPixelTile - 1) / kPixelTile;
+  return run_igemm(a, st);
+}
+
+dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16_t* dx2, const ConvGeom& g, bool accumulate, hipStream_t st) {
+  IgemmArgs a;
+  a.in = dy; a.wt = vb; a.res = accumulate ? dx2 : nullptr; a.out = dx2;
+  a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H / 2; a.Wout = g.W / 2; a.Cout = 32;
+  a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 1;
+  a.outH = a.Hout; a.outW = a.Wout; a.ostep = 1; a.oh0 = a.ow0 = 0;
+  a.M = g.B * a.Hout * a.Wout; a.Ktot = 16 * g.Cout; a.nct = a.npt = 0;
+  set_stats(a, nullptr, 0);
+  return run_igemm(a, st);
+}
+
 dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale,
                                      void* ws, hipStream_t st) {
   if (g.Cin % 8 != 0 || g.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
@@ -666,6 +756,18 @@ dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, i
                                    int pad, hipStream_t st) {
   const int64_t n = (int64_t)Cout * k * k * Cin;
   hipLaunchKernelGGL(weight_transform_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, master, w, wT, Cout, k, cin_real, Cin, stride, pad);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+// dw [Cout][7][7][cin_real] through the blocked layer's gradient dv [Cout][4][4][32] (scratch, fp32).
+dat_status conv_mfma_stem_backward_weight(const bf16_t* x2, const bf16_t* dy, float* dw, float* dv, int cin_real, const ConvGeom& g,
+                                          float scale, void* ws, hipStream_t st) {
+  const ConvGeom q = conv_mfma_stem_blocked_geom(g);
+  const dat_status s = conv_mfma_backward_weight(x2, dy, dv, 32, q, scale, ws, st);
+  if (s != DAT_OK) return s;
+  const int n = g.Cout * 49 * cin_real;
+  hipLaunchKernelGGL(stem_wgrad_gather_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)dv, dw, g.Cout, cin_real);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }

@@ -537,12 +537,18 @@ __global__ void round_bf16_kernel(const float* __restrict__ src, float* __restri
   if (i < n) dst[i] = bf2f(f2bf(src[i]));
 }
 
+// bh, bw > 0: g0 is stored as 2x2 pixel blocks of a bh x bw image ([bh/2][bw/2][4*Cpad] per sample)
 template <typename T>
 __global__ void input_grad_kernel(const T* __restrict__ g0, int Cpad, int64_t rows, float s0, float s1, float s2,
-                                  float* __restrict__ gx) {
+                                  float* __restrict__ gx, int bh, int bw) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= rows * 3) return;
-  const int64_t r = i / 3; const int c = (int)(i % 3);
+  int64_t r = i / 3; const int c = (int)(i % 3);
+  if (bw) {
+    const uint32_t pix = (uint32_t)r, w = pix % (uint32_t)bw, hn = pix / (uint32_t)bw;
+    const uint32_t h = hn % (uint32_t)bh, n = hn / (uint32_t)bh;
+    r = ((int64_t)(n * (uint32_t)(bh >> 1) + (h >> 1)) * (uint32_t)(bw >> 1) + (w >> 1)) * 4 + (h & 1u) * 2 + (w & 1u);
+  }
   float v;
   if (sizeof(T) == 2) v = bf2f(((const bf16_t*)g0)[r * Cpad + c]); else v = ((const float*)g0)[r * Cpad + c];
   gx[i] = __fmul_rn(v, c == 0 ? s0 : (c == 1 ? s1 : s2));
@@ -752,10 +758,12 @@ dat_status launch_round_bf16_values(const float* src, float* dst, int64_t n, hip
   return DAT_OK;
 }
 
-dat_status launch_input_grad(const void* g0, int dtype, int Cpad, int64_t rows, float s0, float s1, float s2, float* gx, hipStream_t st) {
+dat_status launch_input_grad(const void* g0, int dtype, int Cpad, int64_t rows, float s0, float s1, float s2, float* gx,
+                             int block_h, int block_w, hipStream_t st) {
+  if (rows >= (1ll << 32)) return DAT_ERR_UNSUPPORTED;
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(input_grad_kernel<float>, dim3(nblk(rows * 3)), dim3(kT), 0, st, (const float*)g0, Cpad, rows, s0, s1, s2, gx),
-    hipLaunchKernelGGL(input_grad_kernel<bf16_t>, dim3(nblk(rows * 3)), dim3(kT), 0, st, (const bf16_t*)g0, Cpad, rows, s0, s1, s2, gx));
+    hipLaunchKernelGGL(input_grad_kernel<float>, dim3(nblk(rows * 3)), dim3(kT), 0, st, (const float*)g0, Cpad, rows, s0, s1, s2, gx, block_h, block_w),
+    hipLaunchKernelGGL(input_grad_kernel<bf16_t>, dim3(nblk(rows * 3)), dim3(kT), 0, st, (const bf16_t*)g0, Cpad, rows, s0, s1, s2, gx, block_h, block_w));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }

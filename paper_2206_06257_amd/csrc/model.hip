@@ -38,6 +38,8 @@ struct Op {
   bool sums_ready = false;      //   ... already produced by the convolution that completed d(out)
   bool stats_from_conv = false; // BN forward: mean/rstd come from the producing convolution's epilogue
   int fwd_bn = -1;              // conv: BN op normalising this conv's output (statistics fused into the epilogue)
+  bool blocked = false;         // conv: 7x7/2 stem run on the 2x2-pixel-block layout of the network input
+  float* dv = nullptr;          //   its weight gradient in the blocked layer's shape, [Cout][4][4][32]
 };
 
 struct PTensor { int64_t off, numel; int fan_in, kind; };
@@ -66,7 +68,7 @@ struct dat_model {
   float* opt_m = nullptr; float* opt_v = nullptr; float* opt_u = nullptr; double* opt_norms = nullptr;   // LAMB state
   // optional per-launch timing (dat_profile_*): one event pair per launch group
   bool prof = false;
-  struct ProfRec { int cls; hipEvent_t a, b; double work; };
+  struct ProfRec { int cls; hipEvent_t a, b; double work; int64_t nlaunch; };
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> pool;
   hipEvent_t take_event() {
@@ -207,6 +209,16 @@ bool build_graph(dat_model& m) {
         op.stats_from_conv = true;
       }
     }
+    // the ImageNet stem runs on 2x2 pixel blocks of the network input (tensor 0 is stored blocked)
+    Op& first = m.ops[0];
+    if (first.kind == OP_CONV && first.in == 0 && first.res < 0) {
+      ConvGeom g;
+      g.B = 1; g.H = m.tens[0].H; g.W = m.tens[0].W; g.Cin = m.tens[0].C; g.Ho = m.tens[first.out].H; g.Wo = m.tens[first.out].W;
+      g.Cout = m.tens[first.out].C; g.k = first.k; g.stride = first.stride; g.pad = first.pad;
+      bool only_consumer = true;
+      for (size_t i = 1; i < m.ops.size(); ++i) if (m.ops[i].in == 0 || m.ops[i].res == 0) only_consumer = false;
+      first.blocked = only_consumer && conv_mfma_stem_blocked_ok(g, first.cin_real);
+    }
   }
   return true;
 }
@@ -225,14 +237,18 @@ dat_status dev_alloc(dat_model& m, T** p, size_t bytes) {
 #define DAT_TRY(expr) do { dat_status s_ = (expr); if (s_ != DAT_OK) return s_; } while (0)
 
 // Launch group `expr` of class `cls` doing `work` algorithmic FLOPs or bytes; timed when profiling.
+// A group counts as one launch unless it ran MFMA convolution kernels, which are counted one by one
+// (a stride-2 backward-data pass is four of them).
 #define DAT_PROF(m, cls, work, st, expr)                                            \
   do {                                                                              \
     if ((m).prof) {                                                                 \
-      dat_model::ProfRec r_{(cls), (m).take_event(), (m).take_event(), (double)(work)}; \
+      dat_model::ProfRec r_{(cls), (m).take_event(), (m).take_event(), (double)(work), 1}; \
       if (r_.a && r_.b) {                                                           \
+        const int64_t n0_ = conv_mfma_launch_count();                               \
         DAT_HIP(hipEventRecord(r_.a, (st)));                                        \
         DAT_TRY(expr);                                                              \
         DAT_HIP(hipEventRecord(r_.b, (st)));                                        \
+        if (conv_mfma_launch_count() > n0_) r_.nlaunch = conv_mfma_launch_count() - n0_; \
         (m).recs.push_back(r_);                                                     \
       } else { DAT_TRY(expr); }                                                     \
     } else { DAT_TRY(expr); }                                                       \
@@ -278,10 +294,12 @@ dat_status allocate(dat_model& m) {
     }
     if (op.kind == OP_MAXPOOL) DAT_TRY(dev_alloc(m, &op.argmax, (size_t)m.maxB * m.tens[op.out].numel()));
     if (op.kind == OP_CONV && m.dtype == DAT_BF16) {
-      const size_t n = (size_t)m.tens[op.out].C * op.k * op.k * m.tens[op.in].C;
+      const size_t n = op.blocked ? (size_t)m.tens[op.out].C * 16 * 32 : (size_t)m.tens[op.out].C * op.k * op.k * m.tens[op.in].C;
       DAT_TRY(dev_alloc(m, &op.w16, n * 2));
       DAT_TRY(dev_alloc(m, &op.w16T, n * 2));
-      const size_t need = conv_mfma_wgrad_workspace(geom_of(m, op, m.maxB));
+      if (op.blocked) DAT_TRY(dev_alloc(m, &op.dv, n * 4));
+      const ConvGeom gmax = geom_of(m, op, m.maxB);
+      const size_t need = conv_mfma_wgrad_workspace(op.blocked ? conv_mfma_stem_blocked_geom(gmax) : gmax);
       ws = need > ws ? need : ws;
     }
   }
@@ -316,7 +334,9 @@ dat_status refresh_compute(dat_model& m, hipStream_t st) {
   if (m.dtype != DAT_BF16) return DAT_OK;
   DAT_HIP(hipMemcpyAsync(m.compute, m.master, (size_t)m.d * 4, hipMemcpyDeviceToDevice, st));
   for (Op& op : m.ops) {
-    if (op.kind == OP_CONV)
+    if (op.kind == OP_CONV && op.blocked)
+      DAT_TRY(launch_stem_weight_transform(m.master + m.ptab[op.p0].off, op.w16, op.w16T, m.tens[op.out].C, op.cin_real, st));
+    else if (op.kind == OP_CONV)
       DAT_TRY(launch_weight_transform(m.master + m.ptab[op.p0].off, op.w16, op.w16T, m.tens[op.out].C, op.k, op.cin_real,
                                       m.tens[op.in].C, op.stride, op.pad, st));
     if (op.kind == OP_FC)
@@ -329,6 +349,8 @@ NetInputDesc input_desc(const dat_model& m) {
   NetInputDesc d;
   d.ptr = m.act[0]; d.bf16 = m.dtype == DAT_BF16; d.normalize = m.normalize;
   for (int c = 0; c < 3; ++c) { d.mean[c] = m.mean[c]; d.inv_std[c] = m.inv_std[c]; }
+  const bool blocked = m.ops[0].kind == OP_CONV && m.ops[0].blocked;
+  d.block_h = blocked ? m.H : 0; d.block_w = blocked ? m.W : 0;
   return d;
 }
 
@@ -350,7 +372,8 @@ dat_status forward(dat_model& m, int B, hipStream_t st) {
         if (dt == DAT_BF16) {
           ConvStats cs{};
           cs.mode = op.fwd_bn >= 0 ? 1 : 0; cs.partial = m.partial;
-          DAT_PROF(m, DAT_PROF_CONV_FWD, conv_flops(g, op.cin_real), st, conv_mfma_forward((const bf16_t*)m.act[op.in], op.w16, (const bf16_t*)res, (bf16_t*)m.act[op.out], g, &cs, st));
+          if (op.blocked) DAT_PROF(m, DAT_PROF_CONV_FWD, conv_flops(g, op.cin_real), st, conv_mfma_stem_forward((const bf16_t*)m.act[op.in], op.w16, (bf16_t*)m.act[op.out], g, &cs, st));
+          else DAT_PROF(m, DAT_PROF_CONV_FWD, conv_flops(g, op.cin_real), st, conv_mfma_forward((const bf16_t*)m.act[op.in], op.w16, (const bf16_t*)res, (bf16_t*)m.act[op.out], g, &cs, st));
           if (cs.mode) {   // batch statistics of the normalisation that follows, from the epilogue's partial sums
             Op& bn = m.ops[op.fwd_bn];
             DAT_PROF(m, DAT_PROF_BN, 0.0, st, bn_finalize_slabs(m.partial, cs.nslabs, so.C, (int64_t)B * so.H * so.W, 1, bn.mean, bn.rstd, nullptr, nullptr, 1.0f, st));
@@ -408,11 +431,13 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
           m.ghas[op.res] = 1;
         }
         if (g0) {
-          if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, st));
+          if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_mfma_stem_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.dv, op.cin_real, g, 1.0f, m.wgrad_ws, st));
+          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, st));
           else DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_direct_backward_weight((const float*)m.act[op.in], (const float*)m.grad[op.out], g0, g, 1.0f, st));
         }
         if (op.in != 0 || need_input_grad) {
-          if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], nullptr, st));
+          if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_stem_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
+          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], nullptr, st));
           else DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_direct_backward_data((const float*)m.grad[op.out], m.compute + m.ptab[op.p0].off, (float*)m.grad[op.in], g, m.ghas[op.in], st));
           m.ghas[op.in] = 1;
         }
@@ -454,8 +479,9 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
 
 dat_status pixel_grad(dat_model& m, int B, float* gx, hipStream_t st) {
   const bool n = m.normalize;
+  const bool blocked = m.ops[0].kind == OP_CONV && m.ops[0].blocked;
   return launch_input_grad(m.grad[0], m.dtype, m.tens[0].C, (int64_t)B * m.H * m.W, n ? m.inv_std[0] : 1.0f,
-                           n ? m.inv_std[1] : 1.0f, n ? m.inv_std[2] : 1.0f, gx, st);
+                           n ? m.inv_std[1] : 1.0f, n ? m.inv_std[2] : 1.0f, gx, blocked ? m.H : 0, blocked ? m.W : 0, st);
 }
 
 dat_status fetch_losses(dat_model& m, int count, float* host_out, hipStream_t st) {
@@ -626,7 +652,7 @@ extern "C" dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, 
     if (r.cls != cls) continue;
     float t = 0.f;
     DAT_HIP(hipEventElapsedTime(&t, r.a, r.b));
-    ms += t; w += r.work; ++n;
+    ms += t; w += r.work; n += r.nlaunch;
   }
   if (ms_total) *ms_total = ms;
   if (launches) *launches = n;

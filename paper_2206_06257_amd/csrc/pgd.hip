@@ -25,7 +25,7 @@ __device__ __forceinline__ float sign_step(float d, float g, float eps, float al
   return clampf(__fadd_rn(d, s), -eps, eps);
 }
 
-struct InArgs { void* ptr; int bf16; int normalize; float m0, m1, m2, s0, s1, s2; };
+struct InArgs { void* ptr; int bf16; int normalize; float m0, m1, m2, s0, s1, s2; int bh, bw; };
 
 __device__ __forceinline__ float net_value(float x, float d, bool has_delta, const InArgs& a, int c) {
   float v = has_delta ? clampf(__fadd_rn(x, d), 0.0f, 1.0f) : x;
@@ -114,13 +114,19 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
 #pragma unroll
     for (int j = 0; j < 12; ++j) nv[j] = net_value(xv[j], dv[j], has_delta, in, j % 3);
     if (in.bf16) {
-      uint4* dst = reinterpret_cast<uint4*>(in.ptr) + p0;     // 8 bf16 = 16 bytes per pixel
+      uint4* dst = reinterpret_cast<uint4*>(in.ptr);          // 8 bf16 = 16 bytes per pixel
       for (int p = 0; p < np; ++p) {
         uint4 o;
         o.x = (uint32_t)f2bf(nv[3 * p]) | ((uint32_t)f2bf(nv[3 * p + 1]) << 16);
         o.y = (uint32_t)f2bf(nv[3 * p + 2]);
         o.z = 0u; o.w = 0u;
-        dst[p] = o;
+        int64_t slot = p0 + p;
+        if (in.bw) {   // 2x2 pixel blocks: pixel (n,h,w) -> block (n, h/2, w/2), position (h%2)*2 + w%2
+          const uint32_t pix = (uint32_t)slot, w = pix % (uint32_t)in.bw, hn = pix / (uint32_t)in.bw;
+          const uint32_t h = hn % (uint32_t)in.bh, n = hn / (uint32_t)in.bh;
+          slot = ((int64_t)(n * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1) + (w >> 1)) * 4 + (h & 1u) * 2 + (w & 1u);
+        }
+        dst[slot] = o;
       }
     } else {
       float* dst = reinterpret_cast<float*>(in.ptr) + e0;
@@ -140,12 +146,13 @@ InArgs pack(const NetInputDesc& d) {
   a.ptr = d.ptr; a.bf16 = d.bf16; a.normalize = d.normalize;
   a.m0 = d.mean[0]; a.m1 = d.mean[1]; a.m2 = d.mean[2];
   a.s0 = d.inv_std[0]; a.s1 = d.inv_std[1]; a.s2 = d.inv_std[2];
+  a.bh = d.bf16 ? d.block_h : 0; a.bw = d.bf16 ? d.block_w : 0;
   return a;
 }
 
 unsigned grid_for(int64_t npix) { return (unsigned)(((npix + 3) / 4 + kThreads - 1) / kThreads); }
 
-const NetInputDesc kNoInput = {nullptr, 0, 0, {0, 0, 0}, {1, 1, 1}};
+const NetInputDesc kNoInput = {nullptr, 0, 0, {0, 0, 0}, {1, 1, 1}, 0, 0};
 
 }  // namespace
 
