@@ -21,12 +21,14 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 
 typedef uint16_t bf16_t;   // raw bf16 bit pattern
 
-// fp32 -> bf16, round to nearest even; NaN stays NaN.
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// fp32 -> bf16, round to nearest even; NaN stays (quiet) NaN.  Compiles to v_cvt_pk_bf16_f32, whose
+// results equal the integer formulation (u + 0x7fff + lsb) >> 16 for every non-NaN input.
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values in one instruction: `lo` in bits 0..15, `hi` in bits 16..31
+__device__ __forceinline__ uint32_t f2bf_pack(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 

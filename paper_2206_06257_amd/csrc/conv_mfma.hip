@@ -280,8 +280,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
           v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xffff0000u);
         }
         uint2 pk;
-        pk.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
-        pk.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+        pk.x = f2bf_pack(v[0], v[1]);
+        pk.y = f2bf_pack(v[2], v[3]);
         *reinterpret_cast<uint2*>(lds + prow * STG_STRIDE + ch * 2) = pk;
       }
     }

@@ -37,7 +37,7 @@ template <> struct V8<bf16_t> {
   static __device__ __forceinline__ void store(bf16_t* p, const float v[8]) {
     uint32_t w[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w[j] = (uint32_t)f2bf(v[2 * j]) | ((uint32_t)f2bf(v[2 * j + 1]) << 16);
+    for (int j = 0; j < 4; ++j) w[j] = f2bf_pack(v[2 * j], v[2 * j + 1]);
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 };

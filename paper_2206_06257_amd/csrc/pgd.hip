@@ -117,7 +117,7 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
       uint4* dst = reinterpret_cast<uint4*>(in.ptr);          // 8 bf16 = 16 bytes per pixel
       for (int p = 0; p < np; ++p) {
         uint4 o;
-        o.x = (uint32_t)f2bf(nv[3 * p]) | ((uint32_t)f2bf(nv[3 * p + 1]) << 16);
+        o.x = f2bf_pack(nv[3 * p], nv[3 * p + 1]);
         o.y = (uint32_t)f2bf(nv[3 * p + 2]);
         o.z = 0u; o.w = 0u;
         int64_t slot = p0 + p;
