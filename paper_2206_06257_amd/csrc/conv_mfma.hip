@@ -262,34 +262,47 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(IgemmArgs a) {
   // accumulator element e of lane l in tile (i,j): channel = 8*(e/4) + 4*(l/32) + e%4, pixel = l%32.
   // All four waves stage their block at once (one barrier), then every thread streams 16-byte
   // channel vectors of whole pixel rows to global memory.
+  // A residual (or the previously stored gradient) is first brought into the staging buffer with
+  // the same coalesced 16-byte accesses the stores use; each lane then adds its accumulators to
+  // the values at its own staging slots in fp32 and rounds once, in place.
+  constexpr int CV = TC / 8;                       // channel vectors per pixel row
+  constexpr int RPP = kThreads / CV;               // pixel rows per store sweep
+  const int cv = tid % CV, pr0 = tid / CV;
+  const int ch = c0 + cv * 8;
+  if (a.res) {
+    uint4 rv[TP / RPP];
+#pragma unroll
+    for (int u = 0; u < TP / RPP; ++u) {
+      const int m = m0 + pr0 + u * RPP;
+      rv[u] = (m < a.M && ch < a.Cout) ? *reinterpret_cast<const uint4*>(a.res + out_row(a, m) * a.Cout + ch) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    // (the main loop ended with a barrier: every wave is done with the operand tiles)
+#pragma unroll
+    for (int u = 0; u < TP / RPP; ++u) *reinterpret_cast<uint4*>(lds + (pr0 + u * RPP) * STG_STRIDE + cv * 16) = rv[u];
+    __syncthreads();
+  }
 #pragma unroll
   for (int i = 0; i < NI; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int prow = wp * WP + j * 32 + (lane & 31);
-      const int m = m0 + prow;
-      int64_t orow = 0;
-      if (a.res && m < a.M) orow = out_row(a, m);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int ch = wc * WC + i * 32 + 8 * g + 4 * (lane >> 5);
+        const int chl = wc * WC + i * 32 + 8 * g + 4 * (lane >> 5);
         float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        if (a.res && m < a.M && c0 + ch < a.Cout) {
-          const uint2 r = *reinterpret_cast<const uint2*>(a.res + orow * a.Cout + c0 + ch);
+        uint2* slot = reinterpret_cast<uint2*>(lds + prow * STG_STRIDE + chl * 2);
+        if (a.res) {
+          const uint2 r = *slot;
           v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xffff0000u);
           v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xffff0000u);
         }
         uint2 pk;
         pk.x = f2bf_pack(v[0], v[1]);
         pk.y = f2bf_pack(v[2], v[3]);
-        *reinterpret_cast<uint2*>(lds + prow * STG_STRIDE + ch * 2) = pk;
+        *slot = pk;
       }
     }
   __syncthreads();
-  constexpr int CV = TC / 8;                       // channel vectors per pixel row
-  constexpr int RPP = kThreads / CV;               // pixel rows per store sweep
-  const int cv = tid % CV, pr0 = tid / CV;
-  const int ch = c0 + cv * 8;
   float s1[8], s2[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) { s1[j] = 0.f; s2[j] = 0.f; }
