@@ -28,6 +28,12 @@ WORKLOADS = {
     "resnet50_224_b256_pgd3": (3, 224, 224, 1000, 256, 3, 4 / 255, 1 / 255, True, 5),
     "resnet18_cifar_b512_pgd10": (1, 32, 32, 10, 512, 10, 8 / 255, 2 / 255, False, 2),
     "wrn34_10_b256_pgd10": (2, 32, 32, 10, 256, 10, 8 / 255, 2 / 255, False, 3),
+    # the models and shapes of the paper's own runs (Sec. "Experiment setup", "Training setting"):
+    # pre-activation ResNet-18 and WRN-28-10 on 32x32, ResNet-50 with 85 images per GPU and PGD-4
+    # (alpha = 2.5 eps / K, the convention of the configurations above; the paper gives no PGD step size)
+    "preact_resnet18_cifar_b512_pgd10": (4, 32, 32, 10, 512, 10, 8 / 255, 2 / 255, False, 7),
+    "wrn28_10_b256_pgd10": (5, 32, 32, 10, 256, 10, 8 / 255, 2 / 255, False, 8),
+    "resnet50_224_b85_pgd4": (3, 224, 224, 1000, 85, 4, 2 / 255, 1.25 / 255, True, 9),
 }
 PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0

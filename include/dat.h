@@ -59,6 +59,9 @@ typedef enum {
   DAT_ARCH_RESNET18_CIFAR = 1,  /* post-activation BasicBlocks [2,2,2,2], widths 64..512          */
   DAT_ARCH_WRN34_10 = 2,        /* pre-activation wide blocks, widths 160/320/640                 */
   DAT_ARCH_RESNET50 = 3,        /* Bottleneck [3,4,6,3], stride on the 3x3, 7x7 stem + max-pool   */
+  DAT_ARCH_PREACT_RESNET18 = 4, /* pre-activation BasicBlocks [2,2,2,2], widths 64..512 (the      */
+                                /* paper's CIFAR "ResNet-18", Sec. "Experiment setup")            */
+  DAT_ARCH_WRN28_10 = 5,        /* pre-activation wide blocks, 4 per group (semi-supervised runs) */
   DAT_ARCH_TESTNET = 100        /* small net containing every op kind (for parity tests)          */
 } dat_arch;
 

@@ -9,6 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdat_oracle.so")
 
 ARCH_TINYCNN, ARCH_RESNET18_CIFAR, ARCH_WRN34_10, ARCH_RESNET50, ARCH_TESTNET, ARCH_LINEAR = 0, 1, 2, 3, 100, 101
+ARCH_PREACT_RESNET18, ARCH_WRN28_10 = 4, 5
 INIT_ZERO, INIT_UNIFORM, INIT_GIVEN = 0, 1, 2
 
 

@@ -189,7 +189,8 @@ struct Model {
 
 // Architectures.  The paper only names them (Sec. "Experiment setup"); the shapes are the
 // standard ones of the cited architecture papers.
-enum { ARCH_TINYCNN = 0, ARCH_RESNET18_CIFAR = 1, ARCH_WRN34_10 = 2, ARCH_RESNET50 = 3, ARCH_TESTNET = 100, ARCH_LINEAR = 101 };
+enum { ARCH_TINYCNN = 0, ARCH_RESNET18_CIFAR = 1, ARCH_WRN34_10 = 2, ARCH_RESNET50 = 3, ARCH_PREACT_RESNET18 = 4, ARCH_WRN28_10 = 5,
+       ARCH_TESTNET = 100, ARCH_LINEAR = 101 };
 
 void build_tinycnn(Model& m) {
   int t = 0;
@@ -254,6 +255,20 @@ void build_wrn(Model& m, int depth, int widen) {
   const int widths[3] = {16 * widen, 32 * widen, 64 * widen};
   for (int g = 0; g < 3; ++g)
     for (int b = 0; b < n; ++b) t = wide_block(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
+  t = m.bnact(t, 1);
+  t = m.gap(t);
+  m.fc(t, m.classes);
+}
+
+// Pre-activation ResNet-18 (Sec. "Experiment setup": the CIFAR model the paper calls ResNet-18;
+// He et al., identity mappings): a 3x3 stem without normalisation, pre-activation basic blocks
+// [2,2,2,2] of widths 64..512 (the shortcut convolution reads the activated input), a final
+// BN + ReLU, pooling and the classifier.  The block is the wide block with widening factor 1.
+void build_preact_resnet18(Model& m) {
+  int t = m.conv(0, 64, 3, 1, 1);
+  const int widths[4] = {64, 128, 256, 512};
+  for (int g = 0; g < 4; ++g)
+    for (int b = 0; b < 2; ++b) t = wide_block(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
   t = m.bnact(t, 1);
   t = m.gap(t);
   m.fc(t, m.classes);
@@ -757,6 +772,8 @@ void* orc_model_create(int arch, int bf16_storage, int H, int W, int num_classes
     case ARCH_RESNET18_CIFAR: build_resnet18_cifar(*m); break;
     case ARCH_WRN34_10: build_wrn(*m, 34, 10); break;
     case ARCH_RESNET50: build_resnet50(*m); break;
+    case ARCH_PREACT_RESNET18: build_preact_resnet18(*m); break;
+    case ARCH_WRN28_10: build_wrn(*m, 28, 10); break;
     case ARCH_TESTNET: build_testnet(*m); break;
     case ARCH_LINEAR: build_linear(*m); break;
     default: delete m; return nullptr;

@@ -163,11 +163,21 @@ bool build_graph(dat_model& m) {
         for (int b = 0; b < 2; ++b) t = basic_block(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
       break;
     }
-    case DAT_ARCH_WRN34_10: {
+    case DAT_ARCH_WRN34_10:
+    case DAT_ARCH_WRN28_10: {
+      const int per_group = m.arch == DAT_ARCH_WRN34_10 ? 5 : 4;   // (depth - 4) / 6
       t = m.conv(t, 16, 3, 1, 1);
       const int widths[3] = {160, 320, 640};
       for (int g = 0; g < 3; ++g)
-        for (int b = 0; b < 5; ++b) t = wide_block(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
+        for (int b = 0; b < per_group; ++b) t = wide_block(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
+      t = m.bnact(t, 1);
+      break;
+    }
+    case DAT_ARCH_PREACT_RESNET18: {   // pre-activation basic block = wide block of widening factor 1
+      t = m.conv(t, 64, 3, 1, 1);
+      const int widths[4] = {64, 128, 256, 512};
+      for (int g = 0; g < 4; ++g)
+        for (int b = 0; b < 2; ++b) t = wide_block(m, t, widths[g], (b == 0 && g > 0) ? 2 : 1);
       t = m.bnact(t, 1);
       break;
     }

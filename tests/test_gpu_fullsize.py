@@ -104,8 +104,11 @@ def test_pgd_update_full_batch_bit_exact(dat):
     assert np.array_equal(got, oracle.pgd_update(x, G, want0, eps, alpha))
 
 
-def test_attack_and_step_properties_at_full_size(dat):
-    eps, alpha, K = 4 / 255, 1 / 255, 3                      # config 5
+@pytest.mark.parametrize("B,eps,alpha,K", [
+    (256, 4 / 255, 1 / 255, 3),          # config 5
+    (85, 2 / 255, 1.25 / 255, 4),        # the paper's own ImageNet shape: 85 images per GPU, PGD-4 (odd batch: tile tails)
+])
+def test_attack_and_step_properties_at_full_size(dat, B, eps, alpha, K):
     model = dat.Model(dat.ARCH_RESNET50, dat.BF16, B, 224, 224, 1000, MEAN, STD)
     theta = syn.he_normal_params(5, model.offsets, model.fan_in, model.kind)
     model.set_params(theta)

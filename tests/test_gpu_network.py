@@ -106,6 +106,8 @@ CASES = [
     (1, 16, 16, 16, 10, False),     # CIFAR ResNet-18, reduced image
     (2, 4, 8, 8, 10, False),        # WRN-34-10, reduced image
     (3, 6, 96, 96, 12, True),       # ResNet-50, reduced image and classes
+    (4, 12, 16, 16, 10, False),     # pre-activation ResNet-18, reduced image
+    (5, 5, 8, 8, 10, False),        # WRN-28-10, reduced image, odd batch
 ]
 
 
@@ -151,7 +153,9 @@ def test_fp32_models_match_fp64_reference(dat, arch, B, H, W, classes, norm):
     for k in range(3):
         d1 = gpu.attack(xd, yd, EPS, ALPHA, 1, dat.INIT_GIVEN, delta0=_cuda(tr["delta"][k])).cpu().numpy()
         disagree = 1.0 - float((d1 == tr["delta"][k + 1]).mean())
-        assert disagree <= max(1e-3, 2 * fl["sign"]), (k, disagree)
+        # (with ~10^3 coordinates the 1e-3 bar is less than one coordinate: one whose gradient sits at
+        # rounding level may take the other sign)
+        assert disagree <= max(1e-3, 2 * fl["sign"], 1.5 / d1.size), (k, disagree)
     d_gpu = gpu.attack(xd, yd, EPS, ALPHA, 3, dat.INIT_UNIFORM, seed=5).cpu().numpy()
     assert np.abs(d_gpu).max() <= np.float32(EPS) and (x + d_gpu).min() >= 0 and (x + d_gpu).max() <= 1
 

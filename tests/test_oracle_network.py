@@ -71,10 +71,11 @@ def _setup(arch, H, W, classes, B, cfg=7, norm=False):
 
 @pytest.mark.parametrize("arch,H,W,classes,B,norm", [
     (100, 16, 16, 5, 4, True), (0, 8, 8, 10, 3, False), (1, 8, 8, 10, 4, False),
-    (2, 8, 8, 10, 2, False), (3, 64, 64, 12, 3, True), (101, 2, 2, 2, 3, False)])
+    (2, 8, 8, 10, 2, False), (3, 64, 64, 12, 3, True), (101, 2, 2, 2, 3, False),
+    (4, 8, 8, 10, 4, False), (5, 8, 8, 10, 2, False)])
 @pytest.mark.parametrize("reduction", ["sum", "mean"])
 def test_network_matches_autograd_mirror(arch, H, W, classes, B, norm, reduction):
-    if arch in (2, 3) and reduction == "mean":
+    if arch in (2, 3, 4, 5) and reduction == "mean":
         pytest.skip("one reduction is enough for the large nets")
     m, theta, x, y = _setup(arch, H, W, classes, B, norm=norm)
     loss, gx, gt = m.loss_f64(theta, x, y, reduction, want_grads=True)

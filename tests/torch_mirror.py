@@ -87,10 +87,16 @@ def logits(arch, flat, x_nhwc, classes, mean=None, std=None):
         for g, w in enumerate([64, 128, 256, 512]):
             for b in range(2):
                 x = _basic(p, x, w, 2 if (b == 0 and g > 0) else 1)
-    elif arch == 2:    # WRN-34-10
+    elif arch in (2, 5):    # WRN-34-10, WRN-28-10
         x = _conv(p, x, 16, 3, 1, 1)
         for g, w in enumerate([160, 320, 640]):
-            for b in range(5):
+            for b in range(5 if arch == 2 else 4):
+                x = _wide(p, x, w, 2 if (b == 0 and g > 0) else 1)
+        x = _bn(p, x, True)
+    elif arch == 4:    # pre-activation ResNet-18
+        x = _conv(p, x, 64, 3, 1, 1)
+        for g, w in enumerate([64, 128, 256, 512]):
+            for b in range(2):
                 x = _wide(p, x, w, 2 if (b == 0 and g > 0) else 1)
         x = _bn(p, x, True)
     elif arch == 3:    # ResNet-50
