@@ -11,6 +11,7 @@ _LIB_PATH = os.path.join(_HERE, "libdat_oracle.so")
 ARCH_TINYCNN, ARCH_RESNET18_CIFAR, ARCH_WRN34_10, ARCH_RESNET50, ARCH_TESTNET, ARCH_LINEAR = 0, 1, 2, 3, 100, 101
 ARCH_PREACT_RESNET18, ARCH_WRN28_10 = 4, 5
 INIT_ZERO, INIT_UNIFORM, INIT_GIVEN = 0, 1, 2
+PHI_CE, PHI_TRADES_KL = 0, 1
 
 
 def build(force=False):
@@ -59,6 +60,12 @@ _make_xadv = _sig("orc_make_xadv", None, _f32p, _f32p, _f32p, C.c_int64)
 _attack = _sig("orc_attack", None, C.c_void_p, _f32p, _i32p, C.c_int, C.c_float, C.c_float, C.c_int, C.c_int,
                C.c_uint64, C.c_void_p, _f32p, C.c_void_p, C.c_void_p, C.c_void_p)
 _step = _sig("orc_step", C.c_double, C.c_void_p, _f32p, _i32p, C.c_int, _f32p)
+_step_reg = _sig("orc_step_reg", None, C.c_void_p, _f32p, _f32p, _i32p, C.c_int, C.c_double, C.c_int, _f32p, _f64p)
+_phi_gx = _sig("orc_phi_input_grad", C.c_double, C.c_void_p, _f32p, _f32p, _i32p, C.c_int, C.c_int, _f32p)
+_obj_f64 = _sig("orc_objective_f64", C.c_double, C.c_void_p, _f64p, _f64p, _f64p, _i32p, C.c_int, C.c_double, C.c_int,
+                C.c_void_p, C.c_void_p)
+_attack_kl = _sig("orc_attack_kl", None, C.c_void_p, _f32p, C.c_int, C.c_float, C.c_float, C.c_int, C.c_int, C.c_uint64,
+                  C.c_void_p, _f32p, C.c_void_p, C.c_void_p)
 _sgd = _sig("orc_sgd_update", None, C.c_void_p, _f32p, C.c_float)
 _quant = _sig("orc_quantize", None, _f32p, _i64p, C.c_int, C.c_int, C.c_uint64, C.c_int, _i32p, _f32p)
 _dequant = _sig("orc_dequantize", None, _i32p, _f32p, _i64p, C.c_int, C.c_int, _f32p)
@@ -156,6 +163,47 @@ class Model:
         g = np.zeros(self.d, np.float32)
         loss = _step(self._h, x_adv, y, x_adv.shape[0], g)
         return g, loss
+
+    def step_reg(self, x, x_adv, y, lam, phi):
+        """Worker gradient of lam*CE(x) + phi (batch mean); returns (grads, [mean clean CE, mean phi])."""
+        x = np.ascontiguousarray(x, np.float32)
+        x_adv = np.ascontiguousarray(x_adv, np.float32)
+        y = np.ascontiguousarray(y, np.int32)
+        g = np.zeros(self.d, np.float32)
+        losses = np.zeros(2, np.float64)
+        _step_reg(self._h, x, x_adv, y, x.shape[0], float(lam), int(phi), g, losses)
+        return g, losses
+
+    def phi_input_grad(self, x, x_adv, y, phi):
+        """Gradient of sum_n phi_n w.r.t. the perturbed pixels (clean pass constant); returns (gx, mean phi)."""
+        x = np.ascontiguousarray(x, np.float32)
+        x_adv = np.ascontiguousarray(x_adv, np.float32)
+        y = np.ascontiguousarray(y, np.int32)
+        gx = np.zeros_like(x)
+        loss = _phi_gx(self._h, x, x_adv, y, x.shape[0], int(phi), gx)
+        return gx, loss
+
+    def objective_f64(self, theta, x, x_adv, y, lam, phi, want_gtheta=False, want_gxadv=False):
+        theta = np.ascontiguousarray(theta, np.float64)
+        x = np.ascontiguousarray(x, np.float64)
+        x_adv = np.ascontiguousarray(x_adv, np.float64)
+        y = np.ascontiguousarray(y, np.int32)
+        gt = np.zeros(self.d, np.float64) if want_gtheta else None
+        gx = np.zeros_like(x) if want_gxadv else None
+        F = _obj_f64(self._h, theta, x, x_adv, y, x.shape[0], float(lam), int(phi), _opt(gt), _opt(gx))
+        return F, gt, gx
+
+    def attack_kl(self, x, eps, alpha, K, init=INIT_UNIFORM, seed=0, delta0=None, trace=False):
+        x = np.ascontiguousarray(x, np.float32)
+        B = x.shape[0]
+        delta = np.zeros_like(x)
+        d0 = None if delta0 is None else np.ascontiguousarray(delta0, np.float32)
+        losses = np.zeros(K + 1, np.float32) if trace else None
+        dtr = np.zeros((K + 1,) + x.shape, np.float32) if trace else None
+        _attack_kl(self._h, x, B, eps, alpha, K, init, seed, _opt(d0), delta, _opt(losses), _opt(dtr))
+        if trace:
+            return delta, dict(loss=losses, delta=dtr)
+        return delta
 
     def sgd_update(self, grads, lr):
         _sgd(self._h, np.ascontiguousarray(grads, np.float32), lr)

@@ -868,6 +868,182 @@ double orc_loss_f64(void* h, const double* theta64, const double* x64, const int
   return loss;
 }
 
+}  // extern "C"
+
+// ---- the general worker objective of Eq. (prob_DAT) ------------------------------------------------
+//   F = (1/B) sum_n [ lambda * CE(z(x_n), y_n) + phi_n ],
+//   phi = 0 (labeled data):  phi_n = CE(z(x_n + delta_n), y_n)
+//   phi = 1 (TRADES regulariser, "DAT with unlabeled data"): phi_n = KL(p(x_n) || p(x_n + delta_n)),
+//           p(.) = softmax of the logits; no label enters phi.
+// Every network evaluation is its own train-mode forward pass (batch statistics of that pass).
+// d phi_n / d z_adv = q - p;  d phi_n / d z_clean = p .* (log p - log q - phi_n)   (q = p(x+delta)).
+namespace {
+
+void softmax_rows(const std::vector<double>& z, int B, int nc, std::vector<double>& logp) {
+  logp.resize(z.size());
+  for (int n = 0; n < B; ++n) {
+    const double* zn = z.data() + (int64_t)n * nc;
+    double mx = zn[0];
+    for (int c = 1; c < nc; ++c) mx = std::max(mx, zn[c]);
+    double se = 0.0;
+    for (int c = 0; c < nc; ++c) se += std::exp(zn[c] - mx);
+    const double lse = mx + std::log(se);
+    for (int c = 0; c < nc; ++c) logp[(int64_t)n * nc + c] = zn[c] - lse;
+  }
+}
+
+void install_logit_grad(Model& m, const std::vector<double>& dz) {
+  const int t = m.ops.back().out;
+  std::copy(dz.begin(), dz.end(), m.gact[t].begin());
+  std::fill(m.ghas.begin(), m.ghas.end(), 0);
+  m.ghas[t] = 1;
+}
+
+std::vector<double> logits_of(const Model& m, int B) {
+  const int t = m.ops.back().out;
+  return std::vector<double>(m.act[t].begin(), m.act[t].begin() + (int64_t)B * m.classes);
+}
+
+// The two network inputs are already in m's input format when `load` is null (fp64 entry).
+struct RegResult { double loss_clean, loss_phi; };
+
+// Core shared by the fp32 and the fp64 entry: `set_clean` / `set_adv` write the network input.
+template <class SetClean, class SetAdv>
+RegResult objective_and_grads(Model& m, int B, const int32_t* y, double lambda, int phi, bool want_gtheta, bool want_gadv,
+                              SetClean set_clean, SetAdv set_adv, std::vector<double>& gtheta, std::vector<double>& gadv_in) {
+  const int nc = m.classes;
+  const double inv = 1.0 / B;
+  RegResult r{0.0, 0.0};
+  gtheta.assign(want_gtheta ? (size_t)m.d : 0, 0.0);
+  auto add_gtheta = [&]() { for (int64_t i = 0; i < m.d; ++i) gtheta[i] += m.gtheta[i]; };
+  if (phi == 0) {
+    if (lambda != 0.0) {
+      set_clean(); forward(m, B);
+      r.loss_clean = ce_loss_and_grad(m, y, B, lambda * inv);
+      if (want_gtheta) { backward(m, B, true); add_gtheta(); }
+    }
+    set_adv(); forward(m, B);
+    r.loss_phi = ce_loss_and_grad(m, y, B, want_gadv && !want_gtheta ? 1.0 : inv);
+    if (want_gtheta || want_gadv) {
+      backward(m, B, want_gtheta);
+      if (want_gtheta) add_gtheta();
+      if (want_gadv) gadv_in = m.gact[0];
+    }
+    return r;
+  }
+  // TRADES: clean logits first
+  set_clean(); forward(m, B);
+  std::vector<double> lp, lq;
+  softmax_rows(logits_of(m, B), B, nc, lp);
+  set_adv(); forward(m, B);
+  softmax_rows(logits_of(m, B), B, nc, lq);
+  std::vector<double> kl((size_t)B, 0.0), dz((size_t)B * nc);
+  for (int n = 0; n < B; ++n) {
+    double s = 0.0, ce = 0.0;
+    for (int c = 0; c < nc; ++c) { const int64_t i = (int64_t)n * nc + c; s += std::exp(lp[i]) * (lp[i] - lq[i]); }
+    ce = -lp[(int64_t)n * nc + y[n]];
+    kl[n] = s; r.loss_phi += s * inv; r.loss_clean += ce * inv;
+  }
+  // adversarial branch (activations of the x+delta pass are in place)
+  const double sadv = (want_gadv && !want_gtheta) ? 1.0 : inv;   // the attack uses the sum over the batch
+  for (int64_t i = 0; i < (int64_t)B * nc; ++i) dz[i] = (std::exp(lq[i]) - std::exp(lp[i])) * sadv;
+  if (want_gtheta || want_gadv) {
+    install_logit_grad(m, dz);
+    backward(m, B, want_gtheta);
+    if (want_gtheta) add_gtheta();
+    if (want_gadv) gadv_in = m.gact[0];
+  }
+  if (want_gtheta) {
+    // clean branch: its activations were overwritten, run that pass again
+    set_clean(); forward(m, B);
+    for (int n = 0; n < B; ++n)
+      for (int c = 0; c < nc; ++c) {
+        const int64_t i = (int64_t)n * nc + c;
+        const double pc = std::exp(lp[i]);
+        dz[i] = (lambda * (pc - (c == y[n] ? 1.0 : 0.0)) + pc * (lp[i] - lq[i] - kl[n])) * inv;
+      }
+    install_logit_grad(m, dz);
+    backward(m, B, true);
+    add_gtheta();
+  }
+  return r;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Worker gradient of the objective above at fp32 pixels x (clean) and xadv (= clip(x + delta)).
+// grads: fp32 [d] (sum of the passes accumulated in fp64, rounded once).  losses[0] = mean clean CE
+// (0 when lambda = 0 and phi = 0: that pass is not run), losses[1] = mean phi.
+void orc_step_reg(void* h, const float* x, const float* xadv, const int32_t* y, int B, double lambda, int phi,
+                  float* grads, double* losses) {
+  Model* m = (Model*)h;
+  prepare(*m, B);
+  std::vector<double> gt, unused;
+  RegResult r = objective_and_grads(*m, B, y, lambda, phi, true, false, [&]() { load_input(*m, x, B); },
+                                    [&]() { load_input(*m, xadv, B); }, gt, unused);
+  for (int64_t i = 0; i < m->d; ++i) grads[i] = (float)gt[i];
+  if (losses) { losses[0] = r.loss_clean; losses[1] = r.loss_phi; }
+}
+
+// Gradient of sum_n phi_n w.r.t. the perturbed pixels (the clean pass is a constant): what the inner
+// maximisation ascends.  gx: fp32 [B,H,W,3].  Returns mean phi.
+double orc_phi_input_grad(void* h, const float* x, const float* xadv, const int32_t* y, int B, int phi, float* gx) {
+  Model* m = (Model*)h;
+  prepare(*m, B);
+  std::vector<double> gt, gin;
+  RegResult r = objective_and_grads(*m, B, y, 0.0, phi, false, true, [&]() { load_input(*m, x, B); },
+                                    [&]() { load_input(*m, xadv, B); }, gt, gin);
+  m->gact[0] = gin;
+  pixel_grad(*m, B, gx);
+  return r.loss_phi;
+}
+
+// fp64 end to end (parameters from theta64, pixels used as given, no storage rounding): returns
+// F = lambda * mean CE + mean phi; optional gradients of F w.r.t. theta, and of sum_n phi_n w.r.t.
+// xadv with the clean pass held constant.
+double orc_objective_f64(void* h, const double* theta64, const double* x64, const double* xadv64, const int32_t* y, int B,
+                         double lambda, int phi, double* gtheta64, double* gxadv64) {
+  Model* m = (Model*)h;
+  int saved = m->emu; m->emu = 0;
+  prepare(*m, B);
+  std::vector<double> keep = m->theta;
+  std::copy(theta64, theta64 + m->d, m->theta.begin());
+  const Shape s = m->in_shape;
+  const int64_t rows = (int64_t)B * s.H * s.W;
+  auto put = [&](const double* src) {
+    for (int64_t i = 0; i < rows; ++i)
+      for (int c = 0; c < s.C; ++c) {
+        double v = src[i * s.C + c];
+        if (m->normalize) v = (v - (double)m->mean[c]) * (double)m->inv_std[c];
+        m->act[0][i * s.C + c] = v;
+      }
+  };
+  std::vector<double> gt, gin;
+  double F = 0.0;
+  if (gxadv64) {
+    RegResult r = objective_and_grads(*m, B, y, 0.0, phi, false, true, [&]() { put(x64); }, [&]() { put(xadv64); }, gt, gin);
+    (void)r;
+    for (int64_t i = 0; i < rows; ++i)
+      for (int c = 0; c < s.C; ++c)
+        gxadv64[i * s.C + c] = gin[i * s.C + c] * (m->normalize ? (double)m->inv_std[c] : 1.0);
+  }
+  {
+    RegResult r = objective_and_grads(*m, B, y, lambda, phi, gtheta64 != nullptr, false, [&]() { put(x64); },
+                                      [&]() { put(xadv64); }, gt, gin);
+    F = lambda * r.loss_clean + r.loss_phi;   // loss_clean is 0 when that pass is not part of the objective
+    if (gtheta64) std::copy(gt.begin(), gt.end(), gtheta64);
+  }
+  m->theta = keep; m->emu = saved;
+  return F;
+}
+
+// Inner maximisation of phi = KL(p(x) || p(x + delta)) by the same projected sign ascent as orc_attack
+// (no labels).  The clean logits are those of one forward pass on x and stay fixed.
+void orc_attack_kl(void* h, const float* x, int B, float eps, float alpha, int K, int init_mode, uint64_t seed,
+                   const float* delta0, float* delta, float* loss_per_step, float* delta_trace);
+
 // delta0 for the three init modes: 0 zero, 1 uniform in the eps-ball from Philox stream 1
 // (u -> (2u-1)*eps), 2 given.  Always followed by the clip that keeps x+delta in [0,1].
 void orc_init_delta(const float* x, int64_t N, float eps, int mode, uint64_t seed,
@@ -914,6 +1090,27 @@ void orc_attack(void* h, const float* x, const int32_t* y, int B, float eps, flo
 // Outer step: g = (1/B) sum_n grad_theta CE(net(x_adv_n), y_n).
 double orc_step(void* h, const float* xadv, const int32_t* y, int B, float* grads) {
   return orc_loss_grad(h, xadv, y, B, 1, nullptr, nullptr, grads);
+}
+
+void orc_attack_kl(void* h, const float* x, int B, float eps, float alpha, int K, int init_mode, uint64_t seed,
+                   const float* delta0, float* delta, float* loss_per_step, float* delta_trace) {
+  Model* m = (Model*)h;
+  const int64_t N = (int64_t)B * m->in_shape.numel();
+  std::vector<float> xadv((size_t)N), G((size_t)N);
+  std::vector<int32_t> nolabel((size_t)B, 0);
+  orc_init_delta(x, N, eps, init_mode, seed, delta0, delta);
+  if (delta_trace) std::copy(delta, delta + N, delta_trace);
+  for (int k = 0; k < K; ++k) {
+    make_xadv(x, delta, xadv.data(), N);
+    const double loss = orc_phi_input_grad(h, x, xadv.data(), nolabel.data(), B, 1, G.data());
+    if (loss_per_step) loss_per_step[k] = (float)loss;
+    pgd_update(x, G.data(), delta, N, eps, alpha);
+    if (delta_trace) std::copy(delta, delta + N, delta_trace + (int64_t)(k + 1) * N);
+  }
+  if (loss_per_step) {
+    make_xadv(x, delta, xadv.data(), N);
+    loss_per_step[K] = (float)orc_phi_input_grad(h, x, xadv.data(), nolabel.data(), B, 1, G.data());
+  }
 }
 
 void orc_sgd_update(void* h, const float* grads, float lr) {

@@ -130,3 +130,29 @@ def loss_and_grads(arch, flat64, x64_nhwc, y, classes, reduction="sum", mean=Non
     loss = F.cross_entropy(z, torch.tensor(y, dtype=torch.long), reduction=reduction)
     loss.backward()
     return loss.item(), z.detach().numpy(), x.grad.numpy(), flat.grad.numpy()
+
+
+def objective_and_grads(arch, flat64, x64, xadv64, y, classes, lam, phi, mean=None, std=None):
+    """F = lam * mean CE(net(x), y) + mean phi, phi = CE(net(xadv), y) (0) or KL(softmax net(x) || softmax net(xadv)) (1),
+    each network evaluation its own train-mode forward.  Returns F, dF/dtheta, and d(sum_n phi_n)/dxadv with the
+    clean evaluation held constant."""
+    flat = torch.tensor(flat64, dtype=torch.float64, requires_grad=True)
+    x = torch.tensor(x64, dtype=torch.float64)
+    xadv = torch.tensor(xadv64, dtype=torch.float64, requires_grad=True)
+    yt = torch.tensor(y, dtype=torch.long)
+    z_adv = logits(arch, flat, xadv, classes, mean, std)
+    if phi == 0:
+        phi_n = F.cross_entropy(z_adv, yt, reduction="none")
+        total = phi_n.mean()
+        if lam != 0:
+            total = total + lam * F.cross_entropy(logits(arch, flat, x, classes, mean, std), yt, reduction="mean")
+        gx = torch.autograd.grad(phi_n.sum(), xadv, retain_graph=True)[0]
+    else:
+        z = logits(arch, flat, x, classes, mean, std)
+        lp, lq = F.log_softmax(z, dim=1), F.log_softmax(z_adv, dim=1)
+        phi_n = (lp.exp() * (lp - lq)).sum(dim=1)
+        total = phi_n.mean() + lam * F.cross_entropy(z, yt, reduction="mean")
+        lpc = lp.detach()
+        gx = torch.autograd.grad((lpc.exp() * (lpc - lq)).sum(), xadv, retain_graph=True)[0]
+    gt = torch.autograd.grad(total, flat)[0]
+    return total.item(), gt.numpy(), gx.numpy()
