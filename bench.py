@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="resnet50_224_b256_pgd10", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=8)
+    ap.add_argument("--phi", default="ce", choices=["ce", "trades"],
+                    help="robustness regulariser of the worker objective: adversarial cross-entropy (the headline path) or the TRADES KL term")
+    ap.add_argument("--lam", type=float, default=0.0, help="weight of the clean-loss term of the worker objective")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-events", action="store_true", help="do not bracket launches with events")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -111,12 +114,20 @@ def main():
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
 
+    general = args.phi != "ce" or args.lam != 0.0     # the general objective lambda*l + phi (two or three passes per step)
+
     def one_step(i, marks=None):
-        model.attack(x, y, eps, alpha, K, dat.INIT_UNIFORM, seed=seed_init + i, delta=delta)
+        if args.phi == "trades":
+            model.attack_kl(x, eps, alpha, K, dat.INIT_UNIFORM, seed=seed_init + i, delta=delta)
+        else:
+            model.attack(x, y, eps, alpha, K, dat.INIT_UNIFORM, seed=seed_init + i, delta=delta)
         if marks:
             marks[0].record()
         torch.add(x, delta, out=xadv)          # x + delta (already inside [0,1] by construction)
-        model.step(xadv, y, grads=grads)
+        if general:
+            model.step_reg(x, xadv, y, args.lam, dat.PHI_TRADES_KL if args.phi == "trades" else dat.PHI_CE, grads=grads)
+        else:
+            model.step(xadv, y, grads=grads)
         if marks:
             marks[1].record()
         dat.quantize(grads, offs, args.bits, seed_q + i, q=q, scales=scales)
@@ -163,7 +174,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "image": [H, W, 3], "pgd_steps": K, "eps": eps, "alpha": alpha,
-                   "quantizer_bits": args.bits, "params": model.d},
+                   "quantizer_bits": args.bits, "params": model.d, "phi": args.phi, "lambda": args.lam},
         "adv_examples_per_s": B / (t_attack * 1e-3), "train_images_per_s": B / (t_step * 1e-3),
         "phase_ms": {"attack": t_attack, "step": t_step, "quantize": t_quant, "dequantize": t_deq},
     }

@@ -126,6 +126,30 @@ dat_status dat_step(dat_model* m, const float* x_adv, const int32_t* y, int B, f
 dat_status dat_input_grad(dat_model* m, const float* x, const int32_t* y, int B, float* gx,
                           float* logits, float* loss, void* stream);
 
+/* ---- the general worker objective (Eq. (prob_DAT)) ----------------------------------------------
+ *   f = E[ lambda * l(theta; x, y) + max_{|delta|_inf <= eps} phi(theta, delta; x, y) ],  lambda >= 0.
+ * phi = DAT_PHI_CE: phi = l(theta; x + delta, y), DAT with labeled data (lambda = 0 is dat_attack + dat_step).
+ * phi = DAT_PHI_TRADES_KL: phi = KL(p(x; theta) || p(x + delta; theta)), p = softmax of the logits: the
+ *   TRADES regulariser of "DAT with unlabeled data"; no label enters phi.
+ * Every network evaluation is its own train-mode forward pass (batch statistics of that pass).
+ *
+ * dat_attack_kl: inner maximisation of the KL regulariser by the projected sign ascent of dat_attack:
+ *   the logits of one forward pass on x stay fixed; for k = 1..K:  G = grad_delta sum_n KL(p(x_n) || p(x_n + z_{k-1})).
+ *   A zero start is a fixed point (the gradient vanishes where the two passes coincide): use
+ *   DAT_INIT_UNIFORM or DAT_INIT_GIVEN.  loss_per_step: optional host array of K+1 floats, mean KL.
+ * dat_step_reg: grads[d] (device fp32) = grad_theta (1/B) sum_n [ lambda * l(theta; x_n, y_n) + phi_n ]
+ *   at the given perturbed pixels x_adv (= clip(x + delta)); the gradient flows through every pass
+ *   (for the KL regulariser through both the clean and the perturbed logits; the clean pass is run twice
+ *   because the two passes share the activation buffers).  losses: optional host float[2] =
+ *   { mean clean cross-entropy (0 when lambda = 0 and phi = CE: that pass is not run), mean phi }.
+ *   x, x_adv: device fp32 [B,H,W,3], 16-byte aligned; y: device int32 [B].  Allocates a second gradient
+ *   vector inside the model on first use. */
+typedef enum { DAT_PHI_CE = 0, DAT_PHI_TRADES_KL = 1 } dat_phi;
+dat_status dat_attack_kl(dat_model* m, const float* x, int B, float eps, float alpha, int K,
+                         dat_init init, float* delta, float* loss_per_step, void* stream);
+dat_status dat_step_reg(dat_model* m, const float* x, const float* x_adv, const int32_t* y, int B,
+                        float lambda, dat_phi phi, float* grads, float* losses, void* stream);
+
 /* The elementwise pieces of the attack on their own (also what dat_attack launches):
  * dat_pgd_init writes z_0; dat_pgd_update applies one projected sign step in place.
  * N = number of fp32 elements (B*H*W*3); all pointers device; buffers 16-byte aligned. */

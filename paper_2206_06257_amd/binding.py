@@ -11,6 +11,7 @@ LIB_PATH = os.path.join(_HERE, "libdat.so")
 
 ARCH_TINYCNN, ARCH_RESNET18_CIFAR, ARCH_WRN34_10, ARCH_RESNET50, ARCH_TESTNET = 0, 1, 2, 3, 100
 ARCH_PREACT_RESNET18, ARCH_WRN28_10 = 4, 5
+PHI_CE, PHI_TRADES_KL = 0, 1
 F32, BF16 = 0, 1
 INIT_ZERO, INIT_UNIFORM, INIT_GIVEN = 0, 1, 2
 
@@ -20,6 +21,7 @@ EXPORTS = [
     "dat_input_grad", "dat_pgd_init", "dat_pgd_update", "dat_sgd_update", "dat_quantize", "dat_dequantize",
     "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
     "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read", "dat_aggregate", "dat_lamb_update",
+    "dat_attack_kl", "dat_step_reg",
 ]
 
 
@@ -72,6 +74,8 @@ for _n in ("dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weig
 _lib.dat_philox_uniform.argtypes = [_u64, _i64, _u64, C.c_uint32, _vp, _vp]
 _lib.dat_aggregate.argtypes = [_vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp]
 _lib.dat_lamb_update.argtypes = [_vp, _vp, _i, _f, _f, _f, _f, _f, _f, _f, _i, _vp]
+_lib.dat_attack_kl.argtypes = [_vp, _vp, _i, _f, _f, _i, _Init, _vp, _vp, _vp]
+_lib.dat_step_reg.argtypes = [_vp, _vp, _vp, _vp, _i, _f, _i, _vp, _vp, _vp]
 _lib.dat_profile_enable.argtypes = [_vp, _i]
 _lib.dat_profile_read.argtypes = [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]
 PROF_CLASSES = ("conv_fwd", "conv_bwd_data", "conv_wgrad", "bn", "pgd")
@@ -158,6 +162,24 @@ class Model:
         _check(_lib.dat_step(self._h, _ptr(x_adv), _ptr(y), x_adv.shape[0], _ptr(grads),
                              C.byref(loss) if want_loss else None, _stream(stream)), "dat_step")
         return (grads, loss.value) if want_loss else grads
+
+    def attack_kl(self, x, eps, alpha, K, init=INIT_UNIFORM, seed=0, delta0=None, delta=None, want_losses=False, stream=None):
+        _dev(x, torch.float32)
+        if delta is None:
+            delta = torch.empty_like(x)
+        losses = np.zeros(K + 1, np.float32) if want_losses else None
+        _check(_lib.dat_attack_kl(self._h, _ptr(x), x.shape[0], eps, alpha, K, _init(init, seed, delta0), _ptr(delta),
+                                  None if losses is None else losses.ctypes.data, _stream(stream)), "dat_attack_kl")
+        return (delta, losses) if want_losses else delta
+
+    def step_reg(self, x, x_adv, y, lam, phi, grads=None, want_losses=False, stream=None):
+        _dev(x, torch.float32); _dev(x_adv, torch.float32); _dev(y, torch.int32)
+        if grads is None:
+            grads = torch.empty(self.d, dtype=torch.float32, device=x.device)
+        losses = np.zeros(2, np.float32) if want_losses else None
+        _check(_lib.dat_step_reg(self._h, _ptr(x), _ptr(x_adv), _ptr(y), x.shape[0], lam, int(phi), _ptr(grads),
+                                 None if losses is None else losses.ctypes.data, _stream(stream)), "dat_step_reg")
+        return (grads, losses) if want_losses else grads
 
     def input_grad(self, x, y, want_logits=True, want_loss=True, stream=None):
         _dev(x, torch.float32); _dev(y, torch.int32)

@@ -118,6 +118,10 @@ dat_status fc_backward(const float* f, const float* W, const float* dz, float* d
 // Softmax cross-entropy: loss_n per sample, dz = (softmax - onehot) * gscale; loss_mean[0] = mean loss_n.
 dat_status ce_forward_backward(const float* logits, const int32_t* y, float* dz, float* loss_n, float* loss_mean, int B, int O,
                                float gscale, hipStream_t st);
+// TRADES regulariser KL(softmax z_clean || softmax z_adv): logit gradient of one branch (0: the perturbed pass,
+// dz = (q-p)*gscale, loss_n = KL; 1: the clean pass, dz = (lambda*(p-onehot) + p*(log p - log q - KL))*gscale, loss_n = CE).
+dat_status kl_forward_backward(const float* z_clean, const float* z_adv, const int32_t* y, int branch, float lambda, float* dz,
+                               float* loss_n, float* loss_mean, int B, int O, float gscale, hipStream_t st);
 // fp32 -> bf16 copy (linear weights) ; first-layer gradient [rows][Cpad] -> gx[rows][3] * inv_std.
 dat_status launch_round_bf16_values(const float* src, float* dst, int64_t n, hipStream_t st);
 // block_h, block_w > 0: g0 is stored as 2x2 pixel blocks of a block_h x block_w image.

@@ -524,6 +524,48 @@ __global__ __launch_bounds__(64) void ce_kernel(const float* __restrict__ z, con
   if (lane == 0) loss_n[n] = lse - zn[yn];
 }
 
+// TRADES regulariser phi_n = KL(p_n || q_n), p = softmax(z_clean), q = softmax(z_adv); one wavefront per sample.
+//   branch 0 (the x+delta pass): dz = (q - p) * gscale,                                   loss_n = phi_n
+//   branch 1 (the clean pass):   dz = (lambda*(p - onehot) + p*(log p - log q - phi_n)) * gscale, loss_n = CE(z_clean, y)
+// The two passes differ by an eps-sized perturbation, so everything is written in terms of the small
+// differences d_k = z_clean_k - z_adv_k instead of differences of two log-softmax values:
+//   r = sum_k q_k expm1(d_k);  log p_k - log q_k = t_k = d_k - log1p(r);  p_k = q_k exp(t_k);  q_k - p_k = -q_k expm1(t_k).
+__global__ __launch_bounds__(64) void kl_kernel(const float* __restrict__ zc, const float* __restrict__ za,
+                                                const int32_t* __restrict__ y, int branch, float lambda,
+                                                float* __restrict__ dz, float* __restrict__ loss_n, int B, int O, float gscale) {
+  const int n = blockIdx.x, lane = threadIdx.x;
+  const float* c = zc + (int64_t)n * O;
+  const float* a = za + (int64_t)n * O;
+  float ma = -__builtin_inff();
+  for (int k = lane; k < O; k += 64) ma = fmaxf(ma, a[k]);
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) ma = fmaxf(ma, __shfl_xor(ma, s));
+  float sa = 0.f, sr = 0.f;
+  for (int k = lane; k < O; k += 64) { const float e = expf(a[k] - ma); sa += e; sr += e * expm1f(c[k] - a[k]); }
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) { sa += __shfl_xor(sa, s); sr += __shfl_xor(sr, s); }
+  const float la = ma + logf(sa);            // log-sum-exp of the perturbed logits
+  const float dl = log1pf(sr / sa);          // lse(clean) - lse(perturbed)
+  float kl = 0.f;
+  for (int k = lane; k < O; k += 64) { const float t = (c[k] - a[k]) - dl; kl += expf(a[k] - la + t) * t; }
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) kl += __shfl_xor(kl, s);
+  if (branch == 0) {
+    for (int k = lane; k < O; k += 64) {
+      const float t = (c[k] - a[k]) - dl;
+      dz[(int64_t)n * O + k] = -expf(a[k] - la) * expm1f(t) * gscale;
+    }
+    if (lane == 0) loss_n[n] = kl;
+  } else {
+    const int yn = y[n];
+    for (int k = lane; k < O; k += 64) {
+      const float t = (c[k] - a[k]) - dl, p = expf(a[k] - la + t);
+      dz[(int64_t)n * O + k] = (lambda * (p - (k == yn ? 1.f : 0.f)) + p * (t - kl)) * gscale;
+    }
+    if (lane == 0) loss_n[n] = (la + dl) - c[yn];
+  }
+}
+
 __global__ void mean_kernel(const float* __restrict__ v, int n, float* __restrict__ out) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     double s = 0.0;
@@ -745,6 +787,15 @@ dat_status fc_backward(const float* f, const float* W, const float* dz, float* d
 dat_status ce_forward_backward(const float* logits, const int32_t* y, float* dz, float* loss_n, float* loss_mean, int B, int O,
                                float gscale, hipStream_t st) {
   hipLaunchKernelGGL(ce_kernel, dim3(B), dim3(64), 0, st, logits, y, dz, loss_n, B, O, gscale);
+  DAT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(64), 0, st, loss_n, B, loss_mean);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status kl_forward_backward(const float* z_clean, const float* z_adv, const int32_t* y, int branch, float lambda, float* dz,
+                               float* loss_n, float* loss_mean, int B, int O, float gscale, hipStream_t st) {
+  hipLaunchKernelGGL(kl_kernel, dim3(B), dim3(64), 0, st, z_clean, z_adv, y, branch, lambda, dz, loss_n, B, O, gscale);
   DAT_LAUNCH_CHECK();
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(64), 0, st, loss_n, B, loss_mean);
   DAT_LAUNCH_CHECK();

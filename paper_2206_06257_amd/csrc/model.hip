@@ -65,6 +65,9 @@ struct dat_model {
   float* gx = nullptr;
   void* wgrad_ws = nullptr; size_t wgrad_ws_bytes = 0;
   float* host_stage = nullptr;       // pinned staging for loss values
+  float* z_keep = nullptr;           // logits of the clean pass, kept while the perturbed pass runs (TRADES regulariser)
+  float* z_keep2 = nullptr;          //   ... and of the perturbed pass, kept while the clean pass runs again
+  float* g_tmp = nullptr;            // second gradient vector of a two-pass objective (allocated on first use)
   float* opt_m = nullptr; float* opt_v = nullptr; float* opt_u = nullptr; double* opt_norms = nullptr;   // LAMB state
   // optional per-launch timing (dat_profile_*): one event pair per launch group
   bool prof = false;
@@ -329,6 +332,8 @@ dat_status allocate(dat_model& m) {
   m.loss_cap = 1024;
   DAT_TRY(dev_alloc(m, &m.loss_steps, (size_t)m.loss_cap * 4));
   DAT_TRY(dev_alloc(m, &m.gx, (size_t)m.maxB * m.H * m.W * 3 * 4));
+  DAT_TRY(dev_alloc(m, &m.z_keep, (size_t)m.maxB * m.classes * 4));
+  DAT_TRY(dev_alloc(m, &m.z_keep2, (size_t)m.maxB * m.classes * 4));
   if (hipHostMalloc((void**)&m.host_stage, (size_t)m.loss_cap * 4, hipHostMallocDefault) != hipSuccess) {
     (void)hipGetLastError();
     return DAT_ERR_NOMEM;
@@ -617,6 +622,109 @@ extern "C" dat_status dat_step(dat_model* m, const float* x_adv, const int32_t* 
   DAT_TRY(loss_grad(*m, y, B, 1.0f / (float)B, 0, st));
   DAT_TRY(backward(*m, B, grads, false, st));
   if (loss) DAT_TRY(fetch_losses(*m, 1, loss, st));
+  return DAT_OK;
+}
+
+namespace {
+
+// Logit gradient of one branch of the TRADES regulariser, from the kept clean logits and the logits in place.
+dat_status kl_grad(dat_model& m, const float* z_clean, const float* z_adv, const int32_t* y, int branch, float lambda, int B,
+                   float gscale, int loss_slot, hipStream_t st) {
+  const int t = m.ops.back().out;
+  DAT_TRY(kl_forward_backward(z_clean, z_adv, y, branch, lambda, (float*)m.grad[t], m.loss_n, m.loss_steps + loss_slot, B,
+                              m.classes, gscale, st));
+  std::fill(m.ghas.begin(), m.ghas.end(), 0);
+  m.ghas[t] = 1;
+  return DAT_OK;
+}
+
+dat_status keep_logits(dat_model& m, float* dst, int B, hipStream_t st) {
+  DAT_HIP(hipMemcpyAsync(dst, m.act[m.ops.back().out], (size_t)B * m.classes * 4, hipMemcpyDeviceToDevice, st));
+  return DAT_OK;
+}
+
+}  // namespace
+
+extern "C" dat_status dat_attack_kl(dat_model* m, const float* x, int B, float eps, float alpha, int K, dat_init init,
+                                    float* delta, float* loss_per_step, void* stream) {
+  if (!m || !x || !delta || K < 0 || !(eps >= 0.0f) || !(alpha >= 0.0f)) return DAT_ERR_ARG;
+  if (init.mode != DAT_INIT_ZERO && init.mode != DAT_INIT_UNIFORM && init.mode != DAT_INIT_GIVEN) return DAT_ERR_ARG;
+  if (init.mode == DAT_INIT_GIVEN && !init.delta0) return DAT_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(delta, 16)) return DAT_ERR_ARG;
+  if (!batch_ok(m, B)) return DAT_ERR_SHAPE;
+  if (loss_per_step && K + 1 > m->loss_cap) return DAT_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t npix = (int64_t)B * m->H * m->W;
+  const NetInputDesc in = input_desc(*m);
+  const float* z_adv = (const float*)m->act[m->ops.back().out];
+  // the clean pass: its logits stay fixed during the ascent
+  DAT_TRY(launch_make_input(x, nullptr, npix, in, st));
+  DAT_TRY(forward(*m, B, st));
+  DAT_TRY(keep_logits(*m, m->z_keep, B, st));
+  DAT_TRY(launch_attack_init(x, npix, eps, init, delta, in, st));
+  for (int k = 0; k < K; ++k) {
+    DAT_TRY(forward(*m, B, st));
+    DAT_TRY(kl_grad(*m, m->z_keep, z_adv, nullptr, 0, 0.0f, B, 1.0f, loss_per_step ? k : 0, st));
+    DAT_TRY(backward(*m, B, nullptr, true, st));
+    DAT_TRY(pixel_grad(*m, B, m->gx, st));
+    DAT_PROF(*m, DAT_PROF_PGD, (double)npix * 3 * (m->dtype == DAT_BF16 ? 18 : 20), st,
+             launch_attack_update(x, m->gx, delta, npix, eps, alpha, in, st));
+  }
+  if (loss_per_step) {
+    DAT_TRY(forward(*m, B, st));
+    DAT_TRY(kl_grad(*m, m->z_keep, z_adv, nullptr, 0, 0.0f, B, 1.0f, K, st));
+    DAT_TRY(fetch_losses(*m, K + 1, loss_per_step, st));
+  }
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_step_reg(dat_model* m, const float* x, const float* x_adv, const int32_t* y, int B, float lambda,
+                                   dat_phi phi, float* grads, float* losses, void* stream) {
+  if (!m || !x || !x_adv || !y || !grads || !(lambda >= 0.0f)) return DAT_ERR_ARG;
+  if (phi != DAT_PHI_CE && phi != DAT_PHI_TRADES_KL) return DAT_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(x_adv, 16) || !aligned(grads, 16)) return DAT_ERR_ARG;
+  if (!batch_ok(m, B)) return DAT_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t npix = (int64_t)B * m->H * m->W;
+  const NetInputDesc in = input_desc(*m);
+  const float inv = 1.0f / (float)B;
+  const bool two_pass = phi == DAT_PHI_TRADES_KL || lambda != 0.0f;
+  if (two_pass && !m->g_tmp) DAT_TRY(dev_alloc(*m, &m->g_tmp, (size_t)m->d * 4));
+  float host[2] = {0.0f, 0.0f};
+  if (phi == DAT_PHI_CE) {
+    if (lambda != 0.0f) {   // lambda * clean loss, its own forward/backward
+      DAT_TRY(launch_make_input(x, nullptr, npix, in, st));
+      DAT_TRY(forward(*m, B, st));
+      DAT_TRY(loss_grad(*m, y, B, lambda * inv, 0, st));
+      DAT_TRY(backward(*m, B, m->g_tmp, false, st));
+    }
+    DAT_TRY(launch_make_input(x_adv, nullptr, npix, in, st));
+    DAT_TRY(forward(*m, B, st));
+    DAT_TRY(loss_grad(*m, y, B, inv, 1, st));
+    DAT_TRY(backward(*m, B, grads, false, st));
+  } else {
+    const float* z_here = (const float*)m->act[m->ops.back().out];
+    // clean logits, then the perturbed pass and its branch of the gradient
+    DAT_TRY(launch_make_input(x, nullptr, npix, in, st));
+    DAT_TRY(forward(*m, B, st));
+    DAT_TRY(keep_logits(*m, m->z_keep, B, st));
+    DAT_TRY(launch_make_input(x_adv, nullptr, npix, in, st));
+    DAT_TRY(forward(*m, B, st));
+    DAT_TRY(kl_grad(*m, m->z_keep, z_here, y, 0, lambda, B, inv, 1, st));
+    DAT_TRY(keep_logits(*m, m->z_keep2, B, st));
+    DAT_TRY(backward(*m, B, grads, false, st));
+    // the clean pass again (its activations were overwritten), with the clean branch's logit gradient
+    DAT_TRY(launch_make_input(x, nullptr, npix, in, st));
+    DAT_TRY(forward(*m, B, st));
+    DAT_TRY(kl_grad(*m, z_here, m->z_keep2, y, 1, lambda, B, inv, 0, st));
+    DAT_TRY(backward(*m, B, m->g_tmp, false, st));
+  }
+  if (two_pass) DAT_TRY(launch_sgd(grads, m->g_tmp, -1.0f, m->d, st));   // grads <- grads + g_tmp
+  if (losses) {
+    DAT_TRY(fetch_losses(*m, 2, host, st));
+    losses[0] = (phi == DAT_PHI_CE && lambda == 0.0f) ? 0.0f : host[0];
+    losses[1] = host[1];
+  }
   return DAT_OK;
 }
 
