@@ -369,20 +369,21 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* gbl_void_ptr;
 
-template <int TC, int TP, int WGC, int OCC>
+template <int TC, int TP, int WGC, int OCC, int BKT>
 __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
-  constexpr int BKT = 64, KS = BKT / 16;
+  constexpr int KS = BKT / 16, NS = BKT / 8;              // MFMA k-steps per tile; 16-byte slots per tile row
   constexpr int WGP = 4 / WGC;
   constexpr int WC = TC / WGC, WP = TP / WGP;
   constexpr int NI = WC / 32, NJ = WP / 32;
-  constexpr int RB = 128, RPG = kThreads / 8;            // bytes per tile row; tile rows covered by one load per thread
-  constexpr int VW = TC / RPG, VX = TP / RPG;
-  constexpr int TILE_BYTES = (TC + TP) * RB;
+  constexpr int RB = BKT * 2, RPG = kThreads / NS;        // bytes per tile row; tile rows covered by one load per thread
+  constexpr int VW = (TC + RPG - 1) / RPG, VX = TP / RPG;
+  constexpr int TILE_BYTES = (VW * RPG + TP) * RB;       // weight rows rounded up to whole load sweeps
+  constexpr int XBASE = VW * RPG * RB;
   constexpr int STG_STRIDE = TC * 2 + 16;
   constexpr int RED_BYTES = (kThreads / (TC / 8)) * 2 * TC * 4;
   constexpr int E_BYTES = TP * STG_STRIDE > RED_BYTES ? TP * STG_STRIDE : RED_BYTES;
   constexpr int LDS_BYTES = TILE_BYTES > E_BYTES ? TILE_BYTES : E_BYTES;
-  static_assert(TC % RPG == 0 && TP % RPG == 0, "tile rows must be whole load sweeps");
+  static_assert(TP % RPG == 0 && (BKT == 32 || BKT == 64), "tile rows must be whole load sweeps");
   __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
 
   const int bid = blockIdx.x;
@@ -394,8 +395,9 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wc = wave % WGC, wp = wave / WGC;
-  const int lrow = tid >> 3;
-  const int kvec = (tid & 7) ^ ((lrow & 7) ^ ((lrow >> 3) & 1));   // logical k-slot behind physical slot tid & 7 (swz<8>)
+  const int lrow = tid / NS;
+  // logical k-slot behind physical slot tid % NS of row lrow: the XOR of swz<NS> is its own inverse
+  const int kvec = (swz<NS>(lrow, tid % NS) - lrow * RB) >> 4;
 
   int hb[VX], wb[VX], nb[VX]; bool mv[VX];
   const int HW = a.Hout * a.Wout;
@@ -415,12 +417,12 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
 #pragma unroll
   for (int i = 0; i < VW; ++i) {
     const int c = c0 + lrow + RPG * i;
-    wrow[i] = c < a.Cout;
+    wrow[i] = (lrow + RPG * i < TC) & (c < a.Cout);
     woff[i] = (wrow[i] ? c : 0) * a.Ktot + kvec * 8;
   }
   int xoff[VX]; bool xok[VX];
   int kc0 = 0, kr = 0, ks = 0;
-  unsigned char* const wave_base = lds + wave * 1024;     // a wave's 64 vectors = 8 rows of 128 bytes
+  unsigned char* const wave_base = lds + wave * 1024;     // a wave's 64 vectors = 1 KB of consecutive tile rows
   // all loads of the next k-tile (a tile never straddles a filter tap: the tap, the bounds test and the
   // pixel offset change only every Cin/64 tiles, a uniform branch)
   auto fetch = [&]() {
@@ -441,7 +443,7 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
 #pragma unroll
     for (int i = 0; i < VX; ++i) {
       const unsigned char* p = xok[i] ? reinterpret_cast<const unsigned char*>(a.in + xoff[i]) : zero_page;
-      __builtin_amdgcn_global_load_lds((gbl_void_ptr)p, (lds_void_ptr)(wave_base + TC * RB + i * (RPG * RB)), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gbl_void_ptr)p, (lds_void_ptr)(wave_base + XBASE + i * (RPG * RB)), 16, 0, 0);
       xoff[i] += BKT;
     }
     kc0 += BKT;
@@ -450,9 +452,9 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   // fragment byte offsets for k-step 0; k-step kk is the slot pair 2*kk further on, i.e. offset ^ (kk * 32)
   int fa_off[NI], fb_off[NJ];
 #pragma unroll
-  for (int i = 0; i < NI; ++i) fa_off[i] = swz<8>(wc * WC + i * 32 + (lane & 31), lane >> 5);
+  for (int i = 0; i < NI; ++i) fa_off[i] = swz<NS>(wc * WC + i * 32 + (lane & 31), lane >> 5);
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) fb_off[j] = TC * RB + swz<8>(wp * WP + j * 32 + (lane & 31), lane >> 5);
+  for (int j = 0; j < NJ; ++j) fb_off[j] = XBASE + swz<NS>(wp * WP + j * 32 + (lane & 31), lane >> 5);
 
   f32x16 acc[NI][NJ];
 #pragma unroll
@@ -491,15 +493,15 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   igemm_epilogue<TC, TP, WGC>(a, acc, lds, c0, m0, pt);
 }
 
-template <int TC, int TP, int WGC, int OCC>
+template <int TC, int TP, int WGC, int OCC, int BKT = 64>
 dat_status launch_igemm_dma(IgemmArgs a, hipStream_t st) {
   if ((int64_t)a.B * a.Hin * a.Win * a.Cin >= (1ll << 31) || (int64_t)a.Cout * a.Ktot >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;
-  if (a.Cin % 64 != 0 || a.Ktot < 64 || a.Ktot % 64 != 0) return DAT_ERR_UNSUPPORTED;
+  if (a.Cin % BKT != 0 || a.Ktot < BKT || a.Ktot % BKT != 0) return DAT_ERR_UNSUPPORTED;
   a.nct = (a.Cout + TC - 1) / TC;
   a.npt = (a.M + TP - 1) / TP;
   if (a.npt == 0) return DAT_OK;
   const int npt8 = (a.npt + 7) / 8 * 8;
-  hipLaunchKernelGGL((igemm_dma_kernel<TC, TP, WGC, OCC>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<TC, TP, WGC, OCC, BKT>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -549,8 +551,18 @@ std::atomic<int64_t> g_launches{0};
 dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
   g_launches.fetch_add(1, std::memory_order_relaxed);
   if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
-  if (a.Cout <= 32) return pick_depth<32, 128, 1>(a, st);
-  if (a.Cout <= 64) return pick_depth<64, 128, 2>(a, st);
+  // narrow channel tiles: the direct-to-LDS kernel wherever its k-tile divides the contraction channels,
+  // except 1x1 layers with a long contraction into <= 64 channels (HBM-bound reads: deep register
+  // prefetch with two workgroups per CU streams them at the copy rate)
+  if (a.Cout <= 32) {
+    if (a.Cin % 64 == 0 && a.Ktot >= 64) return launch_igemm_dma<32, 128, 1, 6>(a, st);
+    return pick_depth<32, 128, 1>(a, st);
+  }
+  if (a.Cout <= 64) {
+    if (a.Cin % 64 == 0 && a.Ktot >= 64 && (a.KH * a.KW > 1 || a.Ktot < 256)) return launch_igemm_dma<64, 128, 2, 5>(a, st);
+    if (a.Cin % 64 != 0 && a.Cin % 32 == 0 && a.Ktot >= 32) return launch_igemm_dma<64, 128, 2, 5, 32>(a, st);
+    return pick_depth<64, 128, 2>(a, st);
+  }
   return pick_depth_wide(a, st);
 }
 
