@@ -1,22 +1,25 @@
 // bf16 convolutions as implicit GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16,
 // fp32 accumulate): forward, backward-data and backward-weight of the conv layers that make
 // up dat_attack / dat_step.  Written for 64-wide wavefronts: a 256-thread workgroup is four
-// waves in a 2x2 arrangement, each wave owning a (TC/2 channels) x (TP/2 pixels) accumulator
-// block made of 32x32 MFMA tiles.
+// waves (2x2, or 1x4 for 32-channel tiles), each wave owning a block of 32x32 MFMA accumulators.
 //
-// Forward / backward-data (one kernel, `igemm_kernel`):
+// Forward / backward-data:
 //   D[c][p] = sum_k Wt[c][k] * X[p][k],  k = (r, s, ci) flattened, ci fastest.
 //   Wt rows are output channels ([Cout][k*k*Cin], K-contiguous); X[p][k] is the im2col view of
 //   the NHWC input, gathered on the fly: 8 consecutive k are 8 consecutive channels of one tap,
-//   i.e. one 16-byte vector.  Both operands are staged in LDS as [row][32 k] tiles with an XOR
-//   swizzle of the 16-byte slots (slot ^= (row>>1)&3) so that the 16-byte fragment reads of
-//   the 32 lanes sharing a k-slot hit distinct banks; tiles are double buffered and the next
-//   tile's global loads are issued before the current tile's MFMAs.
-//   Backward-data is the same contraction over the output gradient with the flipped,
-//   transposed filter ([Cin][k][k][Cout]), unit output stride, and an input "dilation" equal
-//   to the forward stride (taps that fall between samples contribute zero).
-//   The epilogue adds an optional residual (or the previously stored gradient) in fp32, rounds
-//   once to bf16, transposes through LDS and writes 16-byte channel vectors.
+//   i.e. one 16-byte vector.  Both operands sit in LDS as [row][BK k] tiles (BK = 32 or 64) with
+//   an XOR swizzle of the 16-byte slots so that the 16-byte fragment reads of the 32 lanes
+//   sharing a k-slot hit distinct banks.  Two kernels fill those tiles:
+//   * `igemm_dma_kernel` (contraction channels a multiple of BK): global memory -> LDS directly
+//     (global_load_lds_dwordx4), one LDS stage, four or more workgroups resident per CU;
+//   * `igemm_kernel` (any channel count, and the long 1x1 contractions into <= 64 channels):
+//     global -> registers -> LDS, double buffered, loads running PF k-tiles ahead.
+//   Backward-data is the same contraction over the output gradient: stride 1 with the flipped,
+//   transposed filter ([Cin][k][k][Cout]); stride 2 as four launches, one per parity class of the
+//   input pixels, each a dense stride-1 convolution with that class's sub-filter.
+//   The shared epilogue adds an optional residual (or the previously stored gradient) in fp32,
+//   rounds once to bf16, transposes through LDS, writes 16-byte channel vectors and can emit the
+//   per-channel (sum, sum of squares) of what it stored: the batch statistics of the BN that follows.
 //   Workgroups are numbered so that the channel tiles of one pixel tile land on the same XCD
 //   (ids congruent mod 8 share an L2), which keeps the gathered activations L2-resident.
 //
