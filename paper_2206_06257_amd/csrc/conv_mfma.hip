@@ -65,6 +65,7 @@ struct IgemmArgs {
   const bf16_t* in;     // [B][Hin][Win][Cin]
   const bf16_t* wt;     // [Cout][KH*KW*Cin]
   const bf16_t* res;    // optional [M][Cout] added before rounding
+  const uint8_t* res_mask;   // optional: bit j of byte e/8 gates element e of `res` (a ReLU mask: res*mask is added)
   bf16_t* out;          // [M][Cout], M = B*Hout*Wout
   int B, Hin, Win, Cin, Hout, Wout, Cout;   // Hout x Wout = grid of output pixels this launch computes
   int KH, KW, ostride, pad_h, pad_w;
@@ -114,7 +115,18 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
 #pragma unroll
     for (int u = 0; u < TP / RPP; ++u) {
       const int m = m0 + pr0 + u * RPP;
-      rv[u] = (m < a.M && ch < a.Cout) ? *reinterpret_cast<const uint4*>(a.res + out_row(a, m) * a.Cout + ch) : make_uint4(0u, 0u, 0u, 0u);
+      rv[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (m < a.M && ch < a.Cout) {
+        const int64_t e = out_row(a, m) * a.Cout + ch;
+        rv[u] = *reinterpret_cast<const uint4*>(a.res + e);
+        if (a.res_mask) {
+          const uint32_t k = a.res_mask[e >> 3];
+          rv[u].x &= ((k & 1u) ? 0xffffu : 0u) | ((k & 2u) ? 0xffff0000u : 0u);
+          rv[u].y &= ((k & 4u) ? 0xffffu : 0u) | ((k & 8u) ? 0xffff0000u : 0u);
+          rv[u].z &= ((k & 16u) ? 0xffffu : 0u) | ((k & 32u) ? 0xffff0000u : 0u);
+          rv[u].w &= ((k & 64u) ? 0xffffu : 0u) | ((k & 128u) ? 0xffff0000u : 0u);
+        }
+      }
     }
     // (the main loop ended with a barrier: every wave is done with the operand tiles)
 #pragma unroll
@@ -851,7 +863,7 @@ int conv_stat_slabs(int64_t rows, int stride) {
 
 dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
-  a.in = x; a.wt = w; a.res = res; a.out = y;
+  a.in = x; a.wt = w; a.res = res; a.res_mask = nullptr; a.out = y;
   a.B = g.B; a.Hin = g.H; a.Win = g.W; a.Cin = g.Cin; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
   a.KH = g.k; a.KW = g.k; a.ostride = g.stride; a.pad_h = a.pad_w = g.pad;
   a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
@@ -861,9 +873,11 @@ dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res
   return run_igemm(a, st);
 }
 
-dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st) {
+dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st,
+                                   const bf16_t* masked_res, const uint8_t* res_mask) {
+  if (accumulate && masked_res) return DAT_ERR_ARG;
   IgemmArgs a;
-  a.in = dy; a.res = accumulate ? dx : nullptr; a.out = dx;
+  a.in = dy; a.res = accumulate ? dx : masked_res; a.res_mask = masked_res ? res_mask : nullptr; a.out = dx;
   a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Cout = g.Cin;
   a.ostride = 1; a.outH = g.H; a.outW = g.W; a.nct = a.npt = 0;
   if (g.stride == 1) {
@@ -915,7 +929,7 @@ dat_status launch_stem_weight_transform(const float* master, bf16_t* vf, bf16_t*
 
 dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
-  a.in = x2; a.wt = vf; a.res = nullptr; a.out = y;
+  a.in = x2; a.wt = vf; a.res = nullptr; a.res_mask = nullptr; a.out = y;
   a.B = g.B; a.Hin = g.H / 2; a.Win = g.W / 2; a.Cin = 32; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
   a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 2;
   a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
@@ -927,7 +941,7 @@ dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y,
 
 dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16_t* dx2, const ConvGeom& g, bool accumulate, hipStream_t st) {
   IgemmArgs a;
-  a.in = dy; a.wt = vb; a.res = accumulate ? dx2 : nullptr; a.out = dx2;
+  a.in = dy; a.wt = vb; a.res = accumulate ? dx2 : nullptr; a.res_mask = nullptr; a.out = dx2;
   a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H / 2; a.Wout = g.W / 2; a.Cout = 32;
   a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 1;
   a.outH = a.Hout; a.outW = a.Wout; a.ostep = 1; a.oh0 = a.ow0 = 0;

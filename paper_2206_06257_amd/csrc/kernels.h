@@ -56,7 +56,10 @@ struct ConvStats {
 int64_t conv_mfma_launch_count();
 int conv_stat_slabs(int64_t rows, int stride);
 dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st);
-dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st);
+// masked_res (optional, instead of `accumulate`): dx = conv^T(dy) + masked_res .* mask, mask one bit per element (bit j of
+// byte e/8): the gradient a residual connection carries past a ReLU, taken from the ReLU's output gradient directly.
+dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st,
+                                   const bf16_t* masked_res = nullptr, const uint8_t* res_mask = nullptr);
 // dw fp32 [Cout][k][k][Cin_real] (Cin_real <= g.Cin: padded input channels are dropped), scaled.
 // `ws` is a workspace of conv_mfma_wgrad_workspace(g) bytes.
 size_t conv_mfma_wgrad_workspace(const ConvGeom& g);

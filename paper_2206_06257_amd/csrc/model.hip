@@ -39,6 +39,8 @@ struct Op {
   bool stats_from_conv = false; // BN forward: mean/rstd come from the producing convolution's epilogue
   int fwd_bn = -1;              // conv: BN op normalising this conv's output (statistics fused into the epilogue)
   bool blocked = false;         // conv: 7x7/2 stem run on the 2x2-pixel-block layout of the network input
+  int res_grad_from = -1;       // conv: BN op whose residual gradient (d out .* ReLU mask) this conv's backward-data adds itself
+  bool res_grad_deferred = false;   // BN with residual: that gradient is not written, the conv above picks it up
   float* dv = nullptr;          //   its weight gradient in the blocked layer's shape, [Cout][4][4][32]
 };
 
@@ -221,6 +223,19 @@ bool build_graph(dat_model& m) {
         m.ops[producer[op.in]].fwd_bn = i;
         op.stats_from_conv = true;
       }
+    }
+    // Identity shortcuts: out = relu(bn(y) + r) sends d out .* mask to r, and the only other gradient of r comes
+    // from the backward-data pass of the convolution that reads r (earlier in the graph, so later in the backward
+    // sweep).  That pass can add d out .* mask in its epilogue: the residual gradient is never written on its own.
+    for (int b = 0; b < (int)m.ops.size(); ++b) {
+      Op& bn = m.ops[b];
+      if (bn.kind != OP_BNACT || bn.res <= 0 || !bn.relu) continue;
+      int users = 0, conv = -1;
+      for (int c = 0; c < (int)m.ops.size(); ++c) {
+        if (m.ops[c].in == bn.res) { ++users; if (m.ops[c].kind == OP_CONV && c < b) conv = c; }
+        if (m.ops[c].res == bn.res) ++users;
+      }
+      if (users == 2 && conv >= 0 && m.ops[conv].res_grad_from < 0) { m.ops[conv].res_grad_from = b; bn.res_grad_deferred = true; }
     }
     // the ImageNet stem runs on 2x2 pixel blocks of the network input (tensor 0 is stored blocked)
     Op& first = m.ops[0];
@@ -452,6 +467,11 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         }
         if (op.in != 0 || need_input_grad) {
           if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_stem_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
+          else if (dt == DAT_BF16 && op.res_grad_from >= 0) {
+            if (m.ghas[op.in]) return DAT_ERR_UNSUPPORTED;   // by construction nothing else has written this gradient yet
+            const Op& bn = m.ops[op.res_grad_from];
+            DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, false, nullptr, st, (const bf16_t*)m.grad[bn.out], bn.mask));
+          }
           else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], nullptr, st));
           else DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_direct_backward_data((const float*)m.grad[op.out], m.compute + m.ptab[op.p0].off, (float*)m.grad[op.in], g, m.ghas[op.in], st));
           m.ghas[op.in] = 1;
@@ -463,14 +483,15 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         m.ghas[op.in] = 1;
         break;
       case OP_BNACT: {
-        void* dres = op.res >= 0 ? m.grad[op.res] : nullptr;
-        const bool dres_acc = op.res >= 0 && m.ghas[op.res];
+        const bool deferred = op.res_grad_deferred && dt == DAT_BF16;
+        void* dres = (op.res >= 0 && !deferred) ? m.grad[op.res] : nullptr;
+        const bool dres_acc = op.res >= 0 && !deferred && m.ghas[op.res];
         // algorithmic bytes: read x, out, dout once each; write dx (and dres)
         DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (4 + (op.res >= 0)), st,
                  bnact_backward(m.act[op.in], m.act[op.out], op.mask, m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
                                 si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.sums_ready, g0, g1, 1.0f, st));
         op.sums_ready = false;
-        if (op.res >= 0) m.ghas[op.res] = 1;
+        if (op.res >= 0 && !deferred) m.ghas[op.res] = 1;
         m.ghas[op.in] = 1;
         break;
       }
