@@ -192,7 +192,7 @@ def main():
         tpath = os.path.join(ROOT, "profiles", "traffic_igemm_" + args.workload + ".json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        out["roofline"] = {"bound": "mfma", "kernel": "igemm_kernel (conv forward + backward-data)", "achieved": ach,
+        out["roofline"] = {"bound": "mfma", "kernel": "igemm_dma_kernel + igemm_kernel (all conv forward + backward-data launches)", "achieved": ach,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
                            "launches": n, "avg_launch_ms": ms / max(n, 1), "flops_per_launch": flops / max(n, 1)}
         out["kernel_classes"] = {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps,
