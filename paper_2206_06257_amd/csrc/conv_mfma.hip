@@ -21,7 +21,9 @@
 //   rounds once to bf16, transposes through LDS, writes 16-byte channel vectors and can emit the
 //   per-channel (sum, sum of squares) of what it stored: the batch statistics of the BN that follows.
 //   Workgroups are numbered so that the channel tiles of one pixel tile land on the same XCD
-//   (ids congruent mod 8 share an L2), which keeps the gathered activations L2-resident.
+//   (ids congruent mod 8 share an L2), which keeps the gathered activations L2-resident; layers
+//   with a filter window also give every XCD one contiguous range of pixel tiles, so that the
+//   rows neighbouring tiles share are re-read from that L2.
 //
 // Backward-weight (`wgrad_kernel`): dW[co][(r,s,ci)] = sum_p dY[p][co] * X[p][(r,s,ci)], a
 // contraction over pixels, which are the strided dimension of both operands.  Each thread
@@ -72,6 +74,9 @@ struct IgemmArgs {
   // output pixel (n, a, b) is stored at row (n*outH + a*ostep + oh0)*outW + b*ostep + ow0 of `out`
   int outH, outW, ostep, oh0, ow0;
   int M, Ktot, nct, npt;
+  // pixel tile -> XCD: interleaved (tile t on XCD t mod 8) or one contiguous range of tiles per XCD (neighbouring
+  // tiles, which share filter-window rows, then share an L2)
+  int xcd_contiguous;
   // Optional per-channel sums (sum v, sum v^2) of the stored (bf16-rounded) outputs -- the batch
   // statistics of the normalisation that follows -- one [2][Cout] slab per pixel tile at
   // stat_partial + (stat_slab0 + pixel_tile) * 2 * Cout.
@@ -207,12 +212,12 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
 
   // XCD-aware tile numbering: workgroup ids congruent mod 8 run on the same XCD (one L2 each), so
   // all channel tiles of a pixel tile get ids 8 apart and share the gathered activations in one L2.
-  // Pixel tiles advance through the tensor in dispatch order, which lets the next kernel start from
-  // the most recently written rows.
+  // Pixel tiles are dealt to the XCDs round robin, or (layers with a filter window) in one contiguous
+  // range per XCD.
   const int bid = blockIdx.x;
   const int q = bid >> 3;
   const int ct = q % a.nct;
-  const int pt = (q / a.nct) * 8 + (bid & 7);
+  const int pt = a.xcd_contiguous ? (bid & 7) * ((a.npt + 7) >> 3) + (q / a.nct) : (q / a.nct) * 8 + (bid & 7);
   if (pt >= a.npt) return;
   const int c0 = ct * TC, m0 = pt * TP;
 
@@ -404,7 +409,7 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   const int bid = blockIdx.x;
   const int q = bid >> 3;
   const int ct = q % a.nct;
-  const int pt = (q / a.nct) * 8 + (bid & 7);
+  const int pt = a.xcd_contiguous ? (bid & 7) * ((a.npt + 7) >> 3) + (q / a.nct) : (q / a.nct) * 8 + (bid & 7);
   if (pt >= a.npt) return;
   const int c0 = ct * TC, m0 = pt * TP;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -515,6 +520,7 @@ dat_status launch_igemm_dma(IgemmArgs a, hipStream_t st) {
   a.nct = (a.Cout + TC - 1) / TC;
   a.npt = (a.M + TP - 1) / TP;
   if (a.npt == 0) return DAT_OK;
+  a.xcd_contiguous = a.KH * a.KW > 1;   // filter windows: neighbouring tiles re-read each other's rows
   const int npt8 = (a.npt + 7) / 8 * 8;
   hipLaunchKernelGGL((igemm_dma_kernel<TC, TP, WGC, OCC, BKT>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
   DAT_LAUNCH_CHECK();
@@ -534,6 +540,7 @@ dat_status launch_igemm(IgemmArgs a, hipStream_t st) {
   a.nct = (a.Cout + TC - 1) / TC;
   a.npt = (a.M + TP - 1) / TP;
   if (a.npt == 0) return DAT_OK;
+  a.xcd_contiguous = a.KH * a.KW > 1;   // filter windows: neighbouring tiles re-read each other's rows
   const int npt8 = (a.npt + 7) / 8 * 8;
   if (a.Cin % BKT == 0 && a.Ktot > 0)
     hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC, PF, true, BKT, OCC>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
