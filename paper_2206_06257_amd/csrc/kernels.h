@@ -115,9 +115,12 @@ dat_status maxpool_backward(const uint8_t* arg, const void* dout, void* dx, bool
 dat_status gap_forward(const void* x, float* pooled, int dtype, int B, int HW, int C, hipStream_t st);
 dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dtype, int B, int HW, int C, hipStream_t st);
 // logits[B][O] = f[B][I] . W[O][I]^T + b;  backward: df, and (if dW) dW = scale * dz^T f, db = scale * sum dz.
-dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, hipStream_t st);
+// ws: optional scratch of fc_workspace_floats(B, I, O) floats (long contractions are then split over more workgroups and
+// summed in a fixed order).
+size_t fc_workspace_floats(int B, int I, int O);
+dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, float* ws, hipStream_t st);
 dat_status fc_backward(const float* f, const float* W, const float* dz, float* df, float* dW, float* db, int B, int I, int O,
-                       float scale, hipStream_t st);
+                       float scale, float* ws, hipStream_t st);
 // Softmax cross-entropy: loss_n per sample, dz = (softmax - onehot) * gscale; loss_mean[0] = mean loss_n.
 dat_status ce_forward_backward(const float* logits, const int32_t* y, float* dz, float* loss_n, float* loss_mean, int B, int O,
                                float gscale, hipStream_t st);

@@ -460,15 +460,20 @@ __global__ __launch_bounds__(kT) void gap_bwd_kernel(const float* __restrict__ d
 // One small tiled SGEMM serves the three products of the layer:
 //   C[m][n] = scale * sum_k A(m,k) * B(k,n) (+ bias[n]),  A(m,k) = A[m*sAm + k*sAk],  B(k,n) = B[k*sBk + n*sBn].
 // 32x32 output tile per workgroup, 32-deep k tiles staged in LDS (padded rows), each thread four
-// outputs.  The matrices are a few MB; the point is only not to be latency-bound.
+// outputs.  The matrices are a few MB; the point is only not to be latency-bound: the contraction
+// can be split over gridDim.z (k range [z*kchunk, (z+1)*kchunk)); then raw partial sums go to
+// ws[z][M][N] and splitk_reduce_kernel adds them in a fixed order.
 __global__ __launch_bounds__(kT) void sgemm_kernel(const float* __restrict__ A, const float* __restrict__ Bm,
                                                    const float* __restrict__ bias, float* __restrict__ Cm, int M, int N,
-                                                   int K, int64_t sAm, int64_t sAk, int64_t sBk, int64_t sBn, float scale) {
+                                                   int K, int64_t sAm, int64_t sAk, int64_t sBk, int64_t sBn, float scale,
+                                                   int kchunk, float* __restrict__ ws) {
   __shared__ float As[32][33], Bs[32][33];           // As[m][k], Bs[n][k]
   const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
   const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int k0 = 0; k0 < K; k0 += 32) {
+  const int kbeg = blockIdx.z * kchunk;
+  K = min(K, kbeg + kchunk);
+  for (int k0 = kbeg; k0 < K; k0 += 32) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int idx = tid + 256 * j;
@@ -492,9 +497,20 @@ __global__ __launch_bounds__(kT) void sgemm_kernel(const float* __restrict__ A, 
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int m = m0 + ty + 8 * r;
-      if (m < M) Cm[(int64_t)m * N + n] = acc[r] * scale + (bias ? bias[n] : 0.f);
+      if (m >= M) continue;
+      if (ws) ws[((int64_t)blockIdx.z * M + m) * N + n] = acc[r];
+      else Cm[(int64_t)m * N + n] = acc[r] * scale + (bias ? bias[n] : 0.f);
     }
   }
+}
+
+__global__ void splitk_reduce_kernel(const float* __restrict__ ws, int splits, int64_t MN, int N, float scale,
+                                     const float* __restrict__ bias, float* __restrict__ Cm) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= MN) return;
+  float s = 0.f;
+  for (int z = 0; z < splits; ++z) s += ws[(int64_t)z * MN + i];
+  Cm[i] = s * scale + (bias ? bias[i % N] : 0.f);
 }
 
 __global__ void fc_bias_grad_kernel(const float* __restrict__ dz, float* __restrict__ db, int B, int O, float scale) {
@@ -756,27 +772,47 @@ dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dty
   return DAT_OK;
 }
 
+// ws (optional): room for fc_workspace_floats(B, I, O) floats; then long contractions are split so that the launch
+// has a few hundred workgroups.
 static dat_status sgemm(const float* A, const float* Bm, const float* bias, float* Cm, int M, int N, int K, int64_t sAm,
-                        int64_t sAk, int64_t sBk, int64_t sBn, float scale, hipStream_t st) {
-  hipLaunchKernelGGL(sgemm_kernel, dim3((N + 31) / 32, (M + 31) / 32), dim3(kT), 0, st, A, Bm, bias, Cm, M, N, K, sAm, sAk, sBk,
-                     sBn, scale);
+                        int64_t sAk, int64_t sBk, int64_t sBn, float scale, float* ws, hipStream_t st) {
+  const int tiles = ((N + 31) / 32) * ((M + 31) / 32);
+  int splits = 1;
+  if (ws && K >= 256) {
+    splits = (1024 + tiles - 1) / tiles;
+    if (splits > 8) splits = 8;
+    if (splits > K / 64) splits = K / 64;
+    if (splits < 1) splits = 1;
+  }
+  const int kchunk = ((K + splits - 1) / splits + 31) / 32 * 32;
+  splits = (K + kchunk - 1) / kchunk;
+  if (splits == 1) ws = nullptr;
+  hipLaunchKernelGGL(sgemm_kernel, dim3((N + 31) / 32, (M + 31) / 32, splits), dim3(kT), 0, st, A, Bm, bias, Cm, M, N, K, sAm, sAk, sBk,
+                     sBn, scale, kchunk, ws);
   DAT_LAUNCH_CHECK();
+  if (ws) {
+    const int64_t MN = (int64_t)M * N;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(nblk(MN)), dim3(kT), 0, st, (const float*)ws, splits, MN, N, scale, bias, Cm);
+    DAT_LAUNCH_CHECK();
+  }
   return DAT_OK;
 }
 
-dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, hipStream_t st) {
+size_t fc_workspace_floats(int B, int I, int O) { return (size_t)8 * B * (size_t)(I > O ? I : O); }
+
+dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, float* ws, hipStream_t st) {
   // logits[n][o] = sum_i f[n][i] * W[o][i] + b[o]
-  return sgemm(f, W, b, logits, B, O, I, I, 1, 1, I, 1.0f, st);
+  return sgemm(f, W, b, logits, B, O, I, I, 1, 1, I, 1.0f, ws, st);
 }
 
 dat_status fc_backward(const float* f, const float* W, const float* dz, float* df, float* dW, float* db, int B, int I, int O,
-                       float scale, hipStream_t st) {
+                       float scale, float* ws, hipStream_t st) {
   // df[n][i] = sum_o dz[n][o] * W[o][i]
-  dat_status s = sgemm(dz, W, nullptr, df, B, I, O, O, 1, I, 1, 1.0f, st);
+  dat_status s = sgemm(dz, W, nullptr, df, B, I, O, O, 1, I, 1, 1.0f, ws, st);
   if (s != DAT_OK) return s;
   if (dW) {
     // dW[o][i] = scale * sum_n dz[n][o] * f[n][i];  db[o] = scale * sum_n dz[n][o]
-    s = sgemm(dz, f, nullptr, dW, O, I, B, 1, O, I, 1, scale, st);
+    s = sgemm(dz, f, nullptr, dW, O, I, B, 1, O, I, 1, scale, nullptr, st);
     if (s != DAT_OK) return s;
     hipLaunchKernelGGL(fc_bias_grad_kernel, dim3((O + 255) / 256), dim3(256), 0, st, dz, db, B, O, scale);
     DAT_LAUNCH_CHECK();

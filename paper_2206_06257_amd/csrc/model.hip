@@ -67,6 +67,7 @@ struct dat_model {
   float* gx = nullptr;
   void* wgrad_ws = nullptr; size_t wgrad_ws_bytes = 0;
   float* host_stage = nullptr;       // pinned staging for loss values
+  float* fc_ws = nullptr;            // split-K scratch of the classifier GEMMs
   float* z_keep = nullptr;           // logits of the clean pass, kept while the perturbed pass runs (TRADES regulariser)
   float* z_keep2 = nullptr;          //   ... and of the perturbed pass, kept while the clean pass runs again
   float* g_tmp = nullptr;            // second gradient vector of a two-pass objective (allocated on first use)
@@ -348,6 +349,7 @@ dat_status allocate(dat_model& m) {
   DAT_TRY(dev_alloc(m, &m.loss_steps, (size_t)m.loss_cap * 4));
   DAT_TRY(dev_alloc(m, &m.gx, (size_t)m.maxB * m.H * m.W * 3 * 4));
   DAT_TRY(dev_alloc(m, &m.z_keep, (size_t)m.maxB * m.classes * 4));
+  { const Op& fc = m.ops.back(); DAT_TRY(dev_alloc(m, &m.fc_ws, fc_workspace_floats(m.maxB, m.tens[fc.in].C, m.tens[fc.out].C) * 4)); }
   DAT_TRY(dev_alloc(m, &m.z_keep2, (size_t)m.maxB * m.classes * 4));
   if (hipHostMalloc((void**)&m.host_stage, (size_t)m.loss_cap * 4, hipHostMallocDefault) != hipSuccess) {
     (void)hipGetLastError();
@@ -428,7 +430,7 @@ dat_status forward(dat_model& m, int B, hipStream_t st) {
         break;
       case OP_FC:
         DAT_TRY(fc_forward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off,
-                           (float*)m.act[op.out], B, si.C, so.C, st));
+                           (float*)m.act[op.out], B, si.C, so.C, m.fc_ws, st));
         break;
     }
   }
@@ -505,7 +507,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         break;
       case OP_FC:
         DAT_TRY(fc_backward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, (const float*)m.grad[op.out],
-                            (float*)m.grad[op.in], g0, g1, B, si.C, so.C, 1.0f, st));
+                            (float*)m.grad[op.in], g0, g1, B, si.C, so.C, 1.0f, m.fc_ws, st));
         m.ghas[op.in] = 1;
         break;
     }
