@@ -376,44 +376,67 @@ __global__ __launch_bounds__(kT) void maxpool_fwd_kernel(const T* __restrict__ x
 }
 
 // Gather form: an input pixel receives the gradient of every window (at most four) whose recorded
-// arg-max position it is; contributions are summed in fp32 and stored once.
+// arg-max position it is; contributions are summed in fp32 and stored once.  A thread owns a 2x2 block
+// of input pixels (rows 2i, 2i+1, columns 2j, 2j+1) of 8 channels: those four pixels lie in the windows
+// (i..i+1) x (j..j+1) only, so four window loads serve four pixels.
 template <typename T>
 __global__ __launch_bounds__(kT) void maxpool_bwd_kernel(const uint8_t* __restrict__ arg, const T* __restrict__ dout,
                                                          T* __restrict__ dx, int acc, int B, int H, int W, int C,
                                                          int Ho, int Wo) {
   const int tpr = C / 8;
+  const int Hb = (H + 1) / 2, Wb = (W + 1) / 2;
   const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
-  if (v >= (int64_t)B * H * W * tpr) return;
+  if (v >= (int64_t)B * Hb * Wb * tpr) return;
   const int cv = (int)(v % tpr);
   int64_t p = v / tpr;
-  const int w = (int)(p % W); p /= W;
-  const int h = (int)(p % H);
-  const int n = (int)(p / H);
-  float sum[8];
+  const int j = (int)(p % Wb); p /= Wb;
+  const int i = (int)(p % Hb);
+  const int n = (int)(p / Hb);
+  float sum[2][2][8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) sum[j] = 0.f;
-  const int ho_lo = h / 2, ho_hi = min(Ho - 1, (h + 1) / 2);
-  const int wo_lo = w / 2, wo_hi = min(Wo - 1, (w + 1) / 2);
-  for (int ho = ho_lo; ho <= ho_hi; ++ho)
-    for (int wo = wo_lo; wo <= wo_hi; ++wo) {
-      const int r = h - (ho * 2 - 1), s = w - (wo * 2 - 1);
-      if (r < 0 || r > 2 || s < 0 || s > 2) continue;
-      const uint32_t me = 3 * r + s;
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum[a][b][e] = 0.f;
+#pragma unroll
+  for (int dh = 0; dh < 2; ++dh)
+#pragma unroll
+    for (int dw = 0; dw < 2; ++dw) {
+      const int ho = i + dh, wo = j + dw;
+      if (ho >= Ho || wo >= Wo) continue;
       const int64_t o = (((int64_t)n * Ho + ho) * Wo + wo) * C + cv * 8;
       const uint2 pk = *reinterpret_cast<const uint2*>(arg + o);
       float g[8]; V8<T>::load(dout + o, g);
+      // window (ho, wo) covers rows 2ho-1 .. 2ho+1: position r of pixel row 2i+a is 2i+a - (2ho-1) = a + 1 - 2dh
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const uint32_t pj = ((j < 4 ? pk.x : pk.y) >> (8 * (j & 3))) & 0xffu;
-        if (pj == me) sum[j] += g[j];
-      }
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int r = a + 1 - 2 * dh, c = b + 1 - 2 * dw;
+          if (r < 0 || c < 0) continue;                    // (r, c <= 2 always)
+          const uint32_t me = 3 * r + c;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const uint32_t pe = ((e < 4 ? pk.x : pk.y) >> (8 * (e & 3))) & 0xffu;
+            if (pe == me) sum[a][b][e] += g[e];
+          }
+        }
     }
-  if (acc) {
-    float old[8]; V8<T>::load(dx + v * 8, old);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sum[j] += old[j];
-  }
-  V8<T>::store(dx + v * 8, sum);
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int h = 2 * i + a, w = 2 * j + b;
+      if (h >= H || w >= W) continue;
+      const int64_t o = (((int64_t)n * H + h) * W + w) * C + cv * 8;
+      if (acc) {
+        float old[8]; V8<T>::load(dx + o, old);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum[a][b][e] += old[e];
+      }
+      V8<T>::store(dx + o, sum[a][b]);
+    }
 }
 
 template <typename T>
@@ -746,7 +769,7 @@ dat_status maxpool_forward(const void* x, void* out, uint8_t* arg, int dtype, in
 
 dat_status maxpool_backward(const uint8_t* arg, const void* dout, void* dx, bool accumulate, int dtype, int B, int H, int W, int C,
                             int Ho, int Wo, hipStream_t st) {
-  const int64_t nvec = (int64_t)B * H * W * (C / 8);
+  const int64_t nvec = (int64_t)B * ((H + 1) / 2) * ((W + 1) / 2) * (C / 8);
   DAT_BY_DTYPE(dtype,
     hipLaunchKernelGGL(maxpool_bwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, arg, (const float*)dout, (float*)dx, (int)accumulate, B, H, W, C, Ho, Wo),
     hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, arg, (const bf16_t*)dout, (bf16_t*)dx, (int)accumulate, B, H, W, C, Ho, Wo));
