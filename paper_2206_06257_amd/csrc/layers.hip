@@ -157,15 +157,20 @@ __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ 
   const int c = blockIdx.x * 8 + cl;
   double s1 = 0.0, s2 = 0.0;
   if (c < C) {
-    int s = grp;
-    for (; s + 96 < nslabs; s += 128) {
-      float a[4], b[4];
+    // eight slabs per round trip; slabs past the end contribute +0 (exact), so the order of the adds is fixed
+    for (int s = grp; s < nslabs; s += 256) {
+      float a[8], b[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { a[u] = partial[(int64_t)(s + 32 * u) * 2 * C + c]; b[u] = partial[(int64_t)(s + 32 * u) * 2 * C + C + c]; }
+      for (int u = 0; u < 8; ++u) {
+        const int su = s + 32 * u;
+        const int sc = su < nslabs ? su : nslabs - 1;     // unconditional in-range loads, selected afterwards
+        a[u] = partial[(int64_t)sc * 2 * C + c];
+        b[u] = partial[(int64_t)sc * 2 * C + C + c];
+        if (su >= nslabs) { a[u] = 0.f; b[u] = 0.f; }
+      }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { s1 += (double)a[u]; s2 += (double)b[u]; }
+      for (int u = 0; u < 8; ++u) { s1 += (double)a[u]; s2 += (double)b[u]; }
     }
-    for (; s < nslabs; s += 32) { s1 += (double)partial[(int64_t)s * 2 * C + c]; s2 += (double)partial[(int64_t)s * 2 * C + C + c]; }
   }
   sh[0][grp][cl] = s1; sh[1][grp][cl] = s2;
   __syncthreads();
@@ -190,9 +195,19 @@ __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ 
 __global__ __launch_bounds__(kT) void slab_fold_kernel(const float* __restrict__ in, int S, int W, float* __restrict__ out) {
   const int col = blockIdx.y * kT + threadIdx.x;
   if (col >= W) return;
-  const int s0 = blockIdx.x * 32, s1 = min(S, s0 + 32);
+  const int s0 = blockIdx.x * 32;
+  // all 32 loads are issued before the first add (one memory round trip instead of 32); rows past the
+  // end contribute +0, which leaves the running sum unchanged
+  float v[32];
+#pragma unroll
+  for (int u = 0; u < 32; ++u) {
+    const int su = s0 + u;
+    v[u] = in[(int64_t)(su < S ? su : S - 1) * W + col];
+    if (su >= S) v[u] = 0.f;
+  }
   float t = 0.f;
-  for (int s = s0; s < s1; ++s) t += in[(int64_t)s * W + col];
+#pragma unroll
+  for (int u = 0; u < 32; ++u) t += v[u];
   out[(int64_t)blockIdx.x * W + col] = t;
 }
 

@@ -2,8 +2,7 @@
 // "Methodologies"): start point z_0, the projected sign step
 //     z <- clip(z + alpha*sign(G), -eps, eps);  z <- min(max(z, -x), 1-x)
 // and the network input (x + z, clipped to [0,1], normalised, stored in the model's dtype),
-// fused into one HBM pass.  A thread owns 4 pixels = 12 fp32 values = three 16-byte vectors
-// of each stream, so every access is a full-width coalesced vector access.
+// fused into one HBM pass whose wavefronts read and write whole kilobytes of consecutive memory.
 // All fp32 operations are single correctly rounded operations (-ffp-contract=off).
 #include "kernels.h"
 #include "philox.h"
@@ -37,7 +36,32 @@ __device__ __forceinline__ float net_value(float x, float d, bool has_delta, con
   return v;
 }
 
-// MODE 0: init, 1: update, 2: input only.  One thread = up to 4 pixels starting at pixel 4*q.
+// MODE 0: init, 1: update, 2: input only.  A workgroup owns 1024 consecutive pixels = 768 float4 of each
+// fp32 stream; thread t touches float4 number j*256 + t (j = 0..2) of that chunk, so every load and
+// store of a wavefront covers 1 KB of consecutive memory.  The update itself is elementwise.  The bf16
+// network input is stored per pixel (one 16-byte vector of 8 channels), so the rounded values are
+// regrouped through LDS: thread t then writes pixels 4t .. 4t+3 of the chunk.
+constexpr int kPixPerBlock = 4 * kThreads;        // 1024
+
+__device__ __forceinline__ void load4(const float* __restrict__ p, int64_t e, int64_t n, float v[4]) {
+  if (e + 4 <= n) {
+    const float4 f = *reinterpret_cast<const float4*>(p + e);
+    v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = e + k < n ? p[e + k] : 0.0f;
+  }
+}
+
+__device__ __forceinline__ void store4(float* __restrict__ p, int64_t e, int64_t n, const float v[4]) {
+  if (e + 4 <= n) {
+    *reinterpret_cast<float4*>(p + e) = make_float4(v[0], v[1], v[2], v[3]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) if (e + k < n) p[e + k] = v[k];
+  }
+}
+
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restrict__ x,
                                                           const float* __restrict__ G,
@@ -45,99 +69,96 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
                                                           float* __restrict__ delta, int64_t npix,
                                                           float eps, float alpha, int init_mode,
                                                           uint64_t seed, InArgs in) {
-  const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  const int64_t p0 = q * 4;
-  if (p0 >= npix) return;
-  const int64_t e0 = p0 * 3;
-  const int np = (int)min((int64_t)4, npix - p0);
-  const bool full = np == 4;
-  float xv[12], dv[12], gv[12];
-  if (full) {
-#pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      const float4 f = reinterpret_cast<const float4*>(x + e0)[j];
-      xv[4 * j] = f.x; xv[4 * j + 1] = f.y; xv[4 * j + 2] = f.z; xv[4 * j + 3] = f.w;
-    }
-  } else {
-    for (int j = 0; j < 12; ++j) xv[j] = j < np * 3 ? x[e0 + j] : 0.0f;
-  }
+  __shared__ __attribute__((aligned(16))) uint16_t stage[kPixPerBlock * 3];
+  const int tid = threadIdx.x;
+  const int64_t n = npix * 3;
+  const int64_t ebase = (int64_t)blockIdx.x * (kPixPerBlock * 3);
   const bool has_delta = MODE != 2 || delta != nullptr;
-  if (MODE == 0) {
-    if (init_mode == DAT_INIT_UNIFORM) {
+  const bool to_lds = in.ptr && in.bf16;
 #pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const PhiloxWords w = philox_block((uint64_t)(e0 >> 2) + j, seed, kStreamInit);
-        const uint32_t ww[4] = {w.w0, w.w1, w.w2, w.w3};
+  for (int j = 0; j < 3; ++j) {
+    const int f = j * kThreads + tid;               // float4 number inside the chunk
+    const int64_t e = ebase + 4 * (int64_t)f;
+    float xv[4], dv[4];
+    if (e < n) {
+      load4(x, e, n, xv);
+      if (MODE == 0) {
+        if (init_mode == DAT_INIT_UNIFORM) {
+          const PhiloxWords w = philox_block((uint64_t)(e >> 2), seed, kStreamInit);
+          const uint32_t ww[4] = {w.w0, w.w1, w.w2, w.w3};
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float t = __fsub_rn(__fmul_rn(2.0f, u24(ww[k])), 1.0f);   // exact: (2u-1) on a 2^-23 grid
-          dv[4 * j + k] = __fmul_rn(t, eps);
+          for (int k = 0; k < 4; ++k) {
+            const float t = __fsub_rn(__fmul_rn(2.0f, u24(ww[k])), 1.0f);   // exact: (2u-1) on a 2^-23 grid
+            dv[k] = __fmul_rn(t, eps);
+          }
+        } else if (init_mode == DAT_INIT_GIVEN) {
+          load4(given, e, n, dv);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) dv[k] = clampf(dv[k], -eps, eps);
+        } else {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) dv[k] = 0.0f;
         }
-      }
-    } else if (init_mode == DAT_INIT_GIVEN) {
-      for (int j = 0; j < 12; ++j) dv[j] = j < np * 3 ? clampf(given[e0 + j], -eps, eps) : 0.0f;
-    } else {
 #pragma unroll
-      for (int j = 0; j < 12; ++j) dv[j] = 0.0f;
-    }
+        for (int k = 0; k < 4; ++k) dv[k] = box_clip(dv[k], xv[k]);
+      } else if (MODE == 1) {
+        float gv[4];
+        load4(delta, e, n, dv);
+        load4(G, e, n, gv);
 #pragma unroll
-    for (int j = 0; j < 12; ++j) dv[j] = box_clip(dv[j], xv[j]);
-  } else if (MODE == 1) {
-    if (full) {
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const float4 f = reinterpret_cast<const float4*>(delta + e0)[j];
-        dv[4 * j] = f.x; dv[4 * j + 1] = f.y; dv[4 * j + 2] = f.z; dv[4 * j + 3] = f.w;
-        const float4 h = reinterpret_cast<const float4*>(G + e0)[j];
-        gv[4 * j] = h.x; gv[4 * j + 1] = h.y; gv[4 * j + 2] = h.z; gv[4 * j + 3] = h.w;
-      }
-    } else {
-      for (int j = 0; j < 12; ++j) { dv[j] = j < np * 3 ? delta[e0 + j] : 0.0f; gv[j] = j < np * 3 ? G[e0 + j] : 0.0f; }
-    }
-#pragma unroll
-    for (int j = 0; j < 12; ++j) dv[j] = box_clip(sign_step(dv[j], gv[j], eps, alpha), xv[j]);
-  } else {
-    if (delta) for (int j = 0; j < 12; ++j) dv[j] = j < np * 3 ? delta[e0 + j] : 0.0f;
-    else for (int j = 0; j < 12; ++j) dv[j] = 0.0f;
-  }
-  if (MODE != 2) {
-    if (full) {
-#pragma unroll
-      for (int j = 0; j < 3; ++j)
-        reinterpret_cast<float4*>(delta + e0)[j] = make_float4(dv[4 * j], dv[4 * j + 1], dv[4 * j + 2], dv[4 * j + 3]);
-    } else {
-      for (int j = 0; j < np * 3; ++j) delta[e0 + j] = dv[j];
-    }
-  }
-  if (in.ptr) {
-    float nv[12];
-#pragma unroll
-    for (int j = 0; j < 12; ++j) nv[j] = net_value(xv[j], dv[j], has_delta, in, j % 3);
-    if (in.bf16) {
-      uint4* dst = reinterpret_cast<uint4*>(in.ptr);          // 8 bf16 = 16 bytes per pixel
-      for (int p = 0; p < np; ++p) {
-        uint4 o;
-        o.x = f2bf_pack(nv[3 * p], nv[3 * p + 1]);
-        o.y = (uint32_t)f2bf(nv[3 * p + 2]);
-        o.z = 0u; o.w = 0u;
-        int64_t slot = p0 + p;
-        if (in.bw) {   // 2x2 pixel blocks: pixel (n,h,w) -> block (n, h/2, w/2), position (h%2)*2 + w%2
-          const uint32_t pix = (uint32_t)slot, w = pix % (uint32_t)in.bw, hn = pix / (uint32_t)in.bw;
-          const uint32_t h = hn % (uint32_t)in.bh, n = hn / (uint32_t)in.bh;
-          slot = ((int64_t)(n * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1) + (w >> 1)) * 4 + (h & 1u) * 2 + (w & 1u);
-        }
-        dst[slot] = o;
-      }
-    } else {
-      float* dst = reinterpret_cast<float*>(in.ptr) + e0;
-      if (full) {
-#pragma unroll
-        for (int j = 0; j < 3; ++j)
-          reinterpret_cast<float4*>(dst)[j] = make_float4(nv[4 * j], nv[4 * j + 1], nv[4 * j + 2], nv[4 * j + 3]);
+        for (int k = 0; k < 4; ++k) dv[k] = box_clip(sign_step(dv[k], gv[k], eps, alpha), xv[k]);
       } else {
-        for (int j = 0; j < np * 3; ++j) dst[j] = nv[j];
+        if (delta) load4(delta, e, n, dv);
+        else {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) dv[k] = 0.0f;
+        }
+      }
+      if (MODE != 2) store4(delta, e, n, dv);
+      if (in.ptr) {
+        float nv[4];
+        const int c0 = (4 * f) % 3;                 // the chunk starts on a pixel boundary
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { int c = c0 + k; c = c >= 3 ? c - 3 : c; c = c >= 3 ? c - 3 : c; nv[k] = net_value(xv[k], dv[k], has_delta, in, c); }
+        if (to_lds) {
+          uint2 pk;
+          pk.x = f2bf_pack(nv[0], nv[1]); pk.y = f2bf_pack(nv[2], nv[3]);
+          *reinterpret_cast<uint2*>(&stage[4 * f]) = pk;
+        } else {
+          store4(reinterpret_cast<float*>(in.ptr), e, n, nv);
+        }
       }
     }
+  }
+  if (!to_lds) return;
+  __syncthreads();
+  const int64_t p0 = (int64_t)blockIdx.x * kPixPerBlock + 4 * tid;
+  if (p0 >= npix) return;
+  const int np = (int)min((int64_t)4, npix - p0);
+  uint32_t w[6];                                     // 12 bf16 = pixels 4t .. 4t+3
+  {
+    const uint2* src = reinterpret_cast<const uint2*>(&stage[12 * tid]);
+    const uint2 a = src[0], b = src[1], c = src[2];
+    w[0] = a.x; w[1] = a.y; w[2] = b.x; w[3] = b.y; w[4] = c.x; w[5] = c.y;
+  }
+  uint4* dst = reinterpret_cast<uint4*>(in.ptr);      // 8 bf16 = 16 bytes per pixel
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    if (p >= np) break;
+    // halfwords 3p, 3p+1, 3p+2 of the 12
+    uint4 o;
+    if (p == 0) { o.x = w[0]; o.y = w[1] & 0xffffu; }
+    else if (p == 1) { o.x = (w[1] >> 16) | (w[2] << 16); o.y = w[2] >> 16; }
+    else if (p == 2) { o.x = w[3]; o.y = w[4] & 0xffffu; }
+    else { o.x = (w[4] >> 16) | (w[5] << 16); o.y = w[5] >> 16; }
+    o.z = 0u; o.w = 0u;
+    int64_t slot = p0 + p;
+    if (in.bw) {   // 2x2 pixel blocks: pixel (n,h,w) -> block (n, h/2, w/2), position (h%2)*2 + w%2
+      const uint32_t pix = (uint32_t)slot, ww = pix % (uint32_t)in.bw, hn = pix / (uint32_t)in.bw;
+      const uint32_t h = hn % (uint32_t)in.bh, nimg = hn / (uint32_t)in.bh;
+      slot = ((int64_t)(nimg * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1) + (ww >> 1)) * 4 + (h & 1u) * 2 + (ww & 1u);
+    }
+    dst[slot] = o;
   }
 }
 
@@ -150,7 +171,7 @@ InArgs pack(const NetInputDesc& d) {
   return a;
 }
 
-unsigned grid_for(int64_t npix) { return (unsigned)(((npix + 3) / 4 + kThreads - 1) / kThreads); }
+unsigned grid_for(int64_t npix) { return (unsigned)((npix + kPixPerBlock - 1) / kPixPerBlock); }
 
 const NetInputDesc kNoInput = {nullptr, 0, 0, {0, 0, 0}, {1, 1, 1}, 0, 0};
 
