@@ -192,7 +192,9 @@ def main():
         tpath = os.path.join(ROOT, "profiles", "traffic_igemm_" + args.workload + ".json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        out["roofline"] = {"bound": "mfma", "kernel": "igemm_dma_kernel + igemm_kernel (all conv forward + backward-data launches)", "achieved": ach,
+        out["roofline"] = {"bound": "mfma", "kernel": "igemm_dma_kernel + igemm_kernel (conv forward + backward-data launches; the few backward-data "
+                                                      "launches that also form a batch-norm input gradient from three operand streams are "
+                                                      "listed as kernel_classes.conv_bwd_data_bn)", "achieved": ach,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
                            "launches": n, "avg_launch_ms": ms / max(n, 1), "flops_per_launch": flops / max(n, 1)}
         out["kernel_classes"] = {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps,
@@ -201,7 +203,7 @@ def main():
         if pg[0] > 0:
             out["pgd_update"] = {"GBs": pg[2] / (pg[0] * 1e-3) / 1e9, "frac_hbm": pg[2] / (pg[0] * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                  "bytes_per_element": 18}
-        total_flops = sum(prof[k][2] for k in ("conv_fwd", "conv_bwd_data", "conv_wgrad")) / args.steps
+        total_flops = sum(prof[k][2] for k in ("conv_fwd", "conv_bwd_data", "conv_bwd_data_bn", "conv_wgrad")) / args.steps
         out["roofline"]["measured_over"] = "%d further steps of the same work with a hipEvent pair around every launch (%.1f ms/step with events)" % (args.steps, ms_per_step_events)
         out["step_conv_TFLOPs"] = total_flops / 1e12
         out["step_frac_mfma_peak"] = total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS

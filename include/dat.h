@@ -234,10 +234,23 @@ typedef enum {
   DAT_PROF_CONV_WGRAD = 2,     /* backward-weight + its split reduction                  */
   DAT_PROF_BN = 3,             /* batch-norm statistics + apply, forward and backward    */
   DAT_PROF_PGD = 4,            /* fused projected sign step                              */
-  DAT_PROF_NUM_CLASSES = 5
+  DAT_PROF_CONV_BWD_DATA_BN = 5, /* backward-data passes that also form the batch-norm input
+                                    gradient while loading (DAT_OPT_FUSE_BN_INPUT_GRAD)     */
+  DAT_PROF_NUM_CLASSES = 6
 } dat_prof_class;
 dat_status dat_profile_enable(dat_model* m, int on);
 dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* launches, double* work);
+
+/* ---- execution options (same results either way; for ablations and tests) ---------------------
+ * DAT_OPT_FUSE_BN_INPUT_GRAD (default 1, bf16 models): in backward sweeps that need no weight
+ * gradients (dat_attack, dat_input_grad, dat_attack_kl) the input gradient of a batch
+ * normalisation that follows a 1x1 stride-1 convolution is not written to memory; that
+ * convolution's backward-data pass forms it from d(out), the normalisation's input and the ReLU
+ * mask while loading its operand.  0: always run the stand-alone pass.  Both settings evaluate the
+ * same fp32 expression and round to bf16 once, so they give identical bits.
+ * Returns DAT_ERR_ARG for an unknown option. */
+typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0 } dat_option;
+dat_status dat_model_set_option(dat_model* m, dat_option opt, int value);
 
 /* ---- misc ---------------------------------------------------------------------------------- */
 const char* dat_status_string(dat_status s);

@@ -21,7 +21,7 @@ EXPORTS = [
     "dat_input_grad", "dat_pgd_init", "dat_pgd_update", "dat_sgd_update", "dat_quantize", "dat_dequantize",
     "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
     "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read", "dat_aggregate", "dat_lamb_update",
-    "dat_attack_kl", "dat_step_reg",
+    "dat_attack_kl", "dat_step_reg", "dat_model_set_option",
 ]
 
 
@@ -77,8 +77,10 @@ _lib.dat_lamb_update.argtypes = [_vp, _vp, _i, _f, _f, _f, _f, _f, _f, _f, _i, _
 _lib.dat_attack_kl.argtypes = [_vp, _vp, _i, _f, _f, _i, _Init, _vp, _vp, _vp]
 _lib.dat_step_reg.argtypes = [_vp, _vp, _vp, _vp, _i, _f, _i, _vp, _vp, _vp]
 _lib.dat_profile_enable.argtypes = [_vp, _i]
+_lib.dat_model_set_option.argtypes = [_vp, _i, _i]
+OPT_FUSE_BN_INPUT_GRAD = 0
 _lib.dat_profile_read.argtypes = [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]
-PROF_CLASSES = ("conv_fwd", "conv_bwd_data", "conv_wgrad", "bn", "pgd")
+PROF_CLASSES = ("conv_fwd", "conv_bwd_data", "conv_wgrad", "bn", "pgd", "conv_bwd_data_bn")
 
 
 def _check(status, where):
@@ -197,6 +199,9 @@ class Model:
                     t=1, stream=None):
         _check(_lib.dat_lamb_update(self._h, _ptr(_dev(grads, torch.float32)), int(bool(use_adam)), eta, beta1, beta2, zeta,
                                     weight_decay, c_l, c_u, int(t), _stream(stream)), "dat_lamb_update")
+
+    def set_option(self, opt, value):
+        _check(_lib.dat_model_set_option(self._h, int(opt), int(value)), "dat_model_set_option")
 
     def profile_enable(self, on=True):
         _check(_lib.dat_profile_enable(self._h, int(bool(on))), "dat_profile_enable")

@@ -32,4 +32,16 @@ __device__ __forceinline__ uint32_t f2bf_pack(float lo, float hi) {
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
+// Input gradient of a train-mode batch normalisation for one element, from the per-channel constants
+//   a = gamma*rstd,  p = -a*rstd*(sum dy*xhat)/rows,  q = -a*(sum dy)/rows,  mu = batch mean:
+//   dx = gamma*rstd*(dy - mean(dy) - xhat*mean(dy*xhat)) = a*dy + p*(x - mu) + q.
+// Five single-rounded fp32 operations in this order wherever it is evaluated (the stand-alone pass and
+// the convolution that applies it while loading its operand), so both give the same bits.
+__device__ __forceinline__ float bn_input_grad(float dy, float x, float a, float p, float q, float mu) {
+  const float t = __fmul_rn(p, __fsub_rn(x, mu));
+  return __fadd_rn(__fadd_rn(__fmul_rn(a, dy), t), q);
+}
+// Layout of the constants: channel c at tab[(c/8)*32 + which*8 + c%8], which = 0..3 for a, p, q, mu.
+constexpr int kBnTabFloatsPerChannel = 4;
+
 }  // namespace dat

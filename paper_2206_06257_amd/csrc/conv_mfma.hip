@@ -82,6 +82,13 @@ struct IgemmArgs {
   // stat_partial + (stat_slab0 + pixel_tile) * 2 * Cout.
   int stat_mode, stat_slab0;
   float* stat_partial;
+  // Optional operand transform (1x1 stride-1 layers, igemm_kernel only): `in` is the output gradient of a batch
+  // normalisation, and the operand actually contracted is that normalisation's input gradient,
+  // bn_input_grad(in .* mask, xf_x, constants of the channel), rounded to bf16 -- formed while the tile moves from
+  // registers to LDS instead of being written to memory by a pass of its own.
+  const bf16_t* xf_x;        // [M][Cin] the normalisation's input
+  const uint8_t* xf_mask;    // one bit per element of `in` (ReLU mask), or nullptr
+  const float* xf_tab;       // 4*Cin floats, layout of bn_input_grad's constants
 };
 
 __device__ __forceinline__ int64_t out_row(const IgemmArgs& a, int m) {
@@ -195,8 +202,9 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
   }
 }
 
-template <int TC, int TP, int WGC, int PF, bool FAST, int BKT, int OCC>
+template <int TC, int TP, int WGC, int PF, bool FAST, int BKT, int OCC, bool XF = false>
 __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
+  static_assert(!XF || FAST, "the operand transform needs whole k-tiles of one tap");
   constexpr int WGP = 4 / WGC;                     // waves along channels x waves along pixels
   constexpr int WC = TC / WGC, WP = TP / WGP;      // wave tile
   constexpr int NI = WC / 32, NJ = WP / 32;        // MFMA tiles per wave
@@ -272,8 +280,9 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
   // Global loads run PF tiles ahead of the MFMAs: tile t+1 sits in LDS (other buffer) while tiles
   // t+2 .. t+1+PF are in flight into PF register sets.  Every step issues the same number of
   // unconditional loads (invalid vectors read the zero page), so nothing waits on a load early.
-  struct RegSet { u32x4 w[VW]; u32x4 x[VX]; };
+  struct RegSet { u32x4 w[VW]; u32x4 x[VX]; u32x4 y[XF ? VX : 1]; uint32_t mk[XF ? VX : 1]; int kch; };
   RegSet rs[PF];
+  extern __shared__ __attribute__((aligned(16))) float xf_tab_lds[];   // XF: the constants of all Cin channels
   int kf = 0;                                      // next tile to fetch
   auto fetch = [&](RegSet& r) {
     const bool tile_ok = kf < ntiles;
@@ -286,10 +295,18 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
     }
     if (FAST) {
       if (kc0 == 0) retap(kr, ks, kvec * 8);       // uniform: first tile of a tap
+      if (XF) r.kch = tile_ok ? kc0 : 0;
 #pragma unroll
       for (int i = 0; i < VX; ++i) {
-        const u32x4* p = (tile_ok & xok[i]) ? reinterpret_cast<const u32x4*>(a.in + xoff[i]) : zero_page;
+        const bool ok = tile_ok & xok[i];
+        const u32x4* p = ok ? reinterpret_cast<const u32x4*>(a.in + xoff[i]) : zero_page;
         r.x[i] = *p;
+        if (XF) {
+          const u32x4* py = ok ? reinterpret_cast<const u32x4*>(a.xf_x + xoff[i]) : zero_page;
+          r.y[i] = *py;
+          const uint8_t* pm = (ok && a.xf_mask) ? a.xf_mask + (xoff[i] >> 3) : reinterpret_cast<const uint8_t*>(g_zero_page);
+          r.mk[i] = a.xf_mask ? (uint32_t)*pm : (ok ? 0xffu : 0u);
+        }
         xoff[i] += BKT;
       }
       kc0 += BKT;
@@ -313,8 +330,37 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
 #pragma unroll
     for (int i = 0; i < VW; ++i)
       if (lrow + RPG * i < TC) *reinterpret_cast<u32x4*>(base + st_w + i * (RPG * RB)) = r.w[i];
+    if (XF) {
+      // the 8 channels of this thread's vectors: kch + kvec*8 .. +7
+      const float* tb = xf_tab_lds + ((r.kch >> 3) + kvec) * 32;
+      float ka[8], kp[8], kq[8], mu[8];
 #pragma unroll
-    for (int i = 0; i < VX; ++i) *reinterpret_cast<u32x4*>(base + st_x + i * (RPG * RB)) = r.x[i];
+      for (int h = 0; h < 2; ++h) {
+        const float4 va = reinterpret_cast<const float4*>(tb)[h], vp = reinterpret_cast<const float4*>(tb + 8)[h];
+        const float4 vq = reinterpret_cast<const float4*>(tb + 16)[h], vm = reinterpret_cast<const float4*>(tb + 24)[h];
+        ka[4 * h] = va.x; ka[4 * h + 1] = va.y; ka[4 * h + 2] = va.z; ka[4 * h + 3] = va.w;
+        kp[4 * h] = vp.x; kp[4 * h + 1] = vp.y; kp[4 * h + 2] = vp.z; kp[4 * h + 3] = vp.w;
+        kq[4 * h] = vq.x; kq[4 * h + 1] = vq.y; kq[4 * h + 2] = vq.z; kq[4 * h + 3] = vq.w;
+        mu[4 * h] = vm.x; mu[4 * h + 1] = vm.y; mu[4 * h + 2] = vm.z; mu[4 * h + 3] = vm.w;
+      }
+#pragma unroll
+      for (int i = 0; i < VX; ++i) {
+        u32x4 o;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const uint32_t gw = r.x[i][d], yw = r.y[i][d];
+          const float g0 = ((r.mk[i] >> (2 * d)) & 1u) ? __uint_as_float(gw << 16) : 0.f;
+          const float g1 = ((r.mk[i] >> (2 * d + 1)) & 1u) ? __uint_as_float(gw & 0xffff0000u) : 0.f;
+          const float v0 = bn_input_grad(g0, __uint_as_float(yw << 16), ka[2 * d], kp[2 * d], kq[2 * d], mu[2 * d]);
+          const float v1 = bn_input_grad(g1, __uint_as_float(yw & 0xffff0000u), ka[2 * d + 1], kp[2 * d + 1], kq[2 * d + 1], mu[2 * d + 1]);
+          o[d] = f2bf_pack(v0, v1);
+        }
+        *reinterpret_cast<u32x4*>(base + st_x + i * (RPG * RB)) = o;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < VX; ++i) *reinterpret_cast<u32x4*>(base + st_x + i * (RPG * RB)) = r.x[i];
+    }
   };
   // fragment read offsets (bytes inside a tile) per MFMA k-step
   int fa_off[KS][NI], fb_off[KS][NJ];
@@ -341,6 +387,11 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
     fetch(first);
 #pragma unroll
     for (int p = 0; p < PF; ++p) fetch(rs[p]);
+    if (XF) {
+      for (int i = tid; i < a.Cin; i += kThreads)
+        reinterpret_cast<float4*>(xf_tab_lds)[i] = reinterpret_cast<const float4*>(a.xf_tab)[i];
+      __syncthreads();
+    }
     stash(0, first);
   }
   __syncthreads();
@@ -533,6 +584,23 @@ __global__ void widen_kernel(const bf16_t* __restrict__ src, float* __restrict__
 }
 
 // OCC: waves per SIMD the register allocation is held to (1 = no constraint)
+// 1x1 stride-1 layers whose operand is transformed on the way into LDS (see IgemmArgs::xf_x)
+template <int TC, int TP, int WGC, int PF, int BKT, int OCC>
+dat_status launch_igemm_xf(IgemmArgs a, hipStream_t st) {
+  if ((int64_t)a.B * a.Hin * a.Win * a.Cin >= (1ll << 31) || (int64_t)a.Cout * a.Ktot >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;
+  if (a.KH != 1 || a.KW != 1 || a.ostride != 1 || a.Cin % BKT != 0 || a.Ktot != a.Cin) return DAT_ERR_UNSUPPORTED;
+  const size_t tab_bytes = (size_t)a.Cin * kBnTabFloatsPerChannel * sizeof(float);
+  if (tab_bytes > 32768) return DAT_ERR_UNSUPPORTED;
+  a.nct = (a.Cout + TC - 1) / TC;
+  a.npt = (a.M + TP - 1) / TP;
+  if (a.npt == 0) return DAT_OK;
+  a.xcd_contiguous = 0;
+  const int npt8 = (a.npt + 7) / 8 * 8;
+  hipLaunchKernelGGL((igemm_kernel<TC, TP, WGC, PF, true, BKT, OCC, true>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), tab_bytes, st, a);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
 template <int TC, int TP, int WGC, int PF, int BKT, int OCC = 1>
 dat_status launch_igemm(IgemmArgs a, hipStream_t st) {
   // 32-bit element offsets inside the kernel
@@ -573,6 +641,10 @@ std::atomic<int64_t> g_launches{0};
 dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
   g_launches.fetch_add(1, std::memory_order_relaxed);
   if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
+  if (a.xf_tab) {
+    if (a.Cout <= 64) return launch_igemm_xf<64, 128, 2, 2, 64, 1>(a, st);
+    return launch_igemm_xf<128, 128, 2, 2, 32, 2>(a, st);
+  }
   // narrow channel tiles: the direct-to-LDS kernel wherever its k-tile divides the contraction channels,
   // except 1x1 layers with a long contraction into <= 64 channels (HBM-bound reads: deep register
   // prefetch with two workgroups per CU streams them at the copy rate)
@@ -870,6 +942,7 @@ int conv_stat_slabs(int64_t rows, int stride) {
 
 dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
+  a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
   a.in = x; a.wt = w; a.res = res; a.res_mask = nullptr; a.out = y;
   a.B = g.B; a.Hin = g.H; a.Win = g.W; a.Cin = g.Cin; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
   a.KH = g.k; a.KW = g.k; a.ostride = g.stride; a.pad_h = a.pad_w = g.pad;
@@ -880,10 +953,22 @@ dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res
   return run_igemm(a, st);
 }
 
+bool conv_mfma_bn_operand_ok(const ConvGeom& g) {
+  // The convolution's output channels are the contraction of its backward-data pass, its input channels the
+  // rows of the result.  Every channel tile of the result transforms the operand again, so this pays only when
+  // one tile covers all of them (measured: break-even at two tiles, a loss beyond) and the contraction is at
+  // least two k-tiles long.
+  return g.k == 1 && g.stride == 1 && g.pad == 0 && g.Cin % 8 == 0 && g.Cin > 32 && g.Cin <= 128 && g.Cout >= 2 * g.Cin &&
+         g.Cout % (g.Cin <= 64 ? 64 : 32) == 0 && (size_t)g.Cout * kBnTabFloatsPerChannel * sizeof(float) <= 32768;
+}
+
 dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st,
-                                   const bf16_t* masked_res, const uint8_t* res_mask) {
+                                   const bf16_t* masked_res, const uint8_t* res_mask, const BnOperand* bn) {
   if (accumulate && masked_res) return DAT_ERR_ARG;
+  if (bn && !conv_mfma_bn_operand_ok(g)) return DAT_ERR_UNSUPPORTED;
   IgemmArgs a;
+  a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
+  if (bn) { a.xf_x = bn->x; a.xf_mask = bn->mask; a.xf_tab = bn->tab; }
   a.in = dy; a.res = accumulate ? dx : masked_res; a.res_mask = masked_res ? res_mask : nullptr; a.out = dx;
   a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Cout = g.Cin;
   a.ostride = 1; a.outH = g.H; a.outW = g.W; a.nct = a.npt = 0;
@@ -936,6 +1021,7 @@ dat_status launch_stem_weight_transform(const float* master, bf16_t* vf, bf16_t*
 
 dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
+  a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
   a.in = x2; a.wt = vf; a.res = nullptr; a.res_mask = nullptr; a.out = y;
   a.B = g.B; a.Hin = g.H / 2; a.Win = g.W / 2; a.Cin = 32; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
   a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 2;
@@ -948,6 +1034,7 @@ dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y,
 
 dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16_t* dx2, const ConvGeom& g, bool accumulate, hipStream_t st) {
   IgemmArgs a;
+  a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
   a.in = dy; a.wt = vb; a.res = accumulate ? dx2 : nullptr; a.res_mask = nullptr; a.out = dx2;
   a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H / 2; a.Wout = g.W / 2; a.Cout = 32;
   a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 1;

@@ -58,8 +58,17 @@ int conv_stat_slabs(int64_t rows, int stride);
 dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st);
 // masked_res (optional, instead of `accumulate`): dx = conv^T(dy) + masked_res .* mask, mask one bit per element (bit j of
 // byte e/8): the gradient a residual connection carries past a ReLU, taken from the ReLU's output gradient directly.
+// bn (optional, layers for which conv_mfma_bn_operand_ok holds): `dy` is the output gradient of the batch normalisation
+// that follows this convolution; the pass then contracts bn_input_grad(dy .* mask, x, constants) rounded to bf16, i.e.
+// what bnact_backward would have written as dx, without that tensor ever being stored.
+struct BnOperand {
+  const bf16_t* x;       // the normalisation's input (= this convolution's forward output)
+  const uint8_t* mask;   // ReLU mask of the normalisation's output, or nullptr
+  const float* tab;      // constants written by bnact_backward
+};
+bool conv_mfma_bn_operand_ok(const ConvGeom& g);
 dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st,
-                                   const bf16_t* masked_res = nullptr, const uint8_t* res_mask = nullptr);
+                                   const bf16_t* masked_res = nullptr, const uint8_t* res_mask = nullptr, const BnOperand* bn = nullptr);
 // dw fp32 [Cout][k][k][Cin_real] (Cin_real <= g.Cin: padded input channels are dropped), scaled.
 // `ws` is a workspace of conv_mfma_wgrad_workspace(g) bytes.
 size_t conv_mfma_wgrad_workspace(const ConvGeom& g);
@@ -97,12 +106,13 @@ dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, in
 dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mask, int dtype, int64_t rows, int C, const float* mean,
                          const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st);
 // dy = dout masked by (out > 0) if relu.  sums[0..C) = sum dy (= dbeta), sums[C..2C) = sum dy*xhat (= dgamma).
-// Then dx (+)= gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows); dres (+)= dy.
+// Then dx (+)= gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows), evaluated as bn_input_grad; dres (+)= dy.
 // dgamma/dbeta (fp32, may be null) receive scale*sums.
-// sums_ready: `sums` already holds the two sums (and dgamma/dbeta were written): only apply.
+// tab: 4*C floats, receives the per-channel constants of bn_input_grad.  skip_apply: stop after the sums and
+// the constants (the consumer of dx then applies bn_input_grad itself while loading dout, x and mask).
 dat_status bnact_backward(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
                           bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
-                          const float* gamma, int relu, float* partial, float* sums, bool sums_ready, float* dgamma,
+                          const float* gamma, int relu, float* partial, float* sums, float* tab, bool skip_apply, float* dgamma,
                           float* dbeta, float scale, hipStream_t st);
 dat_status biasact_forward(const void* x, void* out, int dtype, int64_t rows, int C, const float* bias, int relu, hipStream_t st);
 dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx_accumulate, int dtype, int64_t rows, int C,

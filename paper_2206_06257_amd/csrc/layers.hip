@@ -151,7 +151,9 @@ __global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, 
 template <int MODE>
 __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ partial, int nslabs, int C, int64_t rows,
                                                       float* __restrict__ o1, float* __restrict__ o2, float* __restrict__ e1,
-                                                      float* __restrict__ e2, float scale) {
+                                                      float* __restrict__ e2, float scale,
+                                                      const float* __restrict__ gamma = nullptr, const float* __restrict__ mean = nullptr,
+                                                      const float* __restrict__ rstd = nullptr, float* __restrict__ tab = nullptr) {
   __shared__ double sh[2][32][8];
   const int cl = threadIdx.x & 7, grp = threadIdx.x >> 3;
   const int c = blockIdx.x * 8 + cl;
@@ -188,6 +190,14 @@ __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ 
     if (o2) o2[c] = (float)s2;
     if (e1) e1[c] = (float)(s1 * (double)scale);
     if (e2) e2[c] = (float)(s2 * (double)scale);
+    if (tab) {   // constants of bn_input_grad for this channel
+      const double a = (double)gamma[c] * (double)rstd[c];
+      float* t = tab + (c >> 3) * 32 + (c & 7);
+      t[0] = (float)a;
+      t[8] = (float)(-a * (double)rstd[c] * s2 / (double)rows);
+      t[16] = (float)(-a * s1 / (double)rows);
+      t[24] = mean[c];
+    }
   }
 }
 
@@ -263,15 +273,12 @@ __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict
                                                              const T* __restrict__ dout, T* __restrict__ dx,
                                                              int dx_acc, T* __restrict__ dres, int dres_acc,
                                                              int64_t rows, int C, int tpr, int rpp, int64_t rows_per_slab,
-                                                             float inv_rows,
-                                                             const float* __restrict__ mean, const float* __restrict__ rstd,
-                                                             const float* __restrict__ gamma, const float* __restrict__ sums,
-                                                             int relu) {
+                                                             const float* __restrict__ tab, int relu) {
   const int tid = threadIdx.x, rr = tid / tpr, cv = tid % tpr;
   if (rr >= rpp) return;
   const int c0 = cv * 8;
-  float mu[8], rs[8], ga[8], s1[8], s2[8];
-  load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(sums + c0, s1); load8f(sums + C + c0, s2);
+  float ka[8], kp[8], kq[8], mu[8];
+  load8f(tab + cv * 32, ka); load8f(tab + cv * 32 + 8, kp); load8f(tab + cv * 32 + 16, kq); load8f(tab + cv * 32 + 24, mu);
   // slabs are walked from the end of the tensor: the rows the producing kernel wrote (or the
   // preceding reduction read) last are still in the 256 MB memory-side cache
   const int64_t r0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * rows_per_slab;
@@ -314,8 +321,7 @@ __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          const float xh = (xv[u][j] - mu[j]) * rs[j];
-          q[j] = ga[j] * rs[j] * (g[u][j] - s1[j] * inv_rows - xh * s2[j] * inv_rows);
+          q[j] = bn_input_grad(g[u][j], xv[u][j], ka[j], kp[j], kq[j], mu[j]);
           if (dx_acc) q[j] += od[u][j];
         }
         V8<T>::store(dx + o, q);
@@ -723,23 +729,23 @@ dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mas
 
 dat_status bnact_backward(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
                           bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
-                          const float* gamma, int relu, float* partial, float* sums, bool sums_ready, float* dgamma,
+                          const float* gamma, int relu, float* partial, float* sums, float* tab, bool skip_apply, float* dgamma,
                           float* dbeta, float scale, hipStream_t st) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
-  if (!sums_ready) {
+  {
     SlabPlan p; dat_status s;
     DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, mask, dout, mean, rstd, relu, rows, C, partial, st, p)),
                  s = (colreduce<bf16_t, 1>(x, out, mask, dout, mean, rstd, relu, rows, C, partial, st, p)));
     if (s != DAT_OK) return s;
     hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
-                       dbeta, dgamma, scale);
+                       dbeta, dgamma, scale, gamma, mean, rstd, tab);
     DAT_LAUNCH_CHECK();
   }
-  const float inv_rows = (float)(1.0 / (double)rows);
+  if (skip_apply) return DAT_OK;
   const SlabPlan q = plan_slabs(rows, C, kMaxApplySlabs);
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, mask, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, inv_rows, mean, rstd, gamma, sums, relu),
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, mask, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, inv_rows, mean, rstd, gamma, sums, relu));
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, mask, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, (const float*)tab, relu),
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, mask, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, (const float*)tab, relu));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }

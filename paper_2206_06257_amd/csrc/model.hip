@@ -35,7 +35,9 @@ struct Op {
   float* rstd = nullptr;
   uint8_t* mask = nullptr;      // BN with ReLU: one bit per output element (out > 0), read by the backward pass
   float* sums = nullptr;        // BN backward: [2][C] sums (sum dy, sum dy*xhat)
-  bool sums_ready = false;      //   ... already produced by the convolution that completed d(out)
+  float* bn_tab = nullptr;      //   and the per-channel constants of the input gradient (4*C floats)
+  bool apply_fusable = false;   // BN: its input gradient has one consumer, a 1x1 convolution that can form it while loading
+  bool apply_deferred = false;  //   ... and does so in the current backward sweep (the gradient tensor is not written)
   bool stats_from_conv = false; // BN forward: mean/rstd come from the producing convolution's epilogue
   int fwd_bn = -1;              // conv: BN op normalising this conv's output (statistics fused into the epilogue)
   bool blocked = false;         // conv: 7x7/2 stem run on the 2x2-pixel-block layout of the network input
@@ -51,6 +53,7 @@ struct PTensor { int64_t off, numel; int fan_in, kind; };
 struct dat_model {
   dat_arch arch; int dtype; int maxB; int H, W, classes;
   int normalize = 0; float mean[3] = {0, 0, 0}, inv_std[3] = {1, 1, 1};
+  bool fuse_bn_apply = true;         // dat_model_set_option(DAT_OPT_FUSE_BN_INPUT_GRAD)
   std::vector<Shape> tens;           // logical per-sample shapes (channels as stored)
   std::vector<char> is_f32;          // pooled features and logits stay fp32 in every model
   std::vector<Op> ops;
@@ -238,6 +241,22 @@ bool build_graph(dat_model& m) {
       }
       if (users == 2 && conv >= 0 && m.ops[conv].res_grad_from < 0) { m.ops[conv].res_grad_from = b; bn.res_grad_deferred = true; }
     }
+    // A BN whose input is read by nothing else and was produced by a 1x1 stride-1 convolution: in a sweep without
+    // weight gradients that convolution's backward-data pass applies the BN input-gradient formula to d(out) while
+    // loading it, so the BN's input gradient is never stored.
+    for (int b = 0; b < (int)m.ops.size(); ++b) {
+      Op& bn = m.ops[b];
+      if (bn.kind != OP_BNACT || !bn.stats_from_conv) continue;
+      const int c = producer[bn.in];
+      int users = 0;
+      for (const Op& o : m.ops) users += (o.in == bn.in) + (o.res == bn.in);
+      const Op& cv = m.ops[c];
+      if (users != 1 || cv.fwd_bn != b || cv.res >= 0 || cv.in == 0) continue;
+      ConvGeom g;
+      g.B = 1; g.H = m.tens[cv.in].H; g.W = m.tens[cv.in].W; g.Cin = m.tens[cv.in].C; g.Ho = m.tens[cv.out].H; g.Wo = m.tens[cv.out].W;
+      g.Cout = m.tens[cv.out].C; g.k = cv.k; g.stride = cv.stride; g.pad = cv.pad;
+      bn.apply_fusable = conv_mfma_bn_operand_ok(g);
+    }
     // the ImageNet stem runs on 2x2 pixel blocks of the network input (tensor 0 is stored blocked)
     Op& first = m.ops[0];
     if (first.kind == OP_CONV && first.in == 0 && first.res < 0) {
@@ -319,6 +338,7 @@ dat_status allocate(dat_model& m) {
       DAT_TRY(dev_alloc(m, &op.mean, (size_t)m.tens[op.in].C * 4));
       DAT_TRY(dev_alloc(m, &op.rstd, (size_t)m.tens[op.in].C * 4));
       DAT_TRY(dev_alloc(m, &op.sums, (size_t)m.tens[op.in].C * 8));
+      DAT_TRY(dev_alloc(m, &op.bn_tab, (size_t)m.tens[op.in].C * 16));
       if (op.relu) DAT_TRY(dev_alloc(m, &op.mask, (size_t)m.maxB * m.tens[op.in].numel() / 8));
     }
     if (op.kind == OP_MAXPOOL) DAT_TRY(dev_alloc(m, &op.argmax, (size_t)m.maxB * m.tens[op.out].numel()));
@@ -469,6 +489,17 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         }
         if (op.in != 0 || need_input_grad) {
           if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_stem_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
+          else if (dt == DAT_BF16 && op.fwd_bn >= 0 && m.ops[op.fwd_bn].apply_deferred) {
+            Op& bn = m.ops[op.fwd_bn];
+            bn.apply_deferred = false;
+            const BnOperand bo{(const bf16_t*)m.act[bn.in], bn.relu ? bn.mask : nullptr, bn.bn_tab};
+            const bool rg = op.res_grad_from >= 0;
+            if (rg && m.ghas[op.in]) return DAT_ERR_UNSUPPORTED;
+            DAT_PROF(m, DAT_PROF_CONV_BWD_DATA_BN, conv_flops(g, op.cin_real), st,
+                     conv_mfma_backward_data((const bf16_t*)m.grad[bn.out], op.w16T, (bf16_t*)m.grad[op.in], g, rg ? false : (bool)m.ghas[op.in], nullptr, st,
+                                             rg ? (const bf16_t*)m.grad[m.ops[op.res_grad_from].out] : nullptr,
+                                             rg ? m.ops[op.res_grad_from].mask : nullptr, &bo));
+          }
           else if (dt == DAT_BF16 && op.res_grad_from >= 0) {
             if (m.ghas[op.in]) return DAT_ERR_UNSUPPORTED;   // by construction nothing else has written this gradient yet
             const Op& bn = m.ops[op.res_grad_from];
@@ -488,13 +519,15 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         const bool deferred = op.res_grad_deferred && dt == DAT_BF16;
         void* dres = (op.res >= 0 && !deferred) ? m.grad[op.res] : nullptr;
         const bool dres_acc = op.res >= 0 && !deferred && m.ghas[op.res];
+        // no weight gradients wanted, nothing stored in d(in) yet, no residual gradient to write: leave the input
+        // gradient to the convolution below
+        op.apply_deferred = op.apply_fusable && m.fuse_bn_apply && !grads && dt == DAT_BF16 && !m.ghas[op.in] && !dres;
         // algorithmic bytes: read x, out, dout once each; write dx (and dres)
         DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (4 + (op.res >= 0)), st,
                  bnact_backward(m.act[op.in], m.act[op.out], op.mask, m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
-                                si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.sums_ready, g0, g1, 1.0f, st));
-        op.sums_ready = false;
+                                si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.bn_tab, op.apply_deferred, g0, g1, 1.0f, st));
         if (op.res >= 0 && !deferred) m.ghas[op.res] = 1;
-        m.ghas[op.in] = 1;
+        if (!op.apply_deferred) m.ghas[op.in] = 1;
         break;
       }
       case OP_MAXPOOL:
@@ -774,6 +807,14 @@ extern "C" dat_status dat_sgd_update(dat_model* m, const float* grads, float lr,
   DAT_TRY(launch_sgd(m->master, grads, lr, m->d, st));
   DAT_TRY(refresh_compute(*m, st));
   return DAT_OK;
+}
+
+extern "C" dat_status dat_model_set_option(dat_model* m, dat_option opt, int value) {
+  if (!m) return DAT_ERR_ARG;
+  switch (opt) {
+    case DAT_OPT_FUSE_BN_INPUT_GRAD: m->fuse_bn_apply = value != 0; return DAT_OK;
+  }
+  return DAT_ERR_ARG;
 }
 
 extern "C" dat_status dat_profile_enable(dat_model* m, int on) {

@@ -195,6 +195,29 @@ def test_bf16_damped_branches_tight(dat, arch, B, H, W, classes):
     assert got["gx"] < max(2e-2, 1.5 * fl["gx"]) and got["g"] < max(2e-2, 1.5 * fl["g"])
 
 
+@pytest.mark.parametrize("B,H,W", [(5, 64, 64), (3, 96, 64)])
+def test_bn_input_grad_formed_by_the_convolution_gives_the_same_bits(dat, B, H, W):
+    """ResNet-50 bf16: the input gradient and the attack are bit-identical whether the batch-norm input
+    gradients ahead of the 1x1 convolutions are written by their own pass or formed inside the
+    convolution's backward-data pass (pixel counts that are not multiples of the 128-pixel tile)."""
+    mean, std = MEAN, STD
+    gpu = dat.Model(dat.ARCH_RESNET50, dat.BF16, B, H, W, 12, mean, std)
+    gpu.set_params(syn.perturbed_params(41, gpu.offsets, gpu.fan_in, gpu.kind))
+    xd, yd = _cuda(syn.images(41, B, H, W)), _cuda(syn.labels(41, B, 12))
+    res = {}
+    for fuse in (1, 0, 1):
+        gpu.set_option(dat.OPT_FUSE_BN_INPUT_GRAD, fuse)
+        gx, logits, loss = gpu.input_grad(xd, yd)
+        d = gpu.attack(xd, yd, EPS, ALPHA, 2, dat.INIT_UNIFORM, seed=9)
+        cur = (gx.cpu().numpy(), logits.cpu().numpy(), d.cpu().numpy())
+        assert np.isfinite(cur[0]).all() and np.abs(cur[0]).max() > 0
+        if res:
+            for a, b in zip(cur, res["first"]):
+                assert np.array_equal(a, b)
+        else:
+            res["first"] = cur
+
+
 def test_batch_and_argument_errors(dat):
     gpu = dat.Model(dat.ARCH_TINYCNN, dat.F32, 4, 8, 8, 10)
     x = torch.zeros(8, 8, 8, 3, device="cuda"); y = torch.zeros(8, dtype=torch.int32, device="cuda")
