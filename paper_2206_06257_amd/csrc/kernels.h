@@ -103,17 +103,25 @@ dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, in
                              float* dgamma, float scale, hipStream_t st);
 // out = act(gamma*((x-mean)*rstd) + beta [+ res])
 // mask (optional, rows*C/8 bytes): bit j of byte e/8 = (out[e] > 0), what the backward pass needs of `out`.
+// res_bn (optional): `res` is the INPUT of a second normalisation without activation (the one on a projection
+// shortcut); the residual added is its output rounded to the storage type, which is then never stored.
+struct BnParams { const float* mean; const float* rstd; const float* gamma; const float* beta; };
 dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mask, int dtype, int64_t rows, int C, const float* mean,
-                         const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st);
-// dy = dout masked by (out > 0) if relu.  sums[0..C) = sum dy (= dbeta), sums[C..2C) = sum dy*xhat (= dgamma).
-// Then dx (+)= gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows), evaluated as bn_input_grad; dres (+)= dy.
-// dgamma/dbeta (fp32, may be null) receive scale*sums.
-// tab: 4*C floats, receives the per-channel constants of bn_input_grad.  skip_apply: stop after the sums and
-// the constants (the consumer of dx then applies bn_input_grad itself while loading dout, x and mask).
-dat_status bnact_backward(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
-                          bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
-                          const float* gamma, int relu, float* partial, float* sums, float* tab, bool skip_apply, float* dgamma,
-                          float* dbeta, float scale, hipStream_t st);
+                         const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st, const BnParams* res_bn = nullptr);
+// Backward, first half.  dy = dout masked by (out > 0) if relu.  sums[0..C) = sum dy (= dbeta), sums[C..2C) = sum dy*xhat
+// (= dgamma); dgamma/dbeta (fp32, may be null) receive scale*sums; tab (4*C floats) receives the per-channel constants
+// of bn_input_grad.  second (optional; needs relu and mask): a second normalisation that sees the same dy -- its
+// sums, constants and parameter gradients come out of the same pass over dy.
+struct BnSecond {
+  const void* x; const float* mean; const float* rstd; const float* gamma;
+  float* sums; float* tab; float* dgamma; float* dbeta;
+};
+dat_status bn_backward_reduce(const void* x, const void* out, const uint8_t* mask, const void* dout, int dtype, int64_t rows, int C,
+                              const float* mean, const float* rstd, const float* gamma, int relu, float* partial, float* sums,
+                              float* tab, float* dgamma, float* dbeta, float scale, hipStream_t st, const BnSecond* second = nullptr);
+// Backward, second half: dx (+)= bn_input_grad(dy, x, tab) = gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows); dres (+)= dy.
+dat_status bn_backward_apply(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
+                             bool dres_accumulate, int dtype, int64_t rows, int C, const float* tab, int relu, hipStream_t st);
 dat_status biasact_forward(const void* x, void* out, int dtype, int64_t rows, int C, const float* bias, int relu, hipStream_t st);
 dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx_accumulate, int dtype, int64_t rows, int C,
                             int relu, float* partial, float* dbias, float scale, hipStream_t st);

@@ -66,6 +66,73 @@ SlabPlan plan_slabs(int64_t rows, int C, int max_slabs) {
 // MODE 0: (sum x, sum x^2)            -- batch statistics
 // MODE 1: (sum dy, sum dy*xhat)       -- BN backward, dy = dout masked by out > 0 when relu
 // MODE 2: (sum dy, 0)                 -- bias backward
+//
+// dual_reduce_kernel: MODE 1 for two normalisations that share dy (the last one of a residual branch and the
+// one on its projection shortcut, whose sum passes one ReLU): (sum dy, sum dy*xhat) and (sum dy, sum dy*xhat2)
+// from one read of dy and the mask.
+template <typename T>
+__global__ __launch_bounds__(kT) void dual_reduce_kernel(const T* __restrict__ x, const T* __restrict__ x2,
+                                                         const uint8_t* __restrict__ mask, const T* __restrict__ dout,
+                                                         const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                         const float* __restrict__ mean2, const float* __restrict__ rstd2,
+                                                         int64_t rows, int C, int tpr, int rpp, int64_t rows_per_slab,
+                                                         float* __restrict__ partial, float* __restrict__ partial2) {
+  __shared__ float red[3][kT][8];
+  const int tid = threadIdx.x, rr = tid / tpr, cv = tid % tpr;
+  const bool active = rr < rpp;
+  const int c0 = cv * 8;
+  float a1[8], a2[8], a3[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { a1[j] = 0.f; a2[j] = 0.f; a3[j] = 0.f; }
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_slab;
+  const int64_t r1 = min(rows, r0 + rows_per_slab);
+  if (active) {
+    float mu[8], rs[8], mu2[8], rs2[8];
+    load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(mean2 + c0, mu2); load8f(rstd2 + c0, rs2);
+    constexpr int U = 2;
+    for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
+      float xv[U][8], yv[U][8], gv[U][8];
+      uint32_t mk[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t r = rb + (int64_t)u * rpp;
+        const int64_t o = r * C + c0;
+        mk[u] = 0xffu;
+        if (r < r1) {
+          V8<T>::load(x + o, xv[u]); V8<T>::load(x2 + o, yv[u]); V8<T>::load(dout + o, gv[u]);
+          if (mask) mk[u] = mask[o >> 3];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t r = rb + (int64_t)u * rpp;
+        if (r < r1) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float g = ((mk[u] >> j) & 1u) ? gv[u][j] : 0.f;
+            a1[j] += g; a2[j] += g * ((xv[u][j] - mu[j]) * rs[j]); a3[j] += g * ((yv[u][j] - mu2[j]) * rs2[j]);
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { red[0][tid][j] = a1[j]; red[1][tid][j] = a2[j]; red[2][tid][j] = a3[j]; }
+  __syncthreads();
+  if (rr == 0) {
+    for (int q = 1; q < rpp; ++q) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { a1[j] += red[0][q * tpr + cv][j]; a2[j] += red[1][q * tpr + cv][j]; a3[j] += red[2][q * tpr + cv][j]; }
+    }
+    float* p = partial + (int64_t)blockIdx.x * 2 * C;
+    V8<float>::store(p + c0, a1);
+    V8<float>::store(p + C + c0, a2);
+    float* p2 = partial2 + (int64_t)blockIdx.x * 2 * C;
+    V8<float>::store(p2 + c0, a1);
+    V8<float>::store(p2 + C + c0, a3);
+  }
+}
+
 template <typename T, int MODE>
 __global__ __launch_bounds__(kT) void colreduce_kernel(const T* __restrict__ x, const T* __restrict__ out,
                                                        const uint8_t* __restrict__ mask,
@@ -227,12 +294,17 @@ __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, 
                                                        int64_t rows_per_slab,
                                                        const float* __restrict__ mean, const float* __restrict__ rstd,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                       int relu) {
+                                                       int relu, const float* __restrict__ rmean, const float* __restrict__ rrstd,
+                                                       const float* __restrict__ rgamma, const float* __restrict__ rbeta) {
   const int tid = threadIdx.x, rr = tid / tpr, cv = tid % tpr;
   if (rr >= rpp) return;
   const int c0 = cv * 8;
   float mu[8], rs[8], ga[8], be[8];
   load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(beta + c0, be);
+  // rmean != nullptr: `res` is the input of a second normalisation (no activation) whose output is the residual;
+  // it is normalised here and rounded to the storage type, exactly what a pass of its own would have stored
+  float rmu[8], rrs[8], rga[8], rbe[8];
+  if (rmean) { load8f(rmean + c0, rmu); load8f(rrstd + c0, rrs); load8f(rgamma + c0, rga); load8f(rbeta + c0, rbe); }
   // slabs are walked from the end of the tensor: the rows the producing kernel wrote (or the
   // preceding reduction read) last are still in the 256 MB memory-side cache
   const int64_t r0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * rows_per_slab;
@@ -254,7 +326,14 @@ __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, 
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           o[j] = ga[j] * ((xv[u][j] - mu[j]) * rs[j]) + be[j];
-          if (res) o[j] += rv[u][j];
+          if (res) {
+            float rj = rv[u][j];
+            if (rmean) {
+              rj = rga[j] * ((rj - rmu[j]) * rrs[j]) + rbe[j];
+              if (sizeof(T) == 2) rj = bf2f(f2bf(rj));
+            }
+            o[j] += rj;
+          }
           if (relu) o[j] = o[j] > 0.f ? o[j] : 0.f;
           bits |= (o[j] > 0.f ? 1u : 0u) << j;
         }
@@ -680,7 +759,7 @@ dat_status colreduce(const void* x, const void* out, const uint8_t* mask, const 
 
 }  // namespace
 
-size_t bn_partial_floats(int64_t rows, int C) { (void)rows; return (size_t)kMaxSlabs * 2 * C; }
+size_t bn_partial_floats(int64_t rows, int C) { (void)rows; return (size_t)kMaxSlabs * 4 * C; }   // two sets of slabs (dual reduction)
 
 size_t fold_floats(int nslabs, int C) { return nslabs > 512 ? (size_t)((nslabs + 31) / 32) * 2 * C : 0; }
 
@@ -717,35 +796,54 @@ dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partia
 }
 
 dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mask, int dtype, int64_t rows, int C, const float* mean,
-                         const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st) {
+                         const float* rstd, const float* gamma, const float* beta, int relu, hipStream_t st, const BnParams* res_bn) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
+  if (res_bn && !res) return DAT_ERR_ARG;
   const SlabPlan p = plan_slabs(rows, C, kMaxApplySlabs);
+  const float* rm = res_bn ? res_bn->mean : nullptr; const float* rr = res_bn ? res_bn->rstd : nullptr;
+  const float* rg = res_bn ? res_bn->gamma : nullptr; const float* rb = res_bn ? res_bn->beta : nullptr;
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_fwd_kernel<float>, dim3(p.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)res, (float*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu),
-    hipLaunchKernelGGL(bnact_fwd_kernel<bf16_t>, dim3(p.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)res, (bf16_t*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu));
+    hipLaunchKernelGGL(bnact_fwd_kernel<float>, dim3(p.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)res, (float*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu, rm, rr, rg, rb),
+    hipLaunchKernelGGL(bnact_fwd_kernel<bf16_t>, dim3(p.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)res, (bf16_t*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu, rm, rr, rg, rb));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
 
-dat_status bnact_backward(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
-                          bool dres_accumulate, int dtype, int64_t rows, int C, const float* mean, const float* rstd,
-                          const float* gamma, int relu, float* partial, float* sums, float* tab, bool skip_apply, float* dgamma,
-                          float* dbeta, float scale, hipStream_t st) {
+dat_status bn_backward_reduce(const void* x, const void* out, const uint8_t* mask, const void* dout, int dtype, int64_t rows, int C,
+                              const float* mean, const float* rstd, const float* gamma, int relu, float* partial, float* sums,
+                              float* tab, float* dgamma, float* dbeta, float scale, hipStream_t st, const BnSecond* second) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
-  {
-    SlabPlan p; dat_status s;
+  SlabPlan p;
+  if (second) {
+    if (!relu || !mask) return DAT_ERR_ARG;
+    p = plan_slabs(rows, C, kMaxSlabs);
+    float* partial2 = partial + (size_t)kMaxSlabs * 2 * C;
+    DAT_BY_DTYPE(dtype,
+      hipLaunchKernelGGL(dual_reduce_kernel<float>, dim3(p.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)second->x, mask, (const float*)dout, mean, rstd, second->mean, second->rstd, rows, C, p.tpr, p.rpp, p.rows_per_slab, partial, partial2),
+      hipLaunchKernelGGL(dual_reduce_kernel<bf16_t>, dim3(p.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)second->x, mask, (const bf16_t*)dout, mean, rstd, second->mean, second->rstd, rows, C, p.tpr, p.rpp, p.rows_per_slab, partial, partial2));
+    DAT_LAUNCH_CHECK();
+    hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, (const float*)partial2, p.nslabs, C, rows, second->sums, second->sums + C,
+                       second->dbeta, second->dgamma, scale, second->gamma, second->mean, second->rstd, second->tab);
+    DAT_LAUNCH_CHECK();
+  } else {
+    dat_status s;
     DAT_BY_DTYPE(dtype, s = (colreduce<float, 1>(x, out, mask, dout, mean, rstd, relu, rows, C, partial, st, p)),
                  s = (colreduce<bf16_t, 1>(x, out, mask, dout, mean, rstd, relu, rows, C, partial, st, p)));
     if (s != DAT_OK) return s;
-    hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, partial, p.nslabs, C, rows, sums, sums + C,
-                       dbeta, dgamma, scale, gamma, mean, rstd, tab);
-    DAT_LAUNCH_CHECK();
   }
-  if (skip_apply) return DAT_OK;
+  hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, (const float*)partial, p.nslabs, C, rows, sums, sums + C,
+                     dbeta, dgamma, scale, gamma, mean, rstd, tab);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status bn_backward_apply(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
+                             bool dres_accumulate, int dtype, int64_t rows, int C, const float* tab, int relu, hipStream_t st) {
+  if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
   const SlabPlan q = plan_slabs(rows, C, kMaxApplySlabs);
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, mask, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, (const float*)tab, relu),
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, mask, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, (const float*)tab, relu));
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, mask, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, tab, relu),
+    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, mask, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, tab, relu));
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }

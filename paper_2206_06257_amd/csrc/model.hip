@@ -36,6 +36,9 @@ struct Op {
   uint8_t* mask = nullptr;      // BN with ReLU: one bit per output element (out > 0), read by the backward pass
   float* sums = nullptr;        // BN backward: [2][C] sums (sum dy, sum dy*xhat)
   float* bn_tab = nullptr;      //   and the per-channel constants of the input gradient (4*C floats)
+  int res_bn = -1;              // BN with residual: the residual is the output of this BN op (projection shortcut), which
+                                //   this op evaluates itself from that op's input -- forward and the shared backward sums
+  int absorbed_by = -1;         // BN on a projection shortcut: the BN op that evaluates it (its output tensor is never stored)
   bool apply_fusable = false;   // BN: its input gradient has one consumer, a 1x1 convolution that can form it while loading
   bool apply_deferred = false;  //   ... and does so in the current backward sweep (the gradient tensor is not written)
   bool stats_from_conv = false; // BN forward: mean/rstd come from the producing convolution's epilogue
@@ -228,12 +231,25 @@ bool build_graph(dat_model& m) {
         op.stats_from_conv = true;
       }
     }
+    // Projection shortcuts: out = relu(bn(y) + bn_s(y_s)).  bn_s's output has no other reader, so the final BN
+    // normalises y_s itself, and in the backward sweep d out .* mask is the output gradient of both normalisations:
+    // one pass over it gives both pairs of sums.  Neither bn_s's output nor its gradient is ever stored.
+    for (int b = 0; b < (int)m.ops.size() && !getenv("DAT_KEEP_SHORTCUT_BN"); ++b) {   // (environment switch: ablation only)
+      Op& bn = m.ops[b];
+      if (bn.kind != OP_BNACT || bn.res < 0 || !bn.relu) continue;
+      const int p = producer[bn.res];
+      if (p < 0 || m.ops[p].kind != OP_BNACT || m.ops[p].relu || m.ops[p].res >= 0 || !m.ops[p].stats_from_conv || p > b) continue;
+      int users = 0;
+      for (const Op& o : m.ops) users += (o.in == bn.res) + (o.res == bn.res);
+      if (users != 1) continue;
+      bn.res_bn = p; m.ops[p].absorbed_by = b;
+    }
     // Identity shortcuts: out = relu(bn(y) + r) sends d out .* mask to r, and the only other gradient of r comes
     // from the backward-data pass of the convolution that reads r (earlier in the graph, so later in the backward
     // sweep).  That pass can add d out .* mask in its epilogue: the residual gradient is never written on its own.
     for (int b = 0; b < (int)m.ops.size(); ++b) {
       Op& bn = m.ops[b];
-      if (bn.kind != OP_BNACT || bn.res <= 0 || !bn.relu) continue;
+      if (bn.kind != OP_BNACT || bn.res <= 0 || !bn.relu || bn.res_bn >= 0) continue;
       int users = 0, conv = -1;
       for (int c = 0; c < (int)m.ops.size(); ++c) {
         if (m.ops[c].in == bn.res) { ++users; if (m.ops[c].kind == OP_CONV && c < b) conv = c; }
@@ -408,6 +424,12 @@ NetInputDesc input_desc(const dat_model& m) {
 
 dat_status bn_forward_pair(dat_model& m, Op& op, int64_t rows, int C, hipStream_t st) {
   if (!op.stats_from_conv) DAT_TRY(bn_stats(m.act[op.in], m.dtype, rows, C, m.partial, op.mean, op.rstd, st));
+  if (op.res_bn >= 0) {   // the residual is normalised on the fly from the shortcut BN's input
+    const Op& sb = m.ops[op.res_bn];
+    const BnParams rp{sb.mean, sb.rstd, m.compute + m.ptab[sb.p0].off, m.compute + m.ptab[sb.p1].off};
+    return bnact_forward(m.act[op.in], m.act[sb.in], m.act[op.out], op.mask, m.dtype, rows, C, op.mean, op.rstd,
+                         m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off, op.relu, st, &rp);
+  }
   return bnact_forward(m.act[op.in], op.res >= 0 ? m.act[op.res] : nullptr, m.act[op.out], op.mask, m.dtype, rows, C, op.mean,
                        op.rstd, m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off, op.relu, st);
 }
@@ -438,6 +460,7 @@ dat_status forward(dat_model& m, int B, hipStream_t st) {
         DAT_TRY(biasact_forward(m.act[op.in], m.act[op.out], dt, rows_in, si.C, m.compute + m.ptab[op.p0].off, op.relu, st));
         break;
       case OP_BNACT:
+        if (op.absorbed_by >= 0) break;   // statistics came from the convolution; the absorbing BN does the rest
         // algorithmic bytes: read x twice (statistics, apply), read res, write out
         DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (3 - (int)op.stats_from_conv + (op.res >= 0)), st,
                  bn_forward_pair(m, op, rows_in, si.C, st));
@@ -492,11 +515,12 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
           else if (dt == DAT_BF16 && op.fwd_bn >= 0 && m.ops[op.fwd_bn].apply_deferred) {
             Op& bn = m.ops[op.fwd_bn];
             bn.apply_deferred = false;
-            const BnOperand bo{(const bf16_t*)m.act[bn.in], bn.relu ? bn.mask : nullptr, bn.bn_tab};
+            const Op& top = bn.absorbed_by >= 0 ? m.ops[bn.absorbed_by] : bn;   // whose d(out) and mask this BN differentiates
+            const BnOperand bo{(const bf16_t*)m.act[bn.in], top.relu ? top.mask : nullptr, bn.bn_tab};
             const bool rg = op.res_grad_from >= 0;
             if (rg && m.ghas[op.in]) return DAT_ERR_UNSUPPORTED;
             DAT_PROF(m, DAT_PROF_CONV_BWD_DATA_BN, conv_flops(g, op.cin_real), st,
-                     conv_mfma_backward_data((const bf16_t*)m.grad[bn.out], op.w16T, (bf16_t*)m.grad[op.in], g, rg ? false : (bool)m.ghas[op.in], nullptr, st,
+                     conv_mfma_backward_data((const bf16_t*)m.grad[top.out], op.w16T, (bf16_t*)m.grad[op.in], g, rg ? false : (bool)m.ghas[op.in], nullptr, st,
                                              rg ? (const bf16_t*)m.grad[m.ops[op.res_grad_from].out] : nullptr,
                                              rg ? m.ops[op.res_grad_from].mask : nullptr, &bo));
           }
@@ -516,18 +540,39 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         m.ghas[op.in] = 1;
         break;
       case OP_BNACT: {
+        // d(out) and ReLU mask this normalisation differentiates: its own, or (shortcut BN evaluated by the final BN
+        // of the branch) those of that BN, whose backward step also produced this op's sums and constants
+        const bool absorbed = op.absorbed_by >= 0;
+        const Op& top = absorbed ? m.ops[op.absorbed_by] : op;
         const bool deferred = op.res_grad_deferred && dt == DAT_BF16;
-        void* dres = (op.res >= 0 && !deferred) ? m.grad[op.res] : nullptr;
-        const bool dres_acc = op.res >= 0 && !deferred && m.ghas[op.res];
+        const bool writes_dres = op.res >= 0 && !deferred && op.res_bn < 0;
+        void* dres = writes_dres ? m.grad[op.res] : nullptr;
+        const bool dres_acc = writes_dres && m.ghas[op.res];
         // no weight gradients wanted, nothing stored in d(in) yet, no residual gradient to write: leave the input
         // gradient to the convolution below
         op.apply_deferred = op.apply_fusable && m.fuse_bn_apply && !grads && dt == DAT_BF16 && !m.ghas[op.in] && !dres;
-        // algorithmic bytes: read x, out, dout once each; write dx (and dres)
-        DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (4 + (op.res >= 0)), st,
-                 bnact_backward(m.act[op.in], m.act[op.out], op.mask, m.grad[op.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt, rows_in,
-                                si.C, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.bn_tab, op.apply_deferred, g0, g1, 1.0f, st));
-        if (op.res >= 0 && !deferred) m.ghas[op.res] = 1;
-        if (!op.apply_deferred) m.ghas[op.in] = 1;
+        if (!absorbed) {
+          BnSecond sec{}; const BnSecond* second = nullptr;
+          if (op.res_bn >= 0) {
+            Op& sb = m.ops[op.res_bn];
+            sec.x = m.act[sb.in]; sec.mean = sb.mean; sec.rstd = sb.rstd; sec.gamma = m.compute + m.ptab[sb.p0].off;
+            sec.sums = sb.sums; sec.tab = sb.bn_tab;
+            sec.dgamma = grads ? grads + m.ptab[sb.p0].off : nullptr; sec.dbeta = grads ? grads + m.ptab[sb.p1].off : nullptr;
+            second = &sec;
+          }
+          // algorithmic bytes: read x, dout (and mask) once for the sums ...
+          DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (2 + (second ? 1 : 0)), st,
+                   bn_backward_reduce(m.act[op.in], m.act[op.out], op.mask, m.grad[op.out], dt, rows_in, si.C, op.mean, op.rstd,
+                                      m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.bn_tab, g0, g1, 1.0f, st, second));
+        }
+        if (!op.apply_deferred) {
+          // ... and once more, plus writing dx (and dres), for the input gradient
+          DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (3 + (dres ? 1 : 0)), st,
+                   bn_backward_apply(m.act[op.in], m.act[top.out], top.mask, m.grad[top.out], m.grad[op.in], m.ghas[op.in], dres, dres_acc, dt,
+                                     rows_in, si.C, op.bn_tab, top.relu, st));
+          m.ghas[op.in] = 1;
+        }
+        if (writes_dres) m.ghas[op.res] = 1;
         break;
       }
       case OP_MAXPOOL:

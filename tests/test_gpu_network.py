@@ -218,6 +218,27 @@ def test_bn_input_grad_formed_by_the_convolution_gives_the_same_bits(dat, B, H, 
             res["first"] = cur
 
 
+@pytest.mark.parametrize("arch,B,H,W,classes", [(3, 5, 64, 64, 12), (1, 16, 16, 16, 10), (100, 8, 16, 16, 5)])
+def test_shortcut_bn_evaluated_by_the_branch_bn_gives_the_same_bits(dat, arch, B, H, W, classes, monkeypatch):
+    """bf16 models: the normalisation on a projection shortcut is evaluated by the branch's last BN (forward) and
+    shares its pass over d(out) (backward); with the environment switch DAT_KEEP_SHORTCUT_BN set at model creation
+    it runs as passes of its own.  Logits, input gradient and parameter gradients agree bit for bit."""
+    outs = []
+    for keep in (False, True):
+        if keep:
+            monkeypatch.setenv("DAT_KEEP_SHORTCUT_BN", "1")
+        else:
+            monkeypatch.delenv("DAT_KEEP_SHORTCUT_BN", raising=False)
+        gpu = dat.Model(arch, dat.BF16, B, H, W, classes, None, None)
+        gpu.set_params(syn.perturbed_params(41, gpu.offsets, gpu.fan_in, gpu.kind))
+        xd, yd = _cuda(syn.images(41, B, H, W)), _cuda(syn.labels(41, B, classes))
+        gx, logits, loss = gpu.input_grad(xd, yd)
+        g, l = gpu.step(xd, yd, want_loss=True)
+        outs.append((gx.cpu().numpy(), logits.cpu().numpy(), g.cpu().numpy()))
+    for a, b in zip(*outs):
+        assert np.abs(a).max() > 0 and np.array_equal(a, b)
+
+
 def test_batch_and_argument_errors(dat):
     gpu = dat.Model(dat.ARCH_TINYCNN, dat.F32, 4, 8, 8, 10)
     x = torch.zeros(8, 8, 8, 3, device="cuda"); y = torch.zeros(8, dtype=torch.int32, device="cuda")
