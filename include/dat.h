@@ -250,10 +250,12 @@ dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* la
  * same fp32 expression and round to bf16 once, so they give identical bits.
  * Returns DAT_ERR_ARG for an unknown option. */
 typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0 } dat_option;
-/* (One more switch is read from the environment by dat_model_create, because it changes the layer
- * graph: with DAT_KEEP_SHORTCUT_BN set, the batch normalisation on a projection shortcut of a bf16
- * model runs as passes of its own instead of being evaluated by the last normalisation of the
- * residual branch.  Identical bits either way.) */
+/* (Two more switches are read from the environment by dat_model_create, because they change the
+ * layer graph of a bf16 model.  DAT_KEEP_SHORTCUT_BN: the batch normalisation on a projection
+ * shortcut runs as passes of its own instead of being evaluated by the last normalisation of the
+ * residual branch.  DAT_KEEP_STEM_POOL: a BN + ReLU read only by a max-pool stores its output and
+ * the pool runs as passes of its own, instead of one fused forward pass and a backward pass that
+ * gathers d(out) from the pool's output gradient.  Identical bits either way.) */
 dat_status dat_model_set_option(dat_model* m, dat_option opt, int value);
 
 /* ---- misc ---------------------------------------------------------------------------------- */

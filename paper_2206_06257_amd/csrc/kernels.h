@@ -122,6 +122,18 @@ dat_status bn_backward_reduce(const void* x, const void* out, const uint8_t* mas
 // Backward, second half: dx (+)= bn_input_grad(dy, x, tab) = gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows); dres (+)= dy.
 dat_status bn_backward_apply(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
                              bool dres_accumulate, int dtype, int64_t rows, int C, const float* tab, int relu, hipStream_t st);
+// Both halves for a BN + ReLU (mask required) whose output feeds a 3x3/2 max-pool (padding 1) and nothing else, walked
+// in 2x2 pixel blocks.  gather = 1: d(out) is not read from `dout` but gathered from the pool's output gradient through
+// the recorded arg-max positions (the pool's backward pass evaluated in place and rounded to the storage type like the
+// tensor it replaces); gather = 0: d(out) is read from `dout`.  Same summation order either way.
+struct PoolGrad { const uint8_t* arg; const void* dpooled; int B, H, W, Ho, Wo; int gather; };
+dat_status bn_pool_backward(const void* x, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, bool skip_apply, int dtype, int C,
+                            const float* mean, const float* rstd, const float* gamma, float* partial, float* sums, float* tab,
+                            float* dgamma, float* dbeta, float scale, const PoolGrad& pg, hipStream_t st);
+// relu(gamma*((x-mean)*rstd)+beta) followed by the 3x3/2 max-pool in one pass: writes the pooled tensor, the arg-max
+// positions (as maxpool_forward) and the ReLU mask of every input pixel (as bnact_forward); the activated tensor is not stored.
+dat_status bnact_pool_forward(const void* x, void* pooled, uint8_t* arg, uint8_t* mask, int dtype, int B, int H, int W, int C, int Ho, int Wo,
+                              const float* mean, const float* rstd, const float* gamma, const float* beta, hipStream_t st);
 dat_status biasact_forward(const void* x, void* out, int dtype, int64_t rows, int C, const float* bias, int relu, hipStream_t st);
 dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx_accumulate, int dtype, int64_t rows, int C,
                             int relu, float* partial, float* dbias, float scale, hipStream_t st);

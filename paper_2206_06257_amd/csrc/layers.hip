@@ -62,6 +62,160 @@ SlabPlan plan_slabs(int64_t rows, int C, int max_slabs) {
   return p;
 }
 
+// ---- backward of BN + ReLU feeding a 3x3/2 max-pool, on 2x2 pixel blocks ------------------------
+// A thread owns the pixels (2i+a, 2j+b), a, b in {0,1}, of 8 channels.  POOL: d(out) of those pixels is
+// not read from memory but gathered from the pool's output gradient -- the four pixels lie in the windows
+// (i+dh, j+dw), dh, dw in {0,1}, at window position (a+1-2dh, b+1-2dw) when both are >= 0, and receive the
+// gradient of every window whose recorded arg-max position that is, summed in fp32 in the order
+// (dh, dw) = (0,0), (0,1), (1,0), (1,1) and rounded once to the storage type: the value the pool's own
+// backward pass would have stored.  Four window loads serve four pixels.
+struct PoolArgs {
+  const uint8_t* arg;     // [B][Ho][Wo][C] window position of the maximum
+  const void* dpooled;    // [B][Ho][Wo][C]
+  int B, H, W, Ho, Wo;
+};
+
+template <typename T, bool POOL>
+__device__ __forceinline__ void block_dout(const PoolArgs& pa, const T* __restrict__ dout, int n, int i, int j, int C, int c0, float g[2][2][8]) {
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) g[a][b][e] = 0.f;
+  if (POOL) {
+#pragma unroll
+    for (int dh = 0; dh < 2; ++dh)
+#pragma unroll
+      for (int dw = 0; dw < 2; ++dw) {
+        const int ho = i + dh, wo = j + dw;
+        if (ho >= pa.Ho || wo >= pa.Wo) continue;
+        const int64_t o = (((int64_t)n * pa.Ho + ho) * pa.Wo + wo) * C + c0;
+        const uint2 pk = *reinterpret_cast<const uint2*>(pa.arg + o);
+        float d[8]; V8<T>::load(reinterpret_cast<const T*>(pa.dpooled) + o, d);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            const int r = a + 1 - 2 * dh, c = b + 1 - 2 * dw;
+            if (r < 0 || c < 0) continue;
+            const uint32_t me = 3 * r + c;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const uint32_t pe = ((e < 4 ? pk.x : pk.y) >> (8 * (e & 3))) & 0xffu;
+              if (pe == me) g[a][b][e] += d[e];
+            }
+          }
+      }
+    if (sizeof(T) == 2) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) g[a][b][e] = bf2f(f2bf(g[a][b][e]));
+    }
+  } else {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int h = 2 * i + a, w = 2 * j + b;
+        if (h < pa.H && w < pa.W) V8<T>::load(dout + (((int64_t)n * pa.H + h) * pa.W + w) * C + c0, g[a][b]);
+      }
+  }
+}
+
+// (sum dy, sum dy*xhat) per channel, dy = d(out) .* mask, one slab of [2][C] per workgroup: a workgroup walks
+// `blocks_per_slab` consecutive 2x2 blocks, kT / (C/8) at a time; the threads of one channel vector are folded
+// through LDS in a fixed order.
+template <typename T, bool POOL>
+__global__ __launch_bounds__(kT) void block_reduce_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask, const T* __restrict__ dout,
+                                                          const float* __restrict__ mean, const float* __restrict__ rstd, int C, int tpr,
+                                                          int64_t nblocks, int64_t blocks_per_slab, float* __restrict__ partial, PoolArgs pa) {
+  __shared__ float red[2][kT][8];
+  const int tid = threadIdx.x, rr = tid / tpr, cv = tid % tpr, rpp = kT / tpr;
+  const int c0 = cv * 8;
+  const int Hb = (pa.H + 1) / 2, Wb = (pa.W + 1) / 2;
+  float a1[8], a2[8], mu[8], rs[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { a1[e] = 0.f; a2[e] = 0.f; }
+  load8f(mean + c0, mu); load8f(rstd + c0, rs);
+  const int64_t b0 = (int64_t)blockIdx.x * blocks_per_slab, b1 = min(nblocks, b0 + blocks_per_slab);
+  if (rr < rpp) {
+    for (int64_t blk = b0 + rr; blk < b1; blk += rpp) {
+      const int j = (int)(blk % Wb); const int64_t t = blk / Wb;
+      const int i = (int)(t % Hb), n = (int)(t / Hb);
+      float g[2][2][8];
+      block_dout<T, POOL>(pa, dout, n, i, j, C, c0, g);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int h = 2 * i + a, w = 2 * j + b;
+          if (h >= pa.H || w >= pa.W) continue;
+          const int64_t o = (((int64_t)n * pa.H + h) * pa.W + w) * C + c0;
+          float xv[8]; V8<T>::load(x + o, xv);
+          const uint32_t mk = mask[o >> 3];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float ge = ((mk >> e) & 1u) ? g[a][b][e] : 0.f;
+            a1[e] += ge; a2[e] += ge * ((xv[e] - mu[e]) * rs[e]);
+          }
+        }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { red[0][tid][e] = a1[e]; red[1][tid][e] = a2[e]; }
+  __syncthreads();
+  if (rr == 0) {
+    for (int q = 1; q < rpp; ++q) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { a1[e] += red[0][q * tpr + cv][e]; a2[e] += red[1][q * tpr + cv][e]; }
+    }
+    float* p = partial + (int64_t)blockIdx.x * 2 * C;
+    V8<float>::store(p + c0, a1);
+    V8<float>::store(p + C + c0, a2);
+  }
+}
+
+// dx = bn_input_grad(d(out) .* mask, x, constants) for the four pixels of a block.
+template <typename T, bool POOL>
+__global__ __launch_bounds__(kT) void block_apply_kernel(const T* __restrict__ x, const uint8_t* __restrict__ mask, const T* __restrict__ dout,
+                                                         T* __restrict__ dx, int dx_acc, int C, int tpr, int64_t nblocks,
+                                                         const float* __restrict__ tab, PoolArgs pa) {
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= nblocks * tpr) return;
+  const int cv = (int)(v % tpr);
+  const int64_t blk = v / tpr;
+  const int c0 = cv * 8;
+  const int Hb = (pa.H + 1) / 2, Wb = (pa.W + 1) / 2;
+  const int j = (int)(blk % Wb); const int64_t t = blk / Wb;
+  const int i = (int)(t % Hb), n = (int)(t / Hb);
+  float ka[8], kp[8], kq[8], mu[8];
+  load8f(tab + cv * 32, ka); load8f(tab + cv * 32 + 8, kp); load8f(tab + cv * 32 + 16, kq); load8f(tab + cv * 32 + 24, mu);
+  float g[2][2][8];
+  block_dout<T, POOL>(pa, dout, n, i, j, C, c0, g);
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int h = 2 * i + a, w = 2 * j + b;
+      if (h >= pa.H || w >= pa.W) continue;
+      const int64_t o = (((int64_t)n * pa.H + h) * pa.W + w) * C + c0;
+      float xv[8], q[8]; V8<T>::load(x + o, xv);
+      const uint32_t mk = mask[o >> 3];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) q[e] = bn_input_grad(((mk >> e) & 1u) ? g[a][b][e] : 0.f, xv[e], ka[e], kp[e], kq[e], mu[e]);
+      if (dx_acc) {
+        float od[8]; V8<T>::load(dx + o, od);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[e] += od[e];
+      }
+      V8<T>::store(dx + o, q);
+    }
+}
+
 // ---- per-channel two-value reduction -------------------------------------------------------
 // MODE 0: (sum x, sum x^2)            -- batch statistics
 // MODE 1: (sum dy, sum dy*xhat)       -- BN backward, dy = dout masked by out > 0 when relu
@@ -344,6 +498,59 @@ __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, 
       }
     }
   }
+}
+
+// Normalisation + ReLU followed by a 3x3/2 max-pool (padding 1) in one pass: the activated tensor is not
+// stored, only what later passes need of it -- the pooled maxima, the arg-max positions, and the one-bit
+// ReLU mask of every pixel.  A thread owns one pooled pixel x 8 channels and the mask bytes of the pixels
+// (2ho..2ho+1, 2wo..2wo+1), i.e. window positions (1..2, 1..2).  Values are rounded to the storage type
+// before they are compared, so ties fall as they would between stored values.
+template <typename T>
+__global__ __launch_bounds__(kT) void bnact_pool_fwd_kernel(const T* __restrict__ x, T* __restrict__ pooled, uint8_t* __restrict__ arg,
+                                                            uint8_t* __restrict__ mask, int B, int H, int W, int C, int Ho, int Wo,
+                                                            const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                            const float* __restrict__ gamma, const float* __restrict__ beta) {
+  const int tpr = C / 8;
+  const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (v >= (int64_t)B * Ho * Wo * tpr) return;
+  const int cv = (int)(v % tpr);
+  int64_t p = v / tpr;
+  const int wo = (int)(p % Wo); p /= Wo;
+  const int ho = (int)(p % Ho);
+  const int n = (int)(p / Ho);
+  const int c0 = cv * 8;
+  float mu[8], rs[8], ga[8], be[8];
+  load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(beta + c0, be);
+  float best[8]; uint32_t pos[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { best[j] = -__builtin_inff(); pos[j] = 0; }
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+    const int hi = ho * 2 + r - 1;
+    if (hi < 0 || hi >= H) continue;
+#pragma unroll
+    for (int s_ = 0; s_ < 3; ++s_) {
+      const int wi = wo * 2 + s_ - 1;
+      if (wi < 0 || wi >= W) continue;
+      const int64_t o = (((int64_t)n * H + hi) * W + wi) * C + c0;
+      float xv[8]; V8<T>::load(x + o, xv);
+      uint32_t bits = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float a = ga[j] * ((xv[j] - mu[j]) * rs[j]) + be[j];
+        a = a > 0.f ? a : 0.f;
+        bits |= (a > 0.f ? 1u : 0u) << j;
+        if (sizeof(T) == 2) a = bf2f(f2bf(a));
+        if (a > best[j]) { best[j] = a; pos[j] = 3 * r + s_; }
+      }
+      if (r >= 1 && s_ >= 1) mask[o >> 3] = (uint8_t)bits;
+    }
+  }
+  V8<T>::store(pooled + v * 8, best);
+  uint2 pk;
+  pk.x = pos[0] | (pos[1] << 8) | (pos[2] << 16) | (pos[3] << 24);
+  pk.y = pos[4] | (pos[5] << 8) | (pos[6] << 16) | (pos[7] << 24);
+  *reinterpret_cast<uint2*>(arg + v * 8) = pk;
 }
 
 template <typename T>
@@ -809,6 +1016,17 @@ dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mas
   return DAT_OK;
 }
 
+dat_status bnact_pool_forward(const void* x, void* pooled, uint8_t* arg, uint8_t* mask, int dtype, int B, int H, int W, int C, int Ho, int Wo,
+                              const float* mean, const float* rstd, const float* gamma, const float* beta, hipStream_t st) {
+  if (C % 8 != 0 || !mask || !arg) return DAT_ERR_ARG;
+  const int64_t nvec = (int64_t)B * Ho * Wo * (C / 8);
+  DAT_BY_DTYPE(dtype,
+    hipLaunchKernelGGL(bnact_pool_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (float*)pooled, arg, mask, B, H, W, C, Ho, Wo, mean, rstd, gamma, beta),
+    hipLaunchKernelGGL(bnact_pool_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (bf16_t*)pooled, arg, mask, B, H, W, C, Ho, Wo, mean, rstd, gamma, beta));
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
 dat_status bn_backward_reduce(const void* x, const void* out, const uint8_t* mask, const void* dout, int dtype, int64_t rows, int C,
                               const float* mean, const float* rstd, const float* gamma, int relu, float* partial, float* sums,
                               float* tab, float* dgamma, float* dbeta, float scale, hipStream_t st, const BnSecond* second) {
@@ -845,6 +1063,43 @@ dat_status bn_backward_apply(const void* x, const void* out, const uint8_t* mask
     hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, mask, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, tab, relu),
     hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, mask, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, tab, relu));
   DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+// The two halves for a BN + ReLU whose output feeds a 3x3/2 max-pool, on 2x2 pixel blocks.  pool->gather: d(out) is
+// gathered from the pool's output gradient (`dout` is not read); otherwise it is read from `dout`.  Both settings
+// sum in the same order.
+dat_status bn_pool_backward(const void* x, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, bool skip_apply, int dtype, int C,
+                            const float* mean, const float* rstd, const float* gamma, float* partial, float* sums, float* tab,
+                            float* dgamma, float* dbeta, float scale, const PoolGrad& pg, hipStream_t st) {
+  if (C % 8 != 0 || C > 8 * kT || !mask) return DAT_ERR_UNSUPPORTED;
+  PoolArgs pa{pg.arg, pg.dpooled, pg.B, pg.H, pg.W, pg.Ho, pg.Wo};
+  const int tpr = C / 8, rpp = kT / tpr;
+  const int64_t nblocks = (int64_t)pg.B * ((pg.H + 1) / 2) * ((pg.W + 1) / 2);
+  const int64_t rows = (int64_t)pg.B * pg.H * pg.W;
+  int64_t want = (nblocks + (int64_t)rpp * 8 - 1) / ((int64_t)rpp * 8);
+  int nslabs = (int)(want < 1 ? 1 : (want > kMaxSlabs ? kMaxSlabs : want));
+  int64_t bps = (nblocks + nslabs - 1) / nslabs;
+  bps = (bps + rpp - 1) / rpp * rpp;
+  nslabs = (int)((nblocks + bps - 1) / bps);
+#define DAT_BLOCK_REDUCE(T, POOL)                                                                                              \
+  hipLaunchKernelGGL((block_reduce_kernel<T, POOL>), dim3(nslabs), dim3(kT), 0, st, (const T*)x, mask, (const T*)dout, mean, rstd, C, tpr, \
+                     nblocks, bps, partial, pa)
+#define DAT_BLOCK_APPLY(T, POOL)                                                                                               \
+  hipLaunchKernelGGL((block_apply_kernel<T, POOL>), dim3(nblk(nblocks * tpr)), dim3(kT), 0, st, (const T*)x, mask, (const T*)dout, (T*)dx,  \
+                     (int)dx_accumulate, C, tpr, nblocks, (const float*)tab, pa)
+  if (pg.gather) DAT_BY_DTYPE(dtype, DAT_BLOCK_REDUCE(float, true), DAT_BLOCK_REDUCE(bf16_t, true));
+  else DAT_BY_DTYPE(dtype, DAT_BLOCK_REDUCE(float, false), DAT_BLOCK_REDUCE(bf16_t, false));
+  DAT_LAUNCH_CHECK();
+  hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, (const float*)partial, nslabs, C, rows, sums, sums + C,
+                     dbeta, dgamma, scale, gamma, mean, rstd, tab);
+  DAT_LAUNCH_CHECK();
+  if (skip_apply) return DAT_OK;
+  if (pg.gather) DAT_BY_DTYPE(dtype, DAT_BLOCK_APPLY(float, true), DAT_BLOCK_APPLY(bf16_t, true));
+  else DAT_BY_DTYPE(dtype, DAT_BLOCK_APPLY(float, false), DAT_BLOCK_APPLY(bf16_t, false));
+  DAT_LAUNCH_CHECK();
+#undef DAT_BLOCK_REDUCE
+#undef DAT_BLOCK_APPLY
   return DAT_OK;
 }
 

@@ -36,6 +36,8 @@ struct Op {
   uint8_t* mask = nullptr;      // BN with ReLU: one bit per output element (out > 0), read by the backward pass
   float* sums = nullptr;        // BN backward: [2][C] sums (sum dy, sum dy*xhat)
   float* bn_tab = nullptr;      //   and the per-channel constants of the input gradient (4*C floats)
+  int pool = -1;                // BN + ReLU read only by a max-pool: that op (one fused forward pass; the backward pass gathers d(out))
+  int pooled_by = -1;           // max-pool evaluated by the BN before it
   int res_bn = -1;              // BN with residual: the residual is the output of this BN op (projection shortcut), which
                                 //   this op evaluates itself from that op's input -- forward and the shared backward sums
   int absorbed_by = -1;         // BN on a projection shortcut: the BN op that evaluates it (its output tensor is never stored)
@@ -57,6 +59,7 @@ struct dat_model {
   dat_arch arch; int dtype; int maxB; int H, W, classes;
   int normalize = 0; float mean[3] = {0, 0, 0}, inv_std[3] = {1, 1, 1};
   bool fuse_bn_apply = true;         // dat_model_set_option(DAT_OPT_FUSE_BN_INPUT_GRAD)
+  bool fuse_pool = false;            // BN + ReLU + max-pool in one forward pass, pool gradient gathered by the BN backward pass
   std::vector<Shape> tens;           // logical per-sample shapes (channels as stored)
   std::vector<char> is_f32;          // pooled features and logits stay fp32 in every model
   std::vector<Op> ops;
@@ -230,6 +233,19 @@ bool build_graph(dat_model& m) {
         m.ops[producer[op.in]].fwd_bn = i;
         op.stats_from_conv = true;
       }
+    }
+    // BN + ReLU whose only reader is a 3x3/2 max-pool (the ImageNet stem): one pass writes the pooled tensor, the
+    // arg-max positions and the ReLU mask; the full-resolution activation and its gradient are never stored.
+    m.fuse_pool = !getenv("DAT_KEEP_STEM_POOL");   // (environment switch: ablation only)
+    for (int b = 0; b < (int)m.ops.size(); ++b) {
+      Op& bn = m.ops[b];
+      if (bn.kind != OP_BNACT || !bn.relu || bn.res >= 0) continue;
+      int users = 0, pool = -1;
+      for (int c = 0; c < (int)m.ops.size(); ++c) {
+        users += (m.ops[c].in == bn.out) + (m.ops[c].res == bn.out);
+        if (m.ops[c].in == bn.out && m.ops[c].kind == OP_MAXPOOL) pool = c;
+      }
+      if (users == 1 && pool > b) { bn.pool = pool; m.ops[pool].pooled_by = b; }
     }
     // Projection shortcuts: out = relu(bn(y) + bn_s(y_s)).  bn_s's output has no other reader, so the final BN
     // normalises y_s itself, and in the backward sweep d out .* mask is the output gradient of both normalisations:
@@ -424,6 +440,12 @@ NetInputDesc input_desc(const dat_model& m) {
 
 dat_status bn_forward_pair(dat_model& m, Op& op, int64_t rows, int C, hipStream_t st) {
   if (!op.stats_from_conv) DAT_TRY(bn_stats(m.act[op.in], m.dtype, rows, C, m.partial, op.mean, op.rstd, st));
+  if (op.pool >= 0 && m.fuse_pool) {
+    const Op& pl = m.ops[op.pool];
+    const Shape si = m.tens[op.in], so = m.tens[pl.out];
+    return bnact_pool_forward(m.act[op.in], m.act[pl.out], pl.argmax, op.mask, m.dtype, (int)(rows / ((int64_t)si.H * si.W)), si.H, si.W, C,
+                              so.H, so.W, op.mean, op.rstd, m.compute + m.ptab[op.p0].off, m.compute + m.ptab[op.p1].off, st);
+  }
   if (op.res_bn >= 0) {   // the residual is normalised on the fly from the shortcut BN's input
     const Op& sb = m.ops[op.res_bn];
     const BnParams rp{sb.mean, sb.rstd, m.compute + m.ptab[sb.p0].off, m.compute + m.ptab[sb.p1].off};
@@ -466,6 +488,7 @@ dat_status forward(dat_model& m, int B, hipStream_t st) {
                  bn_forward_pair(m, op, rows_in, si.C, st));
         break;
       case OP_MAXPOOL:
+        if (op.pooled_by >= 0 && m.fuse_pool) break;
         DAT_TRY(maxpool_forward(m.act[op.in], m.act[op.out], op.argmax, dt, B, si.H, si.W, si.C, so.H, so.W, st));
         break;
       case OP_GAP:
@@ -551,6 +574,15 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         // no weight gradients wanted, nothing stored in d(in) yet, no residual gradient to write: leave the input
         // gradient to the convolution below
         op.apply_deferred = op.apply_fusable && m.fuse_bn_apply && !grads && dt == DAT_BF16 && !m.ghas[op.in] && !dres;
+        if (op.pool >= 0) {   // BN + ReLU feeding a max-pool: both halves on 2x2 pixel blocks
+          const Op& pl = m.ops[op.pool];
+          PoolGrad pg{pl.argmax, m.grad[pl.out], B, si.H, si.W, m.tens[pl.out].H, m.tens[pl.out].W, m.fuse_pool ? 1 : 0};
+          DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * 4, st,
+                   bn_pool_backward(m.act[op.in], op.mask, m.grad[op.out], m.grad[op.in], m.ghas[op.in], false, dt, si.C, op.mean, op.rstd,
+                                    m.compute + m.ptab[op.p0].off, m.partial, op.sums, op.bn_tab, g0, g1, 1.0f, pg, st));
+          m.ghas[op.in] = 1;
+          break;
+        }
         if (!absorbed) {
           BnSecond sec{}; const BnSecond* second = nullptr;
           if (op.res_bn >= 0) {
@@ -576,6 +608,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         break;
       }
       case OP_MAXPOOL:
+        if (op.pooled_by >= 0 && m.fuse_pool) break;   // the BN above gathers its d(out) from d(pooled)
         DAT_TRY(maxpool_backward(op.argmax, m.grad[op.out], m.grad[op.in], m.ghas[op.in], dt, B, si.H, si.W, si.C, so.H, so.W, st));
         m.ghas[op.in] = 1;
         break;

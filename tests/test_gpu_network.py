@@ -225,10 +225,11 @@ def test_shortcut_bn_evaluated_by_the_branch_bn_gives_the_same_bits(dat, arch, B
     it runs as passes of its own.  Logits, input gradient and parameter gradients agree bit for bit."""
     outs = []
     for keep in (False, True):
-        if keep:
-            monkeypatch.setenv("DAT_KEEP_SHORTCUT_BN", "1")
-        else:
-            monkeypatch.delenv("DAT_KEEP_SHORTCUT_BN", raising=False)
+        for name in ("DAT_KEEP_SHORTCUT_BN", "DAT_KEEP_STEM_POOL"):   # (the max-pool fusion is covered by the same runs)
+            if keep:
+                monkeypatch.setenv(name, "1")
+            else:
+                monkeypatch.delenv(name, raising=False)
         gpu = dat.Model(arch, dat.BF16, B, H, W, classes, None, None)
         gpu.set_params(syn.perturbed_params(41, gpu.offsets, gpu.fan_in, gpu.kind))
         xd, yd = _cuda(syn.images(41, B, H, W)), _cuda(syn.labels(41, B, classes))
