@@ -885,14 +885,35 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
     }
 }
 
-__global__ void wgrad_reduce_kernel(const float* __restrict__ ws, int splits, int64_t per_split, int Cin, int cin_real,
-                                    float scale, float* __restrict__ dw) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= per_split) return;
+// Sums the `splits` partial tiles in a fixed order: a workgroup owns 32 consecutive elements (one cache line per
+// split); thread group g = tid / 32 adds splits g, g+8, ... (eight loads in flight), then the eight group sums
+// are added in order.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ ws, int splits, int64_t per_split, int Cin, int cin_real,
+                                                           float scale, float* __restrict__ dw) {
+  __shared__ float sh[8][32];
+  const int lane = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int64_t i = (int64_t)blockIdx.x * 32 + lane;
+  const int64_t ic = i < per_split ? i : per_split - 1;
+  float s = 0.f;
+  for (int k0 = grp; k0 < splits; k0 += 64) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int k = k0 + 8 * u;
+      v[u] = ws[(int64_t)(k < splits ? k : splits - 1) * per_split + ic];
+      if (k >= splits) v[u] = 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  sh[grp][lane] = s;
+  __syncthreads();
+  if (grp != 0 || i >= per_split) return;
   const int ci = (int)(i % Cin);
   if (ci >= cin_real) return;
-  float s = 0.f;
-  for (int k = 0; k < splits; ++k) s += ws[(int64_t)k * per_split + i];
+  s = 0.f;
+#pragma unroll
+  for (int g = 0; g < 8; ++g) s += sh[g][lane];
   dw[(i / Cin) * cin_real + ci] = s * scale;
 }
 
@@ -1058,7 +1079,7 @@ dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* d
   else hipLaunchKernelGGL((wgrad_kernel<128, 128>), grid, dim3(kThreads), 0, st, a);
   DAT_LAUNCH_CHECK();
   const int64_t per_split = (int64_t)g.Cout * a.Ktot;
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per_split + 255) / 256)), dim3(256), 0, st, (const float*)ws, p.splits,
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per_split + 31) / 32)), dim3(256), 0, st, (const float*)ws, p.splits,
                      per_split, g.Cin, cin_real, scale, dw);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
