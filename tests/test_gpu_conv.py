@@ -30,6 +30,10 @@ SHAPES = [
     (32, 64, 64, 8, 128, 1, 1, 0),     # enough pixel tiles for the 128x256 configuration
     (32, 64, 64, 8, 64, 3, 1, 1),      # ... and the 64x256 one
     (33, 63, 65, 16, 136, 3, 1, 1),    # wide tiles with ragged pixel and channel tails
+    (5, 7, 7, 128, 128, 3, 1, 1),      # 3x3 on 7x7 images: a pixel tile spans several images, ragged tail
+    (3, 14, 14, 256, 72, 3, 1, 1),     # 3x3, four channel chunks, ragged channel tile
+    (2, 28, 28, 64, 64, 3, 1, 1),      # 3x3 into 64 channels (narrow tile), several tiles per image
+    (1, 56, 56, 64, 128, 3, 1, 1),     # widest image the LDS-resident patch supports at this size
 ]
 
 
