@@ -40,11 +40,11 @@ PEAK_HBM_GBS = 8000.0
 
 
 def cpu_baseline(arch, H, W, classes, K, eps, alpha, norm):
-    """CPU reference on a bounded sample: B=2 images, one attack iteration + the outer step,
+    """CPU reference on a bounded sample: B=8 images, one attack iteration + the outer step,
     extrapolated to K attack iterations per example."""
     import oracle
     import synth_inputs as syn
-    B = 2
+    B = 8
     m = oracle.Model(arch, 1, H, W, classes, MEAN if norm else None, STD if norm else None)
     m.set_params(syn.he_normal_params(0, m.offsets, m.fan_in, m.kind))
     x, y = syn.images(0, B, H, W), syn.labels(0, B, classes)
@@ -55,8 +55,8 @@ def cpu_baseline(arch, H, W, classes, K, eps, alpha, norm):
     t2 = time.time()
     per_example = (K * (t1 - t0) + (t2 - t1)) / B
     return {"value": 1.0 / per_example, "unit": "examples/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": "B=2 images of the same shape: 1 attack iteration (%.1f s) + outer step (%.1f s), "
-                      "extrapolated to K=%d iterations per example" % (t1 - t0, t2 - t1, K)}
+            "sample": "B=%d images of the same shape: 1 attack iteration (%.1f s) + outer step (%.1f s), "
+                      "extrapolated to K=%d iterations per example" % (B, t1 - t0, t2 - t1, K)}
 
 
 def main():
