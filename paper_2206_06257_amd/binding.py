@@ -130,7 +130,8 @@ class Model:
         self.offsets_device_ptr = _lib.dat_model_offsets_device(h)
 
     def close(self):
-        if getattr(self, "_h", None):
+        # (at interpreter shutdown the module globals may already be gone: the process is ending anyway)
+        if getattr(self, "_h", None) and _lib is not None:
             _lib.dat_model_destroy(self._h)
             self._h = None
 

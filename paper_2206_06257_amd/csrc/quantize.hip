@@ -18,7 +18,7 @@ constexpr int kThreads = 256;
 constexpr int kIter = 8;          // groups per thread
 constexpr uint32_t kStreamQuant = 0;
 
-__device__ __forceinline__ int find_tensor(const int64_t* __restrict__ off, int T, int64_t i) {
+__device__ __forceinline__ int find_tensor(const int64_t* off, int T, int64_t i) {
   // largest t with off[t] <= i  (off[0] = 0, off[T] = d > i); empty tensors are skipped
   int lo = 0, hi = T;
   while (hi - lo > 1) {
@@ -26,6 +26,16 @@ __device__ __forceinline__ int find_tensor(const int64_t* __restrict__ off, int 
     if (off[mid] <= i) lo = mid; else hi = mid;
   }
   return lo;
+}
+
+// The offset table in LDS (T <= kTabMax): the binary search and every tensor boundary a thread crosses then
+// cost LDS reads instead of dependent global loads.  Returns the table to use (generic pointer).
+constexpr int kTabMax = 1024;
+__device__ __forceinline__ const int64_t* stage_offsets(const int64_t* __restrict__ off, int T, int64_t* s_off) {
+  if (T > kTabMax) return off;
+  for (int i = threadIdx.x; i <= T; i += blockDim.x) s_off[i] = off[i];
+  __syncthreads();
+  return s_off;
 }
 
 __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
@@ -37,7 +47,7 @@ __global__ void fill_u32_kernel(uint32_t* p, int n, uint32_t v) {
 // |g| is compared through its bit pattern (non-negative floats order like unsigned integers,
 // NaN patterns sort above Inf, so a NaN or Inf anywhere surfaces in the scale).
 __global__ __launch_bounds__(kThreads) void absmax_kernel(const float* __restrict__ g,
-                                                          const int64_t* __restrict__ off, int T,
+                                                          const int64_t* off, int T,
                                                           int64_t d, uint32_t* __restrict__ scale_bits) {
   // A workgroup owns 16 K consecutive elements, hence a run of consecutive tensors starting at
   // `tfirst`.  Per-tensor maxima are first combined in LDS (slot = tensor - tfirst) and only the
@@ -47,6 +57,8 @@ __global__ __launch_bounds__(kThreads) void absmax_kernel(const float* __restric
   constexpr int kSlots = 128;
   __shared__ uint32_t s_max[kSlots];
   __shared__ int s_tfirst;
+  __shared__ int64_t s_off[kTabMax + 1];
+  off = stage_offsets(off, T, s_off);
   const int64_t ngroups = (d + 3) >> 2;
   const int64_t grp0 = (int64_t)blockIdx.x * (kThreads * kIterA);
   if (threadIdx.x == 0) s_tfirst = find_tensor(off, T, min(grp0 << 2, d - 1));
@@ -137,28 +149,46 @@ __device__ __forceinline__ int encode_one(float g, float u, const TensorCursor& 
 
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const float* __restrict__ g,
-                                                            const int64_t* __restrict__ off, int T,
+                                                            const int64_t* off, int T,
                                                             int64_t d, uint64_t seed,
                                                             const float* __restrict__ scales,
                                                             uint8_t* __restrict__ q) {
   constexpr int EPT = Fmt<BITS>::kEpt, WORDS = Fmt<BITS>::kWords;
+  __shared__ int64_t s_off[kTabMax + 1];
+  off = stage_offsets(off, T, s_off);
   const int64_t ngroups = (d + EPT - 1) / EPT;
   int64_t grp = (int64_t)blockIdx.x * (kThreads * kIter) + threadIdx.x;
   if (grp >= ngroups) return;
+  // with four elements per group (8 and 16 bit) the eight groups of a thread are fetched before the first one is
+  // encoded: eight loads in flight instead of one
+  constexpr bool PRE = EPT == 4;
+  float4 pre[PRE ? kIter : 1];
+  if (PRE) {
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+      const int64_t gi = grp + (int64_t)it * kThreads;
+      pre[it] = (gi * EPT + EPT <= d) ? *reinterpret_cast<const float4*>(g + gi * EPT) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
   TensorCursor c;
   c.t = find_tensor(off, T, grp * EPT);
   c.next = off[c.t + 1];
   enc_enter<BITS>(c, scales);
+#pragma unroll
   for (int it = 0; it < kIter; ++it, grp += kThreads) {
     if (grp >= ngroups) break;
     const int64_t i0 = grp * EPT;
     float v[EPT]; float u[EPT];
     const bool full = i0 + EPT <= d;
     if (full) {
+      if (PRE) {
+        v[0] = pre[it].x; v[1] = pre[it].y; v[2] = pre[it].z; v[3] = pre[it].w;
+      } else {
 #pragma unroll
-      for (int j = 0; j < EPT; j += 4) {
-        const float4 f = *reinterpret_cast<const float4*>(g + i0 + j);
-        v[j] = f.x; v[j + 1] = f.y; v[j + 2] = f.z; v[j + 3] = f.w;
+        for (int j = 0; j < EPT; j += 4) {
+          const float4 f = *reinterpret_cast<const float4*>(g + i0 + j);
+          v[j] = f.x; v[j + 1] = f.y; v[j + 2] = f.z; v[j + 3] = f.w;
+        }
       }
     } else {
       for (int j = 0; j < EPT; ++j) v[j] = (i0 + j < d) ? g[i0 + j] : 0.0f;
@@ -196,10 +226,12 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float* __restr
 
 template <int BITS>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __restrict__ q,
-                                                              const int64_t* __restrict__ off, int T,
+                                                              const int64_t* off, int T,
                                                               int64_t d, const float* __restrict__ scales,
                                                               float* __restrict__ out) {
   constexpr int EPT = Fmt<BITS>::kEpt, WORDS = Fmt<BITS>::kWords;
+  __shared__ int64_t s_off[kTabMax + 1];
+  off = stage_offsets(off, T, s_off);
   const int64_t ngroups = (d + EPT - 1) / EPT;
   int64_t grp = (int64_t)blockIdx.x * (kThreads * kIter) + threadIdx.x;
   if (grp >= ngroups) return;
