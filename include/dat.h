@@ -241,15 +241,19 @@ typedef enum {
 dat_status dat_profile_enable(dat_model* m, int on);
 dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* launches, double* work);
 
-/* ---- execution options (same results either way; for ablations and tests) ---------------------
+/* ---- execution options (for ablations and tests) ------------------------------------------------
  * DAT_OPT_FUSE_BN_INPUT_GRAD (default 1, bf16 models): in backward sweeps that need no weight
  * gradients (dat_attack, dat_input_grad, dat_attack_kl) the input gradient of a batch
  * normalisation that follows a 1x1 stride-1 convolution is not written to memory; that
  * convolution's backward-data pass forms it from d(out), the normalisation's input and the ReLU
  * mask while loading its operand.  0: always run the stand-alone pass.  Both settings evaluate the
  * same fp32 expression and round to bf16 once, so they give identical bits.
+ * DAT_OPT_FUSE_BN_SUMS (default 1, bf16 models): the two per-channel sums of a batch normalisation's
+ * backward pass (sum dy, sum dy*xhat) are accumulated by the epilogue of the backward-data
+ * convolution whose launch completes d(out), from the tile it is storing.  0: a pass of its own
+ * reads d(out) again.  The two orders of summation agree to fp32 rounding, not bit for bit.
  * Returns DAT_ERR_ARG for an unknown option. */
-typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0 } dat_option;
+typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1 } dat_option;
 /* (Two more switches are read from the environment by dat_model_create, because they change the
  * layer graph of a bf16 model.  DAT_KEEP_SHORTCUT_BN: the batch normalisation on a projection
  * shortcut runs as passes of its own instead of being evaluated by the last normalisation of the

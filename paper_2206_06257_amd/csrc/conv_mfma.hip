@@ -82,6 +82,10 @@ struct IgemmArgs {
   // stat_partial + (stat_slab0 + pixel_tile) * 2 * Cout.
   int stat_mode, stat_slab0;
   float* stat_partial;
+  // stat_mode 2: the stored tensor is the output gradient of a batch normalisation with input stat_x (same
+  // layout as `out`), ReLU mask stat_mask (or nullptr) and batch statistics stat_mean / stat_rstd; the slabs then
+  // hold (sum v*m, sum v*m*xhat), the two sums of that normalisation's backward pass.
+  const bf16_t* stat_x; const uint8_t* stat_mask; const float* stat_mean; const float* stat_rstd;
   // Optional operand transform (1x1 stride-1 layers, igemm_kernel only): `in` is the output gradient of a batch
   // normalisation, and the operand actually contracted is that normalisation's input gradient,
   // bn_input_grad(in .* mask, xf_x, constants of the channel), rounded to bf16 -- formed while the tile moves from
@@ -170,6 +174,45 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
   float s1[8], s2[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) { s1[j] = 0.f; s2[j] = 0.f; }
+  if (a.stat_mode == 2) {
+    // BN backward sums of the tile just computed: the normalisation's input and mask are fetched for all of this
+    // thread's rows before the first one is used
+    float mu[8], rs[8];
+    if (ch < a.Cout) {
+      const float4 m0v = *reinterpret_cast<const float4*>(a.stat_mean + ch), m1v = *reinterpret_cast<const float4*>(a.stat_mean + ch + 4);
+      const float4 r0v = *reinterpret_cast<const float4*>(a.stat_rstd + ch), r1v = *reinterpret_cast<const float4*>(a.stat_rstd + ch + 4);
+      mu[0] = m0v.x; mu[1] = m0v.y; mu[2] = m0v.z; mu[3] = m0v.w; mu[4] = m1v.x; mu[5] = m1v.y; mu[6] = m1v.z; mu[7] = m1v.w;
+      rs[0] = r0v.x; rs[1] = r0v.y; rs[2] = r0v.z; rs[3] = r0v.w; rs[4] = r1v.x; rs[5] = r1v.y; rs[6] = r1v.z; rs[7] = r1v.w;
+    }
+    uint4 xv[TP / RPP]; uint32_t mk[TP / RPP];
+#pragma unroll
+    for (int u = 0; u < TP / RPP; ++u) {
+      const int m = m0 + pr0 + u * RPP;
+      xv[u] = make_uint4(0u, 0u, 0u, 0u); mk[u] = 0u;
+      if (m < a.M && ch < a.Cout) {
+        const int64_t e = out_row(a, m) * a.Cout + ch;
+        xv[u] = *reinterpret_cast<const uint4*>(a.stat_x + e);
+        mk[u] = a.stat_mask ? (uint32_t)a.stat_mask[e >> 3] : 0xffu;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < TP / RPP; ++u) {
+      const int prow = pr0 + u * RPP, m = m0 + prow;
+      if (m < a.M && ch < a.Cout) {
+        const uint4 pk = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
+        *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = pk;
+        const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w}, xw[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float v0 = ((mk[u] >> (2 * j)) & 1u) ? __uint_as_float(w[j] << 16) : 0.f;
+          const float v1 = ((mk[u] >> (2 * j + 1)) & 1u) ? __uint_as_float(w[j] & 0xffff0000u) : 0.f;
+          const float x0 = __uint_as_float(xw[j] << 16), x1 = __uint_as_float(xw[j] & 0xffff0000u);
+          s1[2 * j] += v0; s2[2 * j] += v0 * ((x0 - mu[2 * j]) * rs[2 * j]);
+          s1[2 * j + 1] += v1; s2[2 * j + 1] += v1 * ((x1 - mu[2 * j + 1]) * rs[2 * j + 1]);
+        }
+      }
+    }
+  } else {
 #pragma unroll
   for (int prow = pr0; prow < TP; prow += RPP) {
     const int m = m0 + prow;
@@ -185,6 +228,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
         }
       }
     }
+  }
   }
   if (a.stat_mode) {
     // fold the RPP row groups in a fixed order through LDS, one slab per pixel tile
@@ -948,8 +992,10 @@ size_t conv_mfma_wgrad_workspace(const ConvGeom& g) {
 
 static void set_stats(IgemmArgs& a, const ConvStats* s, int slab0) {
   a.stat_mode = 0; a.stat_slab0 = slab0; a.stat_partial = nullptr;
+  a.stat_x = nullptr; a.stat_mask = nullptr; a.stat_mean = nullptr; a.stat_rstd = nullptr;
   if (!s || !s->mode) return;
-  a.stat_mode = 1; a.stat_partial = s->partial;
+  a.stat_mode = s->mode; a.stat_partial = s->partial;
+  if (s->mode == 2) { a.stat_x = s->bn_x; a.stat_mask = s->bn_mask; a.stat_mean = s->bn_mean; a.stat_rstd = s->bn_rstd; }
 }
 
 int64_t conv_mfma_launch_count() { return g_launches.load(std::memory_order_relaxed); }

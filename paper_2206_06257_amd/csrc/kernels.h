@@ -47,10 +47,14 @@ dat_status conv_direct_backward_weight(const float* x, const float* dy, float* d
 // per-channel (sum v, sum v^2) of everything it stores, as `nslabs` slabs of [2][C] floats in
 // `partial` (C = channels of the stored tensor); conv_stat_slabs gives an upper bound for sizing.
 // Reduce them with bn_finalize_slabs.
+// Mode 2 (backward-data): the stored tensor is d(out) of a batch normalisation with input bn_x (same layout),
+// ReLU mask bn_mask (or nullptr) and batch statistics bn_mean / bn_rstd; the slabs then hold
+// (sum dy, sum dy*xhat), dy = d(out) .* mask: the sums of that normalisation's backward pass.
 struct ConvStats {
   int mode;
   float* partial;
   int nslabs;            // out
+  const bf16_t* bn_x; const uint8_t* bn_mask; const float* bn_mean; const float* bn_rstd;   // mode 2
 };
 // Number of MFMA convolution kernels (igemm) launched by this process so far.
 int64_t conv_mfma_launch_count();
@@ -99,8 +103,10 @@ dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partia
 //           dbeta = scale*sum dy, dgamma = scale*sum dy*xhat when the pointers are non-null.
 // `partial` must have room for fold_floats(nslabs, C) more floats after the slabs.
 size_t fold_floats(int nslabs, int C);
+//           With gamma/mean/rstd/tab the constants of bn_input_grad are written too.
 dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
-                             float* dgamma, float scale, hipStream_t st);
+                             float* dgamma, float scale, hipStream_t st, const float* gamma = nullptr, const float* mean = nullptr,
+                             const float* rstd = nullptr, float* tab = nullptr);
 // out = act(gamma*((x-mean)*rstd) + beta [+ res])
 // mask (optional, rows*C/8 bytes): bit j of byte e/8 = (out[e] > 0), what the backward pass needs of `out`.
 // res_bn (optional): `res` is the INPUT of a second normalisation without activation (the one on a projection

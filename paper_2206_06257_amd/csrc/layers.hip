@@ -971,7 +971,8 @@ size_t bn_partial_floats(int64_t rows, int C) { (void)rows; return (size_t)kMaxS
 size_t fold_floats(int nslabs, int C) { return nslabs > 512 ? (size_t)((nslabs + 31) / 32) * 2 * C : 0; }
 
 dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
-                             float* dgamma, float scale, hipStream_t st) {
+                             float* dgamma, float scale, hipStream_t st, const float* gamma, const float* mean, const float* rstd,
+                             float* tab) {
   const float* src = partial;
   if (nslabs > 512) {   // two-level: keep the final per-channel loop short
     float* folded = partial + (size_t)nslabs * 2 * C;
@@ -983,7 +984,7 @@ dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, in
   if (mode == 1)
     hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, (float*)nullptr, (float*)nullptr, 1.0f);
   else
-    hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, dbeta, dgamma, scale);
+    hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, dbeta, dgamma, scale, gamma, mean, rstd, tab);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }

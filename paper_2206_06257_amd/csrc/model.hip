@@ -36,6 +36,8 @@ struct Op {
   uint8_t* mask = nullptr;      // BN with ReLU: one bit per output element (out > 0), read by the backward pass
   float* sums = nullptr;        // BN backward: [2][C] sums (sum dy, sum dy*xhat)
   float* bn_tab = nullptr;      //   and the per-channel constants of the input gradient (4*C floats)
+  int dy_bn = -1;               // conv: BN op whose output only this conv reads -- its backward-data epilogue can emit that BN's sums
+  bool sums_ready = false;      // BN: sums and constants already produced by the convolution that wrote d(out)
   int pool = -1;                // BN + ReLU read only by a max-pool: that op (one fused forward pass; the backward pass gathers d(out))
   int pooled_by = -1;           // max-pool evaluated by the BN before it
   int res_bn = -1;              // BN with residual: the residual is the output of this BN op (projection shortcut), which
@@ -59,6 +61,8 @@ struct dat_model {
   dat_arch arch; int dtype; int maxB; int H, W, classes;
   int normalize = 0; float mean[3] = {0, 0, 0}, inv_std[3] = {1, 1, 1};
   bool fuse_bn_apply = true;         // dat_model_set_option(DAT_OPT_FUSE_BN_INPUT_GRAD)
+  bool fuse_bn_sums = true;          // dat_model_set_option(DAT_OPT_FUSE_BN_SUMS)
+  int64_t bn_sums_max_bytes = (int64_t)1 << 62;   //   ... only for d(out) tensors up to this size
   bool fuse_pool = false;            // BN + ReLU + max-pool in one forward pass, pool gradient gathered by the BN backward pass
   std::vector<Shape> tens;           // logical per-sample shapes (channels as stored)
   std::vector<char> is_f32;          // pooled features and logits stay fp32 in every model
@@ -288,6 +292,18 @@ bool build_graph(dat_model& m) {
       g.B = 1; g.H = m.tens[cv.in].H; g.W = m.tens[cv.in].W; g.Cin = m.tens[cv.in].C; g.Ho = m.tens[cv.out].H; g.Wo = m.tens[cv.out].W;
       g.Cout = m.tens[cv.out].C; g.k = cv.k; g.stride = cv.stride; g.pad = cv.pad;
       bn.apply_fusable = conv_mfma_bn_operand_ok(g);
+    }
+    // A BN whose output is read by one convolution only: d(out) is complete when that convolution's backward-data
+    // pass has written it, so its epilogue can accumulate the BN's backward sums from the tile it is storing.
+    for (int c = 0; c < (int)m.ops.size(); ++c) {
+      Op& cv = m.ops[c];
+      if (cv.kind != OP_CONV || cv.in <= 0 || producer[cv.in] < 0) continue;
+      const Op& bn = m.ops[producer[cv.in]];
+      if (bn.kind != OP_BNACT || bn.absorbed_by >= 0 || bn.res_bn >= 0 || bn.pool >= 0) continue;
+      int users = 0;
+      for (const Op& o : m.ops) users += (o.in == cv.in) + (o.res == cv.in);
+      // (two readers when the other one is an identity shortcut whose gradient this convolution's epilogue adds itself)
+      if (users == 1 || (users == 2 && cv.res_grad_from >= 0)) cv.dy_bn = producer[cv.in];
     }
     // the ImageNet stem runs on 2x2 pixel blocks of the network input (tensor 0 is stored blocked)
     Op& first = m.ops[0];
@@ -534,6 +550,15 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
           else DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_direct_backward_weight((const float*)m.act[op.in], (const float*)m.grad[op.out], g0, g, 1.0f, st));
         }
         if (op.in != 0 || need_input_grad) {
+          // sums of the BN whose output gradient this pass completes (nothing else has written it, nothing else will)
+          ConvStats bs{}; ConvStats* bsp = nullptr;
+          if (dt == DAT_BF16 && !op.blocked && op.dy_bn >= 0 && m.fuse_bn_sums && !m.ghas[op.in] &&
+              (int64_t)si.H * si.W * si.C * B * 2 <= m.bn_sums_max_bytes) {
+            const Op& bn = m.ops[op.dy_bn];
+            bs.mode = 2; bs.partial = m.partial; bs.bn_x = (const bf16_t*)m.act[bn.in]; bs.bn_mask = bn.relu ? bn.mask : nullptr;
+            bs.bn_mean = bn.mean; bs.bn_rstd = bn.rstd;
+            bsp = &bs;
+          }
           if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_stem_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
           else if (dt == DAT_BF16 && op.fwd_bn >= 0 && m.ops[op.fwd_bn].apply_deferred) {
             Op& bn = m.ops[op.fwd_bn];
@@ -543,18 +568,26 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
             const bool rg = op.res_grad_from >= 0;
             if (rg && m.ghas[op.in]) return DAT_ERR_UNSUPPORTED;
             DAT_PROF(m, DAT_PROF_CONV_BWD_DATA_BN, conv_flops(g, op.cin_real), st,
-                     conv_mfma_backward_data((const bf16_t*)m.grad[top.out], op.w16T, (bf16_t*)m.grad[op.in], g, rg ? false : (bool)m.ghas[op.in], nullptr, st,
+                     conv_mfma_backward_data((const bf16_t*)m.grad[top.out], op.w16T, (bf16_t*)m.grad[op.in], g, rg ? false : (bool)m.ghas[op.in], bsp, st,
                                              rg ? (const bf16_t*)m.grad[m.ops[op.res_grad_from].out] : nullptr,
                                              rg ? m.ops[op.res_grad_from].mask : nullptr, &bo));
           }
           else if (dt == DAT_BF16 && op.res_grad_from >= 0) {
             if (m.ghas[op.in]) return DAT_ERR_UNSUPPORTED;   // by construction nothing else has written this gradient yet
             const Op& bn = m.ops[op.res_grad_from];
-            DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, false, nullptr, st, (const bf16_t*)m.grad[bn.out], bn.mask));
+            DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, false, bsp, st, (const bf16_t*)m.grad[bn.out], bn.mask));
           }
-          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], nullptr, st));
+          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], bsp, st));
           else DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_direct_backward_data((const float*)m.grad[op.out], m.compute + m.ptab[op.p0].off, (float*)m.grad[op.in], g, m.ghas[op.in], st));
           m.ghas[op.in] = 1;
+          if (bsp) {   // finish that BN's sums, parameter gradients and input-gradient constants now
+            Op& bn = m.ops[op.dy_bn];
+            float* bg0 = grads ? grads + m.ptab[bn.p0].off : nullptr;
+            float* bg1 = grads ? grads + m.ptab[bn.p1].off : nullptr;
+            DAT_PROF(m, DAT_PROF_BN, 0.0, st, bn_finalize_slabs(m.partial, bs.nslabs, si.C, rows_in, 2, bn.sums, bn.sums + si.C, bg1, bg0, 1.0f, st,
+                                                                 m.compute + m.ptab[bn.p0].off, bn.mean, bn.rstd, bn.bn_tab));
+            bn.sums_ready = true;
+          }
         }
         break;
       }
@@ -583,7 +616,9 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
           m.ghas[op.in] = 1;
           break;
         }
-        if (!absorbed) {
+        const bool have_sums = op.sums_ready;
+        op.sums_ready = false;
+        if (!absorbed && !have_sums) {
           BnSecond sec{}; const BnSecond* second = nullptr;
           if (op.res_bn >= 0) {
             Op& sb = m.ops[op.res_bn];
@@ -891,6 +926,7 @@ extern "C" dat_status dat_model_set_option(dat_model* m, dat_option opt, int val
   if (!m) return DAT_ERR_ARG;
   switch (opt) {
     case DAT_OPT_FUSE_BN_INPUT_GRAD: m->fuse_bn_apply = value != 0; return DAT_OK;
+    case DAT_OPT_FUSE_BN_SUMS: m->fuse_bn_sums = value != 0; return DAT_OK;
   }
   return DAT_ERR_ARG;
 }

@@ -231,6 +231,9 @@ def test_shortcut_bn_evaluated_by_the_branch_bn_gives_the_same_bits(dat, arch, B
             else:
                 monkeypatch.delenv(name, raising=False)
         gpu = dat.Model(arch, dat.BF16, B, H, W, classes, None, None)
+        # (which BN sums come out of a convolution epilogue depends on the layer graph; with that option off both
+        # graphs sum in the same order and the comparison isolates the two fusions)
+        gpu.set_option(dat.OPT_FUSE_BN_SUMS, 0)
         gpu.set_params(syn.perturbed_params(41, gpu.offsets, gpu.fan_in, gpu.kind))
         xd, yd = _cuda(syn.images(41, B, H, W)), _cuda(syn.labels(41, B, classes))
         gx, logits, loss = gpu.input_grad(xd, yd)
@@ -238,6 +241,37 @@ def test_shortcut_bn_evaluated_by_the_branch_bn_gives_the_same_bits(dat, arch, B
         outs.append((gx.cpu().numpy(), logits.cpu().numpy(), g.cpu().numpy()))
     for a, b in zip(*outs):
         assert np.abs(a).max() > 0 and np.array_equal(a, b)
+
+
+def test_bn_backward_sums_from_the_convolution_epilogue(dat):
+    """bf16: the two sums of a BN backward pass come from the epilogue of the backward-data convolution that
+    completes d(out), or (option off) from a pass of their own.  The two sum in different orders, so they agree
+    to fp32 rounding, not bit for bit: on the shallow test net (every op kind) that is 1e-6 of the gradients;
+    deep nets amplify such differences like any other reordering of fp32 sums (module docstring), there the
+    check is that both settings stay within the same distance of each other as the reference's own floor."""
+    B, H, W, classes = 8, 16, 16, 5
+    gpu = dat.Model(dat.ARCH_TESTNET, dat.BF16, B, H, W, classes, MEAN, STD)
+    gpu.set_params(syn.perturbed_params(43, gpu.offsets, gpu.fan_in, gpu.kind))
+    xd, yd = _cuda(syn.images(43, B, H, W)), _cuda(syn.labels(43, B, classes))
+    outs = []
+    for fuse in (1, 0):
+        gpu.set_option(dat.OPT_FUSE_BN_SUMS, fuse)
+        gx, logits, loss = gpu.input_grad(xd, yd)
+        g, l = gpu.step(xd, yd, want_loss=True)
+        outs.append((gx.cpu().numpy(), g.cpu().numpy()))
+    assert np.abs(outs[0][0]).max() > 0
+    assert _rel2(outs[0][0], outs[1][0]) < 1e-6 and _rel2(outs[0][1], outs[1][1]) < 1e-6
+    # ResNet-50, reduced image: both settings against each other, bounded by the bf16 bar of this file
+    gpu = dat.Model(dat.ARCH_RESNET50, dat.BF16, 5, 64, 64, 12, MEAN, STD)
+    gpu.set_params(syn.perturbed_params(44, gpu.offsets, gpu.fan_in, gpu.kind))
+    xd, yd = _cuda(syn.images(44, 5, 64, 64)), _cuda(syn.labels(44, 5, 12))
+    outs = []
+    for fuse in (1, 0):
+        gpu.set_option(dat.OPT_FUSE_BN_SUMS, fuse)
+        gx, logits, loss = gpu.input_grad(xd, yd)
+        outs.append((gx.cpu().numpy(), logits.cpu().numpy()))
+    assert np.array_equal(outs[0][1], outs[1][1])          # the forward pass is not affected
+    assert _rel2(outs[0][0], outs[1][0]) < 5e-2
 
 
 def test_batch_and_argument_errors(dat):
