@@ -823,7 +823,6 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
   constexpr int WC = TC / 2, WJ = TJ / 2;
   constexpr int NI = WC / 32, NJ = WJ / 32;
   constexpr int NBLK_A = (TC / 8) * (BP / 8), NBLK_B = (TJ / 8) * (BP / 8);
-  constexpr int PER_A = (NBLK_A + kThreads - 1) / kThreads, PER_B = (NBLK_B + kThreads - 1) / kThreads;
   __shared__ __attribute__((aligned(16))) unsigned char lds[(TC + TJ) * 128];
   unsigned char* abase = lds;
   unsigned char* bbase = lds + TC * 128;
@@ -844,59 +843,72 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // column (r,s,ci) decode for this thread's B blocks is loop invariant
-  int b_cv[PER_B], b_pg[PER_B], b_r[PER_B], b_s[PER_B], b_ci[PER_B]; bool b_ok[PER_B];
+  // The 8x8 (pixel x channel) blocks of both operands form one list, A (dy) first; a thread owns blocks
+  // tid, tid + 256, ... (a wavefront's blocks are all of one kind).  Everything about a block except the pixel
+  // position is loop invariant.
+  constexpr int NBLK = NBLK_A + NBLK_B, PER = (NBLK + kThreads - 1) / kThreads;
+  bool k_b[PER], k_ok[PER]; int k_cv[PER], k_pg[PER], k_r[PER], k_s[PER], k_ci[PER];
 #pragma unroll
-  for (int u = 0; u < PER_B; ++u) {
+  for (int u = 0; u < PER; ++u) {
     const int blk = tid + u * kThreads;
-    b_cv[u] = blk % (TJ / 8); b_pg[u] = blk / (TJ / 8);
-    const int j = j0 + b_cv[u] * 8;
-    b_ok[u] = blk < NBLK_B && j < a.Ktot;
-    const int jj = b_ok[u] ? j : 0;
-    const int tap = jj / a.Cin;
-    b_ci[u] = jj - tap * a.Cin; b_r[u] = tap / a.k; b_s[u] = tap - b_r[u] * a.k;
+    k_b[u] = blk >= NBLK_A;
+    const int lb = k_b[u] ? blk - NBLK_A : blk, nv = k_b[u] ? TJ / 8 : TC / 8;
+    k_cv[u] = lb % nv; k_pg[u] = lb / nv;
+    k_r[u] = 0; k_s[u] = 0; k_ci[u] = 0;
+    if (!k_b[u]) {
+      k_ok[u] = blk < NBLK && c0 + k_cv[u] * 8 < a.Cout;
+    } else {
+      const int j = j0 + k_cv[u] * 8;
+      k_ok[u] = blk < NBLK && j < a.Ktot;
+      const int jj = k_ok[u] ? j : 0;
+      const int tap = jj / a.Cin;
+      k_ci[u] = jj - tap * a.Cin; k_r[u] = tap / a.k; k_s[u] = tap - k_r[u] * a.k;
+    }
   }
-
-  for (int p0 = p_begin; p0 < p_end; p0 += BP) {
-    // ---- global -> registers -> transpose -> LDS
+  // global -> registers: the eight pixel vectors of every block of this thread for the tile at p0
+  auto load_tile = [&](int p0, uint4 (&in)[PER][8]) {
 #pragma unroll
-    for (int u = 0; u < PER_A; ++u) {
-      const int blk = tid + u * kThreads;
-      if (blk < NBLK_A) {
-        const int cv = blk % (TC / 8), pg = blk / (TC / 8);
-        const int c = c0 + cv * 8;
-        uint4 in[8], out[8];
+    for (int u = 0; u < PER; ++u) {
+      const int pb = p0 + k_pg[u] * 8;
+      if (!k_b[u]) {
 #pragma unroll
         for (int qd = 0; qd < 8; ++qd) {
-          const int p = p0 + pg * 8 + qd;
-          in[qd] = (p < p_end && c < a.Cout) ? *reinterpret_cast<const uint4*>(a.dy + (int64_t)p * a.Cout + c) : make_uint4(0, 0, 0, 0);
+          const int p = pb + qd;
+          in[u][qd] = (k_ok[u] && p < p_end) ? *reinterpret_cast<const uint4*>(a.dy + (int64_t)p * a.Cout + c0 + k_cv[u] * 8) : make_uint4(0, 0, 0, 0);
         }
-        transpose8x8(in, out);
-#pragma unroll
-        for (int cc = 0; cc < 8; ++cc) *reinterpret_cast<uint4*>(abase + swz128(cv * 8 + cc, pg)) = out[cc];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < PER_B; ++u) {
-      const int blk = tid + u * kThreads;
-      if (blk < NBLK_B) {
-        uint4 in[8], out[8];
-        int p = p0 + b_pg[u] * 8;
-        int n = p / HW, rem = p - n * HW;
+      } else {
+        int n = pb / HW, rem = pb - n * HW;
         int ho = rem / a.Wo, wo = rem - ho * a.Wo;
 #pragma unroll
         for (int qd = 0; qd < 8; ++qd) {
-          const int hi = ho * a.stride + b_r[u] - a.pad, wi = wo * a.stride + b_s[u] - a.pad;
-          const bool ok = b_ok[u] && (p + qd) < p_end && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
-          in[qd] = ok ? *reinterpret_cast<const uint4*>(a.x + (((int64_t)n * a.H + hi) * a.W + wi) * a.Cin + b_ci[u]) : make_uint4(0, 0, 0, 0);
+          const int hi = ho * a.stride + k_r[u] - a.pad, wi = wo * a.stride + k_s[u] - a.pad;
+          const bool ok = k_ok[u] && (pb + qd) < p_end && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
+          in[u][qd] = ok ? *reinterpret_cast<const uint4*>(a.x + (((int64_t)n * a.H + hi) * a.W + wi) * a.Cin + k_ci[u]) : make_uint4(0, 0, 0, 0);
           if (++wo == a.Wo) { wo = 0; if (++ho == a.Ho) { ho = 0; ++n; } }
         }
-        transpose8x8(in, out);
-#pragma unroll
-        for (int cc = 0; cc < 8; ++cc) *reinterpret_cast<uint4*>(bbase + swz128(b_cv[u] * 8 + cc, b_pg[u])) = out[cc];
       }
     }
+  };
+  // registers -> transpose -> LDS
+  auto stash_tile = [&](const uint4 (&in)[PER][8]) {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      if (tid + u * kThreads < NBLK) {
+        uint4 out[8];
+        transpose8x8(in[u], out);
+        unsigned char* base = k_b[u] ? bbase : abase;
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) *reinterpret_cast<uint4*>(base + swz128(k_cv[u] * 8 + cc, k_pg[u])) = out[cc];
+      }
+    }
+  };
+
+  uint4 regs[PER][8];
+  if (p_begin < p_end) load_tile(p_begin, regs);
+  for (int p0 = p_begin; p0 < p_end; p0 += BP) {
+    stash_tile(regs);
     __syncthreads();
+    if (p0 + BP < p_end) load_tile(p0 + BP, regs);         // the next tile's loads fly under this tile's MFMAs
     // ---- MFMA over the 64 pixels (4 k-steps of 16)
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
