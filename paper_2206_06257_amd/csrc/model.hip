@@ -36,7 +36,8 @@ struct Op {
   uint8_t* mask = nullptr;      // BN with ReLU: one bit per output element (out > 0), read by the backward pass
   float* sums = nullptr;        // BN backward: [2][C] sums (sum dy, sum dy*xhat)
   float* bn_tab = nullptr;      //   and the per-channel constants of the input gradient (4*C floats)
-  int dy_bn = -1;               // conv: BN op whose output only this conv reads -- its backward-data epilogue can emit that BN's sums
+  int dy_bn = -1;               // conv: BN op whose output gradient this conv's backward-data launch completes -- its epilogue can emit that BN's sums
+  bool dy_bn_last_of_many = false;   //   ... as the last of several convolutions that read that output (accumulating launch)
   bool sums_ready = false;      // BN: sums and constants already produced by the convolution that wrote d(out)
   int pool = -1;                // BN + ReLU read only by a max-pool: that op (one fused forward pass; the backward pass gathers d(out))
   int pooled_by = -1;           // max-pool evaluated by the BN before it
@@ -300,10 +301,17 @@ bool build_graph(dat_model& m) {
       if (cv.kind != OP_CONV || cv.in <= 0 || producer[cv.in] < 0) continue;
       const Op& bn = m.ops[producer[cv.in]];
       if (bn.kind != OP_BNACT || bn.absorbed_by >= 0 || bn.res_bn >= 0 || bn.pool >= 0) continue;
-      int users = 0;
-      for (const Op& o : m.ops) users += (o.in == cv.in) + (o.res == cv.in);
-      // (two readers when the other one is an identity shortcut whose gradient this convolution's epilogue adds itself)
+      int users = 0, conv_users = 0, first_user = -1;
+      for (int o = 0; o < (int)m.ops.size(); ++o) {
+        const int u = (m.ops[o].in == cv.in) + (m.ops[o].res == cv.in);
+        users += u;
+        if (u && first_user < 0) first_user = o;
+        if (m.ops[o].in == cv.in && m.ops[o].kind == OP_CONV) ++conv_users;
+      }
+      // one reader; or two when the other one is an identity shortcut whose gradient this convolution's epilogue adds
+      // itself; or several convolutions, of which this is the first in the graph and so the last to add its part
       if (users == 1 || (users == 2 && cv.res_grad_from >= 0)) cv.dy_bn = producer[cv.in];
+      else if (conv_users == users && first_user == c) { cv.dy_bn = producer[cv.in]; cv.dy_bn_last_of_many = true; }
     }
     // the ImageNet stem runs on 2x2 pixel blocks of the network input (tensor 0 is stored blocked)
     Op& first = m.ops[0];
@@ -552,7 +560,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         if (op.in != 0 || need_input_grad) {
           // sums of the BN whose output gradient this pass completes (nothing else has written it, nothing else will)
           ConvStats bs{}; ConvStats* bsp = nullptr;
-          if (dt == DAT_BF16 && !op.blocked && op.dy_bn >= 0 && m.fuse_bn_sums && !m.ghas[op.in] &&
+          if (dt == DAT_BF16 && !op.blocked && op.dy_bn >= 0 && m.fuse_bn_sums && (bool)m.ghas[op.in] == op.dy_bn_last_of_many &&
               (int64_t)si.H * si.W * si.C * B * 2 <= m.bn_sums_max_bytes) {
             const Op& bn = m.ops[op.dy_bn];
             bs.mode = 2; bs.partial = m.partial; bs.bn_x = (const bf16_t*)m.act[bn.in]; bs.bn_mask = bn.relu ? bn.mask : nullptr;
