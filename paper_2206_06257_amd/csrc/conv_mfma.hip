@@ -86,6 +86,9 @@ struct IgemmArgs {
   // layout as `out`), ReLU mask stat_mask (or nullptr) and batch statistics stat_mean / stat_rstd; the slabs then
   // hold (sum v*m, sum v*m*xhat), the two sums of that normalisation's backward pass.
   const bf16_t* stat_x; const uint8_t* stat_mask; const float* stat_mean; const float* stat_rstd;
+  // stat_mode 3 (128-channel tiles only): a second normalisation (input stat_x2, statistics stat_mean2 / stat_rstd2)
+  // shares that output gradient; slabs are [3][Cout]: (sum v*m, sum v*m*xhat, sum v*m*xhat2).
+  const bf16_t* stat_x2; const float* stat_mean2; const float* stat_rstd2;
   // Optional operand transform (1x1 stride-1 layers, igemm_kernel only): `in` is the output gradient of a batch
   // normalisation, and the operand actually contracted is that normalisation's input gradient,
   // bn_input_grad(in .* mask, xf_x, constants of the channel), rounded to bf16 -- formed while the tile moves from
@@ -171,10 +174,52 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
       }
     }
   __syncthreads();
-  float s1[8], s2[8];
+  float s1[8], s2[8], s3[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) { s1[j] = 0.f; s2[j] = 0.f; }
-  if (a.stat_mode == 2) {
+  for (int j = 0; j < 8; ++j) { s1[j] = 0.f; s2[j] = 0.f; s3[j] = 0.f; }
+  if (a.stat_mode == 3) {
+    // as mode 2 below, for two normalisations sharing d(out)
+    float mu[8], rs[8], mu2[8], rs2[8];
+    if (ch < a.Cout) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { mu[j] = a.stat_mean[ch + j]; rs[j] = a.stat_rstd[ch + j]; mu2[j] = a.stat_mean2[ch + j]; rs2[j] = a.stat_rstd2[ch + j]; }
+    }
+    constexpr int H = (TP / RPP + 1) / 2;              // rows in two batches: half the operand registers
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      uint4 xv[H], yv[H]; uint32_t mk[H];
+#pragma unroll
+      for (int u = 0; u < H; ++u) {
+        const int m = m0 + pr0 + (b * H + u) * RPP;
+        xv[u] = make_uint4(0u, 0u, 0u, 0u); yv[u] = xv[u]; mk[u] = 0u;
+        if (b * H + u < TP / RPP && m < a.M && ch < a.Cout) {
+          const int64_t e = out_row(a, m) * a.Cout + ch;
+          xv[u] = *reinterpret_cast<const uint4*>(a.stat_x + e);
+          yv[u] = *reinterpret_cast<const uint4*>(a.stat_x2 + e);
+          mk[u] = a.stat_mask ? (uint32_t)a.stat_mask[e >> 3] : 0xffu;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < H; ++u) {
+        const int prow = pr0 + (b * H + u) * RPP, m = m0 + prow;
+        if (b * H + u < TP / RPP && m < a.M && ch < a.Cout) {
+          const uint4 pk = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
+          *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = pk;
+          const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w}, xw[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w}, yw[4] = {yv[u].x, yv[u].y, yv[u].z, yv[u].w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float v0 = ((mk[u] >> (2 * j)) & 1u) ? __uint_as_float(w[j] << 16) : 0.f;
+            const float v1 = ((mk[u] >> (2 * j + 1)) & 1u) ? __uint_as_float(w[j] & 0xffff0000u) : 0.f;
+            s1[2 * j] += v0; s1[2 * j + 1] += v1;
+            s2[2 * j] += v0 * ((__uint_as_float(xw[j] << 16) - mu[2 * j]) * rs[2 * j]);
+            s2[2 * j + 1] += v1 * ((__uint_as_float(xw[j] & 0xffff0000u) - mu[2 * j + 1]) * rs[2 * j + 1]);
+            s3[2 * j] += v0 * ((__uint_as_float(yw[j] << 16) - mu2[2 * j]) * rs2[2 * j]);
+            s3[2 * j + 1] += v1 * ((__uint_as_float(yw[j] & 0xffff0000u) - mu2[2 * j + 1]) * rs2[2 * j + 1]);
+          }
+        }
+      }
+    }
+  } else if (a.stat_mode == 2) {
     // BN backward sums of the tile just computed: the normalisation's input and mask are fetched for all of this
     // thread's rows before the first one is used
     float mu[8], rs[8];
@@ -233,15 +278,19 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
   if (a.stat_mode) {
     // fold the RPP row groups in a fixed order through LDS, one slab per pixel tile
     __syncthreads();
-    float* red = reinterpret_cast<float*>(lds);     // [RPP][2][TC]
+    const int ns = a.stat_mode == 3 ? 3 : 2;        // sums per channel
+    float* red = reinterpret_cast<float*>(lds);     // [RPP][ns][TC]
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { red[(pr0 * 2 + 0) * TC + cv * 8 + j] = s1[j]; red[(pr0 * 2 + 1) * TC + cv * 8 + j] = s2[j]; }
+    for (int j = 0; j < 8; ++j) {
+      red[(pr0 * ns + 0) * TC + cv * 8 + j] = s1[j]; red[(pr0 * ns + 1) * TC + cv * 8 + j] = s2[j];
+      if (ns == 3) red[(pr0 * ns + 2) * TC + cv * 8 + j] = s3[j];
+    }
     __syncthreads();
-    if (tid < 2 * TC) {
-      const int which = tid / TC, c = tid % TC;
+    for (int q = tid; q < ns * TC; q += kThreads) {
+      const int which = q / TC, c = q % TC;
       float t = 0.f;
-      for (int g = 0; g < RPP; ++g) t += red[(g * 2 + which) * TC + c];
-      if (c0 + c < a.Cout) a.stat_partial[((int64_t)(a.stat_slab0 + pt) * 2 + which) * a.Cout + c0 + c] = t;
+      for (int g = 0; g < RPP; ++g) t += red[(g * ns + which) * TC + c];
+      if (c0 + c < a.Cout) a.stat_partial[((int64_t)(a.stat_slab0 + pt) * ns + which) * a.Cout + c0 + c] = t;
     }
   }
 }
@@ -495,7 +544,7 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   constexpr int TILE_BYTES = (VW * RPG + TP) * RB;       // weight rows rounded up to whole load sweeps
   constexpr int XBASE = VW * RPG * RB;
   constexpr int STG_STRIDE = TC * 2 + 16;
-  constexpr int RED_BYTES = (kThreads / (TC / 8)) * 2 * TC * 4;
+  constexpr int RED_BYTES = (kThreads / (TC / 8)) * (TC >= 128 ? 3 : 2) * TC * 4;
   constexpr int E_BYTES = TP * STG_STRIDE > RED_BYTES ? TP * STG_STRIDE : RED_BYTES;
   constexpr int LDS_BYTES = TILE_BYTES > E_BYTES ? TILE_BYTES : E_BYTES;
   static_assert(TP % RPG == 0 && (BKT == 32 || BKT == 64), "tile rows must be whole load sweeps");
@@ -685,6 +734,7 @@ std::atomic<int64_t> g_launches{0};
 dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
   g_launches.fetch_add(1, std::memory_order_relaxed);
   if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
+  if (a.stat_mode == 3 && (a.Cout <= 64 || a.xf_tab)) return DAT_ERR_UNSUPPORTED;   // three sums: 128-channel tiles only
   if (a.xf_tab) {
     if (a.Cout <= 64) return launch_igemm_xf<64, 128, 2, 2, 64, 1>(a, st);
     return launch_igemm_xf<128, 128, 2, 2, 32, 2>(a, st);
@@ -1005,9 +1055,11 @@ size_t conv_mfma_wgrad_workspace(const ConvGeom& g) {
 static void set_stats(IgemmArgs& a, const ConvStats* s, int slab0) {
   a.stat_mode = 0; a.stat_slab0 = slab0; a.stat_partial = nullptr;
   a.stat_x = nullptr; a.stat_mask = nullptr; a.stat_mean = nullptr; a.stat_rstd = nullptr;
+  a.stat_x2 = nullptr; a.stat_mean2 = nullptr; a.stat_rstd2 = nullptr;
   if (!s || !s->mode) return;
   a.stat_mode = s->mode; a.stat_partial = s->partial;
-  if (s->mode == 2) { a.stat_x = s->bn_x; a.stat_mask = s->bn_mask; a.stat_mean = s->bn_mean; a.stat_rstd = s->bn_rstd; }
+  if (s->mode >= 2) { a.stat_x = s->bn_x; a.stat_mask = s->bn_mask; a.stat_mean = s->bn_mean; a.stat_rstd = s->bn_rstd; }
+  if (s->mode == 3) { a.stat_x2 = s->bn_x2; a.stat_mean2 = s->bn_mean2; a.stat_rstd2 = s->bn_rstd2; }
 }
 
 int64_t conv_mfma_launch_count() { return g_launches.load(std::memory_order_relaxed); }

@@ -54,7 +54,10 @@ struct ConvStats {
   int mode;
   float* partial;
   int nslabs;            // out
-  const bf16_t* bn_x; const uint8_t* bn_mask; const float* bn_mean; const float* bn_rstd;   // mode 2
+  const bf16_t* bn_x; const uint8_t* bn_mask; const float* bn_mean; const float* bn_rstd;   // mode 2, 3
+  // mode 3 (results with more than 64 channels): a second normalisation with input bn_x2 shares d(out); slabs are
+  // [3][C]: (sum dy, sum dy*xhat, sum dy*xhat2)
+  const bf16_t* bn_x2; const float* bn_mean2; const float* bn_rstd2;
 };
 // Number of MFMA convolution kernels (igemm) launched by this process so far.
 int64_t conv_mfma_launch_count();
@@ -104,9 +107,11 @@ dat_status bn_stats(const void* x, int dtype, int64_t rows, int C, float* partia
 // `partial` must have room for fold_floats(nslabs, C) more floats after the slabs.
 size_t fold_floats(int nslabs, int C);
 //           With gamma/mean/rstd/tab the constants of bn_input_grad are written too.
+//           nsum / col2: the slabs hold nsum rows of C sums each; the pair reduced is (row 0, row col2).  With three rows
+//           call it once per pair; `fold` = false skips the folding of many slabs (done by an earlier call).
 dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
                              float* dgamma, float scale, hipStream_t st, const float* gamma = nullptr, const float* mean = nullptr,
-                             const float* rstd = nullptr, float* tab = nullptr);
+                             const float* rstd = nullptr, float* tab = nullptr, int nsum = 2, int col2 = 1, bool fold = true);
 // out = act(gamma*((x-mean)*rstd) + beta [+ res])
 // mask (optional, rows*C/8 bytes): bit j of byte e/8 = (out[e] > 0), what the backward pass needs of `out`.
 // res_bn (optional): `res` is the INPUT of a second normalisation without activation (the one on a projection

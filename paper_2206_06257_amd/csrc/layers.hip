@@ -374,7 +374,9 @@ __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ 
                                                       float* __restrict__ o1, float* __restrict__ o2, float* __restrict__ e1,
                                                       float* __restrict__ e2, float scale,
                                                       const float* __restrict__ gamma = nullptr, const float* __restrict__ mean = nullptr,
-                                                      const float* __restrict__ rstd = nullptr, float* __restrict__ tab = nullptr) {
+                                                      const float* __restrict__ rstd = nullptr, float* __restrict__ tab = nullptr,
+                                                      int stride = 0, int off2 = 0) {
+  if (stride == 0) { stride = 2 * C; off2 = C; }     // slab = [2][C]: the two sums are rows 0 and 1
   __shared__ double sh[2][32][8];
   const int cl = threadIdx.x & 7, grp = threadIdx.x >> 3;
   const int c = blockIdx.x * 8 + cl;
@@ -387,8 +389,8 @@ __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ 
       for (int u = 0; u < 8; ++u) {
         const int su = s + 32 * u;
         const int sc = su < nslabs ? su : nslabs - 1;     // unconditional in-range loads, selected afterwards
-        a[u] = partial[(int64_t)sc * 2 * C + c];
-        b[u] = partial[(int64_t)sc * 2 * C + C + c];
+        a[u] = partial[(int64_t)sc * stride + c];
+        b[u] = partial[(int64_t)sc * stride + off2 + c];
         if (su >= nslabs) { a[u] = 0.f; b[u] = 0.f; }
       }
 #pragma unroll
@@ -968,23 +970,28 @@ dat_status colreduce(const void* x, const void* out, const uint8_t* mask, const 
 
 size_t bn_partial_floats(int64_t rows, int C) { (void)rows; return (size_t)kMaxSlabs * 4 * C; }   // two sets of slabs (dual reduction)
 
-size_t fold_floats(int nslabs, int C) { return nslabs > 512 ? (size_t)((nslabs + 31) / 32) * 2 * C : 0; }
+size_t fold_floats(int nslabs, int C) { return nslabs > 512 ? (size_t)((nslabs + 31) / 32) * 3 * C : 0; }   // up to three sums per channel
 
 dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
                              float* dgamma, float scale, hipStream_t st, const float* gamma, const float* mean, const float* rstd,
-                             float* tab) {
+                             float* tab, int nsum, int col2, bool fold) {
   const float* src = partial;
+  const int W = nsum * C;
   if (nslabs > 512) {   // two-level: keep the final per-channel loop short
-    float* folded = partial + (size_t)nslabs * 2 * C;
+    float* folded = partial + (size_t)nslabs * W;
     const int S2 = (nslabs + 31) / 32;
-    hipLaunchKernelGGL(slab_fold_kernel, dim3(S2, (2 * C + kT - 1) / kT), dim3(kT), 0, st, partial, nslabs, 2 * C, folded);
-    DAT_LAUNCH_CHECK();
+    if (fold) {
+      hipLaunchKernelGGL(slab_fold_kernel, dim3(S2, (W + kT - 1) / kT), dim3(kT), 0, st, partial, nslabs, W, folded);
+      DAT_LAUNCH_CHECK();
+    }
     src = folded; nslabs = S2;
   }
   if (mode == 1)
-    hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, (float*)nullptr, (float*)nullptr, 1.0f);
+    hipLaunchKernelGGL(colfinal_kernel<0>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, (float*)nullptr, (float*)nullptr, 1.0f,
+                       (const float*)nullptr, (const float*)nullptr, (const float*)nullptr, (float*)nullptr, W, col2 * C);
   else
-    hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, dbeta, dgamma, scale, gamma, mean, rstd, tab);
+    hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, dbeta, dgamma, scale, gamma, mean, rstd, tab,
+                       W, col2 * C);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }

@@ -300,7 +300,8 @@ bool build_graph(dat_model& m) {
       Op& cv = m.ops[c];
       if (cv.kind != OP_CONV || cv.in <= 0 || producer[cv.in] < 0) continue;
       const Op& bn = m.ops[producer[cv.in]];
-      if (bn.kind != OP_BNACT || bn.absorbed_by >= 0 || bn.res_bn >= 0 || bn.pool >= 0) continue;
+      if (bn.kind != OP_BNACT || bn.absorbed_by >= 0 || bn.pool >= 0) continue;
+      if (bn.res_bn >= 0 && m.tens[cv.in].C < 128) continue;   // two BNs on one d(out): three sums, wide tiles only
       int users = 0, conv_users = 0, first_user = -1;
       for (int o = 0; o < (int)m.ops.size(); ++o) {
         const int u = (m.ops[o].in == cv.in) + (m.ops[o].res == cv.in);
@@ -415,7 +416,7 @@ dat_status allocate(dat_model& m) {
     if (op.kind != OP_CONV || m.dtype != DAT_BF16) continue;
     const Shape si = m.tens[op.in], so = m.tens[op.out];
     const int sf = conv_stat_slabs((int64_t)m.maxB * so.H * so.W, 1), sb = conv_stat_slabs((int64_t)m.maxB * si.H * si.W, op.stride);
-    const size_t need_f = (size_t)sf * 2 * so.C + fold_floats(sf, so.C), need_b = (size_t)sb * 2 * si.C + fold_floats(sb, si.C);
+    const size_t need_f = (size_t)sf * 2 * so.C + fold_floats(sf, so.C), need_b = (size_t)sb * 3 * si.C + fold_floats(sb, si.C);
     partial_floats = std::max(partial_floats, std::max(need_f, need_b));
   }
   DAT_TRY(dev_alloc(m, &m.partial, partial_floats * 4));
@@ -565,6 +566,10 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
             const Op& bn = m.ops[op.dy_bn];
             bs.mode = 2; bs.partial = m.partial; bs.bn_x = (const bf16_t*)m.act[bn.in]; bs.bn_mask = bn.relu ? bn.mask : nullptr;
             bs.bn_mean = bn.mean; bs.bn_rstd = bn.rstd;
+            if (bn.res_bn >= 0) {   // the BN on the projection shortcut sees the same d(out)
+              const Op& sb = m.ops[bn.res_bn];
+              bs.mode = 3; bs.bn_x2 = (const bf16_t*)m.act[sb.in]; bs.bn_mean2 = sb.mean; bs.bn_rstd2 = sb.rstd;
+            }
             bsp = &bs;
           }
           if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_stem_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], st));
@@ -592,8 +597,16 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
             Op& bn = m.ops[op.dy_bn];
             float* bg0 = grads ? grads + m.ptab[bn.p0].off : nullptr;
             float* bg1 = grads ? grads + m.ptab[bn.p1].off : nullptr;
+            const int nsum = bs.mode == 3 ? 3 : 2;
             DAT_PROF(m, DAT_PROF_BN, 0.0, st, bn_finalize_slabs(m.partial, bs.nslabs, si.C, rows_in, 2, bn.sums, bn.sums + si.C, bg1, bg0, 1.0f, st,
-                                                                 m.compute + m.ptab[bn.p0].off, bn.mean, bn.rstd, bn.bn_tab));
+                                                                 m.compute + m.ptab[bn.p0].off, bn.mean, bn.rstd, bn.bn_tab, nsum, 1, true));
+            if (bs.mode == 3) {
+              Op& sb = m.ops[bn.res_bn];
+              float* sg0 = grads ? grads + m.ptab[sb.p0].off : nullptr;
+              float* sg1 = grads ? grads + m.ptab[sb.p1].off : nullptr;
+              DAT_PROF(m, DAT_PROF_BN, 0.0, st, bn_finalize_slabs(m.partial, bs.nslabs, si.C, rows_in, 2, sb.sums, sb.sums + si.C, sg1, sg0, 1.0f, st,
+                                                                   m.compute + m.ptab[sb.p0].off, sb.mean, sb.rstd, sb.bn_tab, 3, 2, false));
+            }
             bn.sums_ready = true;
           }
         }
