@@ -18,6 +18,7 @@ constexpr int kMaxApplySlabs = 8192;  // slabs of an elementwise pass
 
 template <typename T> struct V8;
 template <> struct V8<float> {
+  static __device__ __forceinline__ void load_nt(const float* p, float v[8]) { load(p, v); }
   static __device__ __forceinline__ void load(const float* p, float v[8]) {
     const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
@@ -28,6 +29,14 @@ template <> struct V8<float> {
   }
 };
 template <> struct V8<bf16_t> {
+  // streaming read: the line is not needed again soon (leaves the caches to the tensors that are)
+  static __device__ __forceinline__ void load_nt(const bf16_t* p, float v[8]) {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    const u4 a = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { v[2 * j] = __uint_as_float(w[j] << 16); v[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u); }
+  }
   static __device__ __forceinline__ void load(const bf16_t* p, float v[8]) {
     const uint4 a = *reinterpret_cast<const uint4*>(p);
     const uint32_t w[4] = {a.x, a.y, a.z, a.w};
@@ -471,7 +480,7 @@ __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = rb + (int64_t)u * rpp;
-      if (r < r1) { V8<T>::load(x + r * C + c0, xv[u]); if (res) V8<T>::load(res + r * C + c0, rv[u]); }
+      if (r < r1) { V8<T>::load_nt(x + r * C + c0, xv[u]); if (res) V8<T>::load_nt(res + r * C + c0, rv[u]); }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
