@@ -196,7 +196,12 @@ def main():
                                                       "launches that also form a batch-norm input gradient from three operand streams are "
                                                       "listed as kernel_classes.conv_bwd_data_bn)", "achieved": ach,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
-                           "launches": n, "avg_launch_ms": ms / max(n, 1), "flops_per_launch": flops / max(n, 1)}
+                           "launches": n, "avg_launch_ms": ms / max(n, 1), "flops_per_launch": flops / max(n, 1),
+                           "achieved_forward": prof["conv_fwd"][2] / (prof["conv_fwd"][0] * 1e-3) / 1e12,
+                           "achieved_backward_data": prof["conv_bwd_data"][2] / (prof["conv_bwd_data"][0] * 1e-3) / 1e12,
+                           "note": "launch times include the fused epilogue work: the batch statistics of the next BN (forward), the "
+                                   "residual gradient and the two BN backward sums of the producing BN, which re-read its input and "
+                                   "ReLU mask (backward-data)"}
         out["kernel_classes"] = {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps,
                                      "work_per_step": v[2] / args.steps} for k, v in prof.items()}
         pg = prof["pgd"]
