@@ -259,7 +259,10 @@ typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1 } dat_op
  * shortcut runs as passes of its own instead of being evaluated by the last normalisation of the
  * residual branch.  DAT_KEEP_STEM_POOL: a BN + ReLU read only by a max-pool stores its output and
  * the pool runs as passes of its own, instead of one fused forward pass and a backward pass that
- * gathers d(out) from the pool's output gradient.  Identical bits either way.) */
+ * gathers d(out) from the pool's output gradient.  Identical bits either way.
+ * DAT_NO_RING_KERNEL, read at every convolution launch: layers that would run as one round of
+ * 256-channel tiles through the multi-stage kernel go through the 128x128 kernels instead; the
+ * convolution outputs are bit-identical, the grouping of the batch-norm partial sums differs.) */
 dat_status dat_model_set_option(dat_model* m, dat_option opt, int value);
 
 /* ---- misc ---------------------------------------------------------------------------------- */

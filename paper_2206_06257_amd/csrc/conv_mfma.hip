@@ -32,6 +32,7 @@
 // 16-byte reads.  The pixel range is split over gridDim.z; partial tiles go to a workspace
 // and a second kernel sums them in a fixed order (deterministic).
 #include <atomic>
+#include <cstdlib>
 #include "kernels.h"
 
 namespace dat {
@@ -109,10 +110,10 @@ __device__ __forceinline__ int64_t out_row(const IgemmArgs& a, int m) {
 // ---- epilogue shared by the convolution kernels: (+res) -> bf16 -> LDS transpose -> 16-byte stores ----
 // `lds` must hold TP rows of STG_STRIDE = 2*TC + 16 bytes (and [kThreads/(TC/8)][2][TC] floats for the
 // statistics); every wave must be done with whatever else lived there (the caller ends on a barrier).
-template <int TC, int TP, int WGC>
-__device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)[TC / WGC / 32][TP / (4 / WGC) / 32],
+template <int TC, int TP, int WGC, int NT = kThreads>
+__device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)[TC / WGC / 32][TP / (NT / 64 / WGC) / 32],
                                                unsigned char* lds, int c0, int m0, int pt) {
-  constexpr int WGP = 4 / WGC;
+  constexpr int WGP = NT / 64 / WGC;
   constexpr int WC = TC / WGC, WP = TP / WGP;
   constexpr int NI = WC / 32, NJ = WP / 32;
   constexpr int STG_STRIDE = TC * 2 + 16;
@@ -126,7 +127,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
   // the same coalesced 16-byte accesses the stores use; each lane then adds its accumulators to
   // the values at its own staging slots in fp32 and rounds once, in place.
   constexpr int CV = TC / 8;                       // channel vectors per pixel row
-  constexpr int RPP = kThreads / CV;               // pixel rows per store sweep
+  constexpr int RPP = NT / CV;                     // pixel rows per store sweep
   const int cv = tid % CV, pr0 = tid / CV;
   const int ch = c0 + cv * 8;
   if (a.res) {
@@ -259,8 +260,8 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
     }
   } else {
 #pragma unroll
-  for (int prow = pr0; prow < TP; prow += RPP) {
-    const int m = m0 + prow;
+  for (int u = 0; u < TP / RPP; ++u) {
+    const int prow = pr0 + u * RPP, m = m0 + prow;
     if (m < a.M && ch < a.Cout) {
       const uint4 pk = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
       *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = pk;
@@ -286,7 +287,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
       if (ns == 3) red[(pr0 * ns + 2) * TC + cv * 8 + j] = s3[j];
     }
     __syncthreads();
-    for (int q = tid; q < ns * TC; q += kThreads) {
+    for (int q = tid; q < ns * TC; q += NT) {
       const int which = q / TC, c = q % TC;
       float t = 0.f;
       for (int g = 0; g < RPP; ++g) t += red[(g * ns + which) * TC + c];
@@ -671,6 +672,183 @@ dat_status launch_igemm_dma(IgemmArgs a, hipStream_t st) {
   return DAT_OK;
 }
 
+// ---- ring variant for long contractions that fill the chip with ONE round of large tiles -----------------------
+// 8 waves, 256-channel tiles, S LDS stages of 64-wide k-tiles filled by the same direct-to-LDS loads.  While tile t
+// is multiplied, the loads of tile t+S-1 are issued during its first k-step (spread over the MFMA groups so that the
+// address queue never holds a burst from all waves), and `s_waitcnt vmcnt((S-2)*loads)` at the end of the tile
+// waits for tile t+1 only.  Half the operand bytes per FLOP of the 128x128 kernel; it pays when the layer is one
+// round of at most one workgroup per CU (pick_ring), where the single-stage kernel cannot hide the load latency
+// behind other workgroups.
+template <int TC, int TP, int WGC, int S>
+__global__ __launch_bounds__(512) void igemm_ring_kernel(IgemmArgs a) {
+  constexpr int NT = 512, BKT = 64, KS = BKT / 16;
+  constexpr int WGP = NT / 64 / WGC;
+  constexpr int WC = TC / WGC, WP = TP / WGP;
+  constexpr int NI = WC / 32, NJ = WP / 32;
+  constexpr int RB = 128, RPG = NT / 8;                   // bytes per tile row; tile rows covered by one load per thread
+  constexpr int VW = TC / RPG, VX = TP / RPG;
+  constexpr int NL = VW + VX;                             // loads per thread per tile
+  constexpr int TILE_BYTES = (TC + TP) * RB;
+  constexpr int E_BYTES = TP * (TC * 2 + 16);
+  constexpr int LDS_BYTES = (S * TILE_BYTES > E_BYTES) ? S * TILE_BYTES : E_BYTES;
+  static_assert(TC % RPG == 0 && TP % RPG == 0, "tile rows must be whole load sweeps");
+  static_assert(S >= 2 && (S - 2) * NL <= 63, "vmcnt range");
+  static_assert(NI >= 2 && VW % (NI / 2) == 0 && VX % (NI - NI / 2) == 0, "loads spread evenly over the MFMA groups of a k-step");
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
+
+  const int bid = blockIdx.x;
+  const int q = bid >> 3;
+  const int ct = q % a.nct;
+  const int pt = (q / a.nct) * 8 + (bid & 7);
+  if (pt >= a.npt) return;
+  const int c0 = ct * TC, m0 = pt * TP;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wc = wave % WGC, wp = wave / WGC;
+  const int lrow = tid >> 3;
+  const int kvec = (swz<8>(lrow, tid & 7) - lrow * RB) >> 4;   // logical k-slot behind physical slot tid & 7 of row lrow
+
+  int hb[VX], wb[VX], nb[VX]; bool mv[VX];
+  const int HW = a.Hout * a.Wout;
+#pragma unroll
+  for (int i = 0; i < VX; ++i) {
+    const int m = m0 + lrow + RPG * i;
+    mv[i] = m < a.M;
+    const int mm = mv[i] ? m : 0;
+    const int n = mm / HW, rem = mm - n * HW;
+    const int ho = rem / a.Wout, wo = rem - ho * a.Wout;
+    hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * a.ostride - a.pad_w;
+    nb[i] = n * a.Hin * a.Win;
+  }
+  const int ntiles = a.Ktot / BKT;
+  const unsigned char* zero_page = reinterpret_cast<const unsigned char*>(g_zero_page);
+  int woff[VW]; bool wrow[VW];
+#pragma unroll
+  for (int i = 0; i < VW; ++i) {
+    const int c = c0 + lrow + RPG * i;
+    wrow[i] = c < a.Cout;
+    woff[i] = (wrow[i] ? c : 0) * a.Ktot + kvec * 8;
+  }
+  int xoff[VX]; bool xok[VX];
+  int kc0 = 0, kr = 0, ks = 0, kf = 0;
+  bool tile_ok = true;
+  unsigned char* sb = lds;
+  // the loads of tile kf into ring stage `stage`, one at a time (tiles past the end fetch the zero page so that
+  // every tile issues the same number of loads and the vmcnt arithmetic stays exact)
+  auto fetch_begin = [&](int stage) { tile_ok = kf < ntiles; sb = lds + stage * TILE_BYTES + wave * 1024; };
+  auto fetch_w = [&](int i) {
+    const unsigned char* p = (tile_ok & wrow[i]) ? reinterpret_cast<const unsigned char*>(a.wt + woff[i]) : zero_page;
+    __builtin_amdgcn_global_load_lds((gbl_void_ptr)p, (lds_void_ptr)(sb + i * (RPG * RB)), 16, 0, 0);
+    woff[i] += BKT;
+  };
+  auto fetch_tap = [&]() {
+    if (kc0 != 0) return;
+#pragma unroll
+    for (int i = 0; i < VX; ++i) {
+      const int hi = hb[i] + kr, wi = wb[i] + ks;
+      xok[i] = mv[i] & (hi >= 0) & (wi >= 0) & (hi < a.Hin) & (wi < a.Win);
+      xoff[i] = (nb[i] + hi * a.Win + wi) * a.Cin + kvec * 8;
+    }
+  };
+  auto fetch_x = [&](int i) {
+    const unsigned char* p = (tile_ok & xok[i]) ? reinterpret_cast<const unsigned char*>(a.in + xoff[i]) : zero_page;
+    __builtin_amdgcn_global_load_lds((gbl_void_ptr)p, (lds_void_ptr)(sb + TC * RB + i * (RPG * RB)), 16, 0, 0);
+    xoff[i] += BKT;
+  };
+  auto fetch_end = [&]() {
+    kc0 += BKT;
+    if (kc0 == a.Cin) { kc0 = 0; if (++ks == a.KW) { ks = 0; ++kr; } }
+    ++kf;
+  };
+  int fa_off[NI], fb_off[NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) fa_off[i] = swz<8>(wc * WC + i * 32 + (lane & 31), lane >> 5);
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) fb_off[j] = TC * RB + swz<8>(wp * WP + j * 32 + (lane & 31), lane >> 5);
+
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+#pragma unroll
+  for (int p = 0; p < S - 1; ++p) {
+    fetch_begin(p);
+#pragma unroll
+    for (int i = 0; i < VW; ++i) fetch_w(i);
+    fetch_tap();
+#pragma unroll
+    for (int i = 0; i < VX; ++i) fetch_x(i);
+    fetch_end();
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * NL) : "memory");
+  __builtin_amdgcn_s_barrier();
+  int stage = 0, fstage = S - 1;
+  for (int t = 0; t < ntiles; ++t) {
+    const unsigned char* cur = lds + stage * TILE_BYTES;
+    Frag fa[2][NI], fb[2][NJ];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) fa[0][i].u = *reinterpret_cast<const u32x4*>(cur + fa_off[i]);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) fb[0][j].u = *reinterpret_cast<const u32x4*>(cur + fb_off[j]);
+    fetch_begin(fstage);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i].v, fb[kk & 1][j].v, acc[i][j], 0, 0, 0);
+        if (i == 0 && kk + 1 < KS) {                       // fragments of the next k-step under this one's MFMAs
+#pragma unroll
+          for (int ii = 0; ii < NI; ++ii) fa[(kk + 1) & 1][ii].u = *reinterpret_cast<const u32x4*>(cur + (fa_off[ii] ^ ((kk + 1) * 32)));
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) fb[(kk + 1) & 1][j].u = *reinterpret_cast<const u32x4*>(cur + (fb_off[j] ^ ((kk + 1) * 32)));
+        }
+        if (kk == 0) {   // the next ring tile: weights behind the first half of this k-step's MFMA groups, pixels behind the second
+          constexpr int H = NI / 2;
+          if (i < H) {
+#pragma unroll
+            for (int u = 0; u < VW / H; ++u) fetch_w(i * (VW / H) + u);
+            if (i == H - 1) fetch_tap();
+          } else {
+#pragma unroll
+            for (int u = 0; u < VX / (NI - H); ++u) fetch_x((i - H) * (VX / (NI - H)) + u);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    fetch_end();
+    // this wave's part of tile t+1 has landed once at most (S-2) tiles of loads are outstanding; the barrier then
+    // covers every wave's part, and everyone is done reading `stage`
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((S - 2) * NL) : "memory");
+    __builtin_amdgcn_s_barrier();
+    stage = stage + 1 == S ? 0 : stage + 1;
+    fstage = fstage + 1 == S ? 0 : fstage + 1;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the zero-page loads of the tail land in LDS too
+  __builtin_amdgcn_s_barrier();
+  igemm_epilogue<TC, TP, WGC, NT>(a, acc, lds, c0, m0, pt);
+}
+
+template <int TC, int TP, int WGC, int S>
+dat_status launch_igemm_ring(IgemmArgs a, hipStream_t st) {
+  if ((int64_t)a.B * a.Hin * a.Win * a.Cin >= (1ll << 31) || (int64_t)a.Cout * a.Ktot >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;
+  if (a.Cin % 64 != 0 || a.Ktot < 64 || a.xf_tab) return DAT_ERR_UNSUPPORTED;
+  a.nct = (a.Cout + TC - 1) / TC;
+  a.npt = (a.M + TP - 1) / TP;
+  if (a.npt == 0) return DAT_OK;
+  const int npt8 = (a.npt + 7) / 8 * 8;
+  hipLaunchKernelGGL((igemm_ring_kernel<TC, TP, WGC, S>), dim3((unsigned)(npt8 * a.nct)), dim3(512), 0, st, a);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
 __global__ void widen_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = bf2f(src[i]);
@@ -731,10 +909,44 @@ dat_status pick_depth_wide(const IgemmArgs& a, hipStream_t st) {
 
 std::atomic<int64_t> g_launches{0};
 
+int compute_units() {
+  static std::atomic<int> cached{0};
+  int n = cached.load(std::memory_order_relaxed);
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached.store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+
+// Which ring configuration, if any, runs this launch: 0 none, 1 = 256 channels x 256 pixels, 2 = 256 x 128.
+// Long contractions into a multiple of 256 channels whose tiles make one round of 60-100 % of the CUs (measured at
+// B = 256: 14x14 3x3 256->256 82 -> 66 us and 1024->256 42 -> 35 us with 256x256 tiles; 7x7 3x3 512->512 87 -> 75 us
+// and 2048->512 44 -> 37 us with 256x128; slower than the 128x128 kernel wherever several rounds are needed or the
+// contraction is short).
+int pick_ring(const IgemmArgs& a) {
+  if (a.xf_tab || a.ostep != 1 || a.stat_slab0 != 0 || a.Cin % 64 != 0 || a.Ktot < 1024 || a.Cout % 256 != 0) return 0;
+  if (getenv("DAT_NO_RING_KERNEL")) return 0;   // for A/B runs: every layer through the 128x128 kernels
+  const int64_t cus = compute_units(), nct = a.Cout / 256;
+  const int64_t t256 = ((int64_t)a.M + 255) / 256 * nct, t128 = ((int64_t)a.M + 127) / 128 * nct;
+  if (t256 <= cus && 5 * t256 >= 3 * cus) return 1;
+  if (t128 <= cus && 5 * t128 >= 3 * cus) return 2;
+  return 0;
+}
+
+// pixel rows per tile (= per slab of epilogue statistics) of the configuration run_igemm selects
+int pixel_tile(const IgemmArgs& a) { return pick_ring(a) == 1 ? 256 : 128; }
+
 dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
   g_launches.fetch_add(1, std::memory_order_relaxed);
   if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
   if (a.stat_mode == 3 && (a.Cout <= 64 || a.xf_tab)) return DAT_ERR_UNSUPPORTED;   // three sums: 128-channel tiles only
+  switch (pick_ring(a)) {
+    case 1: return launch_igemm_ring<256, 256, 2, 2>(a, st);
+    case 2: return launch_igemm_ring<256, 128, 4, 3>(a, st);
+    default: break;
+  }
   if (a.xf_tab) {
     if (a.Cout <= 64) return launch_igemm_xf<64, 128, 2, 2, 64, 1>(a, st);
     return launch_igemm_xf<128, 128, 2, 2, 32, 2>(a, st);
@@ -1080,7 +1292,7 @@ dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res
   a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
   a.M = g.B * g.Ho * g.Wo; a.Ktot = g.k * g.k * g.Cin; a.nct = a.npt = 0;
   set_stats(a, stats, 0);
-  if (stats) stats->nslabs = (a.M + kPixelTile - 1) / kPixelTile;
+  if (stats) stats->nslabs = (a.M + pixel_tile(a) - 1) / pixel_tile(a);
   return run_igemm(a, st);
 }
 
@@ -1108,7 +1320,7 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
     a.ostep = 1; a.oh0 = a.ow0 = 0;
     a.M = g.B * g.H * g.W; a.Ktot = g.k * g.k * g.Cout;
     set_stats(a, stats, 0);
-    if (stats) stats->nslabs = (a.M + kPixelTile - 1) / kPixelTile;
+    if (stats) stats->nslabs = (a.M + pixel_tile(a) - 1) / pixel_tile(a);
     return run_igemm(a, st);
   }
   if (g.stride != 2) return DAT_ERR_UNSUPPORTED;

@@ -25,9 +25,10 @@ LAYERS = [
     (56, 128, 128, 3, 2, 1),     # layer2 strided 3x3
     (28, 128, 512, 1, 1, 0),     # layer2 expand
     (28, 512, 1024, 1, 2, 0),    # layer3 projection shortcut
-    (14, 256, 256, 3, 1, 1),     # layer3 3x3
-    (7, 2048, 512, 1, 1, 0),     # layer4 reduce
-    (7, 512, 512, 3, 1, 1),      # layer4 3x3
+    (14, 256, 256, 3, 1, 1),     # layer3 3x3 (one round of 256x256 tiles: ring kernel)
+    (14, 1024, 256, 1, 1, 0),    # layer3 reduce (ring kernel forward)
+    (7, 2048, 512, 1, 1, 0),     # layer4 reduce (one round of 256x128 tiles: ring kernel)
+    (7, 512, 512, 3, 1, 1),      # layer4 3x3 (ring kernel)
 ]
 
 
