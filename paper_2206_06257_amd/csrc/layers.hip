@@ -800,47 +800,65 @@ __global__ __launch_bounds__(kT) void gap_bwd_kernel(const float* __restrict__ d
 // ---- linear classifier (fp32) --------------------------------------------------------------
 // One small tiled SGEMM serves the three products of the layer:
 //   C[m][n] = scale * sum_k A(m,k) * B(k,n) (+ bias[n]),  A(m,k) = A[m*sAm + k*sAk],  B(k,n) = B[k*sBk + n*sBn].
-// 32x32 output tile per workgroup, 32-deep k tiles staged in LDS (padded rows), each thread four
-// outputs.  The matrices are a few MB; the point is only not to be latency-bound: the contraction
+// 64x64 output tile per workgroup, 32-deep k tiles staged in LDS (padded rows), each thread a 4x4 block of
+// outputs (rows ty + 16 r, columns tx + 16 c: conflict-free LDS reads, 8 per 16 multiply-adds).
+// The matrices are a few MB; the point is only not to be latency-bound: the contraction
 // can be split over gridDim.z (k range [z*kchunk, (z+1)*kchunk)); then raw partial sums go to
 // ws[z][M][N] and splitk_reduce_kernel adds them in a fixed order.
 __global__ __launch_bounds__(kT) void sgemm_kernel(const float* __restrict__ A, const float* __restrict__ Bm,
                                                    const float* __restrict__ bias, float* __restrict__ Cm, int M, int N,
                                                    int K, int64_t sAm, int64_t sAk, int64_t sBk, int64_t sBn, float scale,
                                                    int kchunk, float* __restrict__ ws) {
-  __shared__ float As[32][33], Bs[32][33];           // As[m][k], Bs[n][k]
-  const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
-  const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  __shared__ float As[64][33], Bs[64][33];           // As[m][k], Bs[n][k]
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  float acc[4][4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
   const int kbeg = blockIdx.z * kchunk;
   K = min(K, kbeg + kchunk);
   for (int k0 = kbeg; k0 < K; k0 += 32) {
+    float av[8], bv[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < 8; ++j) {
       const int idx = tid + 256 * j;
       // walk the unit-stride dimension with consecutive threads
-      const int am = sAk == 1 ? idx >> 5 : idx & 31, ak = sAk == 1 ? idx & 31 : idx >> 5;
-      As[am][ak] = (m0 + am < M && k0 + ak < K) ? A[(int64_t)(m0 + am) * sAm + (int64_t)(k0 + ak) * sAk] : 0.f;
-      const int bn = sBk == 1 ? idx >> 5 : idx & 31, bk = sBk == 1 ? idx & 31 : idx >> 5;
-      Bs[bn][bk] = (n0 + bn < N && k0 + bk < K) ? Bm[(int64_t)(k0 + bk) * sBk + (int64_t)(n0 + bn) * sBn] : 0.f;
+      const int am = sAk == 1 ? idx >> 5 : idx & 63, ak = sAk == 1 ? idx & 31 : idx >> 6;
+      av[j] = (m0 + am < M && k0 + ak < K) ? A[(int64_t)(m0 + am) * sAm + (int64_t)(k0 + ak) * sAk] : 0.f;
+      const int bn = sBk == 1 ? idx >> 5 : idx & 63, bk = sBk == 1 ? idx & 31 : idx >> 6;
+      bv[j] = (n0 + bn < N && k0 + bk < K) ? Bm[(int64_t)(k0 + bk) * sBk + (int64_t)(n0 + bn) * sBn] : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int idx = tid + 256 * j;
+      As[sAk == 1 ? idx >> 5 : idx & 63][sAk == 1 ? idx & 31 : idx >> 6] = av[j];
+      Bs[sBk == 1 ? idx >> 5 : idx & 63][sBk == 1 ? idx & 31 : idx >> 6] = bv[j];
     }
     __syncthreads();
-#pragma unroll
+#pragma unroll 8
     for (int k = 0; k < 32; ++k) {
-      const float bv = Bs[tx][k];
+      float a[4], b[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) acc[r] += As[ty + 8 * r][k] * bv;
+      for (int r = 0; r < 4; ++r) { a[r] = As[ty + 16 * r][k]; b[r] = Bs[tx + 16 * r][k]; }
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[r][c] += a[r] * b[c];
     }
     __syncthreads();
   }
-  const int n = n0 + tx;
-  if (n < N) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int m = m0 + ty + 8 * r;
-      if (m >= M) continue;
-      if (ws) ws[((int64_t)blockIdx.z * M + m) * N + n] = acc[r];
-      else Cm[(int64_t)m * N + n] = acc[r] * scale + (bias ? bias[n] : 0.f);
+  for (int r = 0; r < 4; ++r) {
+    const int m = m0 + ty + 16 * r;
+    if (m >= M) continue;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int n = n0 + tx + 16 * c;
+      if (n >= N) continue;
+      if (ws) ws[((int64_t)blockIdx.z * M + m) * N + n] = acc[r][c];
+      else Cm[(int64_t)m * N + n] = acc[r][c] * scale + (bias ? bias[n] : 0.f);
     }
   }
 }
@@ -1190,7 +1208,7 @@ dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dty
 // has a few hundred workgroups.
 static dat_status sgemm(const float* A, const float* Bm, const float* bias, float* Cm, int M, int N, int K, int64_t sAm,
                         int64_t sAk, int64_t sBk, int64_t sBn, float scale, float* ws, hipStream_t st) {
-  const int tiles = ((N + 31) / 32) * ((M + 31) / 32);
+  const int tiles = ((N + 63) / 64) * ((M + 63) / 64);
   int splits = 1;
   if (ws && K >= 256) {
     splits = (1024 + tiles - 1) / tiles;
@@ -1201,7 +1219,7 @@ static dat_status sgemm(const float* A, const float* Bm, const float* bias, floa
   const int kchunk = ((K + splits - 1) / splits + 31) / 32 * 32;
   splits = (K + kchunk - 1) / kchunk;
   if (splits == 1) ws = nullptr;
-  hipLaunchKernelGGL(sgemm_kernel, dim3((N + 31) / 32, (M + 31) / 32, splits), dim3(kT), 0, st, A, Bm, bias, Cm, M, N, K, sAm, sAk, sBk,
+  hipLaunchKernelGGL(sgemm_kernel, dim3((N + 63) / 64, (M + 63) / 64, splits), dim3(kT), 0, st, A, Bm, bias, Cm, M, N, K, sAm, sAk, sBk,
                      sBn, scale, kchunk, ws);
   DAT_LAUNCH_CHECK();
   if (ws) {
