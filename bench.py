@@ -192,7 +192,7 @@ def main():
         tpath = os.path.join(ROOT, "profiles", "traffic_igemm_" + args.workload + ".json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        out["roofline"] = {"bound": "mfma", "kernel": "igemm_dma_kernel + igemm_kernel (conv forward + backward-data launches; the few backward-data "
+        out["roofline"] = {"bound": "mfma", "kernel": "igemm_dma_kernel + igemm_ring_kernel + igemm_kernel (conv forward + backward-data launches; the few backward-data "
                                                       "launches that also form a batch-norm input gradient from three operand streams are "
                                                       "listed as kernel_classes.conv_bwd_data_bn)", "achieved": ach,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
