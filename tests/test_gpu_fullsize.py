@@ -105,6 +105,29 @@ def test_pgd_update_full_batch_bit_exact(dat):
     assert np.array_equal(got, oracle.pgd_update(x, G, want0, eps, alpha))
 
 
+@pytest.mark.parametrize("layer", [(14, 256, 256, 3, 1, 1), (14, 1024, 256, 1, 1, 0), (7, 512, 512, 3, 1, 1), (7, 2048, 512, 1, 1, 0),
+                                   (28, 256, 256, 3, 2, 1)])
+def test_ring_kernel_gives_the_bits_of_the_single_stage_kernel(dat, layer, monkeypatch):
+    """Layers that run as one round of 256-channel tiles through the multi-stage kernel: every accumulator sees the
+    same k order as in the 128x128 kernel, so forward and backward-data outputs are identical bit for bit (the
+    environment switch is read at every launch)."""
+    H, Ci, Co, k, st, pad = layer
+    g = torch.Generator(device="cuda"); g.manual_seed(H * 77 + Ci)
+    x = torch.randn(B, H, H, Ci, device="cuda", generator=g).to(torch.bfloat16)
+    w = (torch.randn(Co, k, k, Ci, device="cuda", generator=g) / np.sqrt(Ci * k * k)).to(torch.bfloat16)
+    monkeypatch.delenv("DAT_NO_RING_KERNEL", raising=False)
+    y = dat.conv_forward(x, w, st, pad)
+    dy = torch.randn_like(y)
+    dx = dat.conv_backward_data(dy, w, (H, H), st, pad)
+    monkeypatch.setenv("DAT_NO_RING_KERNEL", "1")
+    y0 = dat.conv_forward(x, w, st, pad)
+    dx0 = dat.conv_backward_data(dy, w, (H, H), st, pad)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y0.view(torch.int16))
+    assert torch.equal(dx.view(torch.int16), dx0.view(torch.int16))
+    assert float(y.float().abs().max()) > 0 and float(dx.float().abs().max()) > 0
+
+
 @pytest.mark.parametrize("B,eps,alpha,K", [
     (256, 4 / 255, 1 / 255, 3),          # config 5
     (85, 2 / 255, 1.25 / 255, 4),        # the paper's own ImageNet shape: 85 images per GPU, PGD-4 (odd batch: tile tails)
