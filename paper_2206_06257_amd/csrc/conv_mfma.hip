@@ -12,6 +12,8 @@
 //   sharing a k-slot hit distinct banks.  Two kernels fill those tiles:
 //   * `igemm_dma_kernel` (contraction channels a multiple of BK): global memory -> LDS directly
 //     (global_load_lds_dwordx4), one LDS stage, four or more workgroups resident per CU;
+//   * `igemm_ring_kernel` (long contractions into a multiple of 256 channels that fill the chip with one
+//     round of tiles): 8 waves, 256-channel tiles, a ring of LDS stages filled by the same direct loads;
 //   * `igemm_kernel` (any channel count, and the long 1x1 contractions into <= 64 channels):
 //     global -> registers -> LDS, double buffered, loads running PF k-tiles ahead.
 //   Backward-data is the same contraction over the output gradient: stride 1 with the flipped,
@@ -26,10 +28,10 @@
 //   rows neighbouring tiles share are re-read from that L2.
 //
 // Backward-weight (`wgrad_kernel`): dW[co][(r,s,ci)] = sum_p dY[p][co] * X[p][(r,s,ci)], a
-// contraction over pixels, which are the strided dimension of both operands.  Each thread
-// loads an 8-pixel x 8-channel block as eight 16-byte vectors, transposes it in registers
-// (v_perm_b32) and stores pixel-contiguous rows to LDS, so the MFMA fragments are again
-// 16-byte reads.  The pixel range is split over gridDim.z; partial tiles go to a workspace
+// contraction over pixels, which are the strided dimension of both operands.  The tiles land in
+// LDS as they are in memory ([pixel][channel], direct-to-LDS loads) and the MFMA fragments are
+// read with the LDS transpose reads of gfx950 (ds_read_b64_tr_b16), which hand every lane four
+// consecutive pixels of its channel.  The pixel range is split over gridDim.z; partial tiles go to a workspace
 // and a second kernel sums them in a fixed order (deterministic).
 #include <atomic>
 #include <cstdlib>
@@ -1063,39 +1065,108 @@ struct WgradArgs {
   int M, Ktot, pix_per_split;
 };
 
-__device__ __forceinline__ void transpose8x8(const uint4 in[8], uint4 out[8]) {
-  // in[q] = 8 channels of pixel q (dword d holds channels 2d, 2d+1); out[c] = 8 pixels of channel c
-  const uint32_t* pi = reinterpret_cast<const uint32_t*>(in);
-  uint32_t* po = reinterpret_cast<uint32_t*>(out);
-#pragma unroll
-  for (int c = 0; c < 8; ++c)
-#pragma unroll
-    for (int qq = 0; qq < 4; ++qq) {
-      const uint32_t lo = pi[(2 * qq) * 4 + (c >> 1)], hi = pi[(2 * qq + 1) * 4 + (c >> 1)];
-      po[c * 4 + qq] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-    }
+// ---- backward-weight through the LDS transpose reads of gfx950 -----------------------------------------------
+// The contraction runs over pixels, but both operands are stored with channels contiguous.  Instead of transposing
+// 8x8 blocks in registers, this kernel lands the tiles in LDS as they are in memory --
+// dY [64 pixels][TC channels] and the shifted X [64 pixels][TJ columns], by the direct-to-LDS loads of the forward
+// kernel -- and reads MFMA fragments with ds_read_b64_tr_b16: inside every group of 16 lanes, lane i receives
+// element i%4 of the 8-byte chunks named by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 (checked on the device).  With
+// source lane j pointing at pixel pb + j/4, channels cb + 4*(j%4) .. +3, lane i ends up with four consecutive pixels
+// of channel cb + i: two such reads are the eight k values of a 32x32x16 operand.
+// LDS rows are 32-byte-segment swizzled by pixel so that the 4 pixels x 2 segments a half-wave touches cover all
+// banks; the swizzle is applied on the source side of the direct loads (16-byte chunks keep their pair).
+typedef short v4s16 __attribute__((ext_vector_type(4)));
+union FragTr { v4s16 h[2]; bf16x8 v; };
+
+template <int ROWB> __device__ __forceinline__ int tr_seg_flip(int pixel) {
+  return ROWB == 256 ? 2 * (pixel & 3) : 2 * ((pixel >> 1) & 1);     // 256-byte rows: 8 segments; 128-byte rows: 4
 }
 
-// LDS tile [row][64 pixels] bf16, rows 128 bytes; 16-byte slots swizzled by row.
-__device__ __forceinline__ int swz128(int row, int slot) { return swz<8>(row, slot); }
-
 template <int TC, int TJ>
-__global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
+__global__ __launch_bounds__(kThreads, 4) void wgrad_kernel(WgradArgs a) {
   constexpr int BP = 64;                           // pixels per LDS tile
+  constexpr int RA = TC * 2, RBJ = TJ * 2;         // bytes per pixel row of the two tiles
+  constexpr int CA = RA / 16, CJ = RBJ / 16;       // 16-byte chunks per row
+  constexpr int NA = TC / 32, NB = TJ / 32;        // direct loads per thread and tile (1 KB per wave instruction)
   constexpr int WC = TC / 2, WJ = TJ / 2;
   constexpr int NI = WC / 32, NJ = WJ / 32;
-  constexpr int NBLK_A = (TC / 8) * (BP / 8), NBLK_B = (TJ / 8) * (BP / 8);
-  __shared__ __attribute__((aligned(16))) unsigned char lds[(TC + TJ) * 128];
-  unsigned char* abase = lds;
-  unsigned char* bbase = lds + TC * 128;
+  static_assert((RA == 128 || RA == 256) && RBJ == 256, "row swizzles are written for 128- and 256-byte rows");
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[BP * (RA + RBJ)];
+  unsigned char* const abase = lds;
+  unsigned char* const bbase = lds + BP * RA;
 
   const int c0 = blockIdx.x * TC, j0 = blockIdx.y * TJ;
   const int split = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wc = wave & 1, wj = wave >> 1;
   const int p_begin = split * a.pix_per_split;
   const int p_end = min(a.M, p_begin + a.pix_per_split);
   const int HW = a.Ho * a.Wo;
+  const unsigned char* zero_page = reinterpret_cast<const unsigned char*>(g_zero_page);
+
+  // ---- what each of this thread's direct loads fetches: wave instruction q = i*4 + wave fills 1 KB = 64/CA pixel rows
+  int a_pr[NA]; bool a_ok[NA]; int64_t a_off[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int pr = (i * 4 + wave) * (64 / CA) + lane / CA, pc = lane % CA;
+    const int lc = ((((pc >> 1) ^ tr_seg_flip<RA>(pr)) << 1) | (pc & 1));     // logical chunk behind physical chunk pc
+    a_pr[i] = pr;
+    a_ok[i] = c0 + lc * 8 < a.Cout;
+    a_off[i] = (int64_t)(p_begin + pr) * a.Cout + c0 + lc * 8;
+  }
+  int b_pr[NB], b_r[NB], b_s[NB], b_ci[NB], b_n[NB], b_ho[NB], b_wo[NB]; bool b_ok[NB];
+  const int step_q = BP / a.Wo, step_r = BP - step_q * a.Wo;     // 64 pixels further = step_q rows and step_r columns
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int pr = (i * 4 + wave) * (64 / CJ) + lane / CJ, pc = lane % CJ;
+    const int lc = ((((pc >> 1) ^ tr_seg_flip<RBJ>(pr)) << 1) | (pc & 1));
+    const int j = j0 + lc * 8;
+    b_pr[i] = pr;
+    b_ok[i] = j < a.Ktot;
+    const int jj = b_ok[i] ? j : 0, tap = jj / a.Cin;
+    b_ci[i] = jj - tap * a.Cin; b_r[i] = tap / a.k; b_s[i] = tap - b_r[i] * a.k;
+    const int p = p_begin + pr;
+    b_n[i] = p / HW; const int rem = p - b_n[i] * HW;
+    b_ho[i] = rem / a.Wo; b_wo[i] = rem - b_ho[i] * a.Wo;
+  }
+  unsigned char* const wave_a = abase + wave * 1024;
+  unsigned char* const wave_b = bbase + wave * 1024;
+  auto fetch = [&](int p0) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+      const bool ok = a_ok[i] && p0 + a_pr[i] < p_end;
+      const unsigned char* src = ok ? reinterpret_cast<const unsigned char*>(a.dy + a_off[i]) : zero_page;
+      __builtin_amdgcn_global_load_lds((gbl_void_ptr)src, (lds_void_ptr)(wave_a + i * 4096), 16, 0, 0);
+      a_off[i] += (int64_t)BP * a.Cout;
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int hi = b_ho[i] * a.stride + b_r[i] - a.pad, wi = b_wo[i] * a.stride + b_s[i] - a.pad;
+      const bool ok = b_ok[i] && p0 + b_pr[i] < p_end && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
+      const unsigned char* src = ok ? reinterpret_cast<const unsigned char*>(a.x + (((int64_t)b_n[i] * a.H + hi) * a.W + wi) * a.Cin + b_ci[i]) : zero_page;
+      __builtin_amdgcn_global_load_lds((gbl_void_ptr)src, (lds_void_ptr)(wave_b + i * 4096), 16, 0, 0);
+      // the same lane's pixel in the next tile
+      b_wo[i] += step_r; b_ho[i] += step_q;
+      if (b_wo[i] >= a.Wo) { b_wo[i] -= a.Wo; ++b_ho[i]; }
+      while (b_ho[i] >= a.Ho) { b_ho[i] -= a.Ho; ++b_n[i]; }
+    }
+  };
+  // ---- fragment addresses: lane = 16 g + j names pixel 8 (g/2) + j/4 (+ 4 for the second read, + 16 per k-step) and
+  // the 8-byte chunk of channels 16 (g%2) + 4 (j%4) of its 32-channel block
+  const int g = lane >> 4, jl = lane & 15;
+  const int fpix = 8 * (g >> 1) + (jl >> 2);
+  int fa_off[NI], fb_off[NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int byte = (wc * WC + i * 32 + 16 * (g & 1) + 4 * (jl & 3)) * 2;
+    fa_off[i] = fpix * RA + ((((byte >> 5) ^ tr_seg_flip<RA>(fpix)) << 5) | (byte & 31));
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int byte = (wj * WJ + j * 32 + 16 * (g & 1) + 4 * (jl & 3)) * 2;
+    fb_off[j] = BP * RA + fpix * RBJ + ((((byte >> 5) ^ tr_seg_flip<RBJ>(fpix)) << 5) | (byte & 31));
+  }
 
   f32x16 acc[NI][NJ];
 #pragma unroll
@@ -1105,88 +1176,31 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(WgradArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // The 8x8 (pixel x channel) blocks of both operands form one list, A (dy) first; a thread owns blocks
-  // tid, tid + 256, ... (a wavefront's blocks are all of one kind).  Everything about a block except the pixel
-  // position is loop invariant.
-  constexpr int NBLK = NBLK_A + NBLK_B, PER = (NBLK + kThreads - 1) / kThreads;
-  bool k_b[PER], k_ok[PER]; int k_cv[PER], k_pg[PER], k_r[PER], k_s[PER], k_ci[PER];
-#pragma unroll
-  for (int u = 0; u < PER; ++u) {
-    const int blk = tid + u * kThreads;
-    k_b[u] = blk >= NBLK_A;
-    const int lb = k_b[u] ? blk - NBLK_A : blk, nv = k_b[u] ? TJ / 8 : TC / 8;
-    k_cv[u] = lb % nv; k_pg[u] = lb / nv;
-    k_r[u] = 0; k_s[u] = 0; k_ci[u] = 0;
-    if (!k_b[u]) {
-      k_ok[u] = blk < NBLK && c0 + k_cv[u] * 8 < a.Cout;
-    } else {
-      const int j = j0 + k_cv[u] * 8;
-      k_ok[u] = blk < NBLK && j < a.Ktot;
-      const int jj = k_ok[u] ? j : 0;
-      const int tap = jj / a.Cin;
-      k_ci[u] = jj - tap * a.Cin; k_r[u] = tap / a.k; k_s[u] = tap - k_r[u] * a.k;
-    }
-  }
-  // global -> registers: the eight pixel vectors of every block of this thread for the tile at p0
-  auto load_tile = [&](int p0, uint4 (&in)[PER][8]) {
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      const int pb = p0 + k_pg[u] * 8;
-      if (!k_b[u]) {
-#pragma unroll
-        for (int qd = 0; qd < 8; ++qd) {
-          const int p = pb + qd;
-          in[u][qd] = (k_ok[u] && p < p_end) ? *reinterpret_cast<const uint4*>(a.dy + (int64_t)p * a.Cout + c0 + k_cv[u] * 8) : make_uint4(0, 0, 0, 0);
-        }
-      } else {
-        int n = pb / HW, rem = pb - n * HW;
-        int ho = rem / a.Wo, wo = rem - ho * a.Wo;
-#pragma unroll
-        for (int qd = 0; qd < 8; ++qd) {
-          const int hi = ho * a.stride + k_r[u] - a.pad, wi = wo * a.stride + k_s[u] - a.pad;
-          const bool ok = k_ok[u] && (pb + qd) < p_end && hi >= 0 && hi < a.H && wi >= 0 && wi < a.W;
-          in[u][qd] = ok ? *reinterpret_cast<const uint4*>(a.x + (((int64_t)n * a.H + hi) * a.W + wi) * a.Cin + k_ci[u]) : make_uint4(0, 0, 0, 0);
-          if (++wo == a.Wo) { wo = 0; if (++ho == a.Ho) { ho = 0; ++n; } }
-        }
-      }
-    }
-  };
-  // registers -> transpose -> LDS
-  auto stash_tile = [&](const uint4 (&in)[PER][8]) {
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      if (tid + u * kThreads < NBLK) {
-        uint4 out[8];
-        transpose8x8(in[u], out);
-        unsigned char* base = k_b[u] ? bbase : abase;
-#pragma unroll
-        for (int cc = 0; cc < 8; ++cc) *reinterpret_cast<uint4*>(base + swz128(k_cv[u] * 8 + cc, k_pg[u])) = out[cc];
-      }
-    }
-  };
-
-  uint4 regs[PER][8];
-  if (p_begin < p_end) load_tile(p_begin, regs);
   for (int p0 = p_begin; p0 < p_end; p0 += BP) {
-    stash_tile(regs);
-    __syncthreads();
-    if (p0 + BP < p_end) load_tile(p0 + BP, regs);         // the next tile's loads fly under this tile's MFMAs
-    // ---- MFMA over the 64 pixels (4 k-steps of 16)
+    fetch(p0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      Frag fa[NI], fb[NJ];
-      const int slot = kk * 2 + (lane >> 5);
+    for (int kk = 0; kk < BP / 16; ++kk) {
+      FragTr fa[NI], fb[NJ];
 #pragma unroll
-      for (int i = 0; i < NI; ++i) fa[i].u = *reinterpret_cast<const u32x4*>(abase + swz128(wc * WC + i * 32 + (lane & 31), slot));
+      for (int i = 0; i < NI; ++i)
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) fb[j].u = *reinterpret_cast<const u32x4*>(bbase + swz128(wj * WJ + j * 32 + (lane & 31), slot));
+        for (int h = 0; h < 2; ++h)
+          fa[i].h[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s16*)(lds + fa_off[i] + (kk * 16 + 4 * h) * RA));
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+          fb[j].h[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s16*)(lds + fb_off[j] + (kk * 16 + 4 * h) * RBJ));
 #pragma unroll
       for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i][j], 0, 0, 0);
     }
-    __syncthreads();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
   }
   // ---- partial tile -> workspace[split][co][j]   (lane: column j = l%32, rows co = 8g+4h+e)
   float* dst = a.ws + (int64_t)split * a.Cout * a.Ktot;
