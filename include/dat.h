@@ -252,8 +252,12 @@ dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* la
  * backward pass (sum dy, sum dy*xhat) are accumulated by the epilogue of the backward-data
  * convolution whose launch completes d(out), from the tile it is storing.  0: a pass of its own
  * reads d(out) again.  The two orders of summation agree to fp32 rounding, not bit for bit.
+ * DAT_OPT_FUSE_PGD_GRADIENT (default 1, bf16 models): the projected sign step of dat_attack /
+ * dat_attack_kl reads the bf16 input gradient the backward pass leaves in the network-input layout
+ * (only its sign enters the step; the normalisation scale 1/std is positive) instead of an fp32
+ * pixel gradient made by a pass of its own.  0: make that copy first.  Identical bits either way.
  * Returns DAT_ERR_ARG for an unknown option. */
-typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1 } dat_option;
+typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1, DAT_OPT_FUSE_PGD_GRADIENT = 2 } dat_option;
 /* (Two more switches are read from the environment by dat_model_create, because they change the
  * layer graph of a bf16 model.  DAT_KEEP_SHORTCUT_BN: the batch normalisation on a projection
  * shortcut runs as passes of its own instead of being evaluated by the last normalisation of the

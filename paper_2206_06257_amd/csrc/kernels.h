@@ -18,6 +18,10 @@ dat_status launch_attack_init(const float* x, int64_t npix, float eps, dat_init 
 // One projected sign step in place (and optionally the network input at the new point).
 dat_status launch_attack_update(const float* x, const float* G, float* delta, int64_t npix, float eps,
                                 float alpha, const NetInputDesc& in, hipStream_t st);
+// The same step with the gradient taken from the bf16 network-input gradient `gnet` (the layout `in` describes; only
+// the sign of its first three channels per pixel is used), for bf16 models: no fp32 copy of the gradient is made.
+dat_status launch_attack_update_netgrad(const float* x, const void* gnet, float* delta, int64_t npix, float eps,
+                                        float alpha, const NetInputDesc& in, hipStream_t st);
 // Network input from pixels alone (delta = nullptr) or from x + delta.
 dat_status launch_make_input(const float* x, const float* delta, int64_t npix, const NetInputDesc& in,
                              hipStream_t st);

@@ -63,6 +63,7 @@ struct dat_model {
   int normalize = 0; float mean[3] = {0, 0, 0}, inv_std[3] = {1, 1, 1};
   bool fuse_bn_apply = true;         // dat_model_set_option(DAT_OPT_FUSE_BN_INPUT_GRAD)
   bool fuse_bn_sums = true;          // dat_model_set_option(DAT_OPT_FUSE_BN_SUMS)
+  bool fuse_pgd_grad = true;         // dat_model_set_option(DAT_OPT_FUSE_PGD_GRADIENT)
   int64_t bn_sums_max_bytes = (int64_t)1 << 62;   //   ... only for d(out) tensors up to this size
   bool fuse_pool = false;            // BN + ReLU + max-pool in one forward pass, pool gradient gathered by the BN backward pass
   std::vector<Shape> tens;           // logical per-sample shapes (channels as stored)
@@ -689,6 +690,23 @@ dat_status pixel_grad(dat_model& m, int B, float* gx, hipStream_t st) {
                            n ? m.inv_std[1] : 1.0f, n ? m.inv_std[2] : 1.0f, gx, blocked ? m.H : 0, blocked ? m.W : 0, st);
 }
 
+// One projected sign step from the input gradient the backward pass has just left in m.grad[0].  bf16 models read
+// that tensor directly (only the sign of the gradient enters the step, and the normalisation scale 1/std is
+// positive); fp32 models, or DAT_OPT_FUSE_PGD_GRADIENT = 0, go through the fp32 pixel gradient.
+dat_status pgd_step(dat_model& m, const float* x, float* delta, int B, float eps, float alpha, const NetInputDesc& in, hipStream_t st) {
+  const int64_t npix = (int64_t)B * m.H * m.W;
+  const bool scales_ok = !m.normalize || (m.inv_std[0] > 0.0f && m.inv_std[1] > 0.0f && m.inv_std[2] > 0.0f);
+  if (m.dtype == DAT_BF16 && m.fuse_pgd_grad && scales_ok) {
+    // algorithmic bytes per element: x, delta, G read (12), delta written (4), bf16 input written (2)
+    DAT_PROF(m, DAT_PROF_PGD, (double)npix * 3 * 18, st, launch_attack_update_netgrad(x, m.grad[0], delta, npix, eps, alpha, in, st));
+    return DAT_OK;
+  }
+  DAT_TRY(pixel_grad(m, B, m.gx, st));
+  DAT_PROF(m, DAT_PROF_PGD, (double)npix * 3 * (m.dtype == DAT_BF16 ? 18 : 20), st,
+           launch_attack_update(x, m.gx, delta, npix, eps, alpha, in, st));
+  return DAT_OK;
+}
+
 dat_status fetch_losses(dat_model& m, int count, float* host_out, hipStream_t st) {
   DAT_HIP(hipMemcpyAsync(m.host_stage, m.loss_steps, (size_t)count * 4, hipMemcpyDeviceToHost, st));
   DAT_HIP(hipStreamSynchronize(st));
@@ -788,10 +806,7 @@ extern "C" dat_status dat_attack(dat_model* m, const float* x, const int32_t* y,
     DAT_TRY(forward(*m, B, st));
     DAT_TRY(loss_grad(*m, y, B, 1.0f, loss_per_step ? k : 0, st));
     DAT_TRY(backward(*m, B, nullptr, true, st));
-    DAT_TRY(pixel_grad(*m, B, m->gx, st));
-    // algorithmic bytes per element: x, delta, G read (12), delta written (4), bf16 input written (2)
-    DAT_PROF(*m, DAT_PROF_PGD, (double)npix * 3 * (m->dtype == DAT_BF16 ? 18 : 20), st,
-             launch_attack_update(x, m->gx, delta, npix, eps, alpha, in, st));
+    DAT_TRY(pgd_step(*m, x, delta, B, eps, alpha, in, st));
   }
   if (loss_per_step) {
     DAT_TRY(forward(*m, B, st));
@@ -856,9 +871,7 @@ extern "C" dat_status dat_attack_kl(dat_model* m, const float* x, int B, float e
     DAT_TRY(forward(*m, B, st));
     DAT_TRY(kl_grad(*m, m->z_keep, z_adv, nullptr, 0, 0.0f, B, 1.0f, loss_per_step ? k : 0, st));
     DAT_TRY(backward(*m, B, nullptr, true, st));
-    DAT_TRY(pixel_grad(*m, B, m->gx, st));
-    DAT_PROF(*m, DAT_PROF_PGD, (double)npix * 3 * (m->dtype == DAT_BF16 ? 18 : 20), st,
-             launch_attack_update(x, m->gx, delta, npix, eps, alpha, in, st));
+    DAT_TRY(pgd_step(*m, x, delta, B, eps, alpha, in, st));
   }
   if (loss_per_step) {
     DAT_TRY(forward(*m, B, st));
@@ -947,6 +960,7 @@ extern "C" dat_status dat_model_set_option(dat_model* m, dat_option opt, int val
   if (!m) return DAT_ERR_ARG;
   switch (opt) {
     case DAT_OPT_FUSE_BN_INPUT_GRAD: m->fuse_bn_apply = value != 0; return DAT_OK;
+    case DAT_OPT_FUSE_PGD_GRADIENT: m->fuse_pgd_grad = value != 0; return DAT_OK;
     case DAT_OPT_FUSE_BN_SUMS: m->fuse_bn_sums = value != 0; return DAT_OK;
   }
   return DAT_ERR_ARG;

@@ -36,7 +36,9 @@ __device__ __forceinline__ float net_value(float x, float d, bool has_delta, con
   return v;
 }
 
-// MODE 0: init, 1: update, 2: input only.  A workgroup owns 1024 consecutive pixels = 768 float4 of each
+// MODE 0: init, 1: update, 2: input only, 3: update with the gradient read from the bf16 network-input gradient
+// (`gnet`, laid out like the network input: one 16-byte vector per pixel) instead of an fp32 copy -- only its sign
+// enters the step, and the positive normalisation scale does not change it.  A workgroup owns 1024 consecutive pixels = 768 float4 of each
 // fp32 stream; thread t touches float4 number j*256 + t (j = 0..2) of that chunk, so every load and
 // store of a wavefront covers 1 KB of consecutive memory.  The update itself is elementwise.  The bf16
 // network input is stored per pixel (one 16-byte vector of 8 channels), so the rounded values are
@@ -68,13 +70,47 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
                                                           const float* __restrict__ given,
                                                           float* __restrict__ delta, int64_t npix,
                                                           float eps, float alpha, int init_mode,
-                                                          uint64_t seed, InArgs in) {
+                                                          uint64_t seed, InArgs in, const void* __restrict__ gnet) {
   __shared__ __attribute__((aligned(16))) uint16_t stage[kPixPerBlock * 3];
+  __shared__ __attribute__((aligned(16))) uint16_t gstage[MODE == 3 ? kPixPerBlock * 3 : 8];
   const int tid = threadIdx.x;
   const int64_t n = npix * 3;
   const int64_t ebase = (int64_t)blockIdx.x * (kPixPerBlock * 3);
   const bool has_delta = MODE != 2 || delta != nullptr;
   const bool to_lds = in.ptr && in.bf16;
+  // where this thread's pixels 4t .. 4t+3 live in the per-pixel tensors (network input and its gradient)
+  const int64_t p0 = (int64_t)blockIdx.x * kPixPerBlock + 4 * tid;
+  int64_t slot[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    slot[p] = p0 + p;
+    if (in.bw) {   // 2x2 pixel blocks: pixel (n,h,w) -> block (n, h/2, w/2), position (h%2)*2 + w%2
+      const uint32_t pix = (uint32_t)slot[p], ww = pix % (uint32_t)in.bw, hn = pix / (uint32_t)in.bw;
+      const uint32_t h = hn % (uint32_t)in.bh, nimg = hn / (uint32_t)in.bh;
+      slot[p] = ((int64_t)(nimg * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1) + (ww >> 1)) * 4 + (h & 1u) * 2 + (ww & 1u);
+    }
+  }
+  if (MODE == 3) {
+    // the three gradient channels of each pixel, regrouped through LDS into the element order of the fp32 streams
+    const uint4* gsrc = reinterpret_cast<const uint4*>(gnet);
+    uint32_t gw[4][2];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      gw[p][0] = 0u; gw[p][1] = 0u;
+      if (p0 + p < npix) { const uint2 v = *reinterpret_cast<const uint2*>(gsrc + slot[p]); gw[p][0] = v.x; gw[p][1] = v.y; }
+    }
+    // halfwords 3p .. 3p+2 of the thread's 12: (c0 c1) (c2 c0') (c1' c2') ...
+    uint32_t o[6];
+    o[0] = gw[0][0];
+    o[1] = (gw[0][1] & 0xffffu) | (gw[1][0] << 16);
+    o[2] = (gw[1][0] >> 16) | (gw[1][1] << 16);
+    o[3] = gw[2][0];
+    o[4] = (gw[2][1] & 0xffffu) | (gw[3][0] << 16);
+    o[5] = (gw[3][0] >> 16) | (gw[3][1] << 16);
+    uint2* d2 = reinterpret_cast<uint2*>(&gstage[12 * tid]);
+    d2[0] = make_uint2(o[0], o[1]); d2[1] = make_uint2(o[2], o[3]); d2[2] = make_uint2(o[4], o[5]);
+    __syncthreads();
+  }
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
     const int f = j * kThreads + tid;               // float4 number inside the chunk
@@ -107,6 +143,12 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
         load4(G, e, n, gv);
 #pragma unroll
         for (int k = 0; k < 4; ++k) dv[k] = box_clip(sign_step(dv[k], gv[k], eps, alpha), xv[k]);
+      } else if (MODE == 3) {
+        load4(delta, e, n, dv);
+        const uint2 gp = *reinterpret_cast<const uint2*>(&gstage[4 * f]);
+        const float gv[4] = {__uint_as_float(gp.x << 16), __uint_as_float(gp.x & 0xffff0000u), __uint_as_float(gp.y << 16), __uint_as_float(gp.y & 0xffff0000u)};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dv[k] = box_clip(sign_step(dv[k], gv[k], eps, alpha), xv[k]);
       } else {
         if (delta) load4(delta, e, n, dv);
         else {
@@ -132,7 +174,6 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
   }
   if (!to_lds) return;
   __syncthreads();
-  const int64_t p0 = (int64_t)blockIdx.x * kPixPerBlock + 4 * tid;
   if (p0 >= npix) return;
   const int np = (int)min((int64_t)4, npix - p0);
   uint32_t w[6];                                     // 12 bf16 = pixels 4t .. 4t+3
@@ -152,13 +193,7 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
     else if (p == 2) { o.x = w[3]; o.y = w[4] & 0xffffu; }
     else { o.x = (w[4] >> 16) | (w[5] << 16); o.y = w[5] >> 16; }
     o.z = 0u; o.w = 0u;
-    int64_t slot = p0 + p;
-    if (in.bw) {   // 2x2 pixel blocks: pixel (n,h,w) -> block (n, h/2, w/2), position (h%2)*2 + w%2
-      const uint32_t pix = (uint32_t)slot, ww = pix % (uint32_t)in.bw, hn = pix / (uint32_t)in.bw;
-      const uint32_t h = hn % (uint32_t)in.bh, nimg = hn / (uint32_t)in.bh;
-      slot = ((int64_t)(nimg * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1) + (ww >> 1)) * 4 + (h & 1u) * 2 + (ww & 1u);
-    }
-    dst[slot] = o;
+    dst[slot[p]] = o;
   }
 }
 
@@ -181,7 +216,7 @@ dat_status launch_attack_init(const float* x, int64_t npix, float eps, dat_init 
                               const NetInputDesc& in, hipStream_t st) {
   if (npix == 0) return DAT_OK;
   hipLaunchKernelGGL(attack_kernel<0>, dim3(grid_for(npix)), dim3(kThreads), 0, st, x, (const float*)nullptr,
-                     init.delta0, delta, npix, eps, 0.0f, (int)init.mode, init.seed, pack(in));
+                     init.delta0, delta, npix, eps, 0.0f, (int)init.mode, init.seed, pack(in), (const void*)nullptr);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -190,7 +225,17 @@ dat_status launch_attack_update(const float* x, const float* G, float* delta, in
                                 float alpha, const NetInputDesc& in, hipStream_t st) {
   if (npix == 0) return DAT_OK;
   hipLaunchKernelGGL(attack_kernel<1>, dim3(grid_for(npix)), dim3(kThreads), 0, st, x, G, (const float*)nullptr,
-                     delta, npix, eps, alpha, 0, (uint64_t)0, pack(in));
+                     delta, npix, eps, alpha, 0, (uint64_t)0, pack(in), (const void*)nullptr);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status launch_attack_update_netgrad(const float* x, const void* gnet, float* delta, int64_t npix, float eps,
+                                        float alpha, const NetInputDesc& in, hipStream_t st) {
+  if (npix == 0) return DAT_OK;
+  if (!in.ptr || !in.bf16 || !gnet) return DAT_ERR_ARG;
+  hipLaunchKernelGGL(attack_kernel<3>, dim3(grid_for(npix)), dim3(kThreads), 0, st, x, (const float*)nullptr, (const float*)nullptr,
+                     delta, npix, eps, alpha, 0, (uint64_t)0, pack(in), gnet);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -199,7 +244,7 @@ dat_status launch_make_input(const float* x, const float* delta, int64_t npix, c
                              hipStream_t st) {
   if (npix == 0) return DAT_OK;
   hipLaunchKernelGGL(attack_kernel<2>, dim3(grid_for(npix)), dim3(kThreads), 0, st, x, (const float*)nullptr,
-                     (const float*)nullptr, const_cast<float*>(delta), npix, 0.0f, 0.0f, 0, (uint64_t)0, pack(in));
+                     (const float*)nullptr, const_cast<float*>(delta), npix, 0.0f, 0.0f, 0, (uint64_t)0, pack(in), (const void*)nullptr);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
