@@ -207,7 +207,11 @@ def main():
         pg = prof["pgd"]
         if pg[0] > 0:
             out["pgd_update"] = {"GBs": pg[2] / (pg[0] * 1e-3) / 1e9, "frac_hbm": pg[2] / (pg[0] * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                 "bytes_per_element": 18}
+                                 "bytes_per_element": 18,
+                                 "moved_GBs": pg[2] / 18.0 * (12.0 + 32.0 / 3.0) / (pg[0] * 1e-3) / 1e9,
+                                 "note": "one launch per iteration; it reads the bf16 input gradient and writes the bf16 network input as "
+                                         "16-byte vectors per pixel (3 of 8 channels used), so it moves 22.7 bytes per element for the 18 "
+                                         "algorithmic ones"}
         total_flops = sum(prof[k][2] for k in ("conv_fwd", "conv_bwd_data", "conv_bwd_data_bn", "conv_wgrad")) / args.steps
         out["roofline"]["measured_over"] = "%d further steps of the same work with a hipEvent pair around every launch (%.1f ms/step with events)" % (args.steps, ms_per_step_events)
         out["step_conv_TFLOPs"] = total_flops / 1e12
