@@ -27,6 +27,8 @@ SHAPES = [
     (2, 15, 13, 8, 64, 7, 2, 3),       # stem on odd sizes
     (2, 7, 9, 64, 128, 1, 2, 0),       # 1x1 stride 2: three parity classes receive zeros
     (3, 16, 16, 128, 128, 3, 1, 1),    # full 128x128 tiles
+    (130, 2, 2, 64, 64, 1, 2, 0),      # 1x1 output maps: every pixel of a 64-pixel tile is another image
+    (70, 3, 3, 16, 40, 3, 1, 1),       # output rows shorter than a tile: several row and image wraps per tile step
     (32, 64, 64, 8, 128, 1, 1, 0),     # enough pixel tiles for the 128x256 configuration
     (32, 64, 64, 8, 64, 3, 1, 1),      # ... and the 64x256 one
     (33, 63, 65, 16, 136, 3, 1, 1),    # wide tiles with ragged pixel and channel tails
