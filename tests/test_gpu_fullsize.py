@@ -128,6 +128,28 @@ def test_ring_kernel_gives_the_bits_of_the_single_stage_kernel(dat, layer, monke
     assert float(y.float().abs().max()) > 0 and float(dx.float().abs().max()) > 0
 
 
+def test_network_with_ring_kernel_agrees_with_single_stage_kernels(dat, monkeypatch):
+    """ResNet-50 224 at batch 256: with the multi-stage kernel on its layers the convolution outputs are the same
+    bits, only the batch-norm partial sums are grouped by 256 pixels instead of 128.  Logits and loss of a forward
+    pass therefore agree to the reference's own bf16 perturbation floor (a wrong slab count or a wrong
+    512-thread epilogue would move them by O(1))."""
+    model = dat.Model(dat.ARCH_RESNET50, dat.BF16, B, 224, 224, 1000, MEAN, STD)
+    model.set_params(syn.he_normal_params(7, model.offsets, model.fan_in, model.kind))
+    xd = torch.from_numpy(syn.images(7, B, 224, 224)).cuda()
+    yd = torch.from_numpy(syn.labels(7, B, 1000)).cuda()
+    monkeypatch.delenv("DAT_NO_RING_KERNEL", raising=False)
+    gx, logits, loss = model.input_grad(xd, yd)
+    monkeypatch.setenv("DAT_NO_RING_KERNEL", "1")
+    gx0, logits0, loss0 = model.input_grad(xd, yd)
+    a, b = logits.cpu().numpy().astype(np.float64), logits0.cpu().numpy().astype(np.float64)
+    rel = np.linalg.norm(a - b) / np.linalg.norm(b)
+    print("ring vs single-stage: logits rel %.3e, loss %.6f vs %.6f" % (rel, loss, loss0))
+    assert np.isfinite(a).all() and rel < 2e-2 and abs(loss - loss0) < 2e-2 * abs(loss0)
+    ga, gb = gx.cpu().numpy().astype(np.float64), gx0.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(ga - gb) / np.linalg.norm(gb) < 0.5      # bf16 gradients of a random-init net: same direction
+    model.close()
+
+
 @pytest.mark.parametrize("B,eps,alpha,K", [
     (256, 4 / 255, 1 / 255, 3),          # config 5
     (85, 2 / 255, 1.25 / 255, 4),        # the paper's own ImageNet shape: 85 images per GPU, PGD-4 (odd batch: tile tails)
