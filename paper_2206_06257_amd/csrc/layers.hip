@@ -18,6 +18,11 @@ constexpr int kMaxApplySlabs = 8192;  // slabs of an elementwise pass
 
 template <typename T> struct V8;
 template <> struct V8<float> {
+  struct Raw { float4 a, b; };
+  static __device__ __forceinline__ Raw load_raw_nt(const float* p) { return Raw{reinterpret_cast<const float4*>(p)[0], reinterpret_cast<const float4*>(p)[1]}; }
+  static __device__ __forceinline__ void unpack(const Raw& r, float v[8]) {
+    v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w; v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+  }
   static __device__ __forceinline__ void load_nt(const float* p, float v[8]) { load(p, v); }
   static __device__ __forceinline__ void load(const float* p, float v[8]) {
     const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
@@ -29,6 +34,14 @@ template <> struct V8<float> {
   }
 };
 template <> struct V8<bf16_t> {
+  // the 16 bytes as loaded (streaming read), unpacked only where they are used: four registers in flight, not eight
+  typedef uint32_t Raw __attribute__((ext_vector_type(4)));
+  static __device__ __forceinline__ Raw load_raw_nt(const bf16_t* p) { return __builtin_nontemporal_load(reinterpret_cast<const Raw*>(p)); }
+  static __device__ __forceinline__ void unpack(const Raw& a, float v[8]) {
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { v[2 * j] = __uint_as_float(w[j] << 16); v[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u); }
+  }
   // streaming read: the line is not needed again soon (leaves the caches to the tensors that are)
   static __device__ __forceinline__ void load_nt(const bf16_t* p, float v[8]) {
     typedef uint32_t u4 __attribute__((ext_vector_type(4)));
@@ -453,7 +466,11 @@ __global__ __launch_bounds__(kT) void slab_fold_kernel(const float* __restrict__
   out[(int64_t)blockIdx.x * W + col] = t;
 }
 
-template <typename T>
+// RES: 0 no residual, 1 a stored residual, 2 the residual is the INPUT of a second normalisation without activation
+// (the one on a projection shortcut), normalised here and rounded to the storage type -- exactly what a pass of its
+// own would have stored.  (Compile-time, so that the common cases do not carry the second set of per-channel constants
+// in registers: occupancy is what keeps this pass at the streaming rate.)
+template <typename T, int RES>
 __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, const T* __restrict__ res,
                                                        T* __restrict__ out, uint8_t* __restrict__ mask, int64_t rows, int C, int tpr, int rpp,
                                                        int64_t rows_per_slab,
@@ -466,39 +483,38 @@ __global__ __launch_bounds__(kT) void bnact_fwd_kernel(const T* __restrict__ x, 
   const int c0 = cv * 8;
   float mu[8], rs[8], ga[8], be[8];
   load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(beta + c0, be);
-  // rmean != nullptr: `res` is the input of a second normalisation (no activation) whose output is the residual;
-  // it is normalised here and rounded to the storage type, exactly what a pass of its own would have stored
-  float rmu[8], rrs[8], rga[8], rbe[8];
-  if (rmean) { load8f(rmean + c0, rmu); load8f(rrstd + c0, rrs); load8f(rgamma + c0, rga); load8f(rbeta + c0, rbe); }
+  float rmu[RES == 2 ? 8 : 1], rrs[RES == 2 ? 8 : 1], rga[RES == 2 ? 8 : 1], rbe[RES == 2 ? 8 : 1];
+  if (RES == 2) { load8f(rmean + c0, rmu); load8f(rrstd + c0, rrs); load8f(rgamma + c0, rga); load8f(rbeta + c0, rbe); }
   // slabs are walked from the end of the tensor: the rows the producing kernel wrote (or the
   // preceding reduction read) last are still in the 256 MB memory-side cache
   const int64_t r0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * rows_per_slab;
   const int64_t r1 = min(rows, r0 + rows_per_slab);
-  constexpr int U = 4;
+  // rows in flight per thread: with a residual stream one (83 registers, five waves per SIMD: 5.8 TB/s on the largest
+  // tensors, against 4.6 TB/s with four rows in flight at two waves per SIMD), without one four
+  constexpr int U = RES ? 1 : 4;
   for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
-    float xv[U][8], rv[U][8];
+    typename V8<T>::Raw xr[U], rv[RES ? U : 1];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = rb + (int64_t)u * rpp;
-      if (r < r1) { V8<T>::load_nt(x + r * C + c0, xv[u]); if (res) V8<T>::load_nt(res + r * C + c0, rv[u]); }
+      if (r < r1) { xr[u] = V8<T>::load_raw_nt(x + r * C + c0); if (RES) rv[u] = V8<T>::load_raw_nt(res + r * C + c0); }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = rb + (int64_t)u * rpp;
       if (r < r1) {
-        float o[8];
+        float xv[8], rj[8], o[8];
+        V8<T>::unpack(xr[u], xv);
+        if (RES) V8<T>::unpack(rv[u], rj);
         uint32_t bits = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          o[j] = ga[j] * ((xv[u][j] - mu[j]) * rs[j]) + be[j];
-          if (res) {
-            float rj = rv[u][j];
-            if (rmean) {
-              rj = rga[j] * ((rj - rmu[j]) * rrs[j]) + rbe[j];
-              if (sizeof(T) == 2) rj = bf2f(f2bf(rj));
-            }
-            o[j] += rj;
+          o[j] = ga[j] * ((xv[j] - mu[j]) * rs[j]) + be[j];
+          if (RES == 2) {
+            rj[j] = rga[j] * ((rj[j] - rmu[j]) * rrs[j]) + rbe[j];
+            if (sizeof(T) == 2) rj[j] = bf2f(f2bf(rj[j]));
           }
+          if (RES) o[j] += rj[j];
           if (relu) o[j] = o[j] > 0.f ? o[j] : 0.f;
           bits |= (o[j] > 0.f ? 1u : 0u) << j;
         }
@@ -564,13 +580,17 @@ __global__ __launch_bounds__(kT) void bnact_pool_fwd_kernel(const T* __restrict_
   *reinterpret_cast<uint2*>(arg + v * 8) = pk;
 }
 
-template <typename T>
+// GATE: how d(out) is gated by the activation: 0 not at all, 1 by the one-bit mask, 2 by the stored output (> 0).
+// DXACC: add to the stored dx.  DRES: 0 no residual gradient, 1 written, 2 added to the stored one.
+// (Compile-time, so that every case carries only the streams it reads in registers: occupancy is what keeps this
+// pass at the streaming rate.)
+template <typename T, int GATE, bool DXACC, int DRES>
 __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ out,
                                                              const uint8_t* __restrict__ mask,
                                                              const T* __restrict__ dout, T* __restrict__ dx,
-                                                             int dx_acc, T* __restrict__ dres, int dres_acc,
+                                                             T* __restrict__ dres,
                                                              int64_t rows, int C, int tpr, int rpp, int64_t rows_per_slab,
-                                                             const float* __restrict__ tab, int relu) {
+                                                             const float* __restrict__ tab) {
   const int tid = threadIdx.x, rr = tid / tpr, cv = tid % tpr;
   if (rr >= rpp) return;
   const int c0 = cv * 8;
@@ -581,8 +601,9 @@ __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict
   const int64_t r0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * rows_per_slab;
   const int64_t r1 = min(rows, r0 + rows_per_slab);
   constexpr int U = 2;
+  typedef typename V8<T>::Raw Raw;
   for (int64_t rb = r0 + rr; rb < r1; rb += (int64_t)rpp * U) {
-    float g[U][8], xv[U][8], ov[U][8], od[U][8], orr[U][8];
+    Raw gr[U], xr[U], ovr[GATE == 2 ? U : 1], odr[DXACC ? U : 1], orr[DRES == 2 ? U : 1];
     uint32_t mk[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -590,10 +611,11 @@ __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict
       mk[u] = 0xffu;
       if (r < r1) {
         const int64_t o = r * C + c0;
-        V8<T>::load(dout + o, g[u]); V8<T>::load(x + o, xv[u]);
-        if (relu) { if (mask) mk[u] = mask[o >> 3]; else V8<T>::load(out + o, ov[u]); }
-        if (dx_acc) V8<T>::load(dx + o, od[u]);
-        if (dres && dres_acc) V8<T>::load(dres + o, orr[u]);
+        gr[u] = V8<T>::load_raw_nt(dout + o); xr[u] = V8<T>::load_raw_nt(x + o);
+        if (GATE == 1) mk[u] = mask[o >> 3];
+        if (GATE == 2) ovr[u] = V8<T>::load_raw_nt(out + o);
+        if (DXACC) odr[u] = V8<T>::load_raw_nt(dx + o);
+        if (DRES == 2) orr[u] = V8<T>::load_raw_nt(dres + o);
       }
     }
 #pragma unroll
@@ -601,25 +623,36 @@ __global__ __launch_bounds__(kT) void bnact_bwd_apply_kernel(const T* __restrict
       const int64_t r = rb + (int64_t)u * rpp;
       if (r < r1) {
         const int64_t o = r * C + c0;
-        float q[8];
-        if (relu) {
-          if (mask) {
+        float g[8], xv[8], q[8];
+        V8<T>::unpack(gr[u], g); V8<T>::unpack(xr[u], xv);
+        if (GATE == 1) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) if (!((mk[u] >> j) & 1u)) g[u][j] = 0.f;
+          for (int j = 0; j < 8; ++j) if (!((mk[u] >> j) & 1u)) g[j] = 0.f;
+        }
+        if (GATE == 2) {
+          float ov[8];
+          V8<T>::unpack(ovr[u], ov);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) if (!(ov[j] > 0.f)) g[j] = 0.f;
+        }
+        if (DRES) {
+          if (DRES == 2) {
+            float od[8];
+            V8<T>::unpack(orr[u], od);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[j] = od[j] + g[j];
           } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) if (!(ov[u][j] > 0.f)) g[u][j] = 0.f;
+            for (int j = 0; j < 8; ++j) q[j] = g[j];
           }
-        }
-        if (dres) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) q[j] = dres_acc ? orr[u][j] + g[u][j] : g[u][j];
           V8<T>::store(dres + o, q);
         }
+        float od[8];
+        if (DXACC) V8<T>::unpack(odr[u], od);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          q[j] = bn_input_grad(g[u][j], xv[u][j], ka[j], kp[j], kq[j], mu[j]);
-          if (dx_acc) q[j] += od[u][j];
+          q[j] = bn_input_grad(g[j], xv[j], ka[j], kp[j], kq[j], mu[j]);
+          if (DXACC) q[j] += od[j];
         }
         V8<T>::store(dx + o, q);
       }
@@ -1044,9 +1077,12 @@ dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mas
   const SlabPlan p = plan_slabs(rows, C, kMaxApplySlabs);
   const float* rm = res_bn ? res_bn->mean : nullptr; const float* rr = res_bn ? res_bn->rstd : nullptr;
   const float* rg = res_bn ? res_bn->gamma : nullptr; const float* rb = res_bn ? res_bn->beta : nullptr;
+#define DAT_BNACT_FWD(T, RES) hipLaunchKernelGGL((bnact_fwd_kernel<T, RES>), dim3(p.nslabs), dim3(kT), 0, st, (const T*)x, (const T*)res, (T*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu, rm, rr, rg, rb)
+  const int rk = res_bn ? 2 : res ? 1 : 0;
   DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_fwd_kernel<float>, dim3(p.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)res, (float*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu, rm, rr, rg, rb),
-    hipLaunchKernelGGL(bnact_fwd_kernel<bf16_t>, dim3(p.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)res, (bf16_t*)out, mask, rows, C, p.tpr, p.rpp, p.rows_per_slab, mean, rstd, gamma, beta, relu, rm, rr, rg, rb));
+    { if (rk == 2) DAT_BNACT_FWD(float, 2); else if (rk == 1) DAT_BNACT_FWD(float, 1); else DAT_BNACT_FWD(float, 0); },
+    { if (rk == 2) DAT_BNACT_FWD(bf16_t, 2); else if (rk == 1) DAT_BNACT_FWD(bf16_t, 1); else DAT_BNACT_FWD(bf16_t, 0); });
+#undef DAT_BNACT_FWD
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -1094,9 +1130,16 @@ dat_status bn_backward_apply(const void* x, const void* out, const uint8_t* mask
                              bool dres_accumulate, int dtype, int64_t rows, int C, const float* tab, int relu, hipStream_t st) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
   const SlabPlan q = plan_slabs(rows, C, kMaxApplySlabs);
-  DAT_BY_DTYPE(dtype,
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<float>, dim3(q.nslabs), dim3(kT), 0, st, (const float*)x, (const float*)out, mask, (const float*)dout, (float*)dx, (int)dx_accumulate, (float*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, tab, relu),
-    hipLaunchKernelGGL(bnact_bwd_apply_kernel<bf16_t>, dim3(q.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)out, mask, (const bf16_t*)dout, (bf16_t*)dx, (int)dx_accumulate, (bf16_t*)dres, (int)dres_accumulate, rows, C, q.tpr, q.rpp, q.rows_per_slab, tab, relu));
+  const int gate = !relu ? 0 : mask ? 1 : 2, dr = !dres ? 0 : dres_accumulate ? 2 : 1;
+#define DAT_BWD_APPLY(T, G, A, R) hipLaunchKernelGGL((bnact_bwd_apply_kernel<T, G, A, R>), dim3(q.nslabs), dim3(kT), 0, st, (const T*)x, (const T*)out, mask, (const T*)dout, (T*)dx, (T*)dres, rows, C, q.tpr, q.rpp, q.rows_per_slab, tab)
+#define DAT_BWD_APPLY_R(T, G, A) do { if (dr == 0) DAT_BWD_APPLY(T, G, A, 0); else if (dr == 1) DAT_BWD_APPLY(T, G, A, 1); else DAT_BWD_APPLY(T, G, A, 2); } while (0)
+#define DAT_BWD_APPLY_A(T, G) do { if (dx_accumulate) DAT_BWD_APPLY_R(T, G, true); else DAT_BWD_APPLY_R(T, G, false); } while (0)
+#define DAT_BWD_APPLY_G(T) do { if (gate == 0) DAT_BWD_APPLY_A(T, 0); else if (gate == 1) DAT_BWD_APPLY_A(T, 1); else DAT_BWD_APPLY_A(T, 2); } while (0)
+  DAT_BY_DTYPE(dtype, DAT_BWD_APPLY_G(float), DAT_BWD_APPLY_G(bf16_t));
+#undef DAT_BWD_APPLY_G
+#undef DAT_BWD_APPLY_A
+#undef DAT_BWD_APPLY_R
+#undef DAT_BWD_APPLY
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
