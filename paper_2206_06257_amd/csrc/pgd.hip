@@ -90,6 +90,16 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
       slot[p] = ((int64_t)(nimg * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1) + (ww >> 1)) * 4 + (h & 1u) * 2 + (ww & 1u);
     }
   }
+  // every global load of the update is issued before the first barrier (the pixels and the perturbation below, the
+  // gradient here): one memory round trip per workgroup instead of two
+  float xs[3][4], ds[3][4];
+  if (MODE == 1 || MODE == 3) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const int64_t e = ebase + 4 * (int64_t)(j * kThreads + tid);
+      if (e < n) { load4(x, e, n, xs[j]); load4(delta, e, n, ds[j]); }
+    }
+  }
   if (MODE == 3) {
     // the three gradient channels of each pixel, regrouped through LDS into the element order of the fp32 streams
     const uint4* gsrc = reinterpret_cast<const uint4*>(gnet);
@@ -117,7 +127,12 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
     const int64_t e = ebase + 4 * (int64_t)f;
     float xv[4], dv[4];
     if (e < n) {
-      load4(x, e, n, xv);
+      if (MODE == 1 || MODE == 3) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { xv[k] = xs[j][k]; dv[k] = ds[j][k]; }
+      } else {
+        load4(x, e, n, xv);
+      }
       if (MODE == 0) {
         if (init_mode == DAT_INIT_UNIFORM) {
           const PhiloxWords w = philox_block((uint64_t)(e >> 2), seed, kStreamInit);
@@ -139,12 +154,10 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
         for (int k = 0; k < 4; ++k) dv[k] = box_clip(dv[k], xv[k]);
       } else if (MODE == 1) {
         float gv[4];
-        load4(delta, e, n, dv);
         load4(G, e, n, gv);
 #pragma unroll
         for (int k = 0; k < 4; ++k) dv[k] = box_clip(sign_step(dv[k], gv[k], eps, alpha), xv[k]);
       } else if (MODE == 3) {
-        load4(delta, e, n, dv);
         const uint2 gp = *reinterpret_cast<const uint2*>(&gstage[4 * f]);
         const float gv[4] = {__uint_as_float(gp.x << 16), __uint_as_float(gp.x & 0xffff0000u), __uint_as_float(gp.y << 16), __uint_as_float(gp.y & 0xffff0000u)};
 #pragma unroll
