@@ -214,10 +214,10 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
             const float v0 = ((mk[u] >> (2 * j)) & 1u) ? __uint_as_float(w[j] << 16) : 0.f;
             const float v1 = ((mk[u] >> (2 * j + 1)) & 1u) ? __uint_as_float(w[j] & 0xffff0000u) : 0.f;
             s1[2 * j] += v0; s1[2 * j + 1] += v1;
-            s2[2 * j] += v0 * ((__uint_as_float(xw[j] << 16) - mu[2 * j]) * rs[2 * j]);
-            s2[2 * j + 1] += v1 * ((__uint_as_float(xw[j] & 0xffff0000u) - mu[2 * j + 1]) * rs[2 * j + 1]);
-            s3[2 * j] += v0 * ((__uint_as_float(yw[j] << 16) - mu2[2 * j]) * rs2[2 * j]);
-            s3[2 * j + 1] += v1 * ((__uint_as_float(yw[j] & 0xffff0000u) - mu2[2 * j + 1]) * rs2[2 * j + 1]);
+            s2[2 * j] = __builtin_fmaf(v0, (__uint_as_float(xw[j] << 16) - mu[2 * j]) * rs[2 * j], s2[2 * j]);
+            s2[2 * j + 1] = __builtin_fmaf(v1, (__uint_as_float(xw[j] & 0xffff0000u) - mu[2 * j + 1]) * rs[2 * j + 1], s2[2 * j + 1]);
+            s3[2 * j] = __builtin_fmaf(v0, (__uint_as_float(yw[j] << 16) - mu2[2 * j]) * rs2[2 * j], s3[2 * j]);
+            s3[2 * j + 1] = __builtin_fmaf(v1, (__uint_as_float(yw[j] & 0xffff0000u) - mu2[2 * j + 1]) * rs2[2 * j + 1], s3[2 * j + 1]);
           }
         }
       }
@@ -255,8 +255,8 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
           const float v0 = ((mk[u] >> (2 * j)) & 1u) ? __uint_as_float(w[j] << 16) : 0.f;
           const float v1 = ((mk[u] >> (2 * j + 1)) & 1u) ? __uint_as_float(w[j] & 0xffff0000u) : 0.f;
           const float x0 = __uint_as_float(xw[j] << 16), x1 = __uint_as_float(xw[j] & 0xffff0000u);
-          s1[2 * j] += v0; s2[2 * j] += v0 * ((x0 - mu[2 * j]) * rs[2 * j]);
-          s1[2 * j + 1] += v1; s2[2 * j + 1] += v1 * ((x1 - mu[2 * j + 1]) * rs[2 * j + 1]);
+          s1[2 * j] += v0; s2[2 * j] = __builtin_fmaf(v0, (x0 - mu[2 * j]) * rs[2 * j], s2[2 * j]);
+          s1[2 * j + 1] += v1; s2[2 * j + 1] = __builtin_fmaf(v1, (x1 - mu[2 * j + 1]) * rs[2 * j + 1], s2[2 * j + 1]);
         }
       }
     }
@@ -272,7 +272,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const float v0 = __uint_as_float(w[j] << 16), v1 = __uint_as_float(w[j] & 0xffff0000u);
-          s1[2 * j] += v0; s2[2 * j] += v0 * v0; s1[2 * j + 1] += v1; s2[2 * j + 1] += v1 * v1;
+          s1[2 * j] += v0; s2[2 * j] = __builtin_fmaf(v0, v0, s2[2 * j]); s1[2 * j + 1] += v1; s2[2 * j + 1] = __builtin_fmaf(v1, v1, s2[2 * j + 1]);
         }
       }
     }
