@@ -256,8 +256,15 @@ dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* la
  * dat_attack_kl reads the bf16 input gradient the backward pass leaves in the network-input layout
  * (only its sign enters the step; the normalisation scale 1/std is positive) instead of an fp32
  * pixel gradient made by a pass of its own.  0: make that copy first.  Identical bits either way.
+ * DAT_OPT_SPARSE_SHORTCUT_GRADIENT (default 1, bf16 models): the input gradient of a strided 1x1
+ * projection shortcut is non-zero at the pixels the projection reads only (even row, even column).
+ * Its backward-data pass writes just those, and the backward-data pass of the block's first
+ * convolution, which adds its own part to the same tensor, reads the stored values there and takes
+ * zero elsewhere.  0: the projection's pass also writes the zeros and the other pass reads them
+ * back.  Identical bits either way.
  * Returns DAT_ERR_ARG for an unknown option. */
-typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1, DAT_OPT_FUSE_PGD_GRADIENT = 2 } dat_option;
+typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1, DAT_OPT_FUSE_PGD_GRADIENT = 2,
+               DAT_OPT_SPARSE_SHORTCUT_GRADIENT = 3 } dat_option;
 /* (Two more switches are read from the environment by dat_model_create, because they change the
  * layer graph of a bf16 model.  DAT_KEEP_SHORTCUT_BN: the batch normalisation on a projection
  * shortcut runs as passes of its own instead of being evaluated by the last normalisation of the

@@ -71,6 +71,7 @@ struct IgemmArgs {
   const bf16_t* wt;     // [Cout][KH*KW*Cin]
   const bf16_t* res;    // optional [M][Cout] added before rounding
   const uint8_t* res_mask;   // optional: bit j of byte e/8 gates element e of `res` (a ReLU mask: res*mask is added)
+  int res_even_only;         // `res` holds values only at pixels with even row and even column (ostep 1); the rest counts as zero
   bf16_t* out;          // [M][Cout], M = B*Hout*Wout
   int B, Hin, Win, Cin, Hout, Wout, Cout;   // Hout x Wout = grid of output pixels this launch computes
   int KH, KW, ostride, pad_h, pad_w;
@@ -138,7 +139,9 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
     for (int u = 0; u < TP / RPP; ++u) {
       const int m = m0 + pr0 + u * RPP;
       rv[u] = make_uint4(0u, 0u, 0u, 0u);
-      if (m < a.M && ch < a.Cout) {
+      bool take = m < a.M && ch < a.Cout;
+      if (a.res_even_only && take) { const int q = m / a.Wout; take = !(((m - q * a.Wout) | (q % a.Hout)) & 1); }
+      if (take) {
         const int64_t e = out_row(a, m) * a.Cout + ch;
         rv[u] = *reinterpret_cast<const uint4*>(a.res + e);
         if (a.res_mask) {
@@ -1303,7 +1306,7 @@ int conv_stat_slabs(int64_t rows, int stride) {
 dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
   a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
-  a.in = x; a.wt = w; a.res = res; a.res_mask = nullptr; a.out = y;
+  a.in = x; a.wt = w; a.res = res; a.res_mask = nullptr; a.res_even_only = 0; a.out = y;
   a.B = g.B; a.Hin = g.H; a.Win = g.W; a.Cin = g.Cin; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
   a.KH = g.k; a.KW = g.k; a.ostride = g.stride; a.pad_h = a.pad_w = g.pad;
   a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
@@ -1312,6 +1315,8 @@ dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res
   if (stats) stats->nslabs = (a.M + pixel_tile(a) - 1) / pixel_tile(a);
   return run_igemm(a, st);
 }
+
+bool conv_mfma_sparse_writer_ok(const ConvGeom& g) { return g.k == 1 && g.stride == 2 && g.pad == 0; }
 
 bool conv_mfma_bn_operand_ok(const ConvGeom& g) {
   // The convolution's output channels are the contraction of its backward-data pass, its input channels the
@@ -1323,13 +1328,16 @@ bool conv_mfma_bn_operand_ok(const ConvGeom& g) {
 }
 
 dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st,
-                                   const bf16_t* masked_res, const uint8_t* res_mask, const BnOperand* bn) {
+                                   const bf16_t* masked_res, const uint8_t* res_mask, const BnOperand* bn, int sparse) {
   if (accumulate && masked_res) return DAT_ERR_ARG;
+  if (sparse == 1 && (!conv_mfma_sparse_writer_ok(g) || accumulate || masked_res || bn || (stats && stats->mode))) return DAT_ERR_ARG;
+  if (sparse == 2 && !accumulate) return DAT_ERR_ARG;
   if (bn && !conv_mfma_bn_operand_ok(g)) return DAT_ERR_UNSUPPORTED;
   IgemmArgs a;
   a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
   if (bn) { a.xf_x = bn->x; a.xf_mask = bn->mask; a.xf_tab = bn->tab; }
   a.in = dy; a.res = accumulate ? dx : masked_res; a.res_mask = masked_res ? res_mask : nullptr; a.out = dx;
+  a.res_even_only = (sparse == 2 && g.stride == 1) ? 1 : 0;
   a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Cout = g.Cin;
   a.ostride = 1; a.outH = g.H; a.outW = g.W; a.nct = a.npt = 0;
   if (g.stride == 1) {
@@ -1351,8 +1359,11 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
     a.KH = ch.nr; a.KW = cw.nr; a.pad_h = ch.pad; a.pad_w = cw.pad;
     a.ostep = 2; a.oh0 = ph; a.ow0 = pw;
     a.M = g.B * a.Hout * a.Wout; a.Ktot = ch.nr * cw.nr * g.Cout;
-    if (a.Ktot == 0) a.KH = a.KW = 1;   // class without taps: the launch only writes zeros (or keeps the stored gradient)
+    const bool taps = a.Ktot != 0;
+    if (!taps) a.KH = a.KW = 1;         // class without taps: the launch only writes zeros (or keeps the stored gradient)
+    if (sparse == 2) a.res = q == 0 ? dx : nullptr;   // the stored gradient exists at even rows and columns only
     set_stats(a, stats, slab0);
+    if (sparse == 1 && !taps) continue;               // left unwritten: the accumulating pass that follows skips them
     if (a.M > 0) { dat_status s = run_igemm(a, st); if (s != DAT_OK) return s; }
     slab0 += (a.M + kPixelTile - 1) / kPixelTile;
     base += (int64_t)ch.nr * cw.nr;
@@ -1382,7 +1393,7 @@ dat_status launch_stem_weight_transform(const float* master, bf16_t* vf, bf16_t*
 dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
   a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
-  a.in = x2; a.wt = vf; a.res = nullptr; a.res_mask = nullptr; a.out = y;
+  a.in = x2; a.wt = vf; a.res = nullptr; a.res_mask = nullptr; a.res_even_only = 0; a.out = y;
   a.B = g.B; a.Hin = g.H / 2; a.Win = g.W / 2; a.Cin = 32; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
   a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 2;
   a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
@@ -1395,7 +1406,7 @@ dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y,
 dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16_t* dx2, const ConvGeom& g, bool accumulate, hipStream_t st) {
   IgemmArgs a;
   a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
-  a.in = dy; a.wt = vb; a.res = accumulate ? dx2 : nullptr; a.res_mask = nullptr; a.out = dx2;
+  a.in = dy; a.wt = vb; a.res = accumulate ? dx2 : nullptr; a.res_mask = nullptr; a.res_even_only = 0; a.out = dx2;
   a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H / 2; a.Wout = g.W / 2; a.Cout = 32;
   a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 1;
   a.outH = a.Hout; a.outW = a.Wout; a.ostep = 1; a.oh0 = a.ow0 = 0;

@@ -78,8 +78,15 @@ struct BnOperand {
   const float* tab;      // constants written by bnact_backward
 };
 bool conv_mfma_bn_operand_ok(const ConvGeom& g);
+// sparse: 1 (1x1 stride-2 layers without padding, conv_mfma_sparse_writer_ok, not accumulating): only the input pixels
+// the layer reads (even row, even column) are written; the other three quarters of dx, which would be zero, are
+// left as they are.  2 (accumulating): the stored dx is such a tensor -- it is read at even rows and columns only
+// and counts as zero elsewhere.  A pair of such calls gives the bits of a pair of plain calls without the zeros ever
+// being written or read back.
+bool conv_mfma_sparse_writer_ok(const ConvGeom& g);
 dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* dx, const ConvGeom& g, bool accumulate, ConvStats* stats, hipStream_t st,
-                                   const bf16_t* masked_res = nullptr, const uint8_t* res_mask = nullptr, const BnOperand* bn = nullptr);
+                                   const bf16_t* masked_res = nullptr, const uint8_t* res_mask = nullptr, const BnOperand* bn = nullptr,
+                                   int sparse = 0);
 // dw fp32 [Cout][k][k][Cin_real] (Cin_real <= g.Cin: padded input channels are dropped), scaled.
 // `ws` is a workspace of conv_mfma_wgrad_workspace(g) bytes.
 size_t conv_mfma_wgrad_workspace(const ConvGeom& g);

@@ -38,6 +38,7 @@ struct Op {
   float* bn_tab = nullptr;      //   and the per-channel constants of the input gradient (4*C floats)
   int dy_bn = -1;               // conv: BN op whose output gradient this conv's backward-data launch completes -- its epilogue can emit that BN's sums
   bool dy_bn_last_of_many = false;   //   ... as the last of several convolutions that read that output (accumulating launch)
+  bool sparse_first = false;    // conv (1x1, stride 2): its backward-data pass runs first of two convolutions' and writes only the pixels it reads
   bool sums_ready = false;      // BN: sums and constants already produced by the convolution that wrote d(out)
   int pool = -1;                // BN + ReLU read only by a max-pool: that op (one fused forward pass; the backward pass gathers d(out))
   int pooled_by = -1;           // max-pool evaluated by the BN before it
@@ -64,6 +65,7 @@ struct dat_model {
   bool fuse_bn_apply = true;         // dat_model_set_option(DAT_OPT_FUSE_BN_INPUT_GRAD)
   bool fuse_bn_sums = true;          // dat_model_set_option(DAT_OPT_FUSE_BN_SUMS)
   bool fuse_pgd_grad = true;         // dat_model_set_option(DAT_OPT_FUSE_PGD_GRADIENT)
+  bool sparse_shortcut_grad = true;  // dat_model_set_option(DAT_OPT_SPARSE_SHORTCUT_GRADIENT)
   int64_t bn_sums_max_bytes = (int64_t)1 << 62;   //   ... only for d(out) tensors up to this size
   bool fuse_pool = false;            // BN + ReLU + max-pool in one forward pass, pool gradient gathered by the BN backward pass
   std::vector<Shape> tens;           // logical per-sample shapes (channels as stored)
@@ -315,6 +317,24 @@ bool build_graph(dat_model& m) {
       if (users == 1 || (users == 2 && cv.res_grad_from >= 0)) cv.dy_bn = producer[cv.in];
       else if (conv_users == users && first_user == c) { cv.dy_bn = producer[cv.in]; cv.dy_bn_last_of_many = true; }
     }
+    // A strided 1x1 projection whose input is read by exactly one other convolution, earlier in the graph: in the
+    // backward sweep the projection writes its input gradient first, at the quarter of the pixels it reads, and the
+    // other convolution adds to it knowing that the rest is zero (three quarters of the tensor neither written nor read).
+    for (int c = 0; c < (int)m.ops.size(); ++c) {
+      Op& cv = m.ops[c];
+      if (cv.kind != OP_CONV || cv.in <= 0 || cv.blocked) continue;
+      ConvGeom g; g.k = cv.k; g.stride = cv.stride; g.pad = cv.pad;
+      if (!conv_mfma_sparse_writer_ok(g) || m.tens[cv.in].H % 2 != 0 || m.tens[cv.in].W % 2 != 0) continue;
+      int users = 0, conv_users = 0, first_user = -1;
+      for (int o = 0; o < (int)m.ops.size(); ++o) {
+        const int u = (m.ops[o].in == cv.in) + (m.ops[o].res == cv.in);
+        users += u;
+        if (u && first_user < 0) first_user = o;
+        if (m.ops[o].in == cv.in && m.ops[o].kind == OP_CONV) ++conv_users;
+      }
+      if (users == 2 && conv_users == 2 && first_user != c && m.ops[first_user].res_grad_from < 0 && (m.ops[first_user].stride == 1 || m.ops[first_user].stride == 2))
+        cv.sparse_first = true;
+    }
     // the ImageNet stem runs on 2x2 pixel blocks of the network input (tensor 0 is stored blocked)
     Op& first = m.ops[0];
     if (first.kind == OP_CONV && first.in == 0 && first.res < 0) {
@@ -562,6 +582,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         if (op.in != 0 || need_input_grad) {
           // sums of the BN whose output gradient this pass completes (nothing else has written it, nothing else will)
           ConvStats bs{}; ConvStats* bsp = nullptr;
+          bool sparse_written = false;
           if (dt == DAT_BF16 && !op.blocked && op.dy_bn >= 0 && m.fuse_bn_sums && (bool)m.ghas[op.in] == op.dy_bn_last_of_many &&
               (int64_t)si.H * si.W * si.C * B * 2 <= m.bn_sums_max_bytes) {
             const Op& bn = m.ops[op.dy_bn];
@@ -584,16 +605,22 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
             DAT_PROF(m, DAT_PROF_CONV_BWD_DATA_BN, conv_flops(g, op.cin_real), st,
                      conv_mfma_backward_data((const bf16_t*)m.grad[top.out], op.w16T, (bf16_t*)m.grad[op.in], g, rg ? false : (bool)m.ghas[op.in], bsp, st,
                                              rg ? (const bf16_t*)m.grad[m.ops[op.res_grad_from].out] : nullptr,
-                                             rg ? m.ops[op.res_grad_from].mask : nullptr, &bo));
+                                             rg ? m.ops[op.res_grad_from].mask : nullptr, &bo, (!rg && m.ghas[op.in] == 2) ? 2 : 0));
           }
           else if (dt == DAT_BF16 && op.res_grad_from >= 0) {
             if (m.ghas[op.in]) return DAT_ERR_UNSUPPORTED;   // by construction nothing else has written this gradient yet
             const Op& bn = m.ops[op.res_grad_from];
             DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, false, bsp, st, (const bf16_t*)m.grad[bn.out], bn.mask));
           }
-          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], bsp, st));
+          else if (dt == DAT_BF16) {
+            // (see Op::sparse_first: the first of the two passes writes a quarter of the pixels, the second knows)
+            const bool first_sparse = op.sparse_first && !m.ghas[op.in] && !bsp && m.sparse_shortcut_grad;
+            const int sparse = first_sparse ? 1 : m.ghas[op.in] == 2 ? 2 : 0;
+            DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_mfma_backward_data((const bf16_t*)m.grad[op.out], op.w16T, (bf16_t*)m.grad[op.in], g, m.ghas[op.in], bsp, st, nullptr, nullptr, nullptr, sparse));
+            if (first_sparse) sparse_written = true;
+          }
           else DAT_PROF(m, DAT_PROF_CONV_BWD_DATA, conv_flops(g, op.cin_real), st, conv_direct_backward_data((const float*)m.grad[op.out], m.compute + m.ptab[op.p0].off, (float*)m.grad[op.in], g, m.ghas[op.in], st));
-          m.ghas[op.in] = 1;
+          m.ghas[op.in] = sparse_written ? 2 : 1;
           if (bsp) {   // finish that BN's sums, parameter gradients and input-gradient constants now
             Op& bn = m.ops[op.dy_bn];
             float* bg0 = grads ? grads + m.ptab[bn.p0].off : nullptr;
@@ -962,6 +989,7 @@ extern "C" dat_status dat_model_set_option(dat_model* m, dat_option opt, int val
     case DAT_OPT_FUSE_BN_INPUT_GRAD: m->fuse_bn_apply = value != 0; return DAT_OK;
     case DAT_OPT_FUSE_PGD_GRADIENT: m->fuse_pgd_grad = value != 0; return DAT_OK;
     case DAT_OPT_FUSE_BN_SUMS: m->fuse_bn_sums = value != 0; return DAT_OK;
+    case DAT_OPT_SPARSE_SHORTCUT_GRADIENT: m->sparse_shortcut_grad = value != 0; return DAT_OK;
   }
   return DAT_ERR_ARG;
 }

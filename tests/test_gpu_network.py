@@ -297,6 +297,30 @@ def test_bn_backward_sums_from_the_convolution_epilogue(dat):
     assert _rel2(outs[0][0], outs[1][0]) < 5e-2
 
 
+@pytest.mark.parametrize("arch,B,H,W,classes", [(3, 5, 64, 64, 12), (3, 3, 96, 64, 12), (1, 16, 16, 16, 10), (2, 4, 8, 8, 10), (4, 12, 16, 16, 10)])
+def test_shortcut_gradient_written_only_where_the_projection_reads(dat, arch, B, H, W, classes):
+    """bf16: the input gradient of a strided 1x1 projection shortcut is written at the pixels it reads only, and the
+    block's first convolution, which adds its part to the same tensor (a stride-1 1x1 layer in ResNet-50, a strided 3x3
+    layer in the basic and pre-activation blocks), takes zero elsewhere; with the option off the zeros are written and
+    read back.  Input gradient, attack and parameter gradients agree bit for bit."""
+    gpu = dat.Model(arch, dat.BF16, B, H, W, classes, MEAN, STD)
+    gpu.set_params(syn.perturbed_params(53, gpu.offsets, gpu.fan_in, gpu.kind))
+    xd, yd = _cuda(syn.images(53, B, H, W)), _cuda(syn.labels(53, B, classes))
+    first = None
+    for on in (1, 0, 1):
+        gpu.set_option(dat.OPT_SPARSE_SHORTCUT_GRADIENT, on)
+        gx, logits, loss = gpu.input_grad(xd, yd)
+        d = gpu.attack(xd, yd, EPS, ALPHA, 2, dat.INIT_UNIFORM, seed=9)
+        g, l = gpu.step(xd, yd, want_loss=True)
+        cur = (gx.cpu().numpy(), d.cpu().numpy(), g.cpu().numpy())
+        assert np.isfinite(cur[2]).all() and np.abs(cur[0]).max() > 0
+        if first is None:
+            first = cur
+        else:
+            for a, b in zip(cur, first):
+                assert np.array_equal(a, b)
+
+
 def test_batch_and_argument_errors(dat):
     gpu = dat.Model(dat.ARCH_TINYCNN, dat.F32, 4, 8, 8, 10)
     x = torch.zeros(8, 8, 8, 3, device="cuda"); y = torch.zeros(8, dtype=torch.int32, device="cuda")
