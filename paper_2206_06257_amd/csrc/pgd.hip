@@ -47,7 +47,8 @@ constexpr int kPixPerBlock = 4 * kThreads;        // 1024
 
 __device__ __forceinline__ void load4(const float* __restrict__ p, int64_t e, int64_t n, float v[4]) {
   if (e + 4 <= n) {
-    const float4 f = *reinterpret_cast<const float4*>(p + e);
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 f = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p + e));   // streamed once
     v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
   } else {
 #pragma unroll
