@@ -262,9 +262,14 @@ dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* la
  * convolution, which adds its own part to the same tensor, reads the stored values there and takes
  * zero elsewhere.  0: the projection's pass also writes the zeros and the other pass reads them
  * back.  Identical bits either way.
+ * DAT_OPT_OVERLAP_WEIGHT_GRADIENTS (default 1, bf16 models): in dat_step / dat_step_reg the
+ * backward-weight launches of the convolutions run on a stream owned by the model, each after an
+ * event that marks its output gradient complete on the caller's stream, and the caller's stream
+ * waits for them before the call's work on it ends (fork / join: the call stays asynchronous on
+ * `stream` and can be captured).  0: everything on the caller's stream.  Identical bits either way.
  * Returns DAT_ERR_ARG for an unknown option. */
 typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1, DAT_OPT_FUSE_PGD_GRADIENT = 2,
-               DAT_OPT_SPARSE_SHORTCUT_GRADIENT = 3 } dat_option;
+               DAT_OPT_SPARSE_SHORTCUT_GRADIENT = 3, DAT_OPT_OVERLAP_WEIGHT_GRADIENTS = 4 } dat_option;
 /* (Two more switches are read from the environment by dat_model_create, because they change the
  * layer graph of a bf16 model.  DAT_KEEP_SHORTCUT_BN: the batch normalisation on a projection
  * shortcut runs as passes of its own instead of being evaluated by the last normalisation of the

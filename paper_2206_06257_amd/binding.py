@@ -82,6 +82,7 @@ OPT_FUSE_BN_INPUT_GRAD = 0
 OPT_FUSE_BN_SUMS = 1
 OPT_FUSE_PGD_GRADIENT = 2
 OPT_SPARSE_SHORTCUT_GRADIENT = 3
+OPT_OVERLAP_WEIGHT_GRADIENTS = 4
 _lib.dat_profile_read.argtypes = [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]
 PROF_CLASSES = ("conv_fwd", "conv_bwd_data", "conv_wgrad", "bn", "pgd", "conv_bwd_data_bn")
 

@@ -66,6 +66,14 @@ struct dat_model {
   bool fuse_bn_sums = true;          // dat_model_set_option(DAT_OPT_FUSE_BN_SUMS)
   bool fuse_pgd_grad = true;         // dat_model_set_option(DAT_OPT_FUSE_PGD_GRADIENT)
   bool sparse_shortcut_grad = true;  // dat_model_set_option(DAT_OPT_SPARSE_SHORTCUT_GRADIENT)
+  bool overlap_wgrad = true;         // dat_model_set_option(DAT_OPT_OVERLAP_WEIGHT_GRADIENTS)
+  // Weight gradients of the convolutions run on a stream of the model's own beside the caller's: nothing later in the
+  // backward sweep reads them, and they are bound by the matrix units and the operand gather while the normalisation
+  // passes between the backward-data launches are bound by HBM.  One event per convolution orders each launch after
+  // its output gradient is complete; wg_join brings the side stream back before the sweep returns.
+  hipStream_t wg_stream = nullptr;
+  std::vector<hipEvent_t> wg_events;
+  hipEvent_t wg_join = nullptr;
   int64_t bn_sums_max_bytes = (int64_t)1 << 62;   //   ... only for d(out) tensors up to this size
   bool fuse_pool = false;            // BN + ReLU + max-pool in one forward pass, pool gradient gathered by the BN backward pass
   std::vector<Shape> tens;           // logical per-sample shapes (channels as stored)
@@ -441,6 +449,12 @@ dat_status allocate(dat_model& m) {
     partial_floats = std::max(partial_floats, std::max(need_f, need_b));
   }
   DAT_TRY(dev_alloc(m, &m.partial, partial_floats * 4));
+  if (m.dtype == DAT_BF16) {   // default priority: work on streams of different priorities must not be mixed
+    DAT_HIP(hipStreamCreateWithFlags(&m.wg_stream, hipStreamNonBlocking));
+    DAT_HIP(hipEventCreateWithFlags(&m.wg_join, hipEventDisableTiming));
+    for (const Op& op : m.ops)
+      if (op.kind == OP_CONV) { hipEvent_t e; DAT_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming)); m.wg_events.push_back(e); }
+  }
   DAT_TRY(dev_alloc(m, &m.sums, (size_t)2 * cmax * 4));
   DAT_TRY(dev_alloc(m, &m.loss_n, (size_t)m.maxB * 4));
   m.loss_cap = 1024;
@@ -561,6 +575,9 @@ dat_status loss_grad(dat_model& m, const int32_t* y, int B, float gscale, int lo
 // grads == nullptr: backward to the input only (attack); otherwise also parameter gradients.
 dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hipStream_t st) {
   const int dt = m.dtype;
+  // (per-launch timing keeps everything on one stream: its event pairs bracket launches on `st`)
+  const bool side = grads && dt == DAT_BF16 && m.overlap_wgrad && m.wg_stream && !m.prof;
+  size_t wg_used = 0;
   for (int i = (int)m.ops.size() - 1; i >= 0; --i) {
     Op& op = m.ops[i];
     const Shape si = m.tens[op.in], so = m.tens[op.out];
@@ -575,8 +592,15 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
           m.ghas[op.res] = 1;
         }
         if (g0) {
-          if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_mfma_stem_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.dv, op.cin_real, g, 1.0f, m.wgrad_ws, st));
-          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, st));
+          hipStream_t wst = st;
+          if (side && wg_used < m.wg_events.size()) {   // d(out) of this layer is complete at this point of `st`
+            hipEvent_t e = m.wg_events[wg_used++];
+            DAT_HIP(hipEventRecord(e, st));
+            DAT_HIP(hipStreamWaitEvent(m.wg_stream, e, 0));
+            wst = m.wg_stream;
+          }
+          if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), wst, conv_mfma_stem_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.dv, op.cin_real, g, 1.0f, m.wgrad_ws, wst));
+          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), wst, conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, wst));
           else DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_direct_backward_weight((const float*)m.act[op.in], (const float*)m.grad[op.out], g0, g, 1.0f, st));
         }
         if (op.in != 0 || need_input_grad) {
@@ -707,6 +731,10 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         break;
     }
   }
+  if (wg_used) {   // whatever follows on `st` (the caller's reads of `grads`, the next sweep's writes) waits for the side stream
+    DAT_HIP(hipEventRecord(m.wg_join, m.wg_stream));
+    DAT_HIP(hipStreamWaitEvent(st, m.wg_join, 0));
+  }
   return DAT_OK;
 }
 
@@ -777,6 +805,9 @@ extern "C" dat_status dat_model_destroy(dat_model* m) {
   for (void* p : m->allocs) (void)hipFree(p);
   for (auto& r : m->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   for (hipEvent_t e : m->pool) (void)hipEventDestroy(e);
+  for (hipEvent_t e : m->wg_events) (void)hipEventDestroy(e);
+  if (m->wg_join) (void)hipEventDestroy(m->wg_join);
+  if (m->wg_stream) (void)hipStreamDestroy(m->wg_stream);
   if (m->host_stage) (void)hipHostFree(m->host_stage);
   delete m;
   return DAT_OK;
@@ -990,6 +1021,7 @@ extern "C" dat_status dat_model_set_option(dat_model* m, dat_option opt, int val
     case DAT_OPT_FUSE_PGD_GRADIENT: m->fuse_pgd_grad = value != 0; return DAT_OK;
     case DAT_OPT_FUSE_BN_SUMS: m->fuse_bn_sums = value != 0; return DAT_OK;
     case DAT_OPT_SPARSE_SHORTCUT_GRADIENT: m->sparse_shortcut_grad = value != 0; return DAT_OK;
+    case DAT_OPT_OVERLAP_WEIGHT_GRADIENTS: m->overlap_wgrad = value != 0; return DAT_OK;
   }
   return DAT_ERR_ARG;
 }

@@ -321,6 +321,40 @@ def test_shortcut_gradient_written_only_where_the_projection_reads(dat, arch, B,
                 assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("arch,B,H,W,classes", [(3, 5, 64, 64, 12), (1, 16, 16, 16, 10), (2, 4, 8, 8, 10), (100, 8, 16, 16, 5)])
+def test_weight_gradients_on_the_side_stream_give_the_same_bits(dat, arch, B, H, W, classes):
+    """bf16: the backward-weight launches run on a stream of the model's own, ordered by events after their output
+    gradients and joined before the call's work on the caller's stream ends (on the default stream and on a stream
+    of the caller's), or (option off) in line.  Parameter gradients of repeated calls agree bit for bit, and a call
+    that follows immediately (which overwrites the activations and gradients the launches read) sees them finished."""
+    gpu = dat.Model(arch, dat.BF16, B, H, W, classes, MEAN, STD)
+    gpu.set_params(syn.perturbed_params(57, gpu.offsets, gpu.fan_in, gpu.kind))
+    xd, yd = _cuda(syn.images(57, B, H, W)), _cuda(syn.labels(57, B, classes))
+    x2 = _cuda(syn.images(58, B, H, W))
+    first = None
+    own = torch.cuda.Stream()
+    for on, stream in ((1, None), (0, None), (1, own), (1, None)):
+        gpu.set_option(dat.OPT_OVERLAP_WEIGHT_GRADIENTS, on)
+        if stream is None:
+            g = gpu.step(xd, yd)
+            g2 = gpu.step(x2, yd)              # back to back: must not disturb g's launches
+            g3 = gpu.step(xd, yd)
+        else:
+            stream.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(stream):
+                g = gpu.step(xd, yd, stream=stream)
+                g2 = gpu.step(x2, yd, stream=stream)
+                g3 = gpu.step(xd, yd, stream=stream)
+            stream.synchronize()
+        cur = (g.cpu().numpy(), g2.cpu().numpy(), g3.cpu().numpy())
+        assert np.isfinite(cur[0]).all() and np.abs(cur[0]).max() > 0 and np.array_equal(cur[0], cur[2])
+        if first is None:
+            first = cur
+        else:
+            for a, b in zip(cur, first):
+                assert np.array_equal(a, b)
+
+
 def test_batch_and_argument_errors(dat):
     gpu = dat.Model(dat.ARCH_TINYCNN, dat.F32, 4, 8, 8, 10)
     x = torch.zeros(8, 8, 8, 3, device="cuda"); y = torch.zeros(8, dtype=torch.int32, device="cuda")
