@@ -266,7 +266,7 @@ dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* la
  * backward-weight launches of the convolutions run on a stream owned by the model, each after an
  * event that marks its output gradient complete on the caller's stream, and the caller's stream
  * waits for them before the call's work on it ends (fork / join: the call stays asynchronous on
- * `stream` and can be captured).  0: everything on the caller's stream.  Identical bits either way.
+ * `stream`).  0: everything on the caller's stream.  Identical bits either way.
  * Returns DAT_ERR_ARG for an unknown option. */
 typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1, DAT_OPT_FUSE_PGD_GRADIENT = 2,
                DAT_OPT_SPARSE_SHORTCUT_GRADIENT = 3, DAT_OPT_OVERLAP_WEIGHT_GRADIENTS = 4 } dat_option;
