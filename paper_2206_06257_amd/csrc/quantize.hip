@@ -174,6 +174,32 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float* __restr
   c.t = find_tensor(off, T, grp * EPT);
   c.next = off[c.t + 1];
   enc_enter<BITS>(c, scales);
+  if (PRE) {
+    // all eight groups of this thread inside the current tensor and inside the vector (the common case: tensors are
+    // much longer than the 8 K elements a workgroup covers): one scale, no boundary tests, whole words stored
+    const int64_t ilast = (grp + (int64_t)(kIter - 1) * kThreads) * EPT + (EPT - 1);
+    if (ilast < c.next && ilast < d) {
+      uint32_t* dst = reinterpret_cast<uint32_t*>(q);
+#pragma unroll
+      for (int it = 0; it < kIter; ++it) {
+        const int64_t gi = grp + (int64_t)it * kThreads;
+        const PhiloxWords w = philox_block((uint64_t)gi, seed, kStreamQuant);      // EPT == 4: element index / 4 = group index
+        const float v[4] = {pre[it].x, pre[it].y, pre[it].z, pre[it].w};
+        const float u[4] = {u24(w.w0), u24(w.w1), u24(w.w2), u24(w.w3)};
+        uint32_t word[WORDS];
+#pragma unroll
+        for (int wd = 0; wd < WORDS; ++wd) word[wd] = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t field = (uint32_t)encode_one<BITS>(v[j], u[j], c) & ((1u << BITS) - 1u);
+          word[(j * BITS) / 32] |= field << ((j * BITS) % 32);
+        }
+#pragma unroll
+        for (int wd = 0; wd < WORDS; ++wd) dst[gi * WORDS + wd] = word[wd];
+      }
+      return;
+    }
+  }
 #pragma unroll
   for (int it = 0; it < kIter; ++it, grp += kThreads) {
     if (grp >= ngroups) break;
