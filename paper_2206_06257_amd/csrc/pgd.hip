@@ -82,13 +82,24 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
   // where this thread's pixels 4t .. 4t+3 live in the per-pixel tensors (network input and its gradient)
   const int64_t p0 = (int64_t)blockIdx.x * kPixPerBlock + 4 * tid;
   int64_t slot[4];
+  if (in.bw && (in.bw & 3) == 0) {
+    // 2x2 pixel blocks, image width a multiple of 4: the thread's four pixels share a row (p0 is a multiple of 4), so
+    // one decomposition of p0 serves all of them (the divisions by the run-time width and height are ~35 VALU
+    // operations each)
+    const uint32_t pix = (uint32_t)p0, w0 = pix % (uint32_t)in.bw, hn = pix / (uint32_t)in.bw;
+    const uint32_t h = hn % (uint32_t)in.bh, nimg = hn / (uint32_t)in.bh;
+    const int64_t rowbase = (int64_t)(nimg * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1);
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    slot[p] = p0 + p;
-    if (in.bw) {   // 2x2 pixel blocks: pixel (n,h,w) -> block (n, h/2, w/2), position (h%2)*2 + w%2
-      const uint32_t pix = (uint32_t)slot[p], ww = pix % (uint32_t)in.bw, hn = pix / (uint32_t)in.bw;
-      const uint32_t h = hn % (uint32_t)in.bh, nimg = hn / (uint32_t)in.bh;
-      slot[p] = ((int64_t)(nimg * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1) + (ww >> 1)) * 4 + (h & 1u) * 2 + (ww & 1u);
+    for (int p = 0; p < 4; ++p) slot[p] = (rowbase + ((w0 + p) >> 1)) * 4 + (h & 1u) * 2 + ((w0 + p) & 1u);
+  } else {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      slot[p] = p0 + p;
+      if (in.bw) {   // 2x2 pixel blocks: pixel (n,h,w) -> block (n, h/2, w/2), position (h%2)*2 + w%2
+        const uint32_t pix = (uint32_t)slot[p], ww = pix % (uint32_t)in.bw, hn = pix / (uint32_t)in.bw;
+        const uint32_t h = hn % (uint32_t)in.bh, nimg = hn / (uint32_t)in.bh;
+        slot[p] = ((int64_t)(nimg * (uint32_t)(in.bh >> 1) + (h >> 1)) * (uint32_t)(in.bw >> 1) + (ww >> 1)) * 4 + (h & 1u) * 2 + (ww & 1u);
+      }
     }
   }
   // every global load of the update is issued before the first barrier (the pixels and the perturbation below, the
