@@ -166,8 +166,9 @@ __global__ __launch_bounds__(kT) void block_reduce_kernel(const T* __restrict__ 
   const int64_t b0 = (int64_t)blockIdx.x * blocks_per_slab, b1 = min(nblocks, b0 + blocks_per_slab);
   if (rr < rpp) {
     for (int64_t blk = b0 + rr; blk < b1; blk += rpp) {
-      const int j = (int)(blk % Wb); const int64_t t = blk / Wb;
-      const int i = (int)(t % Hb), n = (int)(t / Hb);
+      // (block counts stay below 2^31, checked on the host: 32-bit divisions, a quarter of the 64-bit ones' cost)
+      const uint32_t t = (uint32_t)blk / (uint32_t)Wb;
+      const int j = (int)((uint32_t)blk - t * (uint32_t)Wb), n = (int)(t / (uint32_t)Hb), i = (int)(t - (uint32_t)n * (uint32_t)Hb);
       float g[2][2][8];
       block_dout<T, POOL>(pa, dout, n, i, j, C, c0, g);
 #pragma unroll
@@ -208,12 +209,13 @@ __global__ __launch_bounds__(kT) void block_apply_kernel(const T* __restrict__ x
                                                          const float* __restrict__ tab, PoolArgs pa) {
   const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (v >= nblocks * tpr) return;
-  const int cv = (int)(v % tpr);
-  const int64_t blk = v / tpr;
+  // (vector counts stay below 2^31, checked on the host: 32-bit divisions)
+  const uint32_t blk = (uint32_t)v / (uint32_t)tpr;
+  const int cv = (int)((uint32_t)v - blk * (uint32_t)tpr);
   const int c0 = cv * 8;
   const int Hb = (pa.H + 1) / 2, Wb = (pa.W + 1) / 2;
-  const int j = (int)(blk % Wb); const int64_t t = blk / Wb;
-  const int i = (int)(t % Hb), n = (int)(t / Hb);
+  const uint32_t t = blk / (uint32_t)Wb;
+  const int j = (int)(blk - t * (uint32_t)Wb), n = (int)(t / (uint32_t)Hb), i = (int)(t - (uint32_t)n * (uint32_t)Hb);
   float ka[8], kp[8], kq[8], mu[8];
   load8f(tab + cv * 32, ka); load8f(tab + cv * 32 + 8, kp); load8f(tab + cv * 32 + 16, kq); load8f(tab + cv * 32 + 24, mu);
   float g[2][2][8];
@@ -540,11 +542,10 @@ __global__ __launch_bounds__(kT) void bnact_pool_fwd_kernel(const T* __restrict_
   const int tpr = C / 8;
   const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (v >= (int64_t)B * Ho * Wo * tpr) return;
-  const int cv = (int)(v % tpr);
-  int64_t p = v / tpr;
-  const int wo = (int)(p % Wo); p /= Wo;
-  const int ho = (int)(p % Ho);
-  const int n = (int)(p / Ho);
+  // (vector counts stay below 2^31, checked on the host: 32-bit divisions)
+  const uint32_t p = (uint32_t)v / (uint32_t)tpr, q = p / (uint32_t)Wo;
+  const int cv = (int)((uint32_t)v - p * (uint32_t)tpr), wo = (int)(p - q * (uint32_t)Wo);
+  const int n = (int)(q / (uint32_t)Ho), ho = (int)(q - (uint32_t)n * (uint32_t)Ho);
   const int c0 = cv * 8;
   float mu[8], rs[8], ga[8], be[8];
   load8f(mean + c0, mu); load8f(rstd + c0, rs); load8f(gamma + c0, ga); load8f(beta + c0, be);
@@ -700,11 +701,10 @@ __global__ __launch_bounds__(kT) void maxpool_fwd_kernel(const T* __restrict__ x
   const int tpr = C / 8;
   const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (v >= (int64_t)B * Ho * Wo * tpr) return;
-  const int cv = (int)(v % tpr);
-  int64_t p = v / tpr;
-  const int wo = (int)(p % Wo); p /= Wo;
-  const int ho = (int)(p % Ho);
-  const int n = (int)(p / Ho);
+  // (vector counts stay below 2^31, checked on the host: 32-bit divisions)
+  const uint32_t p = (uint32_t)v / (uint32_t)tpr, q = p / (uint32_t)Wo;
+  const int cv = (int)((uint32_t)v - p * (uint32_t)tpr), wo = (int)(p - q * (uint32_t)Wo);
+  const int n = (int)(q / (uint32_t)Ho), ho = (int)(q - (uint32_t)n * (uint32_t)Ho);
   float best[8]; uint32_t pos[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) { best[j] = -__builtin_inff(); pos[j] = 0; }
@@ -738,11 +738,10 @@ __global__ __launch_bounds__(kT) void maxpool_bwd_kernel(const uint8_t* __restri
   const int Hb = (H + 1) / 2, Wb = (W + 1) / 2;
   const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (v >= (int64_t)B * Hb * Wb * tpr) return;
-  const int cv = (int)(v % tpr);
-  int64_t p = v / tpr;
-  const int j = (int)(p % Wb); p /= Wb;
-  const int i = (int)(p % Hb);
-  const int n = (int)(p / Hb);
+  // (vector counts stay below 2^31, checked on the host: 32-bit divisions)
+  const uint32_t p = (uint32_t)v / (uint32_t)tpr, q = p / (uint32_t)Wb;
+  const int cv = (int)((uint32_t)v - p * (uint32_t)tpr), j = (int)(p - q * (uint32_t)Wb);
+  const int n = (int)(q / (uint32_t)Hb), i = (int)(q - (uint32_t)n * (uint32_t)Hb);
   float sum[2][2][8];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -1091,6 +1090,7 @@ dat_status bnact_pool_forward(const void* x, void* pooled, uint8_t* arg, uint8_t
                               const float* mean, const float* rstd, const float* gamma, const float* beta, hipStream_t st) {
   if (C % 8 != 0 || !mask || !arg) return DAT_ERR_ARG;
   const int64_t nvec = (int64_t)B * Ho * Wo * (C / 8);
+  if (nvec >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;   // 32-bit vector indices in the kernel
   DAT_BY_DTYPE(dtype,
     hipLaunchKernelGGL(bnact_pool_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (float*)pooled, arg, mask, B, H, W, C, Ho, Wo, mean, rstd, gamma, beta),
     hipLaunchKernelGGL(bnact_pool_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (bf16_t*)pooled, arg, mask, B, H, W, C, Ho, Wo, mean, rstd, gamma, beta));
@@ -1154,6 +1154,7 @@ dat_status bn_pool_backward(const void* x, const uint8_t* mask, const void* dout
   PoolArgs pa{pg.arg, pg.dpooled, pg.B, pg.H, pg.W, pg.Ho, pg.Wo};
   const int tpr = C / 8, rpp = kT / tpr;
   const int64_t nblocks = (int64_t)pg.B * ((pg.H + 1) / 2) * ((pg.W + 1) / 2);
+  if (nblocks * tpr >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;   // 32-bit block / vector indices in the kernels
   const int64_t rows = (int64_t)pg.B * pg.H * pg.W;
   int64_t want = (nblocks + (int64_t)rpp * 8 - 1) / ((int64_t)rpp * 8);
   int nslabs = (int)(want < 1 ? 1 : (want > kMaxSlabs ? kMaxSlabs : want));
@@ -1212,6 +1213,7 @@ dat_status biasact_backward(const void* out, const void* dout, void* dx, bool dx
 
 dat_status maxpool_forward(const void* x, void* out, uint8_t* arg, int dtype, int B, int H, int W, int C, int Ho, int Wo, hipStream_t st) {
   const int64_t nvec = (int64_t)B * Ho * Wo * (C / 8);
+  if (nvec >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;   // 32-bit vector indices in the kernel
   DAT_BY_DTYPE(dtype,
     hipLaunchKernelGGL(maxpool_fwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, (const float*)x, (float*)out, arg, B, H, W, C, Ho, Wo),
     hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, (const bf16_t*)x, (bf16_t*)out, arg, B, H, W, C, Ho, Wo));
@@ -1222,6 +1224,7 @@ dat_status maxpool_forward(const void* x, void* out, uint8_t* arg, int dtype, in
 dat_status maxpool_backward(const uint8_t* arg, const void* dout, void* dx, bool accumulate, int dtype, int B, int H, int W, int C,
                             int Ho, int Wo, hipStream_t st) {
   const int64_t nvec = (int64_t)B * ((H + 1) / 2) * ((W + 1) / 2) * (C / 8);
+  if (nvec >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;   // 32-bit vector indices in the kernel
   DAT_BY_DTYPE(dtype,
     hipLaunchKernelGGL(maxpool_bwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, arg, (const float*)dout, (float*)dx, (int)accumulate, B, H, W, C, Ho, Wo),
     hipLaunchKernelGGL(maxpool_bwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, arg, (const bf16_t*)dout, (bf16_t*)dx, (int)accumulate, B, H, W, C, Ho, Wo));
