@@ -973,12 +973,14 @@ __global__ __launch_bounds__(64) void kl_kernel(const float* __restrict__ zc, co
   }
 }
 
-__global__ void mean_kernel(const float* __restrict__ v, int n, float* __restrict__ out) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    double s = 0.0;
-    for (int i = 0; i < n; ++i) s += (double)v[i];
-    out[0] = (float)(s / n);
-  }
+// one wavefront: lane l adds elements l, l + 64, ... in fp64, then the lanes are combined in a fixed butterfly order
+__global__ __launch_bounds__(64) void mean_kernel(const float* __restrict__ v, int n, float* __restrict__ out) {
+  if (blockIdx.x != 0) return;
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += 64) s += (double)v[i];
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d);
+  if (threadIdx.x == 0) out[0] = (float)(s / n);
 }
 
 __global__ void round_bf16_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
