@@ -798,10 +798,22 @@ __global__ __launch_bounds__(kT) void gap_fwd_kernel(const T* __restrict__ x, fl
   float s[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) s[j] = 0.f;
-  for (int i = 0; i < HW; ++i) {
-    float xv[8]; V8<T>::load(x + ((int64_t)n * HW + i) * C + cv * 8, xv);
+  // eight pixels per round trip, added in pixel order (pixels past the end are not loaded and add +0)
+  const T* base = x + (int64_t)n * HW * C + cv * 8;
+  for (int i0 = 0; i0 < HW; i0 += 8) {
+    float xv[8][8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) s[j] += xv[j];
+    for (int u = 0; u < 8; ++u) {
+      if (i0 + u < HW) V8<T>::load(base + (int64_t)(i0 + u) * C, xv[u]);
+      else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) xv[u][j] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s[j] += xv[u][j];
   }
   const float inv = 1.0f / (float)HW;
 #pragma unroll
@@ -815,8 +827,9 @@ __global__ __launch_bounds__(kT) void gap_bwd_kernel(const float* __restrict__ d
   const int tpr = C / 8;
   const int64_t v = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (v >= (int64_t)B * HW * tpr) return;
-  const int cv = (int)(v % tpr);
-  const int n = (int)(v / ((int64_t)tpr * HW));
+  // (vector counts stay below 2^31, checked on the host: 32-bit divisions)
+  const uint32_t pix = (uint32_t)v / (uint32_t)tpr;
+  const int cv = (int)((uint32_t)v - pix * (uint32_t)tpr), n = (int)(pix / (uint32_t)HW);
   float g[8]; load8f(dpooled + (int64_t)n * C + cv * 8, g);
   const float inv = 1.0f / (float)HW;
 #pragma unroll
@@ -1245,6 +1258,7 @@ dat_status gap_forward(const void* x, float* pooled, int dtype, int B, int HW, i
 
 dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dtype, int B, int HW, int C, hipStream_t st) {
   const int64_t nvec = (int64_t)B * HW * (C / 8);
+  if (nvec >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;   // 32-bit vector indices in the kernel
   DAT_BY_DTYPE(dtype,
     hipLaunchKernelGGL(gap_bwd_kernel<float>, dim3(nblk(nvec)), dim3(kT), 0, st, dpooled, (float*)dx, (int)accumulate, B, HW, C),
     hipLaunchKernelGGL(gap_bwd_kernel<bf16_t>, dim3(nblk(nvec)), dim3(kT), 0, st, dpooled, (bf16_t*)dx, (int)accumulate, B, HW, C));
