@@ -202,6 +202,10 @@ def main():
                            "note": "launch times include the fused epilogue work: the batch statistics of the next BN (forward), the "
                                    "residual gradient and the two BN backward sums of the producing BN, which re-read its input and "
                                    "ReLU mask (backward-data)"}
+        if traffic:   # the same launches against the HBM roofline: measured bytes per launch / measured time per launch
+            gbs = traffic / (ms / max(n, 1) * 1e-3) / 1e9
+            out["roofline"]["traffic_GBs"] = gbs
+            out["roofline"]["traffic_frac_hbm"] = gbs / PEAK_HBM_GBS
         out["kernel_classes"] = {k: {"ms_per_step": v[0] / args.steps, "launches_per_step": v[1] / args.steps,
                                      "work_per_step": v[2] / args.steps} for k, v in prof.items()}
         pg = prof["pgd"]
