@@ -123,7 +123,7 @@ def main():
             model.attack(x, y, eps, alpha, K, dat.INIT_UNIFORM, seed=seed_init + i, delta=delta)
         if marks:
             marks[0].record()
-        torch.add(x, delta, out=xadv)          # x + delta (already inside [0,1] by construction)
+        dat.make_xadv(x, delta, out=xadv)      # clip(x + delta, 0, 1): the batch the outer step sees
         if general:
             model.step_reg(x, xadv, y, args.lam, dat.PHI_TRADES_KL if args.phi == "trades" else dat.PHI_CE, grads=grads)
         else:

@@ -157,6 +157,11 @@ dat_status dat_pgd_init(const float* x, int64_t N, float eps, dat_init init, flo
                         void* stream);
 dat_status dat_pgd_update(const float* x, const float* G, float* delta, int64_t N, float eps,
                           float alpha, void* stream);
+/* The adversarial batch handed to dat_step (Alg. A1 step 6 evaluates the loss at x + delta):
+ * x_adv = clip(x + delta, 0, 1), one single-rounded fp32 addition per element.  Same argument
+ * conventions as above; x_adv may not alias x or delta.  DAT_ERR_ARG for null or misaligned pointers
+ * or N not a multiple of 3; nothing is written on error. */
+dat_status dat_make_xadv(const float* x, const float* delta, int64_t N, float* x_adv, void* stream);
 
 /* Plain SGD on the fp32 master parameters: theta <- theta - lr * grads (then the bf16 compute
  * copy is refreshed).  The outer-minimisation oracle A(.) of Alg. A1 in its simplest form. */

@@ -21,7 +21,7 @@ EXPORTS = [
     "dat_input_grad", "dat_pgd_init", "dat_pgd_update", "dat_sgd_update", "dat_quantize", "dat_dequantize",
     "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
     "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read", "dat_aggregate", "dat_lamb_update",
-    "dat_attack_kl", "dat_step_reg", "dat_model_set_option",
+    "dat_attack_kl", "dat_step_reg", "dat_model_set_option", "dat_make_xadv",
 ]
 
 
@@ -64,6 +64,7 @@ _lib.dat_step.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp]
 _lib.dat_input_grad.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _vp]
 _lib.dat_pgd_init.argtypes = [_vp, _i64, _f, _Init, _vp, _vp]
 _lib.dat_pgd_update.argtypes = [_vp, _vp, _vp, _i64, _f, _f, _vp]
+_lib.dat_make_xadv.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.dat_sgd_update.argtypes = [_vp, _vp, _f, _vp]
 _lib.dat_quantize.argtypes = [_vp, _vp, _i, _i64, _i, _u64, _vp, _vp, _vp]
 _lib.dat_dequantize.argtypes = [_vp, _vp, _vp, _i, _i64, _i, _vp, _vp]
@@ -237,6 +238,15 @@ def pgd_update(x, G, delta, eps, alpha, stream=None):
     _dev(x, torch.float32); _dev(G, torch.float32); _dev(delta, torch.float32)
     _check(_lib.dat_pgd_update(_ptr(x), _ptr(G), _ptr(delta), x.numel(), eps, alpha, _stream(stream)), "dat_pgd_update")
     return delta
+
+
+def make_xadv(x, delta, out=None, stream=None):
+    _dev(x, torch.float32); _dev(delta, torch.float32)
+    if out is None:
+        out = torch.empty_like(x)
+    _dev(out, torch.float32)
+    _check(_lib.dat_make_xadv(_ptr(x), _ptr(delta), x.numel(), _ptr(out), _stream(stream)), "dat_make_xadv")
+    return out
 
 
 def quantized_bytes(d, bits):

@@ -291,6 +291,13 @@ extern "C" dat_status dat_pgd_init(const float* x, int64_t N, float eps, dat_ini
   return launch_attack_init(x, N / 3, eps, init, delta, kNoInput, (hipStream_t)stream);
 }
 
+extern "C" dat_status dat_make_xadv(const float* x, const float* delta, int64_t N, float* x_adv, void* stream) {
+  if (!x || !delta || !x_adv || N < 0 || N % 3 != 0) return DAT_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(delta, 16) || !aligned(x_adv, 16)) return DAT_ERR_ARG;
+  const NetInputDesc out = {x_adv, 0, 0, {0, 0, 0}, {1, 1, 1}, 0, 0};   // fp32 pixels, no normalisation
+  return launch_make_input(x, delta, N / 3, out, (hipStream_t)stream);
+}
+
 extern "C" dat_status dat_pgd_update(const float* x, const float* G, float* delta, int64_t N, float eps,
                                      float alpha, void* stream) {
   if (!x || !G || !delta || N < 0 || N % 3 != 0 || !(eps >= 0.0f) || !(alpha >= 0.0f)) return DAT_ERR_ARG;

@@ -130,3 +130,9 @@ def test_pgd_init_and_update_bit_exact(dat, shape):
         assert np.array_equal(got, want)
         assert np.abs(got).max() <= np.float32(eps) and (x + got).min() >= 0 and (x + got).max() <= 1
         delta = want
+    # the batch handed to the outer step: clip(x + delta, 0, 1), also for perturbations that leave the box
+    for d in (delta, (4.0 * delta).astype(np.float32)):
+        xa = dat.make_xadv(xd, _cuda(d)).cpu().numpy()
+        assert np.array_equal(xa, oracle.make_xadv(x, d)) and xa.min() >= 0 and xa.max() <= 1
+    with pytest.raises(dat.DatError):
+        dat.make_xadv(torch.zeros(4, device="cuda"), torch.zeros(4, device="cuda"))      # not whole pixels
