@@ -286,6 +286,30 @@ typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1, DAT_OPT
  * convolution outputs are bit-identical, the grouping of the batch-norm partial sums differs.) */
 dat_status dat_model_set_option(dat_model* m, dat_option opt, int value);
 
+/* ---- introspection for parity tests (not part of the paper's method) --------------------------------
+ * The layer graph and the tensors a model keeps on the device, so that a test can compare every stored
+ * activation, activation gradient and batch statistic of the last pass with a reference element by element,
+ * and restart the reference from the library's own tensors op by op (teacher forcing).
+ *   dat_inspect_counts  number of ops and of activation tensors (tensor 0 = the network input).
+ *   dat_inspect_op      info[10] = kind (0 conv, 1 bias+act, 2 BN+act, 3 max-pool, 4 global average pool,
+ *                       5 linear), input tensor, output tensor, residual tensor or -1, k, stride, pad, relu,
+ *                       first and second parameter tensor of the table or -1.
+ *   dat_inspect_tensor  info[6] = H, W, C (channels as stored), bytes per element (2: bf16, 4: fp32),
+ *                       act_stored, grad_stored.  act_stored = 0: the model never writes this tensor in plain
+ *                       NHWC form (a fused pass consumes it, or it is the padded network input of a bf16
+ *                       model).  grad_stored = 1: the last backward sweep left the complete gradient of this
+ *                       tensor in memory (sweeps without parameter gradients skip some).
+ *   dat_inspect_read    copies the B*H*W*C stored elements of tensor t (which = 0) or of its gradient
+ *                       (which = 1) to host memory as they are; `bytes` must be exactly that size.
+ *                       Synchronises the device.
+ *   dat_inspect_bn      batch mean and 1/sqrt(var + 1e-5) of BN op `op` from the last forward pass, host
+ *                       arrays of C floats.  DAT_ERR_ARG if `op` is not a batch normalisation. */
+dat_status dat_inspect_counts(const dat_model* m, int* num_ops, int* num_tensors);
+dat_status dat_inspect_op(const dat_model* m, int op, int32_t* info);
+dat_status dat_inspect_tensor(const dat_model* m, int t, int32_t* info);
+dat_status dat_inspect_read(dat_model* m, int which, int t, int B, void* host_dst, size_t bytes);
+dat_status dat_inspect_bn(dat_model* m, int op, float* mean_host, float* rstd_host);
+
 /* ---- misc ---------------------------------------------------------------------------------- */
 const char* dat_status_string(dat_status s);
 /* Text of the last HIP error seen by this thread's calls ("" if none). */

@@ -81,6 +81,21 @@ _pts = [_sig(n, None, _f32p, _f32p, *([C.c_int] * 8), _i64p, C.c_int, _f64p)
 _lamb = _sig("orc_lamb_update", None, _f32p, _f32p, _f32p, _f32p, _i64p, C.c_int, C.c_int, *([C.c_double] * 7), C.c_int)
 _aggregate = _sig("orc_aggregate", None, C.c_void_p, C.c_void_p, C.c_int, _i64p, C.c_int, C.c_int, _f32p)
 _threads = _sig("orc_threads", C.c_int)
+_num_ops = _sig("orc_num_ops", C.c_int, C.c_void_p)
+_num_act = _sig("orc_num_act_tensors", C.c_int, C.c_void_p)
+_op_info = _sig("orc_op_info", None, C.c_void_p, C.c_int, _i32p)
+_tshape = _sig("orc_tensor_shape", None, C.c_void_p, C.c_int, _i32p)
+_begin = _sig("orc_begin", None, C.c_void_p, _f32p, C.c_int)
+_fwd_op = _sig("orc_forward_op", None, C.c_void_p, C.c_int)
+_loss_bwd = _sig("orc_loss_backward_begin", C.c_double, C.c_void_p, _i32p, C.c_double)
+_bwd_op = _sig("orc_backward_op", None, C.c_void_p, C.c_int, C.c_int)
+_grad_present = _sig("orc_grad_present", C.c_int, C.c_void_p, C.c_int)
+_get_tensor = _sig("orc_get_tensor", None, C.c_void_p, C.c_int, C.c_int, _f32p)
+_set_tensor = _sig("orc_set_tensor", None, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int)
+_cmp_tensor = _sig("orc_compare_tensor", None, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_double, C.c_double, _f64p)
+_bn_stats = _sig("orc_get_bn_stats", None, C.c_void_p, C.c_int, _f64p, _f64p)
+_param_grads = _sig("orc_get_param_grads", None, C.c_void_p, _f64p)
+_pixel_grad = _sig("orc_pixel_grad", None, C.c_void_p, _f32p)
 
 
 def _opt(a):
@@ -207,6 +222,82 @@ class Model:
 
     def sgd_update(self, grads, lr):
         _sgd(self._h, np.ascontiguousarray(grads, np.float32), lr)
+
+    # ---- op-by-op stepping (teacher-forced comparisons); which: 0 activations, 1 gradients ----
+    def ops(self):
+        """List of dicts (kind, in, out, res, k, stride, pad, relu, p0, p1), in op order."""
+        names = ("kind", "in", "out", "res", "k", "stride", "pad", "relu", "p0", "p1")
+        out = []
+        for i in range(int(_num_ops(self._h))):
+            info = np.zeros(10, np.int32)
+            _op_info(self._h, i, info)
+            out.append(dict(zip(names, (int(v) for v in info))))
+        return out
+
+    def tensor_shapes(self):
+        out = []
+        for t in range(int(_num_act(self._h))):
+            hwc = np.zeros(3, np.int32)
+            _tshape(self._h, t, hwc)
+            out.append(tuple(int(v) for v in hwc))
+        return out
+
+    def begin(self, x):
+        x = np.ascontiguousarray(x, np.float32)
+        self._B = x.shape[0]
+        _begin(self._h, x, self._B)
+
+    def forward_op(self, i):
+        _fwd_op(self._h, i)
+
+    def loss_backward_begin(self, y, scale):
+        return float(_loss_bwd(self._h, np.ascontiguousarray(y, np.int32), float(scale)))
+
+    def backward_op(self, i, want_wgrad):
+        _bwd_op(self._h, i, int(bool(want_wgrad)))
+
+    def grad_present(self, t):
+        return int(_grad_present(self._h, t))
+
+    def _numel(self, t):
+        hwc = np.zeros(3, np.int32)
+        _tshape(self._h, t, hwc)
+        return self._B * int(hwc[0]) * int(hwc[1]) * int(hwc[2])
+
+    def get_tensor(self, which, t):
+        out = np.zeros(self._numel(t), np.float32)
+        _get_tensor(self._h, which, t, out)
+        return out
+
+    def set_tensor(self, which, t, values):
+        """values: float32 array, or uint16 array of bf16 bit patterns."""
+        values = np.ascontiguousarray(values)
+        assert values.size == self._numel(t) and values.dtype in (np.float32, np.uint16), (values.size, values.dtype)
+        _set_tensor(self._h, which, t, values.ctypes.data_as(C.c_void_p), int(values.dtype == np.uint16))
+
+    def compare_tensor(self, which, t, got, rel, abs_frac):
+        """Element-wise |got - ref| <= rel*|ref| + abs_frac*max|ref|; returns a dict of counts and maxima."""
+        got = np.ascontiguousarray(got)
+        assert got.size == self._numel(t) and got.dtype in (np.float32, np.uint16), (got.size, got.dtype)
+        st = np.zeros(8, np.float64)
+        _cmp_tensor(self._h, which, t, got.ctypes.data_as(C.c_void_p), int(got.dtype == np.uint16), float(rel), float(abs_frac), st)
+        return dict(n=int(st[0]), exact=int(st[1]), viol=int(st[2]), worst=float(st[3]), max_ref=float(st[4]),
+                    max_err=float(st[5]), nonfinite=int(st[6]), worst_index=int(st[7]))
+
+    def bn_stats(self, op_index, C_):
+        mean, rstd = np.zeros(C_, np.float64), np.zeros(C_, np.float64)
+        _bn_stats(self._h, op_index, mean, rstd)
+        return mean, rstd
+
+    def param_grads(self):
+        out = np.zeros(self.d, np.float64)
+        _param_grads(self._h, out)
+        return out
+
+    def pixel_grad(self, shape):
+        out = np.zeros(shape, np.float32)
+        _pixel_grad(self._h, out.reshape(-1))
+        return out
 
 
 def init_delta(x, eps, mode, seed=0, given=None):

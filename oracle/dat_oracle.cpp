@@ -463,14 +463,21 @@ void bnact_forward(Model& m, int opi, int B) {
   int64_t rows = (int64_t)B * s.H * s.W;
   std::vector<double>& mu = m.bn_mean[opi]; std::vector<double>& rs = m.bn_rstd[opi];
   mu.assign(s.C, 0.0); rs.assign(s.C, 0.0);
+  // (channels are walked eight at a time so that a cache line is read once; every channel's sums
+  // still run over the rows in order, one add per row)
 #pragma omp parallel for schedule(static)
-  for (int c = 0; c < s.C; ++c) {
-    double sum = 0.0;
-    for (int64_t i = 0; i < rows; ++i) sum += in[i * s.C + c];
-    double mean = sum / (double)rows, sq = 0.0;
-    for (int64_t i = 0; i < rows; ++i) { double dlt = in[i * s.C + c] - mean; sq += dlt * dlt; }
-    mu[c] = mean;
-    rs[c] = 1.0 / std::sqrt(sq / (double)rows + 1e-5);
+  for (int c0 = 0; c0 < s.C; c0 += 8) {
+    const int nc = std::min(8, s.C - c0);
+    double sum[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sq[8] = {0, 0, 0, 0, 0, 0, 0, 0}, mean[8];
+    for (int64_t i = 0; i < rows; ++i)
+      for (int j = 0; j < nc; ++j) sum[j] += in[i * s.C + c0 + j];
+    for (int j = 0; j < nc; ++j) mean[j] = sum[j] / (double)rows;
+    for (int64_t i = 0; i < rows; ++i)
+      for (int j = 0; j < nc; ++j) { double dlt = in[i * s.C + c0 + j] - mean[j]; sq[j] += dlt * dlt; }
+    for (int j = 0; j < nc; ++j) {
+      mu[c0 + j] = mean[j];
+      rs[c0 + j] = 1.0 / std::sqrt(sq[j] / (double)rows + 1e-5);
+    }
   }
 #pragma omp parallel for schedule(static)
   for (int64_t i = 0; i < rows; ++i)
@@ -508,13 +515,16 @@ void bnact_backward(Model& m, int opi, int B) {
     for (int64_t i = 0; i < rows * s.C; ++i) sink.put(i, dy[i]);
   }
 #pragma omp parallel for schedule(static)
-  for (int c = 0; c < s.C; ++c) {
-    double sb = 0.0, sg = 0.0;
-    for (int64_t i = 0; i < rows; ++i) {
-      double xh = (in[i * s.C + c] - mu[c]) * rs[c];
-      sb += dy[i * s.C + c]; sg += dy[i * s.C + c] * xh;
-    }
-    dbeta[c] = sb; dgamma[c] = sg;
+  for (int c0 = 0; c0 < s.C; c0 += 8) {   // (eight channels per cache line; per channel the rows in order)
+    const int nc = std::min(8, s.C - c0);
+    double sb[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sg[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int64_t i = 0; i < rows; ++i)
+      for (int j = 0; j < nc; ++j) {
+        const int c = c0 + j;
+        double xh = (in[i * s.C + c] - mu[c]) * rs[c];
+        sb[j] += dy[i * s.C + c]; sg[j] += dy[i * s.C + c] * xh;
+      }
+    for (int j = 0; j < nc; ++j) { dbeta[c0 + j] = sb[j]; dgamma[c0 + j] = sg[j]; }
   }
   GradSink sink(m, op.in);
   const double invM = 1.0 / (double)rows;
@@ -1347,6 +1357,148 @@ void orc_conv_bwd_weight_points(const float* x, const float* dy, int B, int H, i
     out[q] = acc;
   }
 }
+
+// ----------------------------------------------------------------------------------------
+// Op-by-op stepping, for teacher-forced comparisons of another implementation's stored
+// tensors with this reference.  Nothing below does arithmetic of the method: it runs the
+// layer functions above one op at a time, copies tensors in and out, and counts differences.
+//   which: 0 = activation tensors, 1 = their gradients.
+// ----------------------------------------------------------------------------------------
+int orc_num_ops(void* h) { return (int)((Model*)h)->ops.size(); }
+int orc_num_act_tensors(void* h) { return (int)((Model*)h)->tens.size(); }
+
+// info[10] = kind (0 conv, 1 bias+act, 2 BN+act, 3 max-pool, 4 global pool, 5 linear), in, out, res,
+//            k, stride, pad, relu, p0, p1
+void orc_op_info(void* h, int i, int32_t* info) {
+  const Op& op = ((Model*)h)->ops[(size_t)i];
+  const int32_t v[10] = {(int32_t)op.kind, op.in, op.out, op.res, op.k, op.stride, op.pad, op.relu, op.p0, op.p1};
+  std::copy(v, v + 10, info);
+}
+
+void orc_tensor_shape(void* h, int t, int32_t* hwc) {
+  const Shape s = ((Model*)h)->tens[(size_t)t];
+  hwc[0] = s.H; hwc[1] = s.W; hwc[2] = s.C;
+}
+
+// Allocates the per-call state for batch B and loads the network input from pixels x.
+void orc_begin(void* h, const float* x, int B) {
+  Model* m = (Model*)h;
+  prepare(*m, B);
+  load_input(*m, x, B);
+  std::fill(m->ghas.begin(), m->ghas.end(), 0);
+}
+
+void orc_forward_op(void* h, int i) {
+  Model* m = (Model*)h;
+  const Op& op = m->ops[(size_t)i];
+  switch (op.kind) {
+    case OP_CONV: conv_forward(*m, op, m->B); break;
+    case OP_BIASACT: biasact_forward(*m, op, m->B); break;
+    case OP_BNACT: bnact_forward(*m, i, m->B); break;
+    case OP_MAXPOOL: maxpool_forward(*m, op, m->B); break;
+    case OP_GAP: gap_forward(*m, op, m->B); break;
+    case OP_FC: fc_forward(*m, op, m->B); break;
+  }
+}
+
+// Installs the logit gradient of the cross-entropy (scale 1: sum over the batch, 1/B: mean) and
+// clears every other gradient slot.  Returns the mean loss.
+double orc_loss_backward_begin(void* h, const int32_t* y, double scale) {
+  Model* m = (Model*)h;
+  return ce_loss_and_grad(*m, y, m->B, scale);
+}
+
+void orc_backward_op(void* h, int i, int want_wgrad) {
+  Model* m = (Model*)h;
+  const Op& op = m->ops[(size_t)i];
+  switch (op.kind) {
+    case OP_CONV: conv_backward(*m, op, m->B, want_wgrad != 0); break;
+    case OP_BIASACT: biasact_backward(*m, op, m->B); break;
+    case OP_BNACT: bnact_backward(*m, i, m->B); break;
+    case OP_MAXPOOL: maxpool_backward(*m, op, m->B); break;
+    case OP_GAP: gap_backward(*m, op, m->B); break;
+    case OP_FC: fc_backward(*m, op, m->B); break;
+  }
+}
+
+int orc_grad_present(void* h, int t) { return ((Model*)h)->ghas[(size_t)t]; }
+
+static std::vector<double>& tensor_of(Model* m, int which, int t) { return which ? m->gact[(size_t)t] : m->act[(size_t)t]; }
+
+static inline double bf16_bits_to_double(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16; float f; std::memcpy(&f, &u, 4); return (double)f;
+}
+
+void orc_get_tensor(void* h, int which, int t, float* out) {
+  Model* m = (Model*)h;
+  const std::vector<double>& v = tensor_of(m, which, t);
+  const int64_t n = (int64_t)m->B * m->tens[(size_t)t].numel();
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i) out[i] = (float)v[(size_t)i];
+}
+
+// src: fp32 values (is_bf16 = 0) or bf16 bit patterns (is_bf16 = 1), B * numel(t) of them.
+void orc_set_tensor(void* h, int which, int t, const void* src, int is_bf16) {
+  Model* m = (Model*)h;
+  std::vector<double>& v = tensor_of(m, which, t);
+  const int64_t n = (int64_t)m->B * m->tens[(size_t)t].numel();
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i)
+    v[(size_t)i] = is_bf16 ? bf16_bits_to_double(((const uint16_t*)src)[i]) : (double)((const float*)src)[i];
+  if (which) m->ghas[(size_t)t] = 1;
+}
+
+// Element-by-element comparison of `got` (fp32 values or bf16 bit patterns) with tensor t:
+// an element violates when |got - ref| > rel*|ref| + abs_frac*max|ref| (max over the tensor).
+// stats[8] = { count, exactly equal, violations, max |got-ref| / tolerance, max|ref|, max|got-ref|,
+//              non-finite values in got, index of the worst element }.
+void orc_compare_tensor(void* h, int which, int t, const void* got, int is_bf16, double rel, double abs_frac, double* stats) {
+  Model* m = (Model*)h;
+  const std::vector<double>& v = tensor_of(m, which, t);
+  const int64_t n = (int64_t)m->B * m->tens[(size_t)t].numel();
+  double mx = 0.0;
+#pragma omp parallel for schedule(static) reduction(max : mx)
+  for (int64_t i = 0; i < n; ++i) mx = std::max(mx, std::fabs(v[(size_t)i]));
+  int64_t exact = 0, viol = 0, bad = 0;
+  double worst = 0.0, maxerr = 0.0; int64_t worst_i = -1;
+#pragma omp parallel
+  {
+    int64_t le = 0, lv = 0, lb = 0; double lw = 0.0, lm = 0.0; int64_t li = -1;
+#pragma omp for schedule(static) nowait
+    for (int64_t i = 0; i < n; ++i) {
+      const double g = is_bf16 ? bf16_bits_to_double(((const uint16_t*)got)[i]) : (double)((const float*)got)[i];
+      const double r = v[(size_t)i];
+      if (!(g == g) || std::isinf(g)) { ++lb; ++lv; continue; }
+      const double e = std::fabs(g - r), tol = rel * std::fabs(r) + abs_frac * mx;
+      if (e == 0.0) { ++le; continue; }
+      if (e > tol) ++lv;
+      const double ratio = tol > 0.0 ? e / tol : INFINITY;
+      if (ratio > lw) { lw = ratio; li = i; }
+      lm = std::max(lm, e);
+    }
+#pragma omp critical
+    {
+      exact += le; viol += lv; bad += lb; maxerr = std::max(maxerr, lm);
+      if (lw > worst) { worst = lw; worst_i = li; }
+    }
+  }
+  stats[0] = (double)n; stats[1] = (double)exact; stats[2] = (double)viol; stats[3] = worst;
+  stats[4] = mx; stats[5] = maxerr; stats[6] = (double)bad; stats[7] = (double)worst_i;
+}
+
+// Batch statistics of BN op i from the last forward pass over it; parameter gradients accumulated so far.
+void orc_get_bn_stats(void* h, int i, double* mean, double* rstd) {
+  Model* m = (Model*)h;
+  std::copy(m->bn_mean[(size_t)i].begin(), m->bn_mean[(size_t)i].end(), mean);
+  std::copy(m->bn_rstd[(size_t)i].begin(), m->bn_rstd[(size_t)i].end(), rstd);
+}
+
+void orc_get_param_grads(void* h, double* out) {
+  Model* m = (Model*)h;
+  std::copy(m->gtheta.begin(), m->gtheta.end(), out);
+}
+
+void orc_pixel_grad(void* h, float* gx) { Model* m = (Model*)h; pixel_grad(*m, m->B, gx); }
 
 int orc_threads() {
 #ifdef _OPENMP

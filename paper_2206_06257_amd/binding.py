@@ -22,6 +22,7 @@ EXPORTS = [
     "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
     "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read", "dat_aggregate", "dat_lamb_update",
     "dat_attack_kl", "dat_step_reg", "dat_model_set_option", "dat_make_xadv",
+    "dat_inspect_counts", "dat_inspect_op", "dat_inspect_tensor", "dat_inspect_read", "dat_inspect_bn",
 ]
 
 
@@ -78,6 +79,11 @@ _lib.dat_lamb_update.argtypes = [_vp, _vp, _i, _f, _f, _f, _f, _f, _f, _f, _i, _
 _lib.dat_attack_kl.argtypes = [_vp, _vp, _i, _f, _f, _i, _Init, _vp, _vp, _vp]
 _lib.dat_step_reg.argtypes = [_vp, _vp, _vp, _vp, _i, _f, _i, _vp, _vp, _vp]
 _lib.dat_profile_enable.argtypes = [_vp, _i]
+_lib.dat_inspect_counts.argtypes = [_vp, C.POINTER(_i), C.POINTER(_i)]
+_lib.dat_inspect_op.argtypes = [_vp, _i, _vp]
+_lib.dat_inspect_tensor.argtypes = [_vp, _i, _vp]
+_lib.dat_inspect_read.argtypes = [_vp, _i, _i, _i, _vp, C.c_size_t]
+_lib.dat_inspect_bn.argtypes = [_vp, _i, _vp, _vp]
 _lib.dat_model_set_option.argtypes = [_vp, _i, _i]
 OPT_FUSE_BN_INPUT_GRAD = 0
 OPT_FUSE_BN_SUMS = 1
@@ -224,6 +230,41 @@ class Model:
     def offsets_device(self):
         """int64 device pointer to the tensor table (owned by the model)."""
         return self.offsets_device_ptr
+
+    # ---- introspection (parity tests) ----
+    def inspect_ops(self):
+        n_ops, n_t = _i(), _i()
+        _check(_lib.dat_inspect_counts(self._h, C.byref(n_ops), C.byref(n_t)), "dat_inspect_counts")
+        names = ("kind", "in", "out", "res", "k", "stride", "pad", "relu", "p0", "p1")
+        ops = []
+        for i in range(n_ops.value):
+            info = np.zeros(10, np.int32)
+            _check(_lib.dat_inspect_op(self._h, i, info.ctypes.data), "dat_inspect_op")
+            ops.append(dict(zip(names, (int(v) for v in info))))
+        return ops
+
+    def inspect_tensors(self):
+        n_ops, n_t = _i(), _i()
+        _check(_lib.dat_inspect_counts(self._h, C.byref(n_ops), C.byref(n_t)), "dat_inspect_counts")
+        names = ("H", "W", "C", "elem_bytes", "act_stored", "grad_stored")
+        out = []
+        for t in range(n_t.value):
+            info = np.zeros(6, np.int32)
+            _check(_lib.dat_inspect_tensor(self._h, t, info.ctypes.data), "dat_inspect_tensor")
+            out.append(dict(zip(names, (int(v) for v in info))))
+        return out
+
+    def inspect_read(self, which, t, B, info):
+        """Raw stored elements of tensor t (which = 0) or its gradient (1): uint16 bf16 bit patterns or float32."""
+        n = B * info["H"] * info["W"] * info["C"]
+        out = np.empty(n, np.uint16 if info["elem_bytes"] == 2 else np.float32)
+        _check(_lib.dat_inspect_read(self._h, which, t, B, out.ctypes.data, out.nbytes), "dat_inspect_read")
+        return out
+
+    def inspect_bn(self, op, C_):
+        mean, rstd = np.zeros(C_, np.float32), np.zeros(C_, np.float32)
+        _check(_lib.dat_inspect_bn(self._h, op, mean.ctypes.data, rstd.ctypes.data), "dat_inspect_bn")
+        return mean, rstd
 
 
 def pgd_init(x, eps, init=INIT_ZERO, seed=0, delta0=None, delta=None, stream=None):

@@ -1074,3 +1074,61 @@ extern "C" dat_status dat_lamb_update(dat_model* m, const float* grads, int use_
   DAT_TRY(refresh_compute(*m, st));
   return DAT_OK;
 }
+
+// ---- introspection for parity tests ---------------------------------------------------------------
+extern "C" dat_status dat_inspect_counts(const dat_model* m, int* num_ops, int* num_tensors) {
+  if (!m) return DAT_ERR_ARG;
+  if (num_ops) *num_ops = (int)m->ops.size();
+  if (num_tensors) *num_tensors = (int)m->tens.size();
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_inspect_op(const dat_model* m, int op, int32_t* info) {
+  if (!m || !info || op < 0 || op >= (int)m->ops.size()) return DAT_ERR_ARG;
+  const Op& o = m->ops[op];
+  const int32_t v[10] = {(int32_t)o.kind, o.in, o.out, o.res, o.k, o.stride, o.pad, o.relu, o.p0, o.p1};
+  for (int i = 0; i < 10; ++i) info[i] = v[i];
+  return DAT_OK;
+}
+
+namespace {
+// Activation tensors that exist in the layer graph but are never written in plain NHWC form by this model.
+bool act_stored(const dat_model& m, int t) {
+  if (t == 0) return m.dtype != DAT_BF16;   // bf16 network input: channels padded to 8, 2x2 pixel blocks behind a 7x7/2 stem
+  for (const Op& o : m.ops) {
+    if (o.out != t || o.kind != OP_BNACT) continue;
+    if (o.absorbed_by >= 0) return false;
+    if (o.pool >= 0 && m.fuse_pool) return false;
+  }
+  return true;
+}
+}  // namespace
+
+extern "C" dat_status dat_inspect_tensor(const dat_model* m, int t, int32_t* info) {
+  if (!m || !info || t < 0 || t >= (int)m->tens.size()) return DAT_ERR_ARG;
+  const Shape s = m->tens[t];
+  info[0] = s.H; info[1] = s.W; info[2] = s.C;
+  info[3] = m->is_f32[t] ? 4 : m->esize();
+  info[4] = act_stored(*m, t) ? 1 : 0;
+  info[5] = (act_stored(*m, t) && m->ghas[t] == 1) ? 1 : 0;
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_inspect_read(dat_model* m, int which, int t, int B, void* host_dst, size_t bytes) {
+  if (!m || !host_dst || t < 0 || t >= (int)m->tens.size() || (which != 0 && which != 1)) return DAT_ERR_ARG;
+  if (!batch_ok(m, B)) return DAT_ERR_SHAPE;
+  const size_t want = (size_t)B * m->tens[t].numel() * (m->is_f32[t] ? 4 : m->esize());
+  if (bytes != want) return DAT_ERR_ARG;
+  DAT_HIP(hipDeviceSynchronize());
+  DAT_HIP(hipMemcpy(host_dst, which ? m->grad[t] : m->act[t], bytes, hipMemcpyDeviceToHost));
+  return DAT_OK;
+}
+
+extern "C" dat_status dat_inspect_bn(dat_model* m, int op, float* mean_host, float* rstd_host) {
+  if (!m || !mean_host || !rstd_host || op < 0 || op >= (int)m->ops.size() || m->ops[op].kind != OP_BNACT) return DAT_ERR_ARG;
+  const size_t bytes = (size_t)m->tens[m->ops[op].in].C * 4;
+  DAT_HIP(hipDeviceSynchronize());
+  DAT_HIP(hipMemcpy(mean_host, m->ops[op].mean, bytes, hipMemcpyDeviceToHost));
+  DAT_HIP(hipMemcpy(rstd_host, m->ops[op].rstd, bytes, hipMemcpyDeviceToHost));
+  return DAT_OK;
+}
