@@ -226,6 +226,22 @@ dat_status dat_conv_backward_weight(const uint16_t* x, const uint16_t* dy, float
                                     int H, int W, int Cin, int Cout, int k, int stride, int pad,
                                     void* stream);
 
+/* The same backward-weight contraction for callers that cannot allocate device memory (code under HIP graph
+ * capture, serving loops that must not call hipMalloc, harnesses that forbid it): it calls no hipMalloc, hipFree
+ * or other allocating routine and does not synchronise.  The split partial sums of the contraction, which
+ * dat_conv_backward_weight keeps in a workspace allocated per call, go to a buffer of
+ * dat_conv_backward_weight_static_limit() = 32 MiB that is part of the library's device image (each GPU the
+ * library runs on holds it until the process ends).  Same arguments, same kernels, same bits as
+ * dat_conv_backward_weight.  Returns DAT_ERR_UNSUPPORTED (text in dat_last_error) when the shape's partial sums
+ * (splits * Cout*k*k*Cin * 4 bytes; the split count grows with B*Ho*Wo) do not fit, and launches nothing then.
+ * All calls on one GPU share that buffer: calls that overlap in time on one GPU (different streams or threads)
+ * race; calls on one stream are ordered and safe.  Nothing in the buffer needs clearing between calls: every
+ * partial sum a call reads was written by its own first launch. */
+dat_status dat_conv_backward_weight_static(const uint16_t* x, const uint16_t* dy, float* dw, int B, int H,
+                                           int W, int Cin, int Cout, int k, int stride, int pad,
+                                           void* stream);
+size_t dat_conv_backward_weight_static_limit(void);
+
 /* ---- per-launch timing (for benchmarks; not part of the paper's method) ----------------------
  * While enabled, every launch group of dat_attack / dat_step / dat_input_grad on this model is
  * bracketed by a hipEvent pair on the caller's stream.  dat_profile_read synchronises the device

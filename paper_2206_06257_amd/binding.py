@@ -22,6 +22,7 @@ EXPORTS = [
     "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
     "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read", "dat_aggregate", "dat_lamb_update",
     "dat_attack_kl", "dat_step_reg", "dat_model_set_option", "dat_make_xadv",
+    "dat_conv_backward_weight_static", "dat_conv_backward_weight_static_limit",
     "dat_inspect_counts", "dat_inspect_op", "dat_inspect_tensor", "dat_inspect_read", "dat_inspect_bn",
 ]
 
@@ -31,7 +32,7 @@ class DatError(RuntimeError):
         self.status = int(status)
         msg = _lib.dat_status_string(status).decode()
         extra = _lib.dat_last_error().decode()
-        super().__init__("%s: %s (%d)%s" % (where, msg, self.status, (" -- " + extra) if extra and self.status == 5 else ""))
+        super().__init__("%s: %s (%d)%s" % (where, msg, self.status, (" -- " + extra) if extra and self.status in (5, 6) else ""))
 
 
 def _load():
@@ -71,7 +72,9 @@ _lib.dat_quantize.argtypes = [_vp, _vp, _i, _i64, _i, _u64, _vp, _vp, _vp]
 _lib.dat_dequantize.argtypes = [_vp, _vp, _vp, _i, _i64, _i, _vp, _vp]
 _lib.dat_quantized_bytes.restype = C.c_size_t
 _lib.dat_quantized_bytes.argtypes = [_i64, _i]
-for _n in ("dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight"):
+_lib.dat_conv_backward_weight_static_limit.restype = C.c_size_t
+_lib.dat_conv_backward_weight_static_limit.argtypes = []
+for _n in ("dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight", "dat_conv_backward_weight_static"):
     getattr(_lib, _n).argtypes = [_vp, _vp, _vp] + [_i] * 8 + [_vp]
 _lib.dat_philox_uniform.argtypes = [_u64, _i64, _u64, C.c_uint32, _vp, _vp]
 _lib.dat_aggregate.argtypes = [_vp, _vp, _i, _vp, _i, _i64, _i, _vp, _vp]
@@ -369,10 +372,18 @@ def conv_backward_data(dy, w, in_hw, stride, pad, stream=None):
     return dx
 
 
-def conv_backward_weight(x, dy, k, stride, pad, stream=None):
+def conv_backward_weight(x, dy, k, stride, pad, stream=None, dw=None, static=False):
+    """static: through dat_conv_backward_weight_static (no allocation inside the call; pass `dw`)."""
     _dev(x, torch.bfloat16); _dev(dy, torch.bfloat16)
     B, H, W, Cin = x.shape
     Cout = dy.shape[3]
-    dw = torch.empty(Cout, k, k, Cin, dtype=torch.float32, device=x.device)
-    _check(_lib.dat_conv_backward_weight(_ptr(x), _ptr(dy), _ptr(dw), B, H, W, Cin, Cout, k, stride, pad, _stream(stream)), "dat_conv_backward_weight")
+    if dw is None:
+        dw = torch.empty(Cout, k, k, Cin, dtype=torch.float32, device=x.device)
+    fn, name = (_lib.dat_conv_backward_weight_static, "dat_conv_backward_weight_static") if static else \
+               (_lib.dat_conv_backward_weight, "dat_conv_backward_weight")
+    _check(fn(_ptr(x), _ptr(dy), _ptr(dw), B, H, W, Cin, Cout, k, stride, pad, _stream(stream)), name)
     return dw
+
+
+def conv_backward_weight_static_limit():
+    return int(_lib.dat_conv_backward_weight_static_limit())

@@ -9,6 +9,9 @@ namespace dat {
 // Records the text of a failed HIP call for dat_last_error() and maps it to DAT_ERR_HIP.
 dat_status hip_fail(hipError_t e, const char* what, const char* file, int line);
 
+// Records a message of the library's own for dat_last_error() and returns `status`.
+dat_status fail_with(dat_status status, const char* text);
+
 #define DAT_HIP(call)                                                              \
   do {                                                                             \
     hipError_t e_ = (call);                                                        \

@@ -34,6 +34,7 @@
 // consecutive pixels of its channel.  The pixel range is split over gridDim.z; partial tiles go to a workspace
 // and a second kernel sums them in a fixed order (deterministic).
 #include <atomic>
+#include <mutex>
 #include <cstdlib>
 #include "kernels.h"
 
@@ -1516,4 +1517,51 @@ extern "C" dat_status dat_conv_backward_weight(const uint16_t* x, const uint16_t
   (void)hipStreamSynchronize(st);
   (void)hipFree(ws);
   return s;
+}
+
+// ---- backward-weight without any allocation ------------------------------------------------------
+// The split partial tiles of wgrad_kernel go to a buffer that is part of the library's device image instead
+// of a workspace allocated per call: for callers that may not allocate (stream capture, serving loops).
+// Each GPU holds its own copy of the array at its own address; in host code the array's name is only a handle
+// for hipGetSymbolAddress, so the address is looked up once per device and that pointer is what the kernels get.
+#define DAT_STATIC_SCRATCH_BYTES (32u << 20)
+static __device__ __align__(256) unsigned char scratch[DAT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+dat_status static_scratch(void** out) {
+  int dev = -1;
+  DAT_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail_with(DAT_ERR_UNSUPPORTED, "device ordinal beyond the static scratch table");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    DAT_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail_with(DAT_ERR_HIP, "hipGetSymbolAddress returned a null address for the static scratch");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DAT_OK;
+}
+}  // namespace
+
+extern "C" size_t dat_conv_backward_weight_static_limit(void) { return (size_t)DAT_STATIC_SCRATCH_BYTES; }
+
+extern "C" dat_status dat_conv_backward_weight_static(const uint16_t* x, const uint16_t* dy, float* dw, int B, int H, int W,
+                                                      int Cin, int Cout, int k, int stride, int pad, void* stream) {
+  ConvGeom g;
+  if (!x || !dy || !dw || !geom_from(B, H, W, Cin, Cout, k, stride, pad, &g)) return DAT_ERR_ARG;
+  if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(dw, 16)) return DAT_ERR_ARG;
+  if (conv_mfma_wgrad_workspace(g) > (size_t)DAT_STATIC_SCRATCH_BYTES)
+    return fail_with(DAT_ERR_UNSUPPORTED, "dat_conv_backward_weight_static: the split partial sums of this shape exceed the 32 MiB static scratch "
+                                          "(use dat_conv_backward_weight)");
+  void* ws = nullptr;
+  const dat_status s = static_scratch(&ws);
+  if (s != DAT_OK) return s;
+  // every partial tile the reduction reads is written by this call's first launch: nothing to clear
+  return conv_mfma_backward_weight(x, dy, dw, Cin, g, 1.0f, ws, (hipStream_t)stream);
 }

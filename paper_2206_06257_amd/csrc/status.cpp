@@ -9,6 +9,12 @@ dat_status hip_fail(hipError_t e, const char* what, const char* file, int line) 
   snprintf(g_err, sizeof(g_err), "%s (%d) from %s at %s:%d", hipGetErrorString(e), (int)e, what, file, line);
   return DAT_ERR_HIP;
 }
+
+// Records a message of the library's own for dat_last_error() and returns `status`.
+dat_status fail_with(dat_status status, const char* text) {
+  snprintf(g_err, sizeof(g_err), "%s", text);
+  return status;
+}
 }  // namespace dat
 
 extern "C" const char* dat_last_error(void) { return dat::g_err; }
