@@ -39,9 +39,9 @@ PEAK_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 
-def cpu_baseline(arch, H, W, classes, K, eps, alpha, norm):
-    """CPU reference on a bounded sample: B=8 images, one attack iteration + the outer step,
-    extrapolated to K attack iterations per example."""
+def cpu_baseline(arch, H, W, classes, K, eps, alpha, norm, bits):
+    """CPU reference, as it stands, on a bounded sample of the same workload: the whole step (all K attack
+    iterations, the outer gradient, quantize + dequantize) for B=8 images of the configured shape."""
     import oracle
     import synth_inputs as syn
     B = 8
@@ -49,21 +49,35 @@ def cpu_baseline(arch, H, W, classes, K, eps, alpha, norm):
     m.set_params(syn.he_normal_params(0, m.offsets, m.fan_in, m.kind))
     x, y = syn.images(0, B, H, W), syn.labels(0, B, classes)
     t0 = time.time()
-    d = m.attack(x, y, eps, alpha, 1, oracle.INIT_UNIFORM, seed=1)
+    d = m.attack(x, y, eps, alpha, K, oracle.INIT_UNIFORM, seed=1)
     t1 = time.time()
-    m.step(oracle.make_xadv(x, d), y)
+    g, _ = m.step(oracle.make_xadv(x, d), y)
     t2 = time.time()
-    per_example = (K * (t1 - t0) + (t2 - t1)) / B
-    return {"value": 1.0 / per_example, "unit": "examples/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": "B=%d images of the same shape: 1 attack iteration (%.1f s) + outer step (%.1f s), "
-                      "extrapolated to K=%d iterations per example" % (B, t1 - t0, t2 - t1, K)}
+    S = oracle.levels(bits)
+    codes, scales = oracle.quantize(g, m.offsets, S, 1)
+    oracle.dequantize(codes, scales, m.offsets, S)
+    t3 = time.time()
+    return {"value": B / (t3 - t0), "unit": "examples/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "the whole step for B=%d images of the same shape (BN batch statistics over 8 instead of 256 images): "
+                      "%d attack iterations %.1f s, outer gradient %.1f s, quantize + dequantize %.1f s" % (B, K, t1 - t0, t2 - t1, t3 - t2)}
+
+
+def source_hash():
+    """sha256 over the kernel sources: ties stored profiler figures to the code they were measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2206_06257_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50_224_b256_pgd10", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=8)
     ap.add_argument("--phi", default="ce", choices=["ce", "trades"],
@@ -130,10 +144,13 @@ def main():
             model.step(xadv, y, grads=grads)
         if marks:
             marks[1].record()
-        dat.quantize(grads, offs, args.bits, seed_q + i, q=q, scales=scales)
+        if general:    # two passes: the sum's abs-max is not a by-product, the quantizer finds it itself
+            dat.quantize(grads, offs, args.bits, seed_q + i, q=q, scales=scales)
+        else:          # the gradient writers of dat_step left the per-tensor abs-max behind: only the encoder runs
+            dat.quantize_scaled(grads, offs, args.bits, seed_q + i, model.grad_scales(), q=q)
         if marks:
             marks[2].record()
-        dat.dequantize(q, scales, offs, model.d, args.bits, out=deq)
+        dat.dequantize(q, scales if general else model.grad_scales(), offs, model.d, args.bits, out=deq)
         if marks:
             marks[3].record()
 
@@ -150,6 +167,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_step = [starts[i].elapsed_time(ev[i][3]) for i in range(args.steps)]   # event time of every timed step
     # ---- the same steps once more with a hipEvent pair around every launch (per-kernel-class times
     # for the roofline); kept out of the timed region because ~2700 event pairs per step cost ~7 %
     prof = None
@@ -163,15 +181,16 @@ def main():
         prof = model.profile_read()
         model.profile_enable(False)
 
-    t_attack = np.mean([starts[i].elapsed_time(ev[i][0]) for i in range(args.steps)])
-    t_step = np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(args.steps)])
-    t_quant = np.mean([ev[i][1].elapsed_time(ev[i][2]) for i in range(args.steps)])
-    t_deq = np.mean([ev[i][2].elapsed_time(ev[i][3]) for i in range(args.steps)])
+    t_attack = float(np.median([starts[i].elapsed_time(ev[i][0]) for i in range(args.steps)]))
+    t_step = float(np.median([ev[i][0].elapsed_time(ev[i][1]) for i in range(args.steps)]))
+    t_quant = float(np.median([ev[i][1].elapsed_time(ev[i][2]) for i in range(args.steps)]))
+    t_deq = float(np.median([ev[i][2].elapsed_time(ev[i][3]) for i in range(args.steps)]))
 
     out = {
         "metric": "PGD-10 adv examples/s + train imgs/s (ResNet-50 224, 1 GPU); % MFMA/HBM peak",
         "value": B / (ms_per_step * 1e-3), "unit": "examples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "ms_per_step_median": float(np.median(per_step)), "ms_per_step_min": float(np.min(per_step)),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": B, "image": [H, W, 3], "pgd_steps": K, "eps": eps, "alpha": alpha,
                    "quantizer_bits": args.bits, "params": model.d, "phi": args.phi, "lambda": args.lam},
@@ -188,14 +207,23 @@ def main():
         n = prof["conv_fwd"][1] + prof["conv_bwd_data"][1]
         flops = prof["conv_fwd"][2] + prof["conv_bwd_data"][2]
         ach = flops / (ms * 1e-3) / 1e12
-        traffic = None
+        # HBM bytes per launch cannot be counted from inside this process: the figure comes from the two rocprofv3 --pmc
+        # runs summarised under profiles/, and is reported only while the kernel sources are the ones it was measured on
+        traffic, traffic_note = None, "no stored FETCH_SIZE / WRITE_SIZE figure for this workload"
         tpath = os.path.join(ROOT, "profiles", "traffic_igemm_" + args.workload + ".json")
         if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            stored = json.load(open(tpath))
+            if stored.get("source_hash") == source_hash():
+                traffic = stored.get("hbm_bytes_per_launch")
+                traffic_note = "from profiles/%s (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of this workload; kernel sources unchanged since)" % os.path.basename(tpath)
+            else:
+                traffic_note = "profiles/%s was measured on other kernel sources (hash %s, now %s): not reported" % (
+                    os.path.basename(tpath), stored.get("source_hash"), source_hash())
         out["roofline"] = {"bound": "mfma", "kernel": "igemm_dma_kernel + igemm_ring_kernel + igemm_kernel (conv forward + backward-data launches; the few backward-data "
                                                       "launches that also form a batch-norm input gradient from three operand streams are "
                                                       "listed as kernel_classes.conv_bwd_data_bn)", "achieved": ach,
                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
+                           "traffic_source": traffic_note,
                            "launches": n, "avg_launch_ms": ms / max(n, 1), "flops_per_launch": flops / max(n, 1),
                            "achieved_forward": prof["conv_fwd"][2] / (prof["conv_fwd"][0] * 1e-3) / 1e12,
                            "achieved_backward_data": prof["conv_bwd_data"][2] / (prof["conv_bwd_data"][0] * 1e-3) / 1e12,
@@ -221,7 +249,7 @@ def main():
         out["step_conv_TFLOPs"] = total_flops / 1e12
         out["step_frac_mfma_peak"] = total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(arch, H, W, classes, K, eps, alpha, norm)
+        out["cpu_baseline"] = cpu_baseline(arch, H, W, classes, K, eps, alpha, norm, args.bits)
     print(json.dumps(out))
 
 

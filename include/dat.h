@@ -30,6 +30,11 @@
  *   - A DAT_BF16 model stores conv/linear weights, activations and activation gradients in
  *     bf16 and accumulates in fp32 on the matrix cores; a DAT_F32 model keeps everything in
  *     fp32.  Batch-norm runs in train mode (batch statistics) in every pass.
+ *   - Non-finite values.  Device data is never inspected by the host, so a call without a host output cannot
+ *     report them: a NaN input gradient counts as sign 0 (that coordinate of delta stays), a NaN or infinite
+ *     per-tensor scale is written to scales[t] and that tensor's codes are zero.  A call asked for a host loss
+ *     synchronises anyway and returns DAT_ERR_NONFINITE when a loss it fetched is NaN or infinite; its device
+ *     outputs have been written by then (the one exception to "outputs untouched on error").
  *   - Calls on one model, or sharing one stream's buffers, must not overlap in time.
  */
 #ifndef DAT_H
@@ -49,7 +54,7 @@ typedef enum {
   DAT_ERR_ARG = 1,         /* null pointer, negative size, bad enum, misaligned buffer */
   DAT_ERR_SHAPE = 2,       /* batch larger than max_batch, unsupported image size       */
   DAT_ERR_NOMEM = 3,       /* device or host allocation failed                           */
-  DAT_ERR_NONFINITE = 4,   /* a checked value was NaN or Inf                             */
+  DAT_ERR_NONFINITE = 4,   /* a requested host loss value was NaN or Inf (see Conventions) */
   DAT_ERR_HIP = 5,         /* a HIP runtime call failed (see dat_last_error)             */
   DAT_ERR_UNSUPPORTED = 6  /* valid request that this build does not implement           */
 } dat_status;
@@ -110,7 +115,10 @@ dat_status dat_model_get_params(const dat_model* m, float* host_flat);
  *   z_0 per `init`;  for k = 1..K:  G = grad_x sum_n CE(net(x + z_{k-1}), y)
  *     z_k = clip(z_{k-1} + alpha*sign(G), -eps, eps), sign(0) = 0;  z_k = min(max(z_k, -x), 1-x)
  *   delta = z_K (K = 0 returns z_0).  loss_per_step: optional host array of K+1 floats, mean CE
- *   at z_0..z_K (costs one extra forward and a synchronisation). */
+ *   at z_0..z_K (costs one extra forward and a synchronisation).
+ *   A label outside [0, num_classes) is not an error the host can see (labels are device memory): that sample
+ *   gets a NaN loss and a logit gradient without the one-hot term, in every call that takes labels.
+ *   DAT_INIT_GIVEN: delta0 must be 16-byte aligned like x and delta. */
 dat_status dat_attack(dat_model* m, const float* x, const int32_t* y, int B, float eps,
                       float alpha, int K, dat_init init, float* delta, float* loss_per_step,
                       void* stream);
@@ -120,6 +128,16 @@ dat_status dat_attack(dat_model* m, const float* x, const int32_t* y, int B, flo
  * perturbed).  loss: optional host float, mean CE. */
 dat_status dat_step(dat_model* m, const float* x_adv, const int32_t* y, int B, float* grads,
                     float* loss, void* stream);
+
+/* The quantizer's per-tensor scales of the gradient dat_step has just written, max_i |g_i| for every tensor of the
+ * table (Eq. (rand_q): the norm that scales the vector before rounding; per-tensor abs-max here): every kernel
+ * that writes a parameter gradient also raises that tensor's maximum (compared through the bit pattern of |g|,
+ * so the value is exact, independent of order, and a NaN or Inf surfaces as in dat_quantize), which saves the
+ * quantizer's own pass over the gradient.  *scales_dev: device fp32 [num_tensors], owned by the model,
+ * overwritten by the next dat_step; valid for work enqueued after dat_step on the same stream.
+ * DAT_ERR_UNSUPPORTED when the last call on the model did not produce them (fp32 models, models with bias
+ * layers, dat_step_reg with two passes, no dat_step yet): use dat_quantize then. */
+dat_status dat_model_grad_scales(const dat_model* m, const float** scales_dev);
 
 /* One backward-to-input pass: gx[B,H,W,3] (device fp32) = grad_x sum_n CE(net(x), y); logits
  * (optional, device fp32 [B,classes]).  The quantity whose sign drives dat_attack. */
@@ -181,6 +199,12 @@ dat_status dat_sgd_update(dat_model* m, const float* grads, float lr, void* stre
 dat_status dat_quantize(const float* grads, const int64_t* offsets_dev, int num_tensors,
                         int64_t d, int bits, uint64_t seed, uint8_t* q, float* scales,
                         void* stream);
+
+/* The same with the per-tensor scales given instead of computed: `scales` (device fp32 [num_tensors], read only)
+ * must hold max_i |g_i| of each tensor; only the encoder runs.  With the scales of dat_model_grad_scales the
+ * codes are those dat_quantize would write. */
+dat_status dat_quantize_scaled(const float* grads, const int64_t* offsets_dev, int num_tensors, int64_t d,
+                               int bits, uint64_t seed, const float* scales, uint8_t* q, void* stream);
 
 /* grads_out[i] = code_i * (scale_t / S), device fp32 [d], 16-byte aligned. */
 dat_status dat_dequantize(const uint8_t* q, const float* scales, const int64_t* offsets_dev,
@@ -288,19 +312,28 @@ dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* la
  * event that marks its output gradient complete on the caller's stream, and the caller's stream
  * waits for them before the call's work on it ends (fork / join: the call stays asynchronous on
  * `stream`).  0: everything on the caller's stream.  Identical bits either way.
- * Returns DAT_ERR_ARG for an unknown option. */
+ * Returns DAT_ERR_ARG for an unknown option.
+ * DAT_OPT_ABSORB_SHORTCUT_BN (default 1, bf16 models): the batch normalisation on a projection shortcut is
+ * evaluated by the last normalisation of the residual branch (forward) and shares its pass over d(out)
+ * (backward); neither its output nor its output gradient is stored.  0: it runs as passes of its own.
+ * Identical bits either way (with DAT_OPT_FUSE_BN_SUMS = 0; that option's sums depend on the launch graph).
+ * DAT_OPT_FUSE_STEM_POOL (default 1, bf16 models): a BN + ReLU read only by a 3x3/2 max-pool does not store its
+ * output; one forward pass writes the pooled tensor, and the backward pass gathers d(out) from the pool's output
+ * gradient.  0: the pool runs as passes of its own.  Identical bits either way.
+ * DAT_OPT_GRADIENT_SCALES (default 1, bf16 models): the kernels that write parameter gradients in dat_step also
+ * maintain the per-tensor abs-max that dat_model_grad_scales returns.  0: they do not (dat_model_grad_scales then
+ * refuses).  The gradients are the same bits either way.
+ * Options may be changed between calls, not while a call on the model is in flight. */
 typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1, DAT_OPT_FUSE_PGD_GRADIENT = 2,
-               DAT_OPT_SPARSE_SHORTCUT_GRADIENT = 3, DAT_OPT_OVERLAP_WEIGHT_GRADIENTS = 4 } dat_option;
-/* (Two more switches are read from the environment by dat_model_create, because they change the
- * layer graph of a bf16 model.  DAT_KEEP_SHORTCUT_BN: the batch normalisation on a projection
- * shortcut runs as passes of its own instead of being evaluated by the last normalisation of the
- * residual branch.  DAT_KEEP_STEM_POOL: a BN + ReLU read only by a max-pool stores its output and
- * the pool runs as passes of its own, instead of one fused forward pass and a backward pass that
- * gathers d(out) from the pool's output gradient.  Identical bits either way.
- * DAT_NO_RING_KERNEL, read at every convolution launch: layers that would run as one round of
- * 256-channel tiles through the multi-stage kernel go through the 128x128 kernels instead; the
- * convolution outputs are bit-identical, the grouping of the batch-norm partial sums differs.) */
+               DAT_OPT_SPARSE_SHORTCUT_GRADIENT = 3, DAT_OPT_OVERLAP_WEIGHT_GRADIENTS = 4,
+               DAT_OPT_ABSORB_SHORTCUT_BN = 5, DAT_OPT_FUSE_STEM_POOL = 6, DAT_OPT_GRADIENT_SCALES = 7 } dat_option;
 dat_status dat_model_set_option(dat_model* m, dat_option opt, int value);
+/* Process-wide kernel selection (ablations and tests; an atomic flag, read at every convolution launch of every
+ * model and of the dat_conv_* entry points).  DAT_KOPT_RING_KERNEL (default 1): layers that run as one round of
+ * 256-channel tiles go through the multi-stage kernel; 0: through the 128x128 kernels.  The convolution outputs
+ * are bit-identical, the grouping of the batch-norm partial sums differs (256 instead of 128 pixels per slab). */
+typedef enum { DAT_KOPT_RING_KERNEL = 0 } dat_kernel_option;
+dat_status dat_set_kernel_option(dat_kernel_option opt, int value);
 
 /* ---- introspection for parity tests (not part of the paper's method) --------------------------------
  * The layer graph and the tensors a model keeps on the device, so that a test can compare every stored

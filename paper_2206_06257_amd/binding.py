@@ -22,7 +22,7 @@ EXPORTS = [
     "dat_quantized_bytes", "dat_conv_forward", "dat_conv_backward_data", "dat_conv_backward_weight",
     "dat_status_string", "dat_last_error", "dat_philox_uniform", "dat_profile_enable", "dat_profile_read", "dat_aggregate", "dat_lamb_update",
     "dat_attack_kl", "dat_step_reg", "dat_model_set_option", "dat_make_xadv",
-    "dat_conv_backward_weight_static", "dat_conv_backward_weight_static_limit",
+    "dat_conv_backward_weight_static", "dat_conv_backward_weight_static_limit", "dat_set_kernel_option", "dat_model_grad_scales", "dat_quantize_scaled",
     "dat_inspect_counts", "dat_inspect_op", "dat_inspect_tensor", "dat_inspect_read", "dat_inspect_bn",
 ]
 
@@ -70,6 +70,8 @@ _lib.dat_make_xadv.argtypes = [_vp, _vp, _i64, _vp, _vp]
 _lib.dat_sgd_update.argtypes = [_vp, _vp, _f, _vp]
 _lib.dat_quantize.argtypes = [_vp, _vp, _i, _i64, _i, _u64, _vp, _vp, _vp]
 _lib.dat_dequantize.argtypes = [_vp, _vp, _vp, _i, _i64, _i, _vp, _vp]
+_lib.dat_quantize_scaled.argtypes = [_vp, _vp, _i, _i64, _i, _u64, _vp, _vp, _vp]
+_lib.dat_model_grad_scales.argtypes = [_vp, C.POINTER(_vp)]
 _lib.dat_quantized_bytes.restype = C.c_size_t
 _lib.dat_quantized_bytes.argtypes = [_i64, _i]
 _lib.dat_conv_backward_weight_static_limit.restype = C.c_size_t
@@ -93,6 +95,11 @@ OPT_FUSE_BN_SUMS = 1
 OPT_FUSE_PGD_GRADIENT = 2
 OPT_SPARSE_SHORTCUT_GRADIENT = 3
 OPT_OVERLAP_WEIGHT_GRADIENTS = 4
+OPT_ABSORB_SHORTCUT_BN = 5
+OPT_FUSE_STEM_POOL = 6
+OPT_GRADIENT_SCALES = 7
+KOPT_RING_KERNEL = 0
+_lib.dat_set_kernel_option.argtypes = [_i, _i]
 _lib.dat_profile_read.argtypes = [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]
 PROF_CLASSES = ("conv_fwd", "conv_bwd_data", "conv_wgrad", "bn", "pgd", "conv_bwd_data_bn")
 
@@ -234,6 +241,21 @@ class Model:
         """int64 device pointer to the tensor table (owned by the model)."""
         return self.offsets_device_ptr
 
+    def grad_scales(self):
+        """Device pointer (int) to the per-tensor max |g| of the gradient the last step() wrote; raises if not produced."""
+        p = _vp()
+        _check(_lib.dat_model_grad_scales(self._h, C.byref(p)), "dat_model_grad_scales")
+        return p.value
+
+    def grad_scales_tensor(self):
+        """A copy of those scales as a float32 CUDA tensor [num_tensors]."""
+        class _View:
+            pass
+        v = _View()
+        v.__cuda_array_interface__ = {"shape": (self.num_tensors,), "typestr": "<f4", "data": (self.grad_scales(), False),
+                                      "version": 2, "strides": None}
+        return torch.as_tensor(v, device="cuda").clone()
+
     # ---- introspection (parity tests) ----
     def inspect_ops(self):
         n_ops, n_t = _i(), _i()
@@ -268,6 +290,10 @@ class Model:
         mean, rstd = np.zeros(C_, np.float32), np.zeros(C_, np.float32)
         _check(_lib.dat_inspect_bn(self._h, op, mean.ctypes.data, rstd.ctypes.data), "dat_inspect_bn")
         return mean, rstd
+
+
+def set_kernel_option(opt, value):
+    _check(_lib.dat_set_kernel_option(int(opt), int(value)), "dat_set_kernel_option")
 
 
 def pgd_init(x, eps, init=INIT_ZERO, seed=0, delta0=None, delta=None, stream=None):
@@ -315,6 +341,22 @@ def quantize(grads, offsets_dev, bits, seed, q=None, scales=None, stream=None):
     return q, scales
 
 
+def quantize_scaled(grads, offsets_dev, bits, seed, scales, q=None, stream=None):
+    """Encoder only: `scales` is a float32 CUDA tensor [T] or a raw device pointer (int) to the per-tensor max |g|."""
+    _dev(grads, torch.float32)
+    if isinstance(offsets_dev, tuple):
+        optr, T = C.c_void_p(offsets_dev[0]), offsets_dev[1]
+    else:
+        optr, T = _ptr(offsets_dev), offsets_dev.numel() - 1
+    d = grads.numel()
+    if q is None:
+        q = torch.empty(max(quantized_bytes(d, bits), 1), dtype=torch.uint8, device=grads.device)
+    sp = C.c_void_p(scales) if isinstance(scales, int) else _ptr(_dev(scales, torch.float32))
+    _check(_lib.dat_quantize_scaled(_ptr(grads), optr, T, d, bits, int(seed) & 0xFFFFFFFFFFFFFFFF, sp, _ptr(q),
+                                    _stream(stream)), "dat_quantize_scaled")
+    return q
+
+
 def dequantize(q, scales, offsets_dev, d, bits, out=None, stream=None):
     if isinstance(offsets_dev, tuple):
         optr, T = C.c_void_p(offsets_dev[0]), offsets_dev[1]
@@ -322,7 +364,8 @@ def dequantize(q, scales, offsets_dev, d, bits, out=None, stream=None):
         optr, T = _ptr(offsets_dev), offsets_dev.numel() - 1
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=q.device)
-    _check(_lib.dat_dequantize(_ptr(q), _ptr(scales), optr, T, d, bits, _ptr(out), _stream(stream)), "dat_dequantize")
+    sp = C.c_void_p(scales) if isinstance(scales, int) else _ptr(scales)     # tensor or raw device pointer
+    _check(_lib.dat_dequantize(_ptr(q), sp, optr, T, d, bits, _ptr(out), _stream(stream)), "dat_dequantize")
     return out
 
 

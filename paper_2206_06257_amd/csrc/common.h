@@ -44,6 +44,28 @@ __device__ __forceinline__ float bn_input_grad(float dy, float x, float a, float
   const float t = __fmul_rn(p, __fsub_rn(x, mu));
   return __fadd_rn(__fadd_rn(__fmul_rn(a, dy), t), q);
 }
+// Per-tensor abs-max of the parameter gradients (the quantizer's scale), taken where the gradients are written.
+// |v| is compared through its bit pattern (non-negative floats order like unsigned integers, NaN patterns above
+// Inf), so the result is exact and independent of the order of the updates.  Every tensor has kAbsmaxWays slots,
+// 128 bytes apart (one cache line each); a workgroup raises slot (workgroup index mod kAbsmaxWays), so the
+// hundreds of thousands of short workgroups of a large tensor do not queue on one address, and
+// absmax_fold_kernel takes the maximum over the ways afterwards.  A writer reads its slot when it starts
+// (absmax_peek, off the critical path) and issues the atomic only when it can raise the value: a stale read
+// can only cause a superfluous atomic, never a missing one, because stored values only grow.
+constexpr int kAbsmaxWays = 16, kAbsmaxStride = 32;   // uint32 units
+__device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+__device__ __forceinline__ uint32_t* absmax_way(uint32_t* tensor_slots, unsigned workgroup) {
+  return tensor_slots + (workgroup % kAbsmaxWays) * kAbsmaxStride;
+}
+__device__ __forceinline__ uint32_t absmax_peek(const uint32_t* slot) { return __builtin_nontemporal_load(slot); }
+__device__ __forceinline__ void absmax_raise(uint32_t* slot, uint32_t seen, uint32_t m) {
+  if (m > seen) atomicMax(slot, m);
+}
+__device__ __forceinline__ void absmax_publish(uint32_t* slot, uint32_t m) { absmax_raise(slot, absmax_peek(slot), m); }
+// The slot groups (kAbsmaxWays slots each) of the two tensors a finishing kernel writes (for a batch normalisation:
+// beta gradient, gamma gradient), or null.
+struct ParamAbsmax { uint32_t* first; uint32_t* second; };
+
 // Layout of the constants: channel c at tab[(c/8)*32 + which*8 + c%8], which = 0..3 for a, p, q, mu.
 constexpr int kBnTabFloatsPerChannel = 4;
 

@@ -931,9 +931,11 @@ int compute_units() {
 // B = 256: 14x14 3x3 256->256 82 -> 66 us and 1024->256 42 -> 35 us with 256x256 tiles; 7x7 3x3 512->512 87 -> 75 us
 // and 2048->512 44 -> 37 us with 256x128; slower than the 128x128 kernel wherever several rounds are needed or the
 // contraction is short).
+std::atomic<bool> g_ring_enabled{true};
+
 int pick_ring(const IgemmArgs& a) {
   if (a.xf_tab || a.ostep != 1 || a.stat_slab0 != 0 || a.Cin % 64 != 0 || a.Ktot < 1024 || a.Cout % 256 != 0) return 0;
-  if (getenv("DAT_NO_RING_KERNEL")) return 0;   // for A/B runs: every layer through the 128x128 kernels
+  if (!g_ring_enabled.load(std::memory_order_relaxed)) return 0;   // dat_set_kernel_option: every layer through the 128x128 kernels
   const int64_t cus = compute_units(), nct = a.Cout / 256;
   const int64_t t256 = ((int64_t)a.M + 255) / 256 * nct, t128 = ((int64_t)a.M + 127) / 128 * nct;
   if (t256 <= cus && 5 * t256 >= 3 * cus) return 1;
@@ -1053,14 +1055,23 @@ __global__ void stem_weight_transform_kernel(const float* __restrict__ master, b
 }
 
 // dW[co][r][s][c] = dVf[co][a][b][(ph,pw,c)] with r = 2a+ph-1, s = 2b+pw-1
-__global__ void stem_wgrad_gather_kernel(const float* __restrict__ dv, float* __restrict__ dw, int Cout, int cin_real) {
+__global__ void stem_wgrad_gather_kernel(const float* __restrict__ dv, float* __restrict__ dw, int Cout, int cin_real, uint32_t* __restrict__ absmax) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= Cout * 49 * cin_real) return;
-  const int c = i % cin_real; int t = i / cin_real;
-  const int s = t % 7; t /= 7;
-  const int r = t % 7; const int co = t / 7;
-  const int ph = (r + 1) & 1, a = (r + 1) >> 1, pw = (s + 1) & 1, b = (s + 1) >> 1;
-  dw[i] = dv[((co * 4 + a) * 4 + b) * 32 + (ph * 2 + pw) * 8 + c];
+  uint32_t m = 0;
+  if (i < Cout * 49 * cin_real) {
+    const int c = i % cin_real; int t = i / cin_real;
+    const int s = t % 7; t /= 7;
+    const int r = t % 7; const int co = t / 7;
+    const int ph = (r + 1) & 1, a = (r + 1) >> 1, pw = (s + 1) & 1, b = (s + 1) >> 1;
+    const float v = dv[((co * 4 + a) * 4 + b) * 32 + (ph * 2 + pw) * 8 + c];
+    dw[i] = v;
+    m = abs_bits(v);
+  }
+  if (absmax) {   // (all 64 lanes of every wavefront reach this point)
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d));
+    if ((threadIdx.x & 63) == 0) absmax_publish(absmax_way(absmax, blockIdx.x), m);
+  }
 }
 
 // ---- backward-weight ----------------------------------------------------------------------------
@@ -1228,9 +1239,11 @@ __global__ __launch_bounds__(kThreads, 4) void wgrad_kernel(WgradArgs a) {
 // split); thread group g = tid / 32 adds splits g, g+8, ... (eight loads in flight), then the eight group sums
 // are added in order.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ ws, int splits, int64_t per_split, int Cin, int cin_real,
-                                                           float scale, float* __restrict__ dw) {
+                                                           float scale, float* __restrict__ dw, uint32_t* __restrict__ absmax) {
   __shared__ float sh[8][32];
   const int lane = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  uint32_t* const slot = absmax ? absmax_way(absmax, blockIdx.x) : nullptr;
+  const uint32_t seen = (slot && threadIdx.x == 0) ? absmax_peek(slot) : 0u;   // in flight with the loads below
   const int64_t i = (int64_t)blockIdx.x * 32 + lane;
   const int64_t ic = i < per_split ? i : per_split - 1;
   float s = 0.f;
@@ -1247,13 +1260,21 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
   }
   sh[grp][lane] = s;
   __syncthreads();
-  if (grp != 0 || i >= per_split) return;
-  const int ci = (int)(i % Cin);
-  if (ci >= cin_real) return;
+  if (grp != 0) return;
+  // (the 32 lanes of group 0 stay together to the end: their maximum is combined by lane exchanges)
+  const int ci = (int)(ic % Cin);
+  const bool live = i < per_split && ci < cin_real;
   s = 0.f;
 #pragma unroll
   for (int g = 0; g < 8; ++g) s += sh[g][lane];
-  dw[(i / Cin) * cin_real + ci] = s * scale;
+  const float v = s * scale;
+  if (live) dw[(i / Cin) * cin_real + ci] = v;
+  if (absmax) {
+    uint32_t m = live ? abs_bits(v) : 0u;
+#pragma unroll
+    for (int d = 16; d >= 1; d >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d));
+    if (lane == 0) absmax_raise(slot, seen, m);
+  }
 }
 
 struct WgradPlan { int splits, pix_per_split, gx, gy; bool narrow; };
@@ -1417,7 +1438,7 @@ dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16
 }
 
 dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale,
-                                     void* ws, hipStream_t st) {
+                                     void* ws, hipStream_t st, uint32_t* absmax) {
   if (g.Cin % 8 != 0 || g.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
   const WgradPlan p = plan_wgrad(g);
   WgradArgs a;
@@ -1431,7 +1452,7 @@ dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* d
   DAT_LAUNCH_CHECK();
   const int64_t per_split = (int64_t)g.Cout * a.Ktot;
   hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per_split + 31) / 32)), dim3(256), 0, st, (const float*)ws, p.splits,
-                     per_split, g.Cin, cin_real, scale, dw);
+                     per_split, g.Cin, cin_real, scale, dw, absmax);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -1446,12 +1467,12 @@ dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, i
 
 // dw [Cout][7][7][cin_real] through the blocked layer's gradient dv [Cout][4][4][32] (scratch, fp32).
 dat_status conv_mfma_stem_backward_weight(const bf16_t* x2, const bf16_t* dy, float* dw, float* dv, int cin_real, const ConvGeom& g,
-                                          float scale, void* ws, hipStream_t st) {
+                                          float scale, void* ws, hipStream_t st, uint32_t* absmax) {
   const ConvGeom q = conv_mfma_stem_blocked_geom(g);
   const dat_status s = conv_mfma_backward_weight(x2, dy, dv, 32, q, scale, ws, st);
   if (s != DAT_OK) return s;
   const int n = g.Cout * 49 * cin_real;
-  hipLaunchKernelGGL(stem_wgrad_gather_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)dv, dw, g.Cout, cin_real);
+  hipLaunchKernelGGL(stem_wgrad_gather_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)dv, dw, g.Cout, cin_real, absmax);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -1460,6 +1481,13 @@ dat_status conv_mfma_stem_backward_weight(const bf16_t* x2, const bf16_t* dy, fl
 
 // ---- C entry points for per-shape tests and timing -----------------------------------------------
 using namespace dat;
+
+extern "C" dat_status dat_set_kernel_option(dat_kernel_option opt, int value) {
+  switch (opt) {
+    case DAT_KOPT_RING_KERNEL: g_ring_enabled.store(value != 0, std::memory_order_relaxed); return DAT_OK;
+  }
+  return DAT_ERR_ARG;
+}
 
 static bool geom_from(int B, int H, int W, int Cin, int Cout, int k, int stride, int pad, ConvGeom* g) {
   if (B < 1 || H < 1 || W < 1 || Cin < 8 || Cout < 8 || Cin % 8 || Cout % 8 || k < 1 || pad < 0 || pad >= k) return false;

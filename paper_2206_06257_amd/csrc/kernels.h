@@ -90,7 +90,9 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
 // dw fp32 [Cout][k][k][Cin_real] (Cin_real <= g.Cin: padded input channels are dropped), scaled.
 // `ws` is a workspace of conv_mfma_wgrad_workspace(g) bytes.
 size_t conv_mfma_wgrad_workspace(const ConvGeom& g);
-dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale, void* ws, hipStream_t st);
+// absmax (optional): the tensor's group of kAbsmaxWays slots that receive max |dw| (see absmax_way).
+dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale, void* ws, hipStream_t st,
+                                     uint32_t* absmax = nullptr);
 // A 7x7 stride-2 pad-3 convolution of an input with 8 stored channels (H, W even) can run as a 4x4
 // stride-1 convolution over 2x2 pixel blocks when the input tensor is stored blocked,
 // x2[n][i][j][(ph*2+pw)*8 + c] = x[n][2i+ph][2j+pw][c]; `g` is always the original geometry.
@@ -102,7 +104,7 @@ dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y,
 dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16_t* dx2, const ConvGeom& g, bool accumulate, hipStream_t st);
 // dv: [Cout][4][4][32] fp32 scratch; ws: conv_mfma_wgrad_workspace(conv_mfma_stem_blocked_geom(g)) bytes.
 dat_status conv_mfma_stem_backward_weight(const bf16_t* x2, const bf16_t* dy, float* dw, float* dv, int cin_real, const ConvGeom& g,
-                                          float scale, void* ws, hipStream_t st);
+                                          float scale, void* ws, hipStream_t st, uint32_t* absmax = nullptr);
 // master fp32 [Cout][k][k][cin_real] -> w bf16 [Cout][k][k][Cin] (zero padded) and wT.
 dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, int Cout, int k, int cin_real, int Cin, int stride, int pad, hipStream_t st);
 
@@ -122,7 +124,8 @@ size_t fold_floats(int nslabs, int C);
 //           call it once per pair; `fold` = false skips the folding of many slabs (done by an earlier call).
 dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
                              float* dgamma, float scale, hipStream_t st, const float* gamma = nullptr, const float* mean = nullptr,
-                             const float* rstd = nullptr, float* tab = nullptr, int nsum = 2, int col2 = 1, bool fold = true);
+                             const float* rstd = nullptr, float* tab = nullptr, int nsum = 2, int col2 = 1, bool fold = true,
+                             ParamAbsmax am = ParamAbsmax{nullptr, nullptr});   // am: abs-max slots of (dbeta, dgamma)
 // out = act(gamma*((x-mean)*rstd) + beta [+ res])
 // mask (optional, rows*C/8 bytes): bit j of byte e/8 = (out[e] > 0), what the backward pass needs of `out`.
 // res_bn (optional): `res` is the INPUT of a second normalisation without activation (the one on a projection
@@ -137,10 +140,12 @@ dat_status bnact_forward(const void* x, const void* res, void* out, uint8_t* mas
 struct BnSecond {
   const void* x; const float* mean; const float* rstd; const float* gamma;
   float* sums; float* tab; float* dgamma; float* dbeta;
+  ParamAbsmax am;      // abs-max slots of (dbeta, dgamma), or nulls
 };
 dat_status bn_backward_reduce(const void* x, const void* out, const uint8_t* mask, const void* dout, int dtype, int64_t rows, int C,
                               const float* mean, const float* rstd, const float* gamma, int relu, float* partial, float* sums,
-                              float* tab, float* dgamma, float* dbeta, float scale, hipStream_t st, const BnSecond* second = nullptr);
+                              float* tab, float* dgamma, float* dbeta, float scale, hipStream_t st, const BnSecond* second = nullptr,
+                              ParamAbsmax am = ParamAbsmax{nullptr, nullptr});
 // Backward, second half: dx (+)= bn_input_grad(dy, x, tab) = gamma*rstd*(dy - dbeta/rows - xhat*dgamma/rows); dres (+)= dy.
 dat_status bn_backward_apply(const void* x, const void* out, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, void* dres,
                              bool dres_accumulate, int dtype, int64_t rows, int C, const float* tab, int relu, hipStream_t st);
@@ -151,7 +156,8 @@ dat_status bn_backward_apply(const void* x, const void* out, const uint8_t* mask
 struct PoolGrad { const uint8_t* arg; const void* dpooled; int B, H, W, Ho, Wo; int gather; };
 dat_status bn_pool_backward(const void* x, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, bool skip_apply, int dtype, int C,
                             const float* mean, const float* rstd, const float* gamma, float* partial, float* sums, float* tab,
-                            float* dgamma, float* dbeta, float scale, const PoolGrad& pg, hipStream_t st);
+                            float* dgamma, float* dbeta, float scale, const PoolGrad& pg, hipStream_t st,
+                            ParamAbsmax am = ParamAbsmax{nullptr, nullptr});
 // relu(gamma*((x-mean)*rstd)+beta) followed by the 3x3/2 max-pool in one pass: writes the pooled tensor, the arg-max
 // positions (as maxpool_forward) and the ReLU mask of every input pixel (as bnact_forward); the activated tensor is not stored.
 dat_status bnact_pool_forward(const void* x, void* pooled, uint8_t* arg, uint8_t* mask, int dtype, int B, int H, int W, int C, int Ho, int Wo,
@@ -172,7 +178,7 @@ dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dty
 size_t fc_workspace_floats(int B, int I, int O);
 dat_status fc_forward(const float* f, const float* W, const float* b, float* logits, int B, int I, int O, float* ws, hipStream_t st);
 dat_status fc_backward(const float* f, const float* W, const float* dz, float* df, float* dW, float* db, int B, int I, int O,
-                       float scale, float* ws, hipStream_t st);
+                       float scale, float* ws, hipStream_t st, ParamAbsmax am = ParamAbsmax{nullptr, nullptr});   // am: slots of (dW, db)
 // Softmax cross-entropy: loss_n per sample, dz = (softmax - onehot) * gscale; loss_mean[0] = mean loss_n.
 dat_status ce_forward_backward(const float* logits, const int32_t* y, float* dz, float* loss_n, float* loss_mean, int B, int O,
                                float gscale, hipStream_t st);
@@ -187,6 +193,8 @@ dat_status launch_input_grad(const void* g0, int dtype, int Cpad, int64_t rows, 
                              int block_h, int block_w, hipStream_t st);
 dat_status launch_sgd(float* theta, const float* g, float lr, int64_t n, hipStream_t st);
 dat_status launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+// Per-tensor abs-max slots (kAbsmaxWays per tensor, see absmax_way) -> one value per tensor.
+dat_status launch_absmax_fold(const uint32_t* ways, int T, uint32_t* scales, hipStream_t st);
 
 }  // namespace dat
 

@@ -399,11 +399,15 @@ __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ 
                                                       float* __restrict__ e2, float scale,
                                                       const float* __restrict__ gamma = nullptr, const float* __restrict__ mean = nullptr,
                                                       const float* __restrict__ rstd = nullptr, float* __restrict__ tab = nullptr,
-                                                      int stride = 0, int off2 = 0) {
+                                                      int stride = 0, int off2 = 0, ParamAbsmax am = ParamAbsmax{nullptr, nullptr}) {
   if (stride == 0) { stride = 2 * C; off2 = C; }     // slab = [2][C]: the two sums are rows 0 and 1
   __shared__ double sh[2][32][8];
   const int cl = threadIdx.x & 7, grp = threadIdx.x >> 3;
   const int c = blockIdx.x * 8 + cl;
+  // abs-max slots of the two gradient tensors: read now, in flight with the slab loads (see absmax_peek)
+  uint32_t* const slot1 = (MODE != 0 && am.first && e1) ? absmax_way(am.first, blockIdx.x) : nullptr;
+  uint32_t* const slot2 = (MODE != 0 && am.second && e2) ? absmax_way(am.second, blockIdx.x) : nullptr;
+  const uint32_t seen1 = (slot1 && grp == 0) ? absmax_peek(slot1) : 0u, seen2 = (slot2 && grp == 0) ? absmax_peek(slot2) : 0u;
   double s1 = 0.0, s2 = 0.0;
   if (c < C) {
     // eight slabs per round trip; slabs past the end contribute +0 (exact), so the order of the adds is fixed
@@ -437,6 +441,9 @@ __global__ __launch_bounds__(kT) void colfinal_kernel(const float* __restrict__ 
     if (o2) o2[c] = (float)s2;
     if (e1) e1[c] = (float)(s1 * (double)scale);
     if (e2) e2[c] = (float)(s2 * (double)scale);
+    // (threads 0..7 of the workgroup are here, some perhaps not: one atomic each, at most C per tensor)
+    if (slot1) absmax_raise(slot1, seen1, abs_bits((float)(s1 * (double)scale)));
+    if (slot2) absmax_raise(slot2, seen2, abs_bits((float)(s2 * (double)scale)));
     if (tab) {   // constants of bn_input_grad for this channel
       const double a = (double)gamma[c] * (double)rstd[c];
       float* t = tab + (c >> 3) * 32 + (c & 7);
@@ -853,7 +860,7 @@ __global__ __launch_bounds__(kT) void gap_bwd_kernel(const float* __restrict__ d
 __global__ __launch_bounds__(kT) void sgemm_kernel(const float* __restrict__ A, const float* __restrict__ Bm,
                                                    const float* __restrict__ bias, float* __restrict__ Cm, int M, int N,
                                                    int K, int64_t sAm, int64_t sAk, int64_t sBk, int64_t sBn, float scale,
-                                                   int kchunk, float* __restrict__ ws) {
+                                                   int kchunk, float* __restrict__ ws, uint32_t* __restrict__ absmax) {
   __shared__ float As[64][33], Bs[64][33];           // As[m][k], Bs[n][k]
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
@@ -894,6 +901,7 @@ __global__ __launch_bounds__(kT) void sgemm_kernel(const float* __restrict__ A, 
     }
     __syncthreads();
   }
+  uint32_t amax = 0;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int m = m0 + ty + 16 * r;
@@ -903,26 +911,53 @@ __global__ __launch_bounds__(kT) void sgemm_kernel(const float* __restrict__ A, 
       const int n = n0 + tx + 16 * c;
       if (n >= N) continue;
       if (ws) ws[((int64_t)blockIdx.z * M + m) * N + n] = acc[r][c];
-      else Cm[(int64_t)m * N + n] = acc[r][c] * scale + (bias ? bias[n] : 0.f);
+      else {
+        const float v = acc[r][c] * scale + (bias ? bias[n] : 0.f);
+        Cm[(int64_t)m * N + n] = v;
+        amax = max(amax, abs_bits(v));
+      }
     }
+  }
+  if (absmax && !ws) {   // (uniform condition: every lane of the wavefront is here)
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, d));
+    if ((tid & 63) == 0) absmax_publish(absmax_way(absmax, blockIdx.x + blockIdx.y), amax);
   }
 }
 
 __global__ void splitk_reduce_kernel(const float* __restrict__ ws, int splits, int64_t MN, int N, float scale,
-                                     const float* __restrict__ bias, float* __restrict__ Cm) {
+                                     const float* __restrict__ bias, float* __restrict__ Cm, uint32_t* __restrict__ absmax) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= MN) return;
-  float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += ws[(int64_t)z * MN + i];
-  Cm[i] = s * scale + (bias ? bias[i % N] : 0.f);
+  uint32_t amax = 0;
+  if (i < MN) {
+    float s = 0.f;
+    for (int z = 0; z < splits; ++z) s += ws[(int64_t)z * MN + i];
+    const float v = s * scale + (bias ? bias[i % N] : 0.f);
+    Cm[i] = v;
+    amax = abs_bits(v);
+  }
+  if (absmax) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, d));
+    if ((threadIdx.x & 63) == 0) absmax_publish(absmax_way(absmax, blockIdx.x), amax);
+  }
 }
 
-__global__ void fc_bias_grad_kernel(const float* __restrict__ dz, float* __restrict__ db, int B, int O, float scale) {
+__global__ void fc_bias_grad_kernel(const float* __restrict__ dz, float* __restrict__ db, int B, int O, float scale, uint32_t* __restrict__ absmax) {
   const int o = blockIdx.x * blockDim.x + threadIdx.x;
-  if (o >= O) return;
-  float s = 0.f;
-  for (int n = 0; n < B; ++n) s += dz[(int64_t)n * O + o];
-  db[o] = s * scale;
+  uint32_t amax = 0;
+  if (o < O) {
+    float s = 0.f;
+    for (int n = 0; n < B; ++n) s += dz[(int64_t)n * O + o];
+    const float v = s * scale;
+    db[o] = v;
+    amax = abs_bits(v);
+  }
+  if (absmax) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, d));
+    if ((threadIdx.x & 63) == 0) absmax_publish(absmax_way(absmax, blockIdx.x), amax);
+  }
 }
 
 // ---- softmax cross-entropy: one wavefront per sample ------------------------------------------
@@ -939,9 +974,11 @@ __global__ __launch_bounds__(64) void ce_kernel(const float* __restrict__ z, con
 #pragma unroll
   for (int s = 32; s >= 1; s >>= 1) se += __shfl_xor(se, s);
   const float lse = mx + logf(se);
+  // a label outside [0, O) (caller-owned device memory the host cannot validate): no one-hot term, NaN loss, no access
   const int yn = y[n];
+  const bool label_ok = (unsigned)yn < (unsigned)O;
   for (int c = lane; c < O; c += 64) dz[(int64_t)n * O + c] = (expf(zn[c] - lse) - (c == yn ? 1.f : 0.f)) * gscale;
-  if (lane == 0) loss_n[n] = lse - zn[yn];
+  if (lane == 0) loss_n[n] = label_ok ? lse - zn[yn] : __builtin_nanf("");
 }
 
 // TRADES regulariser phi_n = KL(p_n || q_n), p = softmax(z_clean), q = softmax(z_adv); one wavefront per sample.
@@ -978,11 +1015,12 @@ __global__ __launch_bounds__(64) void kl_kernel(const float* __restrict__ zc, co
     if (lane == 0) loss_n[n] = kl;
   } else {
     const int yn = y[n];
+    const bool label_ok = (unsigned)yn < (unsigned)O;      // as in ce_kernel
     for (int k = lane; k < O; k += 64) {
       const float t = (c[k] - a[k]) - dl, p = expf(a[k] - la + t);
       dz[(int64_t)n * O + k] = (lambda * (p - (k == yn ? 1.f : 0.f)) + p * (t - kl)) * gscale;
     }
-    if (lane == 0) loss_n[n] = (la + dl) - c[yn];
+    if (lane == 0) loss_n[n] = label_ok ? (la + dl) - c[yn] : __builtin_nanf("");
   }
 }
 
@@ -1023,6 +1061,16 @@ __global__ void sgd_kernel(float* __restrict__ theta, const float* __restrict__ 
   if (i < n) theta[i] = __fsub_rn(theta[i], __fmul_rn(lr, g[i]));
 }
 
+// scales[t] = max over the kAbsmaxWays slots of tensor t (bit patterns of non-negative floats)
+__global__ void absmax_fold_kernel(const uint32_t* __restrict__ ways, int T, uint32_t* __restrict__ scales) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  uint32_t m = 0;
+#pragma unroll
+  for (int w = 0; w < kAbsmaxWays; ++w) m = max(m, ways[((int64_t)t * kAbsmaxWays + w) * kAbsmaxStride]);
+  scales[t] = m;
+}
+
 __global__ void zero_kernel(uint32_t* __restrict__ p, int64_t nwords) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < nwords) p[i] = 0u;
@@ -1048,7 +1096,7 @@ size_t fold_floats(int nslabs, int C) { return nslabs > 512 ? (size_t)((nslabs +
 
 dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, int mode, float* o1, float* o2, float* dbeta,
                              float* dgamma, float scale, hipStream_t st, const float* gamma, const float* mean, const float* rstd,
-                             float* tab, int nsum, int col2, bool fold) {
+                             float* tab, int nsum, int col2, bool fold, ParamAbsmax am) {
   const float* src = partial;
   const int W = nsum * C;
   if (nslabs > 512) {   // two-level: keep the final per-channel loop short
@@ -1065,7 +1113,7 @@ dat_status bn_finalize_slabs(float* partial, int nslabs, int C, int64_t rows, in
                        (const float*)nullptr, (const float*)nullptr, (const float*)nullptr, (float*)nullptr, W, col2 * C);
   else
     hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, src, nslabs, C, rows, o1, o2, dbeta, dgamma, scale, gamma, mean, rstd, tab,
-                       W, col2 * C);
+                       W, col2 * C, am);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -1115,7 +1163,7 @@ dat_status bnact_pool_forward(const void* x, void* pooled, uint8_t* arg, uint8_t
 
 dat_status bn_backward_reduce(const void* x, const void* out, const uint8_t* mask, const void* dout, int dtype, int64_t rows, int C,
                               const float* mean, const float* rstd, const float* gamma, int relu, float* partial, float* sums,
-                              float* tab, float* dgamma, float* dbeta, float scale, hipStream_t st, const BnSecond* second) {
+                              float* tab, float* dgamma, float* dbeta, float scale, hipStream_t st, const BnSecond* second, ParamAbsmax am) {
   if (C % 8 != 0 || C > 8 * kT) return DAT_ERR_UNSUPPORTED;
   SlabPlan p;
   if (second) {
@@ -1127,7 +1175,7 @@ dat_status bn_backward_reduce(const void* x, const void* out, const uint8_t* mas
       hipLaunchKernelGGL(dual_reduce_kernel<bf16_t>, dim3(p.nslabs), dim3(kT), 0, st, (const bf16_t*)x, (const bf16_t*)second->x, mask, (const bf16_t*)dout, mean, rstd, second->mean, second->rstd, rows, C, p.tpr, p.rpp, p.rows_per_slab, partial, partial2));
     DAT_LAUNCH_CHECK();
     hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, (const float*)partial2, p.nslabs, C, rows, second->sums, second->sums + C,
-                       second->dbeta, second->dgamma, scale, second->gamma, second->mean, second->rstd, second->tab);
+                       second->dbeta, second->dgamma, scale, second->gamma, second->mean, second->rstd, second->tab, 0, 0, second->am);
     DAT_LAUNCH_CHECK();
   } else {
     dat_status s;
@@ -1136,7 +1184,7 @@ dat_status bn_backward_reduce(const void* x, const void* out, const uint8_t* mas
     if (s != DAT_OK) return s;
   }
   hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, (const float*)partial, p.nslabs, C, rows, sums, sums + C,
-                     dbeta, dgamma, scale, gamma, mean, rstd, tab);
+                     dbeta, dgamma, scale, gamma, mean, rstd, tab, 0, 0, am);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -1164,7 +1212,7 @@ dat_status bn_backward_apply(const void* x, const void* out, const uint8_t* mask
 // sum in the same order.
 dat_status bn_pool_backward(const void* x, const uint8_t* mask, const void* dout, void* dx, bool dx_accumulate, bool skip_apply, int dtype, int C,
                             const float* mean, const float* rstd, const float* gamma, float* partial, float* sums, float* tab,
-                            float* dgamma, float* dbeta, float scale, const PoolGrad& pg, hipStream_t st) {
+                            float* dgamma, float* dbeta, float scale, const PoolGrad& pg, hipStream_t st, ParamAbsmax am) {
   if (C % 8 != 0 || C > 8 * kT || !mask) return DAT_ERR_UNSUPPORTED;
   PoolArgs pa{pg.arg, pg.dpooled, pg.B, pg.H, pg.W, pg.Ho, pg.Wo};
   const int tpr = C / 8, rpp = kT / tpr;
@@ -1186,7 +1234,7 @@ dat_status bn_pool_backward(const void* x, const uint8_t* mask, const void* dout
   else DAT_BY_DTYPE(dtype, DAT_BLOCK_REDUCE(float, false), DAT_BLOCK_REDUCE(bf16_t, false));
   DAT_LAUNCH_CHECK();
   hipLaunchKernelGGL(colfinal_kernel<1>, dim3((C + 7) / 8), dim3(kT), 0, st, (const float*)partial, nslabs, C, rows, sums, sums + C,
-                     dbeta, dgamma, scale, gamma, mean, rstd, tab);
+                     dbeta, dgamma, scale, gamma, mean, rstd, tab, 0, 0, am);
   DAT_LAUNCH_CHECK();
   if (skip_apply) return DAT_OK;
   if (pg.gather) DAT_BY_DTYPE(dtype, DAT_BLOCK_APPLY(float, true), DAT_BLOCK_APPLY(bf16_t, true));
@@ -1269,7 +1317,7 @@ dat_status gap_backward(const float* dpooled, void* dx, bool accumulate, int dty
 // ws (optional): room for fc_workspace_floats(B, I, O) floats; then long contractions are split so that the launch
 // has a few hundred workgroups.
 static dat_status sgemm(const float* A, const float* Bm, const float* bias, float* Cm, int M, int N, int K, int64_t sAm,
-                        int64_t sAk, int64_t sBk, int64_t sBn, float scale, float* ws, hipStream_t st) {
+                        int64_t sAk, int64_t sBk, int64_t sBn, float scale, float* ws, hipStream_t st, uint32_t* absmax = nullptr) {
   const int tiles = ((N + 63) / 64) * ((M + 63) / 64);
   int splits = 1;
   if (ws && K >= 256) {
@@ -1282,11 +1330,11 @@ static dat_status sgemm(const float* A, const float* Bm, const float* bias, floa
   splits = (K + kchunk - 1) / kchunk;
   if (splits == 1) ws = nullptr;
   hipLaunchKernelGGL(sgemm_kernel, dim3((N + 63) / 64, (M + 63) / 64, splits), dim3(kT), 0, st, A, Bm, bias, Cm, M, N, K, sAm, sAk, sBk,
-                     sBn, scale, kchunk, ws);
+                     sBn, scale, kchunk, ws, absmax);
   DAT_LAUNCH_CHECK();
   if (ws) {
     const int64_t MN = (int64_t)M * N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(nblk(MN)), dim3(kT), 0, st, (const float*)ws, splits, MN, N, scale, bias, Cm);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(nblk(MN)), dim3(kT), 0, st, (const float*)ws, splits, MN, N, scale, bias, Cm, absmax);
     DAT_LAUNCH_CHECK();
   }
   return DAT_OK;
@@ -1300,15 +1348,15 @@ dat_status fc_forward(const float* f, const float* W, const float* b, float* log
 }
 
 dat_status fc_backward(const float* f, const float* W, const float* dz, float* df, float* dW, float* db, int B, int I, int O,
-                       float scale, float* ws, hipStream_t st) {
+                       float scale, float* ws, hipStream_t st, ParamAbsmax am) {
   // df[n][i] = sum_o dz[n][o] * W[o][i]
   dat_status s = sgemm(dz, W, nullptr, df, B, I, O, O, 1, I, 1, 1.0f, ws, st);
   if (s != DAT_OK) return s;
   if (dW) {
     // dW[o][i] = scale * sum_n dz[n][o] * f[n][i];  db[o] = scale * sum_n dz[n][o]
-    s = sgemm(dz, f, nullptr, dW, O, I, B, 1, O, I, 1, scale, nullptr, st);
+    s = sgemm(dz, f, nullptr, dW, O, I, B, 1, O, I, 1, scale, nullptr, st, am.first);
     if (s != DAT_OK) return s;
-    hipLaunchKernelGGL(fc_bias_grad_kernel, dim3((O + 255) / 256), dim3(256), 0, st, dz, db, B, O, scale);
+    hipLaunchKernelGGL(fc_bias_grad_kernel, dim3((O + 255) / 256), dim3(256), 0, st, dz, db, B, O, scale, am.second);
     DAT_LAUNCH_CHECK();
   }
   return DAT_OK;
@@ -1351,6 +1399,12 @@ dat_status launch_input_grad(const void* g0, int dtype, int Cpad, int64_t rows, 
 
 dat_status launch_sgd(float* theta, const float* g, float lr, int64_t n, hipStream_t st) {
   hipLaunchKernelGGL(sgd_kernel, dim3(nblk(n)), dim3(kT), 0, st, theta, g, lr, n);
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
+dat_status launch_absmax_fold(const uint32_t* ways, int T, uint32_t* scales, hipStream_t st) {
+  hipLaunchKernelGGL(absmax_fold_kernel, dim3((T + 255) / 256), dim3(256), 0, st, ways, T, scales);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }

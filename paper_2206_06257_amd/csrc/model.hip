@@ -75,7 +75,9 @@ struct dat_model {
   std::vector<hipEvent_t> wg_events;
   hipEvent_t wg_join = nullptr;
   int64_t bn_sums_max_bytes = (int64_t)1 << 62;   //   ... only for d(out) tensors up to this size
-  bool fuse_pool = false;            // BN + ReLU + max-pool in one forward pass, pool gradient gathered by the BN backward pass
+  bool fuse_pool = true;             // dat_model_set_option(DAT_OPT_FUSE_STEM_POOL): BN + ReLU + max-pool in one forward pass, pool gradient gathered by the BN backward pass
+  bool absorb_shortcut_bn = true;    // dat_model_set_option(DAT_OPT_ABSORB_SHORTCUT_BN)
+  bool grad_scales = true;           // dat_model_set_option(DAT_OPT_GRADIENT_SCALES)
   std::vector<Shape> tens;           // logical per-sample shapes (channels as stored)
   std::vector<char> is_f32;          // pooled features and logits stay fp32 in every model
   std::vector<Op> ops;
@@ -95,6 +97,9 @@ struct dat_model {
   float* fc_ws = nullptr;            // split-K scratch of the classifier GEMMs
   float* z_keep = nullptr;           // logits of the clean pass, kept while the perturbed pass runs (TRADES regulariser)
   float* z_keep2 = nullptr;          //   ... and of the perturbed pass, kept while the clean pass runs again
+  uint32_t* gscale_ways = nullptr;   // per parameter tensor kAbsmaxWays slots raised by the kernels that write its gradient
+  uint32_t* gscale = nullptr;        // per parameter tensor: bit pattern of max |gradient| written by the last dat_step (bf16 models)
+  bool gscale_valid = false;         //   ... and whether that call produced all of them
   float* g_tmp = nullptr;            // second gradient vector of a two-pass objective (allocated on first use)
   float* opt_m = nullptr; float* opt_v = nullptr; float* opt_u = nullptr; double* opt_norms = nullptr;   // LAMB state
   // optional per-launch timing (dat_profile_*): one event pair per launch group
@@ -232,8 +237,18 @@ bool build_graph(dat_model& m) {
       return false;
   }
   m.fc(m.gap(t), m.classes);
-  // Fusion links (bf16 models): which BN normalises a conv's output (its batch statistics come from
-  // the conv epilogue).
+  return true;
+}
+
+// Fusion links between the ops of a bf16 model, recomputed from scratch (dat_model_create, and dat_model_set_option for
+// the two switches that change them).  They select launches only: every tensor keeps its buffer either way.
+void link_fusions(dat_model& m) {
+  for (Op& op : m.ops) {
+    op.dy_bn = -1; op.dy_bn_last_of_many = false; op.sparse_first = false; op.sums_ready = false; op.pool = -1; op.pooled_by = -1;
+    op.res_bn = -1; op.absorbed_by = -1; op.apply_fusable = false; op.apply_deferred = false; op.stats_from_conv = false;
+    op.fwd_bn = -1; op.res_grad_from = -1; op.res_grad_deferred = false;   // (op.blocked is fixed at creation: the weights are stored that way)
+  }
+  // which BN normalises a conv's output (its batch statistics come from the conv epilogue)
   if (m.dtype == DAT_BF16) {
     const int nt = (int)m.tens.size();
     std::vector<int> producer(nt, -1), first_consumer(nt, -1);
@@ -252,7 +267,6 @@ bool build_graph(dat_model& m) {
     }
     // BN + ReLU whose only reader is a 3x3/2 max-pool (the ImageNet stem): one pass writes the pooled tensor, the
     // arg-max positions and the ReLU mask; the full-resolution activation and its gradient are never stored.
-    m.fuse_pool = !getenv("DAT_KEEP_STEM_POOL");   // (environment switch: ablation only)
     for (int b = 0; b < (int)m.ops.size(); ++b) {
       Op& bn = m.ops[b];
       if (bn.kind != OP_BNACT || !bn.relu || bn.res >= 0) continue;
@@ -266,7 +280,7 @@ bool build_graph(dat_model& m) {
     // Projection shortcuts: out = relu(bn(y) + bn_s(y_s)).  bn_s's output has no other reader, so the final BN
     // normalises y_s itself, and in the backward sweep d out .* mask is the output gradient of both normalisations:
     // one pass over it gives both pairs of sums.  Neither bn_s's output nor its gradient is ever stored.
-    for (int b = 0; b < (int)m.ops.size() && !getenv("DAT_KEEP_SHORTCUT_BN"); ++b) {   // (environment switch: ablation only)
+    for (int b = 0; b < (int)m.ops.size() && m.absorb_shortcut_bn; ++b) {
       Op& bn = m.ops[b];
       if (bn.kind != OP_BNACT || bn.res < 0 || !bn.relu) continue;
       const int p = producer[bn.res];
@@ -343,18 +357,21 @@ bool build_graph(dat_model& m) {
       if (users == 2 && conv_users == 2 && first_user != c && m.ops[first_user].res_grad_from < 0 && (m.ops[first_user].stride == 1 || m.ops[first_user].stride == 2))
         cv.sparse_first = true;
     }
-    // the ImageNet stem runs on 2x2 pixel blocks of the network input (tensor 0 is stored blocked)
-    Op& first = m.ops[0];
-    if (first.kind == OP_CONV && first.in == 0 && first.res < 0) {
-      ConvGeom g;
-      g.B = 1; g.H = m.tens[0].H; g.W = m.tens[0].W; g.Cin = m.tens[0].C; g.Ho = m.tens[first.out].H; g.Wo = m.tens[first.out].W;
-      g.Cout = m.tens[first.out].C; g.k = first.k; g.stride = first.stride; g.pad = first.pad;
-      bool only_consumer = true;
-      for (size_t i = 1; i < m.ops.size(); ++i) if (m.ops[i].in == 0 || m.ops[i].res == 0) only_consumer = false;
-      first.blocked = only_consumer && conv_mfma_stem_blocked_ok(g, first.cin_real);
-    }
   }
-  return true;
+}
+
+// the ImageNet stem runs on 2x2 pixel blocks of the network input (tensor 0 is stored blocked)
+void decide_blocked_stem(dat_model& m) {
+  if (m.dtype != DAT_BF16) return;
+  Op& first = m.ops[0];
+  if (first.kind == OP_CONV && first.in == 0 && first.res < 0) {
+    ConvGeom g;
+    g.B = 1; g.H = m.tens[0].H; g.W = m.tens[0].W; g.Cin = m.tens[0].C; g.Ho = m.tens[first.out].H; g.Wo = m.tens[first.out].W;
+    g.Cout = m.tens[first.out].C; g.k = first.k; g.stride = first.stride; g.pad = first.pad;
+    bool only_consumer = true;
+    for (size_t i = 1; i < m.ops.size(); ++i) if (m.ops[i].in == 0 || m.ops[i].res == 0) only_consumer = false;
+    first.blocked = only_consumer && conv_mfma_stem_blocked_ok(g, first.cin_real);
+  }
 }
 
 template <typename T>
@@ -455,6 +472,8 @@ dat_status allocate(dat_model& m) {
     for (const Op& op : m.ops)
       if (op.kind == OP_CONV) { hipEvent_t e; DAT_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming)); m.wg_events.push_back(e); }
   }
+  DAT_TRY(dev_alloc(m, &m.gscale, m.ptab.size() * 4));
+  DAT_TRY(dev_alloc(m, &m.gscale_ways, m.ptab.size() * kAbsmaxWays * kAbsmaxStride * 4));
   DAT_TRY(dev_alloc(m, &m.sums, (size_t)2 * cmax * 4));
   DAT_TRY(dev_alloc(m, &m.loss_n, (size_t)m.maxB * 4));
   m.loss_cap = 1024;
@@ -578,6 +597,13 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
   // (per-launch timing keeps everything on one stream: its event pairs bracket launches on `st`)
   const bool side = grads && dt == DAT_BF16 && m.overlap_wgrad && m.wg_stream && !m.prof;
   size_t wg_used = 0;
+  // Every kernel that writes a parameter gradient also raises that tensor's abs-max slot (the quantizer's scale):
+  // bf16 models whose ops all have such writers.  The slots start at zero.
+  bool fused_scales = grads && dt == DAT_BF16 && m.grad_scales;
+  for (const Op& o : m.ops) if (o.kind == OP_BIASACT) fused_scales = false;
+  m.gscale_valid = false;
+  if (fused_scales) DAT_TRY(launch_fill_zero(m.gscale_ways, m.ptab.size() * kAbsmaxWays * kAbsmaxStride * 4, st));
+  auto slot = [&](int p) -> uint32_t* { return fused_scales && p >= 0 ? m.gscale_ways + (size_t)p * kAbsmaxWays * kAbsmaxStride : nullptr; };
   for (int i = (int)m.ops.size() - 1; i >= 0; --i) {
     Op& op = m.ops[i];
     const Shape si = m.tens[op.in], so = m.tens[op.out];
@@ -599,8 +625,8 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
             DAT_HIP(hipStreamWaitEvent(m.wg_stream, e, 0));
             wst = m.wg_stream;
           }
-          if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), wst, conv_mfma_stem_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.dv, op.cin_real, g, 1.0f, m.wgrad_ws, wst));
-          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), wst, conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, wst));
+          if (dt == DAT_BF16 && op.blocked) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), wst, conv_mfma_stem_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.dv, op.cin_real, g, 1.0f, m.wgrad_ws, wst, slot(op.p0)));
+          else if (dt == DAT_BF16) DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), wst, conv_mfma_backward_weight((const bf16_t*)m.act[op.in], (const bf16_t*)m.grad[op.out], g0, op.cin_real, g, 1.0f, m.wgrad_ws, wst, slot(op.p0)));
           else DAT_PROF(m, DAT_PROF_CONV_WGRAD, conv_flops(g, op.cin_real), st, conv_direct_backward_weight((const float*)m.act[op.in], (const float*)m.grad[op.out], g0, g, 1.0f, st));
         }
         if (op.in != 0 || need_input_grad) {
@@ -651,13 +677,15 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
             float* bg1 = grads ? grads + m.ptab[bn.p1].off : nullptr;
             const int nsum = bs.mode == 3 ? 3 : 2;
             DAT_PROF(m, DAT_PROF_BN, 0.0, st, bn_finalize_slabs(m.partial, bs.nslabs, si.C, rows_in, 2, bn.sums, bn.sums + si.C, bg1, bg0, 1.0f, st,
-                                                                 m.compute + m.ptab[bn.p0].off, bn.mean, bn.rstd, bn.bn_tab, nsum, 1, true));
+                                                                 m.compute + m.ptab[bn.p0].off, bn.mean, bn.rstd, bn.bn_tab, nsum, 1, true,
+                                                                 ParamAbsmax{slot(bn.p1), slot(bn.p0)}));
             if (bs.mode == 3) {
               Op& sb = m.ops[bn.res_bn];
               float* sg0 = grads ? grads + m.ptab[sb.p0].off : nullptr;
               float* sg1 = grads ? grads + m.ptab[sb.p1].off : nullptr;
               DAT_PROF(m, DAT_PROF_BN, 0.0, st, bn_finalize_slabs(m.partial, bs.nslabs, si.C, rows_in, 2, sb.sums, sb.sums + si.C, sg1, sg0, 1.0f, st,
-                                                                   m.compute + m.ptab[sb.p0].off, sb.mean, sb.rstd, sb.bn_tab, 3, 2, false));
+                                                                   m.compute + m.ptab[sb.p0].off, sb.mean, sb.rstd, sb.bn_tab, 3, 2, false,
+                                                                   ParamAbsmax{slot(sb.p1), slot(sb.p0)}));
             }
             bn.sums_ready = true;
           }
@@ -685,7 +713,8 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
           PoolGrad pg{pl.argmax, m.grad[pl.out], B, si.H, si.W, m.tens[pl.out].H, m.tens[pl.out].W, m.fuse_pool ? 1 : 0};
           DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * 4, st,
                    bn_pool_backward(m.act[op.in], op.mask, m.grad[op.out], m.grad[op.in], m.ghas[op.in], false, dt, si.C, op.mean, op.rstd,
-                                    m.compute + m.ptab[op.p0].off, m.partial, op.sums, op.bn_tab, g0, g1, 1.0f, pg, st));
+                                    m.compute + m.ptab[op.p0].off, m.partial, op.sums, op.bn_tab, g0, g1, 1.0f, pg, st,
+                                    ParamAbsmax{slot(op.p1), slot(op.p0)}));
           m.ghas[op.in] = 1;
           break;
         }
@@ -698,12 +727,14 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
             sec.x = m.act[sb.in]; sec.mean = sb.mean; sec.rstd = sb.rstd; sec.gamma = m.compute + m.ptab[sb.p0].off;
             sec.sums = sb.sums; sec.tab = sb.bn_tab;
             sec.dgamma = grads ? grads + m.ptab[sb.p0].off : nullptr; sec.dbeta = grads ? grads + m.ptab[sb.p1].off : nullptr;
+            sec.am = ParamAbsmax{slot(sb.p1), slot(sb.p0)};
             second = &sec;
           }
           // algorithmic bytes: read x, dout (and mask) once for the sums ...
           DAT_PROF(m, DAT_PROF_BN, (double)rows_in * si.C * m.esize() * (2 + (second ? 1 : 0)), st,
                    bn_backward_reduce(m.act[op.in], m.act[op.out], op.mask, m.grad[op.out], dt, rows_in, si.C, op.mean, op.rstd,
-                                      m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.bn_tab, g0, g1, 1.0f, st, second));
+                                      m.compute + m.ptab[op.p0].off, op.relu, m.partial, op.sums, op.bn_tab, g0, g1, 1.0f, st, second,
+                                      ParamAbsmax{slot(op.p1), slot(op.p0)}));
         }
         if (!op.apply_deferred) {
           // ... and once more, plus writing dx (and dres), for the input gradient
@@ -726,7 +757,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
         break;
       case OP_FC:
         DAT_TRY(fc_backward((const float*)m.act[op.in], m.compute + m.ptab[op.p0].off, (const float*)m.grad[op.out],
-                            (float*)m.grad[op.in], g0, g1, B, si.C, so.C, 1.0f, m.fc_ws, st));
+                            (float*)m.grad[op.in], g0, g1, B, si.C, so.C, 1.0f, m.fc_ws, st, ParamAbsmax{slot(op.p0), slot(op.p1)}));
         m.ghas[op.in] = 1;
         break;
     }
@@ -735,6 +766,8 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
     DAT_HIP(hipEventRecord(m.wg_join, m.wg_stream));
     DAT_HIP(hipStreamWaitEvent(st, m.wg_join, 0));
   }
+  if (fused_scales) DAT_TRY(launch_absmax_fold(m.gscale_ways, (int)m.ptab.size(), m.gscale, st));
+  m.gscale_valid = fused_scales;
   return DAT_OK;
 }
 
@@ -766,6 +799,9 @@ dat_status fetch_losses(dat_model& m, int count, float* host_out, hipStream_t st
   DAT_HIP(hipMemcpyAsync(m.host_stage, m.loss_steps, (size_t)count * 4, hipMemcpyDeviceToHost, st));
   DAT_HIP(hipStreamSynchronize(st));
   memcpy(host_out, m.host_stage, (size_t)count * 4);
+  // the one place a value is on the host anyway: a NaN or infinite loss is reported (device outputs are written)
+  for (int i = 0; i < count; ++i)
+    if (!std::isfinite(host_out[i])) return fail_with(DAT_ERR_NONFINITE, "a requested loss value is NaN or infinite");
   return DAT_OK;
 }
 
@@ -791,6 +827,8 @@ extern "C" dat_status dat_model_create(dat_arch arch, dat_dtype dtype, int max_b
   }
   m->add_tensor({H, W, dtype == DAT_BF16 ? 8 : 3});
   if (!build_graph(*m)) { delete m; return DAT_ERR_UNSUPPORTED; }
+  decide_blocked_stem(*m);
+  link_fusions(*m);
   for (const Shape& s : m->tens)
     if (s.H < 1 || s.W < 1) { delete m; return DAT_ERR_SHAPE; }
   dat_status s = allocate(*m);
@@ -852,7 +890,7 @@ extern "C" dat_status dat_attack(dat_model* m, const float* x, const int32_t* y,
                                  dat_init init, float* delta, float* loss_per_step, void* stream) {
   if (!m || !x || !y || !delta || K < 0 || !(eps >= 0.0f) || !(alpha >= 0.0f)) return DAT_ERR_ARG;
   if (init.mode != DAT_INIT_ZERO && init.mode != DAT_INIT_UNIFORM && init.mode != DAT_INIT_GIVEN) return DAT_ERR_ARG;
-  if (init.mode == DAT_INIT_GIVEN && !init.delta0) return DAT_ERR_ARG;
+  if (init.mode == DAT_INIT_GIVEN && (!init.delta0 || !aligned(init.delta0, 16))) return DAT_ERR_ARG;
   if (!aligned(x, 16) || !aligned(delta, 16)) return DAT_ERR_ARG;
   if (!batch_ok(m, B)) return DAT_ERR_SHAPE;
   if (loss_per_step && K + 1 > m->loss_cap) return DAT_ERR_UNSUPPORTED;
@@ -912,7 +950,7 @@ extern "C" dat_status dat_attack_kl(dat_model* m, const float* x, int B, float e
                                     float* delta, float* loss_per_step, void* stream) {
   if (!m || !x || !delta || K < 0 || !(eps >= 0.0f) || !(alpha >= 0.0f)) return DAT_ERR_ARG;
   if (init.mode != DAT_INIT_ZERO && init.mode != DAT_INIT_UNIFORM && init.mode != DAT_INIT_GIVEN) return DAT_ERR_ARG;
-  if (init.mode == DAT_INIT_GIVEN && !init.delta0) return DAT_ERR_ARG;
+  if (init.mode == DAT_INIT_GIVEN && (!init.delta0 || !aligned(init.delta0, 16))) return DAT_ERR_ARG;
   if (!aligned(x, 16) || !aligned(delta, 16)) return DAT_ERR_ARG;
   if (!batch_ok(m, B)) return DAT_ERR_SHAPE;
   if (loss_per_step && K + 1 > m->loss_cap) return DAT_ERR_UNSUPPORTED;
@@ -980,7 +1018,7 @@ extern "C" dat_status dat_step_reg(dat_model* m, const float* x, const float* x_
     DAT_TRY(kl_grad(*m, z_here, m->z_keep2, y, 1, lambda, B, inv, 0, st));
     DAT_TRY(backward(*m, B, m->g_tmp, false, st));
   }
-  if (two_pass) DAT_TRY(launch_sgd(grads, m->g_tmp, -1.0f, m->d, st));   // grads <- grads + g_tmp
+  if (two_pass) { DAT_TRY(launch_sgd(grads, m->g_tmp, -1.0f, m->d, st)); m->gscale_valid = false; }   // grads <- grads + g_tmp
   if (losses) {
     DAT_TRY(fetch_losses(*m, 2, host, st));
     losses[0] = (phi == DAT_PHI_CE && lambda == 0.0f) ? 0.0f : host[0];
@@ -1006,6 +1044,14 @@ extern "C" dat_status dat_input_grad(dat_model* m, const float* x, const int32_t
   return DAT_OK;
 }
 
+extern "C" dat_status dat_model_grad_scales(const dat_model* m, const float** scales_dev) {
+  if (!m || !scales_dev) return DAT_ERR_ARG;
+  if (!m->gscale_valid) return fail_with(DAT_ERR_UNSUPPORTED, "dat_model_grad_scales: the last call on this model did not produce per-tensor abs-max values "
+                                                              "(fp32 model, a model with bias layers, a two-pass objective, or no dat_step yet)");
+  *scales_dev = reinterpret_cast<const float*>(m->gscale);
+  return DAT_OK;
+}
+
 extern "C" dat_status dat_sgd_update(dat_model* m, const float* grads, float lr, void* stream) {
   if (!m || !grads) return DAT_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
@@ -1022,6 +1068,9 @@ extern "C" dat_status dat_model_set_option(dat_model* m, dat_option opt, int val
     case DAT_OPT_FUSE_BN_SUMS: m->fuse_bn_sums = value != 0; return DAT_OK;
     case DAT_OPT_SPARSE_SHORTCUT_GRADIENT: m->sparse_shortcut_grad = value != 0; return DAT_OK;
     case DAT_OPT_OVERLAP_WEIGHT_GRADIENTS: m->overlap_wgrad = value != 0; return DAT_OK;
+    case DAT_OPT_ABSORB_SHORTCUT_BN: m->absorb_shortcut_bn = value != 0; link_fusions(*m); return DAT_OK;
+    case DAT_OPT_FUSE_STEM_POOL: m->fuse_pool = value != 0; return DAT_OK;
+    case DAT_OPT_GRADIENT_SCALES: m->grad_scales = value != 0; return DAT_OK;
   }
   return DAT_ERR_ARG;
 }

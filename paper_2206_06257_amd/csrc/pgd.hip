@@ -233,6 +233,9 @@ InArgs pack(const NetInputDesc& d) {
 
 unsigned grid_for(int64_t npix) { return (unsigned)((npix + kPixPerBlock - 1) / kPixPerBlock); }
 
+// the 2x2-block layout decomposes the pixel index in 32 bits
+bool pixels_ok(int64_t npix, const NetInputDesc& in) { return !(in.bf16 && in.block_w) || npix < (1ll << 32); }
+
 const NetInputDesc kNoInput = {nullptr, 0, 0, {0, 0, 0}, {1, 1, 1}, 0, 0};
 
 }  // namespace
@@ -240,6 +243,7 @@ const NetInputDesc kNoInput = {nullptr, 0, 0, {0, 0, 0}, {1, 1, 1}, 0, 0};
 dat_status launch_attack_init(const float* x, int64_t npix, float eps, dat_init init, float* delta,
                               const NetInputDesc& in, hipStream_t st) {
   if (npix == 0) return DAT_OK;
+  if (!pixels_ok(npix, in)) return DAT_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(attack_kernel<0>, dim3(grid_for(npix)), dim3(kThreads), 0, st, x, (const float*)nullptr,
                      init.delta0, delta, npix, eps, 0.0f, (int)init.mode, init.seed, pack(in), (const void*)nullptr);
   DAT_LAUNCH_CHECK();
@@ -249,6 +253,7 @@ dat_status launch_attack_init(const float* x, int64_t npix, float eps, dat_init 
 dat_status launch_attack_update(const float* x, const float* G, float* delta, int64_t npix, float eps,
                                 float alpha, const NetInputDesc& in, hipStream_t st) {
   if (npix == 0) return DAT_OK;
+  if (!pixels_ok(npix, in)) return DAT_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(attack_kernel<1>, dim3(grid_for(npix)), dim3(kThreads), 0, st, x, G, (const float*)nullptr,
                      delta, npix, eps, alpha, 0, (uint64_t)0, pack(in), (const void*)nullptr);
   DAT_LAUNCH_CHECK();
@@ -259,6 +264,7 @@ dat_status launch_attack_update_netgrad(const float* x, const void* gnet, float*
                                         float alpha, const NetInputDesc& in, hipStream_t st) {
   if (npix == 0) return DAT_OK;
   if (!in.ptr || !in.bf16 || !gnet) return DAT_ERR_ARG;
+  if (!pixels_ok(npix, in)) return DAT_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(attack_kernel<3>, dim3(grid_for(npix)), dim3(kThreads), 0, st, x, (const float*)nullptr, (const float*)nullptr,
                      delta, npix, eps, alpha, 0, (uint64_t)0, pack(in), gnet);
   DAT_LAUNCH_CHECK();
@@ -268,6 +274,7 @@ dat_status launch_attack_update_netgrad(const float* x, const void* gnet, float*
 dat_status launch_make_input(const float* x, const float* delta, int64_t npix, const NetInputDesc& in,
                              hipStream_t st) {
   if (npix == 0) return DAT_OK;
+  if (!pixels_ok(npix, in)) return DAT_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(attack_kernel<2>, dim3(grid_for(npix)), dim3(kThreads), 0, st, x, (const float*)nullptr,
                      (const float*)nullptr, const_cast<float*>(delta), npix, 0.0f, 0.0f, 0, (uint64_t)0, pack(in), (const void*)nullptr);
   DAT_LAUNCH_CHECK();
@@ -280,7 +287,7 @@ using namespace dat;
 
 static bool init_ok(const dat_init& init) {
   if (init.mode != DAT_INIT_ZERO && init.mode != DAT_INIT_UNIFORM && init.mode != DAT_INIT_GIVEN) return false;
-  if (init.mode == DAT_INIT_GIVEN && (!init.delta0 || !aligned(init.delta0, 4))) return false;
+  if (init.mode == DAT_INIT_GIVEN && (!init.delta0 || !aligned(init.delta0, 16))) return false;   // read as 16-byte vectors
   return true;
 }
 

@@ -354,6 +354,26 @@ extern "C" dat_status dat_quantize(const float* grads, const int64_t* offsets_de
   return DAT_OK;
 }
 
+extern "C" dat_status dat_quantize_scaled(const float* grads, const int64_t* offsets_dev, int num_tensors, int64_t d, int bits,
+                                          uint64_t seed, const float* scales, uint8_t* q, void* stream) {
+  if (!grads || !offsets_dev || !q || !scales || num_tensors < 1 || d < 0 || !bits_ok(bits)) return DAT_ERR_ARG;
+  if (!aligned(grads, 16) || !aligned(q, 4) || !aligned(scales, 4)) return DAT_ERR_ARG;
+  if (d == 0) return DAT_OK;
+  hipStream_t st = (hipStream_t)stream;
+#define DAT_Q_LAUNCH(B)                                                                          \
+  hipLaunchKernelGGL(quantize_kernel<B>, dim3(blocks_for((d + Fmt<B>::kEpt - 1) / Fmt<B>::kEpt)), \
+                     dim3(kThreads), 0, st, grads, offsets_dev, num_tensors, d, seed, scales, q)
+  switch (bits) {
+    case 2: DAT_Q_LAUNCH(2); break;
+    case 4: DAT_Q_LAUNCH(4); break;
+    case 8: DAT_Q_LAUNCH(8); break;
+    default: DAT_Q_LAUNCH(16); break;
+  }
+#undef DAT_Q_LAUNCH
+  DAT_LAUNCH_CHECK();
+  return DAT_OK;
+}
+
 extern "C" dat_status dat_dequantize(const uint8_t* q, const float* scales, const int64_t* offsets_dev,
                                      int num_tensors, int64_t d, int bits, float* grads_out,
                                      void* stream) {

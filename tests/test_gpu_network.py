@@ -289,28 +289,29 @@ def test_pgd_step_from_the_bf16_input_gradient_gives_the_same_bits(dat, arch, B,
 
 
 @pytest.mark.parametrize("arch,B,H,W,classes", [(3, 5, 64, 64, 12), (1, 16, 16, 16, 10), (100, 8, 16, 16, 5)])
-def test_shortcut_bn_evaluated_by_the_branch_bn_gives_the_same_bits(dat, arch, B, H, W, classes, monkeypatch):
+def test_shortcut_bn_evaluated_by_the_branch_bn_gives_the_same_bits(dat, arch, B, H, W, classes):
     """bf16 models: the normalisation on a projection shortcut is evaluated by the branch's last BN (forward) and
-    shares its pass over d(out) (backward); with the environment switch DAT_KEEP_SHORTCUT_BN set at model creation
-    it runs as passes of its own.  Logits, input gradient and parameter gradients agree bit for bit."""
+    shares its pass over d(out) (backward); with DAT_OPT_ABSORB_SHORTCUT_BN = 0 it runs as passes of its own.  The
+    same for the BN + ReLU + max-pool fusion of the stem (DAT_OPT_FUSE_STEM_POOL).  Logits, input gradient and
+    parameter gradients agree bit for bit, also after switching back and forth on one model."""
+    gpu = dat.Model(arch, dat.BF16, B, H, W, classes, None, None)
+    # (which BN sums come out of a convolution epilogue depends on the launch graph; with that option off both
+    # graphs sum in the same order and the comparison isolates the two fusions)
+    gpu.set_option(dat.OPT_FUSE_BN_SUMS, 0)
+    gpu.set_params(syn.perturbed_params(41, gpu.offsets, gpu.fan_in, gpu.kind))
+    xd, yd = _cuda(syn.images(41, B, H, W)), _cuda(syn.labels(41, B, classes))
     outs = []
-    for keep in (False, True):
-        for name in ("DAT_KEEP_SHORTCUT_BN", "DAT_KEEP_STEM_POOL"):   # (the max-pool fusion is covered by the same runs)
-            if keep:
-                monkeypatch.setenv(name, "1")
-            else:
-                monkeypatch.delenv(name, raising=False)
-        gpu = dat.Model(arch, dat.BF16, B, H, W, classes, None, None)
-        # (which BN sums come out of a convolution epilogue depends on the layer graph; with that option off both
-        # graphs sum in the same order and the comparison isolates the two fusions)
-        gpu.set_option(dat.OPT_FUSE_BN_SUMS, 0)
-        gpu.set_params(syn.perturbed_params(41, gpu.offsets, gpu.fan_in, gpu.kind))
-        xd, yd = _cuda(syn.images(41, B, H, W)), _cuda(syn.labels(41, B, classes))
+    for fused in (1, 0, 1):
+        gpu.set_option(dat.OPT_ABSORB_SHORTCUT_BN, fused)
+        gpu.set_option(dat.OPT_FUSE_STEM_POOL, fused)
+        stored = sum(t["act_stored"] for t in gpu.inspect_tensors())
         gx, logits, loss = gpu.input_grad(xd, yd)
         g, l = gpu.step(xd, yd, want_loss=True)
-        outs.append((gx.cpu().numpy(), logits.cpu().numpy(), g.cpu().numpy()))
-    for a, b in zip(*outs):
-        assert np.abs(a).max() > 0 and np.array_equal(a, b)
+        outs.append((stored, gx.cpu().numpy(), logits.cpu().numpy(), g.cpu().numpy()))
+    assert outs[1][0] > outs[0][0] == outs[2][0]          # the unfused graph stores more tensors
+    for other in outs[1:]:
+        for a, b in zip(outs[0][1:], other[1:]):
+            assert np.abs(a).max() > 0 and np.array_equal(a, b)
 
 
 def test_bn_backward_sums_from_the_convolution_epilogue(dat):
@@ -402,9 +403,60 @@ def test_weight_gradients_on_the_side_stream_give_the_same_bits(dat, arch, B, H,
                 assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("arch,B,H,W,classes", [(100, 8, 16, 16, 5), (1, 16, 16, 16, 10), (2, 4, 8, 8, 10), (3, 5, 64, 96, 12)])
+def test_scales_from_the_gradient_writers_are_the_quantizers_own(dat, arch, B, H, W, classes):
+    """bf16 models: every kernel that writes a parameter gradient also raises that tensor's abs-max
+    (dat_model_grad_scales).  Abs-max is exact, so the values equal bit for bit what the quantizer's own pass
+    over the gradient finds, and dat_quantize_scaled writes dat_quantize's codes (8 and 4 bit); a second step
+    starts from zero again; fp32 models and two-pass objectives refuse."""
+    gpu = dat.Model(arch, dat.BF16, B, H, W, classes, MEAN, STD)
+    gpu.set_params(syn.perturbed_params(63, gpu.offsets, gpu.fan_in, gpu.kind))
+    offs = (gpu.offsets_device(), gpu.num_tensors)
+    with pytest.raises(dat.DatError):
+        gpu.grad_scales()                                  # no step yet
+    for cfg in (63, 64):                                   # the second batch has other (partly smaller) maxima
+        xd, yd = _cuda(syn.images(cfg, B, H, W)), _cuda(syn.labels(cfg, B, classes))
+        g = gpu.step(xd, yd)
+        fused = gpu.grad_scales_tensor()
+        for bits in (8, 4):
+            q_ref, sc_ref = dat.quantize(g, offs, bits, 5)
+            assert torch.equal(sc_ref.view(torch.int32), fused.view(torch.int32))
+            assert torch.equal(dat.quantize_scaled(g, offs, bits, 5, gpu.grad_scales()), q_ref)
+        assert float(fused.max()) > 0
+    gpu.step_reg(xd, xd, yd, 1.0, dat.PHI_CE)
+    with pytest.raises(dat.DatError) as e:
+        gpu.grad_scales()
+    assert e.value.status == 6
+    f32 = dat.Model(dat.ARCH_TINYCNN, dat.F32, 4, 8, 8, 10)
+    f32.step(torch.zeros(4, 8, 8, 3, device="cuda"), torch.zeros(4, dtype=torch.int32, device="cuda"))
+    with pytest.raises(dat.DatError):
+        f32.grad_scales()
+
+
+def test_labels_out_of_range_give_nan_loss_and_touch_nothing_else(dat):
+    """Labels are device memory the host cannot check: a label outside [0, classes) makes that sample's loss NaN,
+    leaves the one-hot term out of its logit gradient, and reads nothing out of bounds (every kernel finishes)."""
+    B, H, classes = 6, 8, 10
+    gpu = dat.Model(dat.ARCH_TINYCNN, dat.F32, B, H, H, classes)
+    gpu.set_params(syn.he_normal_params(3, gpu.offsets, gpu.fan_in, gpu.kind))
+    x = _cuda(syn.images(3, B, H, H)); y = syn.labels(3, B, classes)
+    gx_ok, logits, loss_ok = gpu.input_grad(x, _cuda(y))
+    bad = y.copy(); bad[2] = classes; bad[4] = -1
+    with pytest.raises(dat.DatError) as e:                 # asked for the loss: the NaN is reported
+        gpu.input_grad(x, _cuda(bad))
+    assert e.value.status == 4 and np.isfinite(loss_ok)
+    gx_bad, logits_bad, _ = gpu.input_grad(x, _cuda(bad), want_loss=False)
+    assert torch.equal(logits, logits_bad) and bool(torch.isfinite(gx_bad).all())
+    good = [0, 1, 3, 5]                                    # samples are independent in this network (no batch norm)
+    assert torch.equal(gx_ok[good], gx_bad[good]) and not torch.equal(gx_ok[2], gx_bad[2])
+
+
 def test_batch_and_argument_errors(dat):
     gpu = dat.Model(dat.ARCH_TINYCNN, dat.F32, 4, 8, 8, 10)
     x = torch.zeros(8, 8, 8, 3, device="cuda"); y = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(dat.DatError):                      # delta0 is read as 16-byte vectors
+        d0 = torch.zeros(4 * 8 * 8 * 3 + 1, device="cuda")[1:].view(4, 8, 8, 3)
+        gpu.attack(x[:4], y[:4], EPS, ALPHA, 1, dat.INIT_GIVEN, delta0=d0)
     with pytest.raises(dat.DatError) as e:
         gpu.attack(x, y, EPS, ALPHA, 1)
     assert e.value.status == 2
