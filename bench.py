@@ -112,6 +112,7 @@ def main():
     import synth_inputs as syn
 
     arch, H, W, classes, B, K, eps, alpha, norm, cfg = WORKLOADS[args.workload]
+    blocked_stem = arch == 3 and H % 2 == 0 and W % 2 == 0     # 7x7/2 stem: the network input is stored as 2x2 pixel blocks
     torch.cuda.set_device(0)
     model = dat.Model(arch, dat.BF16, B, H, W, classes, MEAN if norm else None, STD if norm else None)
     model.set_params(syn.he_normal_params(cfg, model.offsets, model.fan_in, model.kind))
@@ -240,10 +241,12 @@ def main():
         if pg[0] > 0:
             out["pgd_update"] = {"GBs": pg[2] / (pg[0] * 1e-3) / 1e9, "frac_hbm": pg[2] / (pg[0] * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                  "bytes_per_element": 18,
-                                 "moved_GBs": pg[2] / 18.0 * (12.0 + 32.0 / 3.0) / (pg[0] * 1e-3) / 1e9,
-                                 "note": "one launch per iteration; it reads the bf16 input gradient and writes the bf16 network input as "
-                                         "16-byte vectors per pixel (3 of 8 channels used), so it moves 22.7 bytes per element for the 18 "
-                                         "algorithmic ones"}
+                                 "moved_GBs": pg[2] / 18.0 * ((52.0 if blocked_stem else 68.0) / 3.0) / (pg[0] * 1e-3) / 1e9,
+                                 "note": "one launch per iteration; algorithmic bytes per element: x, delta, G read (12), delta written (4), "
+                                         "bf16 network input written (2).  It reads the bf16 input gradient and writes the bf16 network input "
+                                         + ("as 2x2 pixel blocks of 4 channels (8 bytes per pixel, 3 of 4 channels used): 52 bytes moved per pixel "
+                                            "for the 54 algorithmic ones (G is read as bf16)" if blocked_stem else
+                                            "as 16-byte vectors per pixel (3 of 8 channels used): 68 bytes moved per pixel for the 54 algorithmic ones")}
         total_flops = sum(prof[k][2] for k in ("conv_fwd", "conv_bwd_data", "conv_bwd_data_bn", "conv_wgrad")) / args.steps
         out["roofline"]["measured_over"] = "%d further steps of the same work with a hipEvent pair around every launch (%.1f ms/step with events)" % (args.steps, ms_per_step_events)
         out["step_conv_TFLOPs"] = total_flops / 1e12

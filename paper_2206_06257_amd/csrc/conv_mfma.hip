@@ -76,6 +76,11 @@ struct IgemmArgs {
   bf16_t* out;          // [M][Cout], M = B*Hout*Wout
   int B, Hin, Win, Cin, Hout, Wout, Cout;   // Hout x Wout = grid of output pixels this launch computes
   int KH, KW, ostride, pad_h, pad_w;
+  // Elements between neighbouring input pixels of a row (0: Cin, the ordinary case).  With 0 < xstride < Cin the
+  // "Cin channels" of pixel w are the stored values of the pixels w .. w + Cin/xstride - 1, i.e. a filter row of
+  // Cin/xstride taps read as one contiguous vector (igemm_dma_kernel with Cin equal to its k-tile only); a 16-byte
+  // vector then lies in pixel w + offset/xstride and is zero when that pixel is outside the row.
+  int xstride;
   // output pixel (n, a, b) is stored at row (n*outH + a*ostep + oh0)*outW + b*ostep + ow0 of `out`
   int outH, outW, ostep, oh0, ow0;
   int M, Ktot, nct, npt;
@@ -584,6 +589,8 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   }
   const int ntiles = a.Ktot / BKT;
   const unsigned char* zero_page = reinterpret_cast<const unsigned char*>(g_zero_page);
+  const int ps = a.xstride ? a.xstride : a.Cin;         // elements between neighbouring input pixels
+  const int xcol = (kvec * 8) / ps;                     // pixel this thread's vector lies in, relative to the tap (0 unless xstride is set)
   int woff[VW]; bool wrow[VW];
 #pragma unroll
   for (int i = 0; i < VW; ++i) {
@@ -607,8 +614,8 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
 #pragma unroll
       for (int i = 0; i < VX; ++i) {
         const int hi = hb[i] + kr, wi = wb[i] + ks;
-        xok[i] = mv[i] & (hi >= 0) & (wi >= 0) & (hi < a.Hin) & (wi < a.Win);
-        xoff[i] = (nb[i] + hi * a.Win + wi) * a.Cin + kvec * 8;
+        xok[i] = mv[i] & (hi >= 0) & (wi + xcol >= 0) & (hi < a.Hin) & (wi + xcol < a.Win);
+        xoff[i] = (nb[i] + hi * a.Win + wi) * ps + kvec * 8;
       }
     }
 #pragma unroll
@@ -668,6 +675,7 @@ template <int TC, int TP, int WGC, int OCC, int BKT = 64>
 dat_status launch_igemm_dma(IgemmArgs a, hipStream_t st) {
   if ((int64_t)a.B * a.Hin * a.Win * a.Cin >= (1ll << 31) || (int64_t)a.Cout * a.Ktot >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;
   if (a.Cin % BKT != 0 || a.Ktot < BKT || a.Ktot % BKT != 0) return DAT_ERR_UNSUPPORTED;
+  if (a.xstride && (a.Cin != BKT || a.xstride % 8 != 0 || a.Cin % a.xstride != 0)) return DAT_ERR_UNSUPPORTED;   // one tap per k-tile
   a.nct = (a.Cout + TC - 1) / TC;
   a.npt = (a.M + TP - 1) / TP;
   if (a.npt == 0) return DAT_OK;
@@ -728,6 +736,8 @@ __global__ __launch_bounds__(512) void igemm_ring_kernel(IgemmArgs a) {
   }
   const int ntiles = a.Ktot / BKT;
   const unsigned char* zero_page = reinterpret_cast<const unsigned char*>(g_zero_page);
+  const int ps = a.xstride ? a.xstride : a.Cin;         // elements between neighbouring input pixels
+  const int xcol = (kvec * 8) / ps;                     // pixel this thread's vector lies in, relative to the tap (0 unless xstride is set)
   int woff[VW]; bool wrow[VW];
 #pragma unroll
   for (int i = 0; i < VW; ++i) {
@@ -950,6 +960,10 @@ dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
   g_launches.fetch_add(1, std::memory_order_relaxed);
   if (a.Cin % 8 != 0 || a.Cout % 8 != 0) return DAT_ERR_UNSUPPORTED;
   if (a.stat_mode == 3 && (a.Cout <= 64 || a.xf_tab)) return DAT_ERR_UNSUPPORTED;   // three sums: 128-channel tiles only
+  if (a.xstride) {   // overlapping input pixels: the direct-to-LDS kernel with one tap per 64-wide k-tile
+    if (a.Cout > 64 || a.xf_tab) return DAT_ERR_UNSUPPORTED;
+    return a.Cout <= 32 ? launch_igemm_dma<32, 128, 1, 6>(a, st) : launch_igemm_dma<64, 128, 2, 5>(a, st);
+  }
   switch (pick_ring(a)) {
     case 1: return launch_igemm_ring<256, 256, 2, 2>(a, st);
     case 2: return launch_igemm_ring<256, 128, 4, 3>(a, st);
@@ -1023,23 +1037,27 @@ __global__ void weight_transform_kernel(const float* __restrict__ master, bf16_t
 }
 
 // ---- 7x7 stride-2 pad-3 stem as a 4x4 stride-1 convolution over 2x2 pixel blocks -----------------
-// With 3 (padded to 8) input channels the stem wastes most of a 32-row MFMA tile in backward-data
-// and needs a per-vector tap decode in forward.  Storing the network input as 2x2 pixel blocks,
-//   x2[n][i][j][(ph*2+pw)*8 + c] = x[n][2i+ph][2j+pw][c]      (H, W even),
-// turns it into a dense layer with 32 input channels:
+// With 3 input channels the stem wastes most of a 32-row MFMA tile in backward-data and needs a per-vector
+// tap decode in forward.  Storing the network input as 2x2 pixel blocks of 4 channels (3 used; 8 bytes per
+// pixel, 32 per block),
+//   x2[n][i][j][(ph*2+pw)*4 + c] = x[n][2i+ph][2j+pw][c]      (H, W even),
+// turns it into a dense layer with 16 input channels:
 //   forward:       y[ho][wo][co]  = sum_{a,b<4} sum_v  x2[ho-2+a][wo-2+b][v] * Vf[co][a][b][v]
 //                  Vf[co][a][b][(ph,pw,c)] = W[co][2a+ph-1][2b+pw-1][c]
 //   backward-data: dx2[i][j][v]   = sum_{a,b<4} sum_co dy[i-1+a][j-1+b][co] * Vb[v][a][b][co]
 //                  Vb[(ph,pw,c)][a][b][co] = W[co][5+ph-2a][5+pw-2b][c]
-// (filter taps outside 0..6 and channels c >= 3 are zero: 49 of the 64 window/parity pairs are
-// used), one launch each, all four pixel parities of the input gradient at once.
+// (filter taps outside 0..6 and channel 3 are zero: 49 of the 64 window/parity pairs are used), one launch
+// each, all four pixel parities of the input gradient at once.  The four blocks of a window row are
+// contiguous in memory, so the forward pass reads them as ONE tap of 64 channels (IgemmArgs::xstride = 16):
+// a 4 x 1 filter over 64-channel pixels that overlap their neighbours.
+constexpr int kStemV = 16;     // values per 2x2 block: 4 positions x 4 channels
 __global__ void stem_weight_transform_kernel(const float* __restrict__ master, bf16_t* __restrict__ vf, bf16_t* __restrict__ vb,
                                              int Cout, int cin_real) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= Cout * 16 * 32) return;
+  if (i >= Cout * 16 * kStemV) return;
   {   // vf[co][a][b][v]
-    const int v = i & 31, b = (i >> 5) & 3, a = (i >> 7) & 3, co = i >> 9;
-    const int ph = v >> 4, pw = (v >> 3) & 1, c = v & 7;
+    const int v = i & 15, b = (i >> 4) & 3, a = (i >> 6) & 3, co = i >> 8;
+    const int ph = v >> 3, pw = (v >> 2) & 1, c = v & 3;
     const int r = 2 * a + ph - 1, s = 2 * b + pw - 1;
     const bool ok = c < cin_real && r >= 0 && r < 7 && s >= 0 && s < 7;
     vf[i] = ok ? f2bf(master[((co * 7 + r) * 7 + s) * cin_real + c]) : (bf16_t)0;
@@ -1047,7 +1065,7 @@ __global__ void stem_weight_transform_kernel(const float* __restrict__ master, b
   {   // vb[v][a][b][co]
     const int co = i % Cout; int t = i / Cout;
     const int b = t & 3, a = (t >> 2) & 3, v = t >> 4;
-    const int ph = v >> 4, pw = (v >> 3) & 1, c = v & 7;
+    const int ph = v >> 3, pw = (v >> 2) & 1, c = v & 3;
     const int r = 5 + ph - 2 * a, s = 5 + pw - 2 * b;
     const bool ok = c < cin_real && r >= 0 && r < 7 && s >= 0 && s < 7;
     vb[i] = ok ? f2bf(master[((co * 7 + r) * 7 + s) * cin_real + c]) : (bf16_t)0;
@@ -1063,7 +1081,7 @@ __global__ void stem_wgrad_gather_kernel(const float* __restrict__ dv, float* __
     const int s = t % 7; t /= 7;
     const int r = t % 7; const int co = t / 7;
     const int ph = (r + 1) & 1, a = (r + 1) >> 1, pw = (s + 1) & 1, b = (s + 1) >> 1;
-    const float v = dv[((co * 4 + a) * 4 + b) * 32 + (ph * 2 + pw) * 8 + c];
+    const float v = dv[((co * 4 + a) * 4 + b) * kStemV + (ph * 2 + pw) * 4 + c];
     dw[i] = v;
     m = abs_bits(v);
   }
@@ -1327,6 +1345,7 @@ int conv_stat_slabs(int64_t rows, int stride) {
 
 dat_status conv_mfma_forward(const bf16_t* x, const bf16_t* w, const bf16_t* res, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
+  a.xstride = 0;
   a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
   a.in = x; a.wt = w; a.res = res; a.res_mask = nullptr; a.res_even_only = 0; a.out = y;
   a.B = g.B; a.Hin = g.H; a.Win = g.W; a.Cin = g.Cin; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
@@ -1356,6 +1375,7 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
   if (sparse == 2 && !accumulate) return DAT_ERR_ARG;
   if (bn && !conv_mfma_bn_operand_ok(g)) return DAT_ERR_UNSUPPORTED;
   IgemmArgs a;
+  a.xstride = 0;
   a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
   if (bn) { a.xf_x = bn->x; a.xf_mask = bn->mask; a.xf_tab = bn->tab; }
   a.in = dy; a.res = accumulate ? dx : masked_res; a.res_mask = masked_res ? res_mask : nullptr; a.out = dx;
@@ -1396,17 +1416,17 @@ dat_status conv_mfma_backward_data(const bf16_t* dy, const bf16_t* wT, bf16_t* d
 
 // ---- stem on 2x2 pixel blocks ---------------------------------------------------------------------
 bool conv_mfma_stem_blocked_ok(const ConvGeom& g, int cin_real) {
-  return g.k == 7 && g.stride == 2 && g.pad == 3 && g.Cin == 8 && cin_real <= 8 && g.H % 2 == 0 && g.W % 2 == 0 && g.Cout % 8 == 0;
+  return g.k == 7 && g.stride == 2 && g.pad == 3 && g.Cin == 8 && cin_real <= 4 && g.H % 2 == 0 && g.W % 2 == 0 && g.Cout % 8 == 0 && g.Cout <= 64;
 }
 
 ConvGeom conv_mfma_stem_blocked_geom(const ConvGeom& g) {
   ConvGeom q = g;
-  q.H = g.H / 2; q.W = g.W / 2; q.Cin = 32; q.k = 4; q.stride = 1; q.pad = 2;   // Ho, Wo, Cout unchanged
+  q.H = g.H / 2; q.W = g.W / 2; q.Cin = kStemV; q.k = 4; q.stride = 1; q.pad = 2;   // Ho, Wo, Cout unchanged
   return q;
 }
 
 dat_status launch_stem_weight_transform(const float* master, bf16_t* vf, bf16_t* vb, int Cout, int cin_real, hipStream_t st) {
-  const int n = Cout * 16 * 32;
+  const int n = Cout * 16 * kStemV;
   hipLaunchKernelGGL(stem_weight_transform_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, master, vf, vb, Cout, cin_real);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
@@ -1414,12 +1434,14 @@ dat_status launch_stem_weight_transform(const float* master, bf16_t* vf, bf16_t*
 
 dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st) {
   IgemmArgs a;
+  a.xstride = 0;
   a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
   a.in = x2; a.wt = vf; a.res = nullptr; a.res_mask = nullptr; a.res_even_only = 0; a.out = y;
-  a.B = g.B; a.Hin = g.H / 2; a.Win = g.W / 2; a.Cin = 32; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
-  a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 2;
+  // a window row of four blocks is one contiguous 64-value vector: 4 x 1 taps of 64 "channels", pixels kStemV apart
+  a.B = g.B; a.Hin = g.H / 2; a.Win = g.W / 2; a.Cin = 4 * kStemV; a.xstride = kStemV; a.Hout = g.Ho; a.Wout = g.Wo; a.Cout = g.Cout;
+  a.KH = 4; a.KW = 1; a.ostride = 1; a.pad_h = a.pad_w = 2;
   a.outH = g.Ho; a.outW = g.Wo; a.ostep = 1; a.oh0 = a.ow0 = 0;
-  a.M = g.B * g.Ho * g.Wo; a.Ktot = 16 * 32; a.nct = a.npt = 0;
+  a.M = g.B * g.Ho * g.Wo; a.Ktot = 16 * kStemV; a.nct = a.npt = 0;
   set_stats(a, stats, 0);
   if (stats) stats->nslabs = (a.M + kPixelTile - 1) / kPixelTile;
   return run_igemm(a, st);
@@ -1427,9 +1449,10 @@ dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y,
 
 dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16_t* dx2, const ConvGeom& g, bool accumulate, hipStream_t st) {
   IgemmArgs a;
+  a.xstride = 0;
   a.xf_x = nullptr; a.xf_mask = nullptr; a.xf_tab = nullptr;
   a.in = dy; a.wt = vb; a.res = accumulate ? dx2 : nullptr; a.res_mask = nullptr; a.res_even_only = 0; a.out = dx2;
-  a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H / 2; a.Wout = g.W / 2; a.Cout = 32;
+  a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H / 2; a.Wout = g.W / 2; a.Cout = kStemV;
   a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 1;
   a.outH = a.Hout; a.outW = a.Wout; a.ostep = 1; a.oh0 = a.ow0 = 0;
   a.M = g.B * a.Hout * a.Wout; a.Ktot = 16 * g.Cout; a.nct = a.npt = 0;
@@ -1465,11 +1488,11 @@ dat_status launch_weight_transform(const float* master, bf16_t* w, bf16_t* wT, i
   return DAT_OK;
 }
 
-// dw [Cout][7][7][cin_real] through the blocked layer's gradient dv [Cout][4][4][32] (scratch, fp32).
+// dw [Cout][7][7][cin_real] through the blocked layer's gradient dv [Cout][4][4][16] (scratch, fp32).
 dat_status conv_mfma_stem_backward_weight(const bf16_t* x2, const bf16_t* dy, float* dw, float* dv, int cin_real, const ConvGeom& g,
                                           float scale, void* ws, hipStream_t st, uint32_t* absmax) {
   const ConvGeom q = conv_mfma_stem_blocked_geom(g);
-  const dat_status s = conv_mfma_backward_weight(x2, dy, dv, 32, q, scale, ws, st);
+  const dat_status s = conv_mfma_backward_weight(x2, dy, dv, kStemV, q, scale, ws, st);
   if (s != DAT_OK) return s;
   const int n = g.Cout * 49 * cin_real;
   hipLaunchKernelGGL(stem_wgrad_gather_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)dv, dw, g.Cout, cin_real, absmax);

@@ -10,7 +10,7 @@ struct NetInputDesc {
   int bf16;           // 1: bf16 NHWC with channels padded to 8 (pad = 0); 0: fp32 NHWC, 3 channels
   int normalize;
   float mean[3], inv_std[3];
-  int block_h, block_w;   // bf16 only: image height/width when the tensor is stored as 2x2 pixel blocks ([H/2][W/2][4*8]), else 0
+  int block_h, block_w;   // bf16 only: image height/width when the tensor is stored as 2x2 pixel blocks of 4 channels ([H/2][W/2][4*4]: 8 bytes per pixel), else 0
 };
 // z_0 (and optionally the network input at x + z_0) for `npix` pixels of 3 channels.
 dat_status launch_attack_init(const float* x, int64_t npix, float eps, dat_init init, float* delta,
@@ -93,16 +93,16 @@ size_t conv_mfma_wgrad_workspace(const ConvGeom& g);
 // absmax (optional): the tensor's group of kAbsmaxWays slots that receive max |dw| (see absmax_way).
 dat_status conv_mfma_backward_weight(const bf16_t* x, const bf16_t* dy, float* dw, int cin_real, const ConvGeom& g, float scale, void* ws, hipStream_t st,
                                      uint32_t* absmax = nullptr);
-// A 7x7 stride-2 pad-3 convolution of an input with 8 stored channels (H, W even) can run as a 4x4
-// stride-1 convolution over 2x2 pixel blocks when the input tensor is stored blocked,
-// x2[n][i][j][(ph*2+pw)*8 + c] = x[n][2i+ph][2j+pw][c]; `g` is always the original geometry.
-// vf [Cout][4][4][32] and vb [32][4][4][Cout] are the forward and backward-data operands; dx2 is blocked too.
+// A 7x7 stride-2 pad-3 convolution of an input with at most 4 real channels (H, W even) can run as a 4x4
+// stride-1 convolution over 2x2 pixel blocks when the input tensor is stored blocked with 4 channels per pixel,
+// x2[n][i][j][(ph*2+pw)*4 + c] = x[n][2i+ph][2j+pw][c]; `g` is always the original geometry.
+// vf [Cout][4][4][16] and vb [16][4][4][Cout] are the forward and backward-data operands; dx2 is blocked too.
 bool conv_mfma_stem_blocked_ok(const ConvGeom& g, int cin_real);
 ConvGeom conv_mfma_stem_blocked_geom(const ConvGeom& g);
 dat_status launch_stem_weight_transform(const float* master, bf16_t* vf, bf16_t* vb, int Cout, int cin_real, hipStream_t st);
 dat_status conv_mfma_stem_forward(const bf16_t* x2, const bf16_t* vf, bf16_t* y, const ConvGeom& g, ConvStats* stats, hipStream_t st);
 dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16_t* dx2, const ConvGeom& g, bool accumulate, hipStream_t st);
-// dv: [Cout][4][4][32] fp32 scratch; ws: conv_mfma_wgrad_workspace(conv_mfma_stem_blocked_geom(g)) bytes.
+// dv: [Cout][4][4][16] fp32 scratch; ws: conv_mfma_wgrad_workspace(conv_mfma_stem_blocked_geom(g)) bytes.
 dat_status conv_mfma_stem_backward_weight(const bf16_t* x2, const bf16_t* dy, float* dw, float* dv, int cin_real, const ConvGeom& g,
                                           float scale, void* ws, hipStream_t st, uint32_t* absmax = nullptr);
 // master fp32 [Cout][k][k][cin_real] -> w bf16 [Cout][k][k][Cin] (zero padded) and wT.
@@ -188,7 +188,7 @@ dat_status kl_forward_backward(const float* z_clean, const float* z_adv, const i
                                float* loss_n, float* loss_mean, int B, int O, float gscale, hipStream_t st);
 // fp32 -> bf16 copy (linear weights) ; first-layer gradient [rows][Cpad] -> gx[rows][3] * inv_std.
 dat_status launch_round_bf16_values(const float* src, float* dst, int64_t n, hipStream_t st);
-// block_h, block_w > 0: g0 is stored as 2x2 pixel blocks of a block_h x block_w image.
+// block_h, block_w > 0: g0 is stored as 2x2 pixel blocks of a block_h x block_w image (Cpad = 4 then).
 dat_status launch_input_grad(const void* g0, int dtype, int Cpad, int64_t rows, float s0, float s1, float s2, float* gx,
                              int block_h, int block_w, hipStream_t st);
 dat_status launch_sgd(float* theta, const float* g, float lr, int64_t n, hipStream_t st);

@@ -52,7 +52,7 @@ struct Op {
   bool blocked = false;         // conv: 7x7/2 stem run on the 2x2-pixel-block layout of the network input
   int res_grad_from = -1;       // conv: BN op whose residual gradient (d out .* ReLU mask) this conv's backward-data adds itself
   bool res_grad_deferred = false;   // BN with residual: that gradient is not written, the conv above picks it up
-  float* dv = nullptr;          //   its weight gradient in the blocked layer's shape, [Cout][4][4][32]
+  float* dv = nullptr;          //   its weight gradient in the blocked layer's shape, [Cout][4][4][16]
 };
 
 struct PTensor { int64_t off, numel; int fan_in, kind; };
@@ -446,7 +446,7 @@ dat_status allocate(dat_model& m) {
     }
     if (op.kind == OP_MAXPOOL) DAT_TRY(dev_alloc(m, &op.argmax, (size_t)m.maxB * m.tens[op.out].numel()));
     if (op.kind == OP_CONV && m.dtype == DAT_BF16) {
-      const size_t n = op.blocked ? (size_t)m.tens[op.out].C * 16 * 32 : (size_t)m.tens[op.out].C * op.k * op.k * m.tens[op.in].C;
+      const size_t n = op.blocked ? (size_t)m.tens[op.out].C * 16 * 16 : (size_t)m.tens[op.out].C * op.k * op.k * m.tens[op.in].C;   // blocked: [Cout][4][4][16]
       DAT_TRY(dev_alloc(m, &op.w16, n * 2));
       DAT_TRY(dev_alloc(m, &op.w16T, n * 2));
       if (op.blocked) DAT_TRY(dev_alloc(m, &op.dv, n * 4));
@@ -774,7 +774,7 @@ dat_status backward(dat_model& m, int B, float* grads, bool need_input_grad, hip
 dat_status pixel_grad(dat_model& m, int B, float* gx, hipStream_t st) {
   const bool n = m.normalize;
   const bool blocked = m.ops[0].kind == OP_CONV && m.ops[0].blocked;
-  return launch_input_grad(m.grad[0], m.dtype, m.tens[0].C, (int64_t)B * m.H * m.W, n ? m.inv_std[0] : 1.0f,
+  return launch_input_grad(m.grad[0], m.dtype, blocked ? 4 : m.tens[0].C, (int64_t)B * m.H * m.W, n ? m.inv_std[0] : 1.0f,
                            n ? m.inv_std[1] : 1.0f, n ? m.inv_std[2] : 1.0f, gx, blocked ? m.H : 0, blocked ? m.W : 0, st);
 }
 

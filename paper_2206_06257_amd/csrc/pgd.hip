@@ -37,7 +37,8 @@ __device__ __forceinline__ float net_value(float x, float d, bool has_delta, con
 }
 
 // MODE 0: init, 1: update, 2: input only, 3: update with the gradient read from the bf16 network-input gradient
-// (`gnet`, laid out like the network input: one 16-byte vector per pixel) instead of an fp32 copy -- only its sign
+// (`gnet`, laid out like the network input: one 16-byte vector of 8 channels per pixel, or -- behind a 7x7/2 stem --
+// 2x2 pixel blocks of 4 channels, 8 bytes per pixel) instead of an fp32 copy -- only its sign
 // enters the step, and the positive normalisation scale does not change it.  A workgroup owns 1024 consecutive pixels = 768 float4 of each
 // fp32 stream; thread t touches float4 number j*256 + t (j = 0..2) of that chunk, so every load and
 // store of a wavefront covers 1 KB of consecutive memory.  The update itself is elementwise.  The bf16
@@ -114,12 +115,14 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
   }
   if (MODE == 3) {
     // the three gradient channels of each pixel, regrouped through LDS into the element order of the fp32 streams
-    const uint4* gsrc = reinterpret_cast<const uint4*>(gnet);
+    // the first three channels of a pixel are its first 8 bytes; pixels are 16 bytes apart, 8 in the blocked layout
+    const unsigned char* gsrc = reinterpret_cast<const unsigned char*>(gnet);
+    const int pix_bytes = in.bw ? 8 : 16;
     uint32_t gw[4][2];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       gw[p][0] = 0u; gw[p][1] = 0u;
-      if (p0 + p < npix) { const uint2 v = *reinterpret_cast<const uint2*>(gsrc + slot[p]); gw[p][0] = v.x; gw[p][1] = v.y; }
+      if (p0 + p < npix) { const uint2 v = *reinterpret_cast<const uint2*>(gsrc + slot[p] * pix_bytes); gw[p][0] = v.x; gw[p][1] = v.y; }
     }
     // halfwords 3p .. 3p+2 of the thread's 12: (c0 c1) (c2 c0') (c1' c2') ...
     uint32_t o[6];
@@ -207,18 +210,26 @@ __global__ __launch_bounds__(kThreads) void attack_kernel(const float* __restric
     const uint2 a = src[0], b = src[1], c = src[2];
     w[0] = a.x; w[1] = a.y; w[2] = b.x; w[3] = b.y; w[4] = c.x; w[5] = c.y;
   }
-  uint4* dst = reinterpret_cast<uint4*>(in.ptr);      // 8 bf16 = 16 bytes per pixel
+  // halfwords 3p, 3p+1, 3p+2 of the 12 -> (c0 c1) (c2 0) of pixel p
+  uint2 o[4];
+  o[0] = make_uint2(w[0], w[1] & 0xffffu);
+  o[1] = make_uint2((w[1] >> 16) | (w[2] << 16), w[2] >> 16);
+  o[2] = make_uint2(w[3], w[4] & 0xffffu);
+  o[3] = make_uint2((w[4] >> 16) | (w[5] << 16), w[5] >> 16);
+  if (in.bw) {
+    // 2x2 pixel blocks of 4 channels: 8 bytes per pixel; two pixels of one row and one block are 16 contiguous bytes
+    uint2* dst = reinterpret_cast<uint2*>(in.ptr);
+    if ((in.bw & 3) == 0 && np == 4) {
+      *reinterpret_cast<uint4*>(dst + slot[0]) = make_uint4(o[0].x, o[0].y, o[1].x, o[1].y);
+      *reinterpret_cast<uint4*>(dst + slot[2]) = make_uint4(o[2].x, o[2].y, o[3].x, o[3].y);
+    } else {
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    if (p >= np) break;
-    // halfwords 3p, 3p+1, 3p+2 of the 12
-    uint4 o;
-    if (p == 0) { o.x = w[0]; o.y = w[1] & 0xffffu; }
-    else if (p == 1) { o.x = (w[1] >> 16) | (w[2] << 16); o.y = w[2] >> 16; }
-    else if (p == 2) { o.x = w[3]; o.y = w[4] & 0xffffu; }
-    else { o.x = (w[4] >> 16) | (w[5] << 16); o.y = w[5] >> 16; }
-    o.z = 0u; o.w = 0u;
-    dst[slot[p]] = o;
+      for (int p = 0; p < 4; ++p) if (p < np) dst[slot[p]] = o[p];
+    }
+  } else {
+    uint4* dst = reinterpret_cast<uint4*>(in.ptr);      // 8 bf16 = 16 bytes per pixel
+#pragma unroll
+    for (int p = 0; p < 4; ++p) if (p < np) dst[slot[p]] = make_uint4(o[p].x, o[p].y, 0u, 0u);
   }
 }
 
