@@ -63,14 +63,9 @@ def cpu_baseline(arch, H, W, classes, K, eps, alpha, norm, bits):
 
 
 def source_hash():
-    """sha256 over the kernel sources: ties stored profiler figures to the code they were measured on."""
-    import hashlib
-    h = hashlib.sha256()
-    csrc = os.path.join(ROOT, "paper_2206_06257_amd", "csrc")
-    for name in sorted(os.listdir(csrc)):
-        h.update(name.encode())
-        h.update(open(os.path.join(csrc, name), "rb").read())
-    return h.hexdigest()[:16]
+    """Hash of the kernel sources: ties stored profiler figures to the code they were measured on."""
+    from paper_2206_06257_amd.profile_summary import source_hash as h
+    return h()
 
 
 def main():
