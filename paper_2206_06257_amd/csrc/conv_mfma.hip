@@ -736,8 +736,6 @@ __global__ __launch_bounds__(512) void igemm_ring_kernel(IgemmArgs a) {
   }
   const int ntiles = a.Ktot / BKT;
   const unsigned char* zero_page = reinterpret_cast<const unsigned char*>(g_zero_page);
-  const int ps = a.xstride ? a.xstride : a.Cin;         // elements between neighbouring input pixels
-  const int xcol = (kvec * 8) / ps;                     // pixel this thread's vector lies in, relative to the tap (0 unless xstride is set)
   int woff[VW]; bool wrow[VW];
 #pragma unroll
   for (int i = 0; i < VW; ++i) {
