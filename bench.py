@@ -194,10 +194,25 @@ def main():
         "phase_ms": {"attack": t_attack, "step": t_step, "quantize": t_quant, "dequantize": t_deq},
     }
     d = model.d
+    # the stand-alone quantizer (abs-max pass of its own: three launches), timed on the same gradient outside the steps
+    qe = [torch.cuda.Event(enable_timing=True) for _ in range(41)]
+    qe[0].record()
+    for i in range(40):
+        dat.quantize(grads, offs, args.bits, seed_q + i, q=q, scales=scales)
+        qe[i + 1].record()
+    torch.cuda.synchronize()
+    t_quant_alone = float(np.median([qe[i].elapsed_time(qe[i + 1]) for i in range(40)]))
     out["quantizer"] = {
         "quantize_GBs": d * (8 + args.bits / 8) / (t_quant * 1e-3) / 1e9, "dequantize_GBs": d * (4 + args.bits / 8) / (t_deq * 1e-3) / 1e9,
         "frac_hbm_quantize": d * (8 + args.bits / 8) / (t_quant * 1e-3) / 1e9 / PEAK_HBM_GBS,
-        "note": "event time around the whole call (fill + absmax + encode launches); 8+b/8 and 4+b/8 algorithmic bytes per element"}
+        "frac_hbm_quantize_moved": d * ((4 if not general else 8) + args.bits / 8) / (t_quant * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "frac_hbm_dequantize": d * (4 + args.bits / 8) / (t_deq * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "standalone_quantize_ms": t_quant_alone,
+        "frac_hbm_standalone_quantize": d * (8 + args.bits / 8) / (t_quant_alone * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "note": ("frac_hbm_quantize: the 8+b/8 algorithmic bytes per element of abs-max + encode over the event time of the step's quantizer "
+                 "call; in the step the per-tensor abs-max is a by-product of the kernels that write the gradient (dat_model_grad_scales), so that "
+                 "call is the encoder alone and moves 4+b/8 bytes per element (frac_hbm_quantize_moved).  standalone_*: dat_quantize with its own "
+                 "abs-max pass (reset + abs-max + encode launches) on the same gradient.  Dequantize: 4+b/8 bytes per element.")}
     if prof:
         ms = prof["conv_fwd"][0] + prof["conv_bwd_data"][0]
         n = prof["conv_fwd"][1] + prof["conv_bwd_data"][1]

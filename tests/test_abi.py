@@ -43,3 +43,10 @@ def test_host_only_calls_and_argument_errors():
     assert lib.dat_attack(None, None, None, 1, 0.1, 0.1, 1, b._Init(0, 0, None), None, None, None) == 1
     assert lib.dat_step(None, None, None, 1, None, None, None) == 1
     assert lib.dat_conv_forward(None, None, None, 1, 8, 8, 8, 8, 3, 1, 1, None) == 1
+    assert lib.dat_conv_backward_weight_static(None, None, None, 1, 8, 8, 8, 8, 3, 1, 1, None) == 1
+    assert b.conv_backward_weight_static_limit() == 32 << 20
+    assert lib.dat_quantize_scaled(None, None, 1, 10, 8, 0, None, None, None) == 1
+    assert lib.dat_model_grad_scales(None, None) == 1
+    assert lib.dat_set_kernel_option(99, 1) == 1 and lib.dat_set_kernel_option(b.KOPT_RING_KERNEL, 1) == 0
+    assert lib.dat_inspect_counts(None, None, None) == 1 and lib.dat_inspect_read(None, 0, 0, 1, None, 0) == 1
+    assert lib.dat_model_set_option(None, 0, 1) == 1

@@ -166,6 +166,30 @@ def test_network_with_ring_kernel_agrees_with_single_stage_kernels(dat):
     model.close()
 
 
+def test_attack_chains_its_own_gradient_exactly_at_full_size(dat):
+    """dat_attack at ResNet-50 224x224 B = 256 against the reference's update rule applied to the library's own input
+    gradient: z_{k+1} must equal, bit for bit, clip(clip(z_k + alpha sign(G_k), +-eps), -x, 1-x) with G_k the gradient
+    dat_input_grad returns at clip(x + z_k) -- for the first step from a given start and for the second step, which
+    starts from the network input the fused sign-step kernel wrote itself.  (What G_k is worth is the op-by-op
+    test's business; this one pins the wiring of the iteration: start point, input formation, sign step read
+    straight from the bf16 input gradient in its blocked layout, projection, next input.)"""
+    eps, alpha = 4 / 255, 1 / 255
+    model = dat.Model(dat.ARCH_RESNET50, dat.BF16, B, 224, 224, 1000, MEAN, STD)
+    model.set_params(syn.he_normal_params(5, model.offsets, model.fan_in, model.kind))
+    x, y = syn.images(5, B, 224, 224), syn.labels(5, B, 1000)
+    xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    z0 = oracle.init_delta(x, eps, oracle.INIT_UNIFORM, 91)
+    z0d = torch.from_numpy(z0).cuda()
+    z1 = model.attack(xd, yd, eps, alpha, 1, dat.INIT_GIVEN, delta0=z0d).cpu().numpy()
+    z2 = model.attack(xd, yd, eps, alpha, 2, dat.INIT_GIVEN, delta0=z0d).cpu().numpy()
+    for zk, zk1 in ((z0, z1), (z1, z2)):
+        gx, _, _ = model.input_grad(torch.from_numpy(oracle.make_xadv(x, zk)).cuda(), yd, want_logits=False, want_loss=False)
+        want = oracle.pgd_update(x, gx.cpu().numpy(), zk, eps, alpha)
+        assert np.array_equal(zk1, want)
+        assert (zk1 != zk).mean() > 0.5           # the step moved most coordinates
+    model.close()
+
+
 @pytest.mark.parametrize("B,eps,alpha,K", [
     (256, 4 / 255, 1 / 255, 3),          # config 5
     (85, 2 / 255, 1.25 / 255, 4),        # the paper's own ImageNet shape: 85 images per GPU, PGD-4 (odd batch: tile tails)
