@@ -265,12 +265,13 @@ def test_bn_input_grad_formed_by_the_convolution_gives_the_same_bits(dat, B, H, 
             res["first"] = cur
 
 
-@pytest.mark.parametrize("arch,B,H,W,classes", [(3, 5, 64, 64, 12), (3, 3, 96, 64, 12), (1, 7, 16, 16, 10), (100, 8, 16, 16, 5)])
+@pytest.mark.parametrize("arch,B,H,W,classes", [(3, 5, 64, 64, 12), (3, 3, 96, 64, 12), (3, 3, 68, 70, 12), (1, 7, 16, 16, 10), (100, 8, 16, 16, 5)])
 def test_pgd_step_from_the_bf16_input_gradient_gives_the_same_bits(dat, arch, B, H, W, classes):
     """bf16 models: the projected sign step reads the input gradient as the backward pass stores it (bf16, network-input
-    layout, 2x2 pixel blocks behind an ImageNet stem) instead of an fp32 pixel gradient made by a pass of its own.
-    Only the gradient's sign enters the step, so the perturbations agree bit for bit (pixel counts that are not
-    multiples of the 1024-pixel chunk; label-free KL ascent included)."""
+    layout, 2x2 pixel blocks of 4 channels behind an ImageNet stem) instead of an fp32 pixel gradient made by a pass of
+    its own.  Only the gradient's sign enters the step, so the perturbations agree bit for bit (pixel counts that are
+    not multiples of the 1024-pixel chunk, an image width that is not a multiple of four -- the blocked layout's
+    pixel-by-pixel path; label-free KL ascent included)."""
     gpu = dat.Model(arch, dat.BF16, B, H, W, classes, MEAN, STD)
     gpu.set_params(syn.perturbed_params(47, gpu.offsets, gpu.fan_in, gpu.kind))
     xd, yd = _cuda(syn.images(47, B, H, W)), _cuda(syn.labels(47, B, classes))

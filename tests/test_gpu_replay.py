@@ -143,6 +143,7 @@ SMALL = [
     (2, 1, 4, 16, 16, 10, False),
     (3, 1, 6, 96, 96, 12, True),
     (3, 1, 5, 64, 96, 1000, True),     # ragged tiles, the full classifier
+    (3, 1, 3, 68, 70, 12, True),       # odd block counts per row (35) in the stem's 2x2-block layout
     (3, 0, 3, 64, 64, 12, True),
     (4, 1, 12, 16, 16, 10, False),
     (5, 1, 5, 8, 8, 10, False),
