@@ -331,8 +331,11 @@ dat_status dat_model_set_option(dat_model* m, dat_option opt, int value);
 /* Process-wide kernel selection (ablations and tests; an atomic flag, read at every convolution launch of every
  * model and of the dat_conv_* entry points).  DAT_KOPT_RING_KERNEL (default 1): layers that run as one round of
  * 256-channel tiles go through the multi-stage kernel; 0: through the 128x128 kernels.  The convolution outputs
- * are bit-identical, the grouping of the batch-norm partial sums differs (256 instead of 128 pixels per slab). */
-typedef enum { DAT_KOPT_RING_KERNEL = 0 } dat_kernel_option;
+ * are bit-identical, the grouping of the batch-norm partial sums differs (256 instead of 128 pixels per slab).
+ * DAT_KOPT_STEM_PAIRS (default 1): the input gradient of a 7x7/2 stem stored as 2x2 pixel blocks is computed for
+ * two neighbouring blocks per matrix column where a row holds an even number of blocks; 0: one block per column.
+ * Bit-identical results. */
+typedef enum { DAT_KOPT_RING_KERNEL = 0, DAT_KOPT_STEM_PAIRS = 1 } dat_kernel_option;
 dat_status dat_set_kernel_option(dat_kernel_option opt, int value);
 
 /* ---- introspection for parity tests (not part of the paper's method) --------------------------------
