@@ -206,3 +206,14 @@ def test_config3_wrn34_10_batch256_at_its_configured_size(dat):
 def test_config4_5_resnet50_224_batch256_at_its_configured_size(dat):
     s = _replay_case(dat, 3, 1, 256, 224, 224, 1000, True, cfg=4, perturbed=False)
     assert s["elements"] > 5e9
+
+
+def test_imagenet_shape_of_the_papers_runs_resnet50_224_batch85(dat):
+    """85 images per GPU: pixel counts that are no multiple of the kernels' tiles at 56x56 and below."""
+    s = _replay_case(dat, 3, 1, 85, 224, 224, 1000, True, cfg=7, perturbed=False)
+    assert s["elements"] > 1.5e9
+
+
+def test_preact_resnet18_batch512_at_its_configured_size(dat):
+    s = _replay_case(dat, 4, 1, 512, 32, 32, 10, False, cfg=8, perturbed=False)
+    assert s["elements"] > 3e8
