@@ -6,7 +6,8 @@ tensors, logits, batch statistics, every stored activation gradient of the sweep
 (dat_step) and of the sweep without (dat_input_grad, where some BN input gradients are formed inside a
 convolution and never stored), the pixel gradient and every parameter-gradient tensor -- in the launch
 configuration the library picks for that size, fusions on.  The configured sizes of the benchmark configs
-(CIFAR ResNet-18 batch 512, WRN-34-10 batch 256, ResNet-50 224x224 batch 256) run whole.
+(CIFAR ResNet-18 batch 512, WRN-34-10 batch 256, ResNet-50 224x224 batch 256) run whole, and so do ResNet-50 with
+the paper's 85 images per GPU and pre-activation ResNet-18 batch 512.
 
 Bars (per element): bf16-stored tensors |gpu - ref| <= 2^-7 |ref| + 2e-5 max|ref| (one unit in the last place
 of the stored format, plus fp32 accumulation error where a value is small through cancellation); fp32 tensors
