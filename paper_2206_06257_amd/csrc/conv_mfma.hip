@@ -138,15 +138,20 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
   // the values at its own staging slots in fp32 and rounds once, in place.
   constexpr int CV = TC / 8;                       // channel vectors per pixel row
   constexpr int RPP = NT / CV;                     // pixel rows per store sweep
+  constexpr int NU = (TP + RPP - 1) / RPP;         // sweeps
+  // tile widths that are no power of two (160 channels: 20 vectors per row, 12 rows per sweep): the last
+  // threads have no vector and the last sweep is short
+  constexpr bool EXACT = NT % CV == 0 && TP % RPP == 0;
   const int cv = tid % CV, pr0 = tid / CV;
+  auto row_ok = [&](int u) { return EXACT || (pr0 < RPP && pr0 + u * RPP < TP); };
   const int ch = c0 + cv * 8;
   if (a.res) {
-    uint4 rv[TP / RPP];
+    uint4 rv[NU];
 #pragma unroll
-    for (int u = 0; u < TP / RPP; ++u) {
+    for (int u = 0; u < NU; ++u) {
       const int m = m0 + pr0 + u * RPP;
       rv[u] = make_uint4(0u, 0u, 0u, 0u);
-      bool take = m < a.M && ch < a.Cout;
+      bool take = row_ok(u) && m < a.M && ch < a.Cout;
       if (a.res_even_only && take) { const int q = m / a.Wout; take = !(((m - q * a.Wout) | (q % a.Hout)) & 1); }
       if (take) {
         const int64_t e = out_row(a, m) * a.Cout + ch;
@@ -162,7 +167,8 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
     }
     // (the main loop ended with a barrier: every wave is done with the operand tiles)
 #pragma unroll
-    for (int u = 0; u < TP / RPP; ++u) *reinterpret_cast<uint4*>(lds + (pr0 + u * RPP) * STG_STRIDE + cv * 16) = rv[u];
+    for (int u = 0; u < NU; ++u)
+      if (row_ok(u)) *reinterpret_cast<uint4*>(lds + (pr0 + u * RPP) * STG_STRIDE + cv * 16) = rv[u];
     __syncthreads();
   }
 #pragma unroll
@@ -197,7 +203,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
 #pragma unroll
       for (int j = 0; j < 8; ++j) { mu[j] = a.stat_mean[ch + j]; rs[j] = a.stat_rstd[ch + j]; mu2[j] = a.stat_mean2[ch + j]; rs2[j] = a.stat_rstd2[ch + j]; }
     }
-    constexpr int H = (TP / RPP + 1) / 2;              // rows in two batches: half the operand registers
+    constexpr int H = (NU + 1) / 2;              // rows in two batches: half the operand registers
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       uint4 xv[H], yv[H]; uint32_t mk[H];
@@ -205,7 +211,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
       for (int u = 0; u < H; ++u) {
         const int m = m0 + pr0 + (b * H + u) * RPP;
         xv[u] = make_uint4(0u, 0u, 0u, 0u); yv[u] = xv[u]; mk[u] = 0u;
-        if (b * H + u < TP / RPP && m < a.M && ch < a.Cout) {
+        if (b * H + u < NU && row_ok(b * H + u) && m < a.M && ch < a.Cout) {
           const int64_t e = out_row(a, m) * a.Cout + ch;
           xv[u] = *reinterpret_cast<const uint4*>(a.stat_x + e);
           yv[u] = *reinterpret_cast<const uint4*>(a.stat_x2 + e);
@@ -215,7 +221,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
 #pragma unroll
       for (int u = 0; u < H; ++u) {
         const int prow = pr0 + (b * H + u) * RPP, m = m0 + prow;
-        if (b * H + u < TP / RPP && m < a.M && ch < a.Cout) {
+        if (b * H + u < NU && row_ok(b * H + u) && m < a.M && ch < a.Cout) {
           const uint4 pk = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
           *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = pk;
           const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w}, xw[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w}, yw[4] = {yv[u].x, yv[u].y, yv[u].z, yv[u].w};
@@ -242,21 +248,21 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
       mu[0] = m0v.x; mu[1] = m0v.y; mu[2] = m0v.z; mu[3] = m0v.w; mu[4] = m1v.x; mu[5] = m1v.y; mu[6] = m1v.z; mu[7] = m1v.w;
       rs[0] = r0v.x; rs[1] = r0v.y; rs[2] = r0v.z; rs[3] = r0v.w; rs[4] = r1v.x; rs[5] = r1v.y; rs[6] = r1v.z; rs[7] = r1v.w;
     }
-    uint4 xv[TP / RPP]; uint32_t mk[TP / RPP];
+    uint4 xv[NU]; uint32_t mk[NU];
 #pragma unroll
-    for (int u = 0; u < TP / RPP; ++u) {
+    for (int u = 0; u < NU; ++u) {
       const int m = m0 + pr0 + u * RPP;
       xv[u] = make_uint4(0u, 0u, 0u, 0u); mk[u] = 0u;
-      if (m < a.M && ch < a.Cout) {
+      if (row_ok(u) && m < a.M && ch < a.Cout) {
         const int64_t e = out_row(a, m) * a.Cout + ch;
         xv[u] = *reinterpret_cast<const uint4*>(a.stat_x + e);
         mk[u] = a.stat_mask ? (uint32_t)a.stat_mask[e >> 3] : 0xffu;
       }
     }
 #pragma unroll
-    for (int u = 0; u < TP / RPP; ++u) {
+    for (int u = 0; u < NU; ++u) {
       const int prow = pr0 + u * RPP, m = m0 + prow;
-      if (m < a.M && ch < a.Cout) {
+      if (row_ok(u) && m < a.M && ch < a.Cout) {
         const uint4 pk = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
         *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = pk;
         const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w}, xw[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
@@ -272,9 +278,9 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
     }
   } else {
 #pragma unroll
-  for (int u = 0; u < TP / RPP; ++u) {
+  for (int u = 0; u < NU; ++u) {
     const int prow = pr0 + u * RPP, m = m0 + prow;
-    if (m < a.M && ch < a.Cout) {
+    if (row_ok(u) && m < a.M && ch < a.Cout) {
       const uint4 pk = *reinterpret_cast<const uint4*>(lds + prow * STG_STRIDE + cv * 16);
       *reinterpret_cast<uint4*>(a.out + out_row(a, m) * a.Cout + ch) = pk;
       if (a.stat_mode) {
@@ -293,6 +299,7 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
     __syncthreads();
     const int ns = a.stat_mode == 3 ? 3 : 2;        // sums per channel
     float* red = reinterpret_cast<float*>(lds);     // [RPP][ns][TC]
+    if (EXACT || pr0 < RPP)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       red[(pr0 * ns + 0) * TC + cv * 8 + j] = s1[j]; red[(pr0 * ns + 1) * TC + cv * 8 + j] = s2[j];
@@ -546,7 +553,10 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* gbl_void_ptr;
 
-template <int TC, int TP, int WGC, int OCC, int BKT>
+// ANYC: the contraction channels are no multiple of the k-tile (160 channels, 64-wide tiles), so a tile straddles
+// filter taps: every lane follows the tap and channel of its own 16-byte vector (a vector never straddles: Cin % 8
+// == 0), and the last tile is padded from the zero page.
+template <int TC, int TP, int WGC, int OCC, int BKT, bool ANYC = false>
 __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   constexpr int KS = BKT / 16, NS = BKT / 8;              // MFMA k-steps per tile; 16-byte slots per tile row
   constexpr int WGP = 4 / WGC;
@@ -588,7 +598,7 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
     hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * (a.ostride_w ? a.ostride_w : a.ostride) - a.pad_w;
     nb[i] = n * a.Hin * a.Win;
   }
-  const int ntiles = a.Ktot / BKT;
+  const int ntiles = ANYC ? (a.Ktot + BKT - 1) / BKT : a.Ktot / BKT;
   const unsigned char* zero_page = reinterpret_cast<const unsigned char*>(g_zero_page);
   const int ps = a.xstride ? a.xstride : a.Cin;         // elements between neighbouring input pixels
   const int xcol = (kvec * 8) / ps;                     // pixel this thread's vector lies in, relative to the tap (0 unless xstride is set)
@@ -601,15 +611,32 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   }
   int xoff[VX]; bool xok[VX];
   int kc0 = 0, kr = 0, ks = 0;
+  int kc, gr, gs, kw = kvec * 8;                          // ANYC: channel and tap of this lane's vector, its k index
+  {
+    const int tap = kw / a.Cin;
+    kc = kw - tap * a.Cin; gr = tap / a.KW; gs = tap - gr * a.KW;
+  }
   unsigned char* const wave_base = lds + wave * 1024;     // a wave's 64 vectors = 1 KB of consecutive tile rows
   // all loads of the next k-tile (a tile never straddles a filter tap: the tap, the bounds test and the
   // pixel offset change only every Cin/64 tiles, a uniform branch)
   auto fetch = [&]() {
 #pragma unroll
     for (int i = 0; i < VW; ++i) {
-      const unsigned char* p = wrow[i] ? reinterpret_cast<const unsigned char*>(a.wt + woff[i]) : zero_page;
+      const unsigned char* p = (wrow[i] & (!ANYC || kw < a.Ktot)) ? reinterpret_cast<const unsigned char*>(a.wt + woff[i]) : zero_page;
       __builtin_amdgcn_global_load_lds((gbl_void_ptr)p, (lds_void_ptr)(wave_base + i * (RPG * RB)), 16, 0, 0);
       woff[i] += BKT;
+    }
+    if (ANYC) {
+#pragma unroll
+      for (int i = 0; i < VX; ++i) {
+        const int hi = hb[i] + gr, wi = wb[i] + gs;
+        const bool ok = mv[i] & (gr < a.KH) & (hi >= 0) & (wi >= 0) & (hi < a.Hin) & (wi < a.Win);
+        const unsigned char* p = ok ? reinterpret_cast<const unsigned char*>(a.in + (nb[i] + hi * a.Win + wi) * a.Cin + kc) : zero_page;
+        __builtin_amdgcn_global_load_lds((gbl_void_ptr)p, (lds_void_ptr)(wave_base + XBASE + i * (RPG * RB)), 16, 0, 0);
+      }
+      kw += BKT; kc += BKT;
+      while (kc >= a.Cin) { kc -= a.Cin; if (++gs == a.KW) { gs = 0; ++gr; } }
+      return;
     }
     if (kc0 == 0) {
 #pragma unroll
@@ -672,17 +699,18 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
   igemm_epilogue<TC, TP, WGC>(a, acc, lds, c0, m0, pt);
 }
 
-template <int TC, int TP, int WGC, int OCC, int BKT = 64>
+template <int TC, int TP, int WGC, int OCC, int BKT = 64, bool ANYC = false>
 dat_status launch_igemm_dma(IgemmArgs a, hipStream_t st) {
   if ((int64_t)a.B * a.Hin * a.Win * a.Cin >= (1ll << 31) || (int64_t)a.Cout * a.Ktot >= (1ll << 31)) return DAT_ERR_UNSUPPORTED;
-  if (a.Cin % BKT != 0 || a.Ktot < BKT || a.Ktot % BKT != 0) return DAT_ERR_UNSUPPORTED;
+  if (ANYC ? (a.Cin % 8 != 0 || a.Ktot != a.KH * a.KW * a.Cin || a.Ktot < BKT || a.xstride != 0)
+           : (a.Cin % BKT != 0 || a.Ktot < BKT || a.Ktot % BKT != 0)) return DAT_ERR_UNSUPPORTED;
   if (a.xstride && (a.Cin != BKT || a.xstride % 8 != 0 || a.Cin % a.xstride != 0)) return DAT_ERR_UNSUPPORTED;   // one tap per k-tile
   a.nct = (a.Cout + TC - 1) / TC;
   a.npt = (a.M + TP - 1) / TP;
   if (a.npt == 0) return DAT_OK;
   a.xcd_contiguous = a.KH * a.KW > 1;   // filter windows: neighbouring tiles re-read each other's rows
   const int npt8 = (a.npt + 7) / 8 * 8;
-  hipLaunchKernelGGL((igemm_dma_kernel<TC, TP, WGC, OCC, BKT>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<TC, TP, WGC, OCC, BKT, ANYC>), dim3((unsigned)(npt8 * a.nct)), dim3(kThreads), 0, st, a);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
 }
@@ -942,6 +970,7 @@ int compute_units() {
 // contraction is short).
 std::atomic<bool> g_ring_enabled{true};
 std::atomic<bool> g_stem_pairs{true};
+std::atomic<bool> g_tile160{true};
 
 int pick_ring(const IgemmArgs& a) {
   if (a.xf_tab || a.ostep != 1 || a.stat_slab0 != 0 || a.Cin % 64 != 0 || a.Ktot < 1024 || a.Cout % 256 != 0) return 0;
@@ -975,6 +1004,14 @@ dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
     // same change gained nothing
     if (a.Cout <= 64) return launch_igemm_xf<64, 128, 2, 1, 64, 3>(a, st);
     return launch_igemm_xf<128, 128, 2, 2, 32, 2>(a, st);
+  }
+  // widths that are a multiple of 160 but not of 128 (the wide ResNets' 160 and 320 channels): 160-channel tiles, each
+  // wave all channels of 32 pixels -- no empty MFMA rows in a last tile, and the gathered activations are fetched
+  // once per 160 instead of once per 128 output channels
+  if (a.Cout % 160 == 0 && a.Cout % 128 != 0 && g_tile160.load(std::memory_order_relaxed)) {
+    if (a.Cin % 64 == 0 && a.Ktot >= 64) return launch_igemm_dma<160, 128, 1, 3>(a, st);
+    if (a.Cin % 32 == 0 && a.Ktot >= 512 && !a.xstride) return launch_igemm_dma<160, 128, 1, 3, 64, true>(a, st);   // 160 -> 160
+    return launch_igemm<160, 128, 1, 1, 32, 3>(a, st);
   }
   // narrow channel tiles: the direct-to-LDS kernel wherever its k-tile divides the contraction channels,
   // except 1x1 layers with a long contraction into <= 64 channels (HBM-bound reads: deep register
@@ -1524,6 +1561,7 @@ extern "C" dat_status dat_set_kernel_option(dat_kernel_option opt, int value) {
   switch (opt) {
     case DAT_KOPT_RING_KERNEL: g_ring_enabled.store(value != 0, std::memory_order_relaxed); return DAT_OK;
     case DAT_KOPT_STEM_PAIRS: g_stem_pairs.store(value != 0, std::memory_order_relaxed); return DAT_OK;
+    case DAT_KOPT_TILE_160: g_tile160.store(value != 0, std::memory_order_relaxed); return DAT_OK;
   }
   return DAT_ERR_ARG;
 }

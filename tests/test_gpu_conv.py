@@ -36,7 +36,14 @@ SHAPES = [
     (3, 14, 14, 256, 72, 3, 1, 1),     # 3x3, four channel chunks, ragged channel tile
     (2, 28, 28, 64, 64, 3, 1, 1),      # 3x3 into 64 channels (narrow tile), several tiles per image
     (1, 56, 56, 64, 128, 3, 1, 1),     # widest image the LDS-resident patch supports at this size
+    (3, 10, 10, 160, 160, 3, 1, 1),    # wide-ResNet stage 1: a contraction of 160 channels (register-staged 32-wide k-tiles)
+    (2, 12, 12, 64, 160, 3, 1, 1),     # ... and one the direct-to-LDS kernel takes
+    (3, 8, 8, 320, 320, 3, 1, 1),      # stage 2 width
+    (2, 16, 16, 128, 320, 1, 1, 0),    # ... 1x1
+    (2, 16, 16, 160, 320, 1, 2, 0),    # ... strided projection of the wide nets
+    (5, 9, 11, 160, 160, 3, 1, 1),     # 160-channel tiles with a ragged pixel tail
 ]
+WIDE_NET_SHAPES = [s for s in SHAPES if s[4] in (160, 320) or s[3] in (160, 320)]
 
 
 @pytest.fixture(scope="module")
@@ -77,3 +84,29 @@ def test_conv_forward_backward_parity(dat, shape):
     dw = dat.conv_backward_weight(x.cuda(), dy.cuda(), k, st, pad).cpu().numpy().astype(np.float64)
     err = np.abs(dw - dw64).max() / np.abs(dw64).max()
     assert err < 2e-5, ("backward_weight", err)
+
+
+
+@pytest.mark.parametrize("shape", WIDE_NET_SHAPES)
+def test_160_channel_tiles_give_the_bits_of_128_channel_tiles(dat, shape):
+    """Layers 160 or 320 channels wide run in 160-channel tiles (no partly empty last tile).  Every output element is
+    the same chain of MFMA accumulations over the same k order under either tiling, so forward and backward-data
+    results must not differ by a bit; the 128-channel launches stay covered by this test."""
+    B, H, W, Ci, Co, k, st, pad = shape
+    rng = np.random.default_rng(hash(shape) % (2 ** 31) + 1)
+    x = _bf16_values(rng, (B, H, W, Ci)).cuda()
+    w = _bf16_values(rng, (Co, k, k, Ci), 1.0 / np.sqrt(Ci * k * k)).cuda()
+    Ho, Wo = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+    dy = _bf16_values(rng, (B, Ho, Wo, Co)).cuda()
+    res = []
+    try:
+        for wide in (1, 0):
+            dat.set_kernel_option(dat.KOPT_TILE_160, wide)
+            y = dat.conv_forward(x, w, st, pad)
+            dx = dat.conv_backward_data(dy, w, (H, W), st, pad)
+            torch.cuda.synchronize()
+            res.append((y.view(torch.int16).cpu().numpy(), dx.view(torch.int16).cpu().numpy()))
+    finally:
+        dat.set_kernel_option(dat.KOPT_TILE_160, 1)
+    _check(y, oracle.conv_forward(x.double().cpu().numpy(), w.double().cpu().numpy(), st, pad), "forward, 128-channel tiles")
+    assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
