@@ -35,11 +35,11 @@ def _name(n):
 
 def _is_conv(n):
     """conv forward / backward-data launches of the roofline (without those that also form a BN input gradient)."""
-    return n.startswith("igemm") and not n.rstrip().endswith(", true>")
+    return n.startswith("igemm") and not (n.startswith("igemm_kernel<") and n.rstrip().endswith(", true>"))
 
 
 TEMPLATES = [
-    "# Template arguments: igemm_dma_kernel<TC, TP, WGC, OCC, BK>, igemm_ring_kernel<TC, TP, WGC, S>,",
+    "# Template arguments: igemm_dma_kernel<TC, TP, WGC, OCC, BK, ANYC> (ANYC = true: k-tiles straddle filter taps), igemm_ring_kernel<TC, TP, WGC, S>,",
     "# igemm_kernel<TC, TP, WGC, PF, FAST, BK, OCC, XF> (XF = true: the operand is a BN input gradient formed while loading),",
     "# bnact_fwd_kernel<T, RES> (RES 0 none, 1 residual, 2 residual normalised on the fly), bnact_bwd_apply_kernel<T, GATE, DXACC, DRES>.",
 ]
