@@ -36,7 +36,7 @@ from tests import replay
 pytestmark = pytest.mark.gpu
 MEAN, STD = (0.485, 0.456, 0.406), (0.229, 0.224, 0.225)
 ACT_VIOL_FRAC, GRAD_VIOL_FRAC, WORST_CAP = 5e-5, 1e-3, 100.0
-LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+LOG = os.environ.get("DAT_REPLAY_LOG_DIR")     # per-tensor tables go to <dir>/replay.log when set; summaries are always printed
 
 
 @pytest.fixture(scope="module")
@@ -55,6 +55,8 @@ def _report(tag, rec, t0):
         tag, s["items"], s["elements"], s["exact_frac"], s["viol"], s["max_viol_frac"], time.time() - t0)
     print(line, flush=True)
     try:
+        if not LOG:
+            return s
         os.makedirs(LOG, exist_ok=True)
         with open(os.path.join(LOG, "replay.log"), "a") as f:
             f.write(line + "\n")
@@ -187,8 +189,9 @@ def test_config2_end_to_end_against_the_comparison_resolution(dat):
     line = "config 2 end to end (B=512, 32x32): GPU vs reference %s; reference vs itself under 1e-7 jitter %s" % (got, res)
     print(line, flush=True)
     try:
-        with open(os.path.join(LOG, "replay.log"), "a") as f:
-            f.write(line + "\n")
+        if LOG:
+            with open(os.path.join(LOG, "replay.log"), "a") as f:
+                f.write(line + "\n")
     except OSError:
         pass
     assert got["logits"] < 2e-2 and got["loss"] < 2e-2
