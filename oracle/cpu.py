@@ -96,6 +96,7 @@ _cmp_tensor = _sig("orc_compare_tensor", None, C.c_void_p, C.c_int, C.c_int, C.c
 _bn_stats = _sig("orc_get_bn_stats", None, C.c_void_p, C.c_int, _f64p, _f64p)
 _param_grads = _sig("orc_get_param_grads", None, C.c_void_p, _f64p)
 _pixel_grad = _sig("orc_pixel_grad", None, C.c_void_p, _f32p)
+_kl_dz = _sig("orc_kl_logit_grad", None, _f32p, _f32p, C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_int, C.c_double, _f32p, _f64p)
 
 
 def _opt(a):
@@ -298,6 +299,19 @@ class Model:
         out = np.zeros(shape, np.float32)
         _pixel_grad(self._h, out.reshape(-1))
         return out
+
+
+def kl_logit_grad(z_clean, z_adv, y, lam, branch, scale):
+    """Logit gradient of sum_n scale * [lam * CE(z_clean_n, y_n) + KL(p(z_clean_n) || p(z_adv_n))] w.r.t. the perturbed
+    pass's logits (branch 0) or the clean pass's (branch 1), from given fp32 logits [B, classes].  Returns (dz, mean KL)."""
+    zc = np.ascontiguousarray(z_clean, np.float32); za = np.ascontiguousarray(z_adv, np.float32)
+    assert zc.ndim == 2 and zc.shape == za.shape
+    yy = None if y is None else np.ascontiguousarray(y, np.int32)
+    assert yy is not None or (lam == 0.0 or branch == 0)
+    dz = np.zeros_like(zc)
+    kl = np.zeros(1, np.float64)
+    _kl_dz(zc, za, None if yy is None else yy.ctypes.data, zc.shape[0], zc.shape[1], float(lam), int(branch), float(scale), dz, kl)
+    return dz, float(kl[0])
 
 
 def init_delta(x, eps, mode, seed=0, given=None):

@@ -914,6 +914,33 @@ std::vector<double> logits_of(const Model& m, int B) {
   return std::vector<double>(m.act[t].begin(), m.act[t].begin() + (int64_t)B * m.classes);
 }
 
+// Logit gradients of sum_n scale * [ lambda * CE(z_clean_n, y_n) + KL(p(z_clean_n) || p(z_adv_n)) ] from the two
+// passes' log-probabilities lp (clean) and lq (perturbed):
+//   branch 0, d/dz_adv:   scale * (q - p)                       (the CE term does not depend on z_adv)
+//   branch 1, d/dz_clean: scale * (lambda * (p - onehot(y)) + p .* (log p - log q - KL_n))
+// kl[n] = KL_n.  y may be null when lambda is 0 or branch is 0.
+void kl_logit_grad(const std::vector<double>& lp, const std::vector<double>& lq, const int32_t* y, int B, int nc, double lambda,
+                   int branch, double scale, std::vector<double>& kl, std::vector<double>& dz) {
+  kl.assign((size_t)B, 0.0);
+  dz.resize((size_t)B * nc);
+  for (int n = 0; n < B; ++n) {
+    double s = 0.0;
+    for (int c = 0; c < nc; ++c) { const int64_t i = (int64_t)n * nc + c; s += std::exp(lp[i]) * (lp[i] - lq[i]); }
+    kl[n] = s;
+  }
+  if (branch == 0) {
+    for (int64_t i = 0; i < (int64_t)B * nc; ++i) dz[i] = (std::exp(lq[i]) - std::exp(lp[i])) * scale;
+    return;
+  }
+  for (int n = 0; n < B; ++n)
+    for (int c = 0; c < nc; ++c) {
+      const int64_t i = (int64_t)n * nc + c;
+      const double pc = std::exp(lp[i]);
+      const double ce = lambda != 0.0 ? lambda * (pc - (c == y[n] ? 1.0 : 0.0)) : 0.0;
+      dz[i] = (ce + pc * (lp[i] - lq[i] - kl[n])) * scale;
+    }
+}
+
 // The two network inputs are already in m's input format when `load` is null (fp64 entry).
 struct RegResult { double loss_clean, loss_phi; };
 
@@ -947,16 +974,11 @@ RegResult objective_and_grads(Model& m, int B, const int32_t* y, double lambda, 
   softmax_rows(logits_of(m, B), B, nc, lp);
   set_adv(); forward(m, B);
   softmax_rows(logits_of(m, B), B, nc, lq);
-  std::vector<double> kl((size_t)B, 0.0), dz((size_t)B * nc);
-  for (int n = 0; n < B; ++n) {
-    double s = 0.0, ce = 0.0;
-    for (int c = 0; c < nc; ++c) { const int64_t i = (int64_t)n * nc + c; s += std::exp(lp[i]) * (lp[i] - lq[i]); }
-    ce = -lp[(int64_t)n * nc + y[n]];
-    kl[n] = s; r.loss_phi += s * inv; r.loss_clean += ce * inv;
-  }
+  std::vector<double> kl, dz;
   // adversarial branch (activations of the x+delta pass are in place)
   const double sadv = (want_gadv && !want_gtheta) ? 1.0 : inv;   // the attack uses the sum over the batch
-  for (int64_t i = 0; i < (int64_t)B * nc; ++i) dz[i] = (std::exp(lq[i]) - std::exp(lp[i])) * sadv;
+  kl_logit_grad(lp, lq, y, B, nc, lambda, 0, sadv, kl, dz);
+  for (int n = 0; n < B; ++n) { r.loss_phi += kl[n] * inv; r.loss_clean += -lp[(int64_t)n * nc + y[n]] * inv; }
   if (want_gtheta || want_gadv) {
     install_logit_grad(m, dz);
     backward(m, B, want_gtheta);
@@ -966,12 +988,7 @@ RegResult objective_and_grads(Model& m, int B, const int32_t* y, double lambda, 
   if (want_gtheta) {
     // clean branch: its activations were overwritten, run that pass again
     set_clean(); forward(m, B);
-    for (int n = 0; n < B; ++n)
-      for (int c = 0; c < nc; ++c) {
-        const int64_t i = (int64_t)n * nc + c;
-        const double pc = std::exp(lp[i]);
-        dz[i] = (lambda * (pc - (c == y[n] ? 1.0 : 0.0)) + pc * (lp[i] - lq[i] - kl[n])) * inv;
-      }
+    kl_logit_grad(lp, lq, y, B, nc, lambda, 1, inv, kl, dz);
     install_logit_grad(m, dz);
     backward(m, B, true);
     add_gtheta();
@@ -995,6 +1012,20 @@ void orc_step_reg(void* h, const float* x, const float* xadv, const int32_t* y, 
                                     [&]() { load_input(*m, xadv, B); }, gt, unused);
   for (int64_t i = 0; i < m->d; ++i) grads[i] = (float)gt[i];
   if (losses) { losses[0] = r.loss_clean; losses[1] = r.loss_phi; }
+}
+
+// The logit gradients of the TRADES objective (kl_logit_grad above) from given fp32 logits of the two passes, for
+// teacher-forced comparisons: dz fp32 [B][nc]; kl_mean = (1/B) sum_n KL_n.
+void orc_kl_logit_grad(const float* z_clean, const float* z_adv, const int32_t* y, int B, int nc, double lambda, int branch,
+                       double scale, float* dz, double* kl_mean) {
+  std::vector<double> zc(z_clean, z_clean + (int64_t)B * nc), za(z_adv, z_adv + (int64_t)B * nc), lp, lq, kl, d;
+  softmax_rows(zc, B, nc, lp);
+  softmax_rows(za, B, nc, lq);
+  kl_logit_grad(lp, lq, y, B, nc, lambda, branch, scale, kl, d);
+  for (size_t i = 0; i < d.size(); ++i) dz[i] = (float)d[i];
+  double s = 0.0;
+  for (int n = 0; n < B; ++n) s += kl[n];
+  if (kl_mean) *kl_mean = s / B;
 }
 
 // Gradient of sum_n phi_n w.r.t. the perturbed pixels (the clean pass is a constant): what the inner

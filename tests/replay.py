@@ -45,6 +45,20 @@ class Record(list):
                     nonfinite=sum(r["nonfinite"] for r in self))
 
 
+def check(rec, act_viol_frac=5e-5, grad_viol_frac=1e-3, worst_cap=100.0):
+    """The acceptance rule of the GPU comparisons: statistics and parameter gradients meet their bar everywhere; a
+    stored activation (gradient) tensor may miss it in at most act_viol_frac (grad_viol_frac) of its elements, and
+    where one op separates the two sides by no more than the factor worst_cap (tests/test_gpu_replay.py says why)."""
+    def limit(r):
+        if " act t" in r["name"]:
+            return act_viol_frac * r["n"]
+        if " grad t" in r["name"] or "gradient" in r["name"]:
+            return grad_viol_frac * r["n"]
+        return 0
+    bad = [r for r in rec if r["nonfinite"] or r["viol"] > limit(r) or (r["worst"] > worst_cap and not r["composite"])]
+    assert not bad, [(r["name"], r["n"], r["viol"], r["worst"]) for r in bad[:8]]
+
+
 def _tol(arr):
     return TOL_BF16 if arr.dtype == np.uint16 else TOL_F32
 
@@ -94,9 +108,10 @@ def forward(ref, source, x, rec, force=True):
     return own
 
 
-def backward(ref, source, y, scale, want_wgrad, rec, force=True, own_acts=()):
+def backward(ref, source, y, scale, want_wgrad, rec, force=True, own_acts=(), logit_grad=None):
     """After `forward` (own_acts: what it returned): installs the loss gradient (scale 1 = sum over the batch,
-    1/B = mean), then runs the reference backward op by op.  A tensor's gradient is complete once every op that
+    1/B = mean; or `logit_grad`, the expected gradient of another loss w.r.t. the logits, flat fp32), then runs the
+    reference backward op by op.  A tensor's gradient is complete once every op that
     reads the tensor has run; at that point it is compared with the source's and (force) replaced by it.
     Returns (mean loss, whether the comparison of the pixel gradient spans more than one op)."""
     ops = ref.ops()
@@ -110,6 +125,8 @@ def backward(ref, source, y, scale, want_wgrad, rec, force=True, own_acts=()):
             if t >= 0 and t not in first_reader:
                 first_reader[t] = i
     loss = ref.loss_backward_begin(y, scale)
+    if logit_grad is not None:
+        ref.set_tensor(1, ops[-1]["out"], np.ascontiguousarray(logit_grad, np.float32).reshape(-1))
 
     def settle(t, name):
         got = source.grad(t) if t != 0 else None

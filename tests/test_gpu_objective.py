@@ -1,11 +1,20 @@
 """GPU parity of the general worker objective (Eq. (prob_DAT)): lambda * clean loss + phi with phi the
 adversarial cross-entropy or the TRADES KL regulariser, and the KL inner maximisation, against the
-reference through the C ABI."""
+reference through the C ABI.
+
+fp32 models: gradients and losses against the fp64 reference at the spec bar (1e-4), every parameter tensor on
+its own.  bf16 models: an end-to-end comparison of a deep ReLU / batch-norm net cannot be tight (see
+tests/test_gpu_network.py), so the sweeps the objective adds are compared op by op with teacher forcing
+(tests/replay.py): the TRADES step's clean-branch sweep and the KL attack's perturbed-pass sweep, each with the
+reference's logit gradient computed from the GPU's own logits of the two passes; and the cross-entropy objective
+with lambda > 0 must be lambda * dat_step(x) + dat_step(x_adv), the two plain steps that tests/test_gpu_replay.py
+covers."""
 import numpy as np
 import pytest
 
 import oracle
 import synth_inputs as syn
+from tests import replay
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -55,9 +64,13 @@ def test_fp32_objective_gradient(dat, arch, B, H, classes, norm, lam, phi):
     g = g.cpu().numpy()
     print("objective fp32 arch %d lam %.1f phi %d: grad rel %.2e (floor %.2e) losses %s ref %s" %
           (arch, lam, phi, _rel2(g, g_ref), floor, l, l_ref))
-    assert _rel2(g, g_ref) < max(1e-4, 2 * floor)
+    assert _rel2(g, g_ref) < 1e-4
+    for t in range(ref.num_tensors):       # per tensor: small tensors must not hide behind big ones
+        lo, hi = int(ref.offsets[t]), int(ref.offsets[t + 1])
+        if np.abs(g_ref[lo:hi]).max() > 1e-3 * np.abs(g_ref).max():
+            assert _rel2(g[lo:hi], g_ref[lo:hi]) < 1e-3, t
     assert abs(l[0] - l_ref[0]) < 1e-5 * max(1.0, abs(l_ref[0]))
-    assert abs(l[1] - l_ref[1]) < max(1e-4 * abs(l_ref[1]), 2 * lfloor, 1e-7)
+    assert abs(l[1] - l_ref[1]) < 1e-4 * abs(l_ref[1]) + 1e-7
     if lam == 0.0 and phi == 0:   # the plain step, bit for bit
         g0 = gpu.step(torch.from_numpy(xadv).cuda(), torch.from_numpy(y).cuda()).cpu().numpy()
         assert np.array_equal(g, g0)
@@ -82,9 +95,96 @@ def test_bf16_objective_gradient_every_op_kind(dat, lam, phi):
     g, l = gpu.step_reg(torch.from_numpy(x).cuda(), torch.from_numpy(xadv).cuda(), torch.from_numpy(y).cuda(), lam, phi,
                         want_losses=True)
     got = _rel2(g.cpu().numpy(), g_ref)
-    print("objective bf16 lam %.1f phi %d: grad rel %.2e (reference's own jitter floor %.2e)" % (lam, phi, got, floor))
-    assert got < max(2e-2, 1.5 * floor)
+    bound = max(2e-2, 1.5 * floor)
+    print("objective bf16 lam %.1f phi %d: grad rel %.2e (reference's own jitter floor %.2e)%s" % (
+        lam, phi, got, floor, "" if bound <= 0.1 else ": end to end unpinned at this size (op-by-op parity below)"))
+    if bound <= 0.1:     # a wider bound could not tell a correct gradient from a wrong one
+        assert got < bound
     assert abs(l[1] - l_ref[1]) < 2e-2 * max(abs(l_ref[1]), 1e-3)
+
+
+def _cuda(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+REPLAY_CASES = [(100, 1, 8, 16, 5, True), (100, 0, 8, 16, 5, True), (1, 1, 16, 16, 10, False), (3, 1, 4, 64, 12, True), (2, 1, 4, 8, 10, False)]
+
+
+@pytest.mark.parametrize("arch,bf16,B,H,classes,norm", REPLAY_CASES)
+@pytest.mark.parametrize("lam", [0.0, 1.5])
+def test_trades_step_clean_branch_op_by_op(dat, arch, bf16, B, H, classes, norm, lam):
+    """dat_step_reg with the KL regulariser ends with the clean pass and the clean branch's backward sweep.  Every
+    stored tensor of that pass against the reference, stepping from the GPU's own tensors; the logit gradient the
+    reference installs is its own, lambda * (p - onehot) + p .* (log p - log q - KL), evaluated at the GPU's logits of
+    the two passes (so kl_kernel is compared on identical inputs)."""
+    ref, gpu, x, xadv, y = _pair(dat, arch, dat.BF16 if bf16 else dat.F32, B, H, classes, cfg=44, norm=norm)
+    xd, xad, yd = _cuda(x), _cuda(xadv), _cuda(y)
+    z_adv = gpu.input_grad(xad, yd)[1].cpu().numpy()                 # the perturbed pass's logits (same forward kernels)
+    g, losses = gpu.step_reg(xd, xad, yd, lam, dat.PHI_TRADES_KL, want_losses=True)
+    src = replay.GpuSource(gpu, B)
+    rec = replay.Record()
+    own = replay.forward(ref, src, x, rec)
+    t = ref.ops()[-1]["out"]
+    z_clean = src.act(t).reshape(B, classes)
+    dz, kl = oracle.kl_logit_grad(z_clean, z_adv, y, lam, 1, 1.0 / B)
+    replay.backward(ref, src, y, 1.0 / B, True, rec, own_acts=own, logit_grad=dz)
+    replay.check(rec)
+    s = rec.summary()
+    print("TRADES clean branch arch %d %s lam %.1f: %d comparisons, %d elements, exactly equal %.4f, over the bar %d" % (
+        arch, "bf16" if bf16 else "fp32", lam, s["items"], s["elements"], s["exact_frac"], s["viol"]))
+    assert sum(1 for r in rec if " grad t" in r["name"]) >= 5 and np.abs(dz).max() > 0
+    assert abs(losses[1] - kl) <= 1e-4 * abs(kl) + 1e-7
+    gpu.close()
+
+
+@pytest.mark.parametrize("arch,bf16,B,H,classes,norm", REPLAY_CASES)
+def test_kl_attack_perturbed_pass_op_by_op(dat, arch, bf16, B, H, classes, norm):
+    """One step of dat_attack_kl from a given start: the perturbed pass and its backward-to-input sweep op by op (logit
+    gradient q - p at the GPU's logits, summed over the batch), and the projected sign step against the reference's
+    update rule applied to the reference's (teacher-forced) input gradient."""
+    ref, gpu, x, _, y = _pair(dat, arch, dat.BF16 if bf16 else dat.F32, B, H, classes, cfg=45, norm=norm)
+    d0 = oracle.init_delta(x, EPS, oracle.INIT_UNIFORM, seed=11)
+    xadv = oracle.make_xadv(x, d0)
+    xd, yd = _cuda(x), _cuda(y)
+    z_clean = gpu.input_grad(xd, yd)[1].cpu().numpy()
+    d1 = gpu.attack_kl(xd, EPS, ALPHA, 1, dat.INIT_GIVEN, delta0=_cuda(d0)).cpu().numpy()
+    src = replay.GpuSource(gpu, B)
+    rec = replay.Record()
+    own = replay.forward(ref, src, xadv, rec)
+    t = ref.ops()[-1]["out"]
+    dz, _ = oracle.kl_logit_grad(z_clean, src.act(t).reshape(B, classes), None, 0.0, 0, 1.0)
+    replay.backward(ref, src, y, 1.0, False, rec, own_acts=own, logit_grad=dz)
+    replay.check(rec)
+    G = ref.pixel_grad(x.shape)
+    want = oracle.pgd_update(x, G, d0, EPS, ALPHA)
+    big = np.abs(G) > 1e-6 * np.abs(G).max()
+    disagree = float((d1[big] != want[big]).mean())
+    print("KL attack arch %d %s: %d comparisons, delta differs in %.2e of the coordinates with a non-negligible gradient" % (
+        arch, "bf16" if bf16 else "fp32", len(rec), disagree))
+    assert disagree <= (1e-2 if bf16 else 1e-3) and np.abs(d1 - d0).max() > 0
+    gpu.close()
+
+
+@pytest.mark.parametrize("arch,B,H,classes,norm", [(100, 8, 16, 5, True), (1, 16, 16, 10, False), (3, 4, 64, 12, True)])
+def test_bf16_cross_entropy_objective_is_the_sum_of_two_plain_steps(dat, arch, B, H, classes, norm):
+    """phi = CE, lambda > 0: the clean pass is dat_step's sweep on x with its logit gradient scaled by lambda, the
+    perturbed pass is dat_step on x_adv.  For lambda a power of two the scaled sweep makes the same rounding decisions
+    as the plain one (bf16 rounding commutes with an exact scaling), so the result is lambda * dat_step(x) +
+    dat_step(x_adv) bit for bit; for other lambda the roundings of the scaled sweep fall differently and the two
+    agree to bf16 accuracy only (a sanity bound: batch norm's backward pass amplifies single roundings)."""
+    ref, gpu, x, xadv, y = _pair(dat, arch, dat.BF16, B, H, classes, cfg=46, norm=norm)
+    xd, xad, yd = _cuda(x), _cuda(xadv), _cuda(y)
+    g_clean = gpu.step(xd, yd).clone()
+    g_adv = gpu.step(xad, yd).clone()
+    assert float(g_clean.abs().max()) > 0 and not torch.equal(g_clean, g_adv)
+    for lam in (1.0, 0.5, 2.0):
+        assert torch.equal(gpu.step_reg(xd, xad, yd, lam, dat.PHI_CE), lam * g_clean + g_adv), lam
+    lam = 0.7
+    g = gpu.step_reg(xd, xad, yd, lam, dat.PHI_CE).cpu().numpy().astype(np.float64)
+    want = (lam * g_clean.double() + g_adv.double()).cpu().numpy()
+    print("CE objective arch %d lam 0.7 against the two plain steps: rel %.2e" % (arch, _rel2(g, want)))
+    assert _rel2(g, want) < 5e-2
+    gpu.close()
 
 
 def test_kl_attack_matches_reference_step_by_step(dat):

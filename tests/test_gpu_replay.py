@@ -69,14 +69,7 @@ def _report(tag, rec, t0):
 
 
 def _check(rec):
-    def limit(r):
-        if " act t" in r["name"]:
-            return ACT_VIOL_FRAC * r["n"]
-        if " grad t" in r["name"] or "gradient" in r["name"]:
-            return GRAD_VIOL_FRAC * r["n"]
-        return 0
-    bad = [r for r in rec if r["nonfinite"] or r["viol"] > limit(r) or (r["worst"] > WORST_CAP and not r["composite"])]
-    assert not bad, [(r["name"], r["n"], r["viol"], r["worst"]) for r in bad[:8]]
+    replay.check(rec, ACT_VIOL_FRAC, GRAD_VIOL_FRAC, WORST_CAP)
 
 
 def _oracle_bytes(ref, B):

@@ -142,3 +142,44 @@ def test_wrong_batch_statistics_are_flagged():
     replay.forward(ref, src, x, rec)
     assert _flagged(rec, "op%d bn rstd" % bn0) == 1.0
     assert sum(r["viol"] for r in rec if "rstd" not in r["name"]) == 0
+
+
+@pytest.mark.parametrize("arch,B,H,W,classes", [(100, 8, 16, 16, 5), (1, 6, 16, 16, 10)])
+@pytest.mark.parametrize("lam", [0.0, 1.5])
+def test_trades_objective_through_the_stepping_calls(arch, B, H, W, classes, lam):
+    """The TRADES step is three forward and two backward sweeps with the logit gradients of kl_logit_grad installed:
+    done through the stepping interface it reproduces step_reg (whose gradients are pinned in
+    tests/test_oracle_objective.py), so a teacher-forced comparison may install these logit gradients."""
+    make, x, y = _setup(arch, B, H, W, classes)
+    xadv = oracle.make_xadv(x, oracle.init_delta(x, np.float32(8 / 255), oracle.INIT_UNIFORM, seed=3))
+    g_whole, l_whole = make().step_reg(x, xadv, y, lam, 1)
+    m = make()
+    n, t = len(m.ops()), m.ops()[-1]["out"]
+
+    def sweep(inp):
+        m.begin(inp)
+        for i in range(n):
+            m.forward_op(i)
+        return m.get_tensor(0, t).reshape(B, classes)
+
+    def back(dz):
+        m.loss_backward_begin(y, 1.0)
+        m.set_tensor(1, t, dz.reshape(-1))
+        for i in range(n - 1, -1, -1):
+            m.backward_op(i, True)
+        return m.param_grads()
+
+    zc = sweep(x)
+    za = sweep(xadv)
+    dz0, kl = oracle.kl_logit_grad(zc, za, None, 0.0, 0, 1.0 / B)
+    g = back(dz0)
+    zc2 = sweep(x)
+    assert np.array_equal(zc2, zc)
+    dz1, _ = oracle.kl_logit_grad(zc, za, y, lam, 1, 1.0 / B)
+    g = g + back(dz1)
+    assert abs(kl - l_whole[1]) <= 1e-6 * abs(l_whole[1]) + 1e-12
+    # (the logits pass through fp32 on the way into kl_logit_grad, the whole-network entry keeps them in fp64)
+    err = np.abs(g - g_whole).max() / np.abs(g_whole).max()
+    assert err < 2e-6, err
+    # each branch matters: leaving one out is far outside the tolerance
+    assert np.abs(back(dz1) - g_whole).max() / np.abs(g_whole).max() > 1e-2
