@@ -82,6 +82,9 @@ def main():
     ap.add_argument("--no-launch-events", action="store_true", help="do not bracket launches with events")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy 5 times and exit (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--stream-rates", action="store_true",
+                    help="time plain device fill / copy / add passes over a 411 MB tensor (the size of ResNet-50's widest stage-1 "
+                         "activation at batch 256) and exit: what the box streams, as context for the HBM-bound kernels")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus %d is not supported" % args.gpus,
@@ -102,6 +105,22 @@ def main():
         ms = e0.elapsed_time(e1) / 5
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "ms": ms,
                           "GBs_read_plus_write": 2 * src.numel() * 4 / (ms * 1e-3) / 1e9}))
+        return
+    if args.stream_rates:
+        n = 256 * 56 * 56 * 256
+        a = torch.ones(n, dtype=torch.bfloat16, device="cuda"); b = torch.ones_like(a); c = torch.empty_like(a)
+        out = {"bytes_per_tensor": 2 * n, "note": "library elementwise passes (not this package's kernels); median of 20"}
+        for name, f, moved in (("fill", lambda: c.zero_(), 1), ("copy", lambda: c.copy_(a), 2), ("add_2r1w", lambda: torch.add(a, b, out=c), 3)):
+            for _ in range(3):
+                f()
+            ts = []
+            for _ in range(20):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); f(); e1.record(); torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            ms = sorted(ts)[len(ts) // 2]
+            out[name] = {"ms": ms, "TBs": moved * 2 * n / (ms * 1e-3) / 1e12}
+        print(json.dumps(out))
         return
     import paper_2206_06257_amd as dat
     import synth_inputs as syn
