@@ -42,6 +42,8 @@ SHAPES = [
     (2, 16, 16, 128, 320, 1, 1, 0),    # ... 1x1
     (2, 16, 16, 160, 320, 1, 2, 0),    # ... strided projection of the wide nets
     (5, 9, 11, 160, 160, 3, 1, 1),     # 160-channel tiles with a ragged pixel tail
+    (2, 8, 8, 96, 160, 3, 1, 1),       # k-tiles of 64 over 96-channel taps: a tile ends two thirds into a tap
+    (2, 9, 9, 32, 160, 5, 1, 2),       # ... and two taps per k-tile (5x5 window)
 ]
 WIDE_NET_SHAPES = [s for s in SHAPES if s[4] in (160, 320) or s[3] in (160, 320)]
 
