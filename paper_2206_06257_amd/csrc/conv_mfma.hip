@@ -971,6 +971,7 @@ int compute_units() {
 std::atomic<bool> g_ring_enabled{true};
 std::atomic<bool> g_stem_pairs{true};
 std::atomic<bool> g_tile160{true};
+std::atomic<bool> g_narrow_underfilled{true};
 
 int pick_ring(const IgemmArgs& a) {
   if (a.xf_tab || a.ostep != 1 || a.stat_slab0 != 0 || a.Cin % 64 != 0 || a.Ktot < 1024 || a.Cout % 256 != 0) return 0;
@@ -1024,6 +1025,14 @@ dat_status run_igemm(const IgemmArgs& a, hipStream_t st) {
     if (a.Cin % 64 == 0 && a.Ktot >= 64 && (a.KH * a.KW > 1 || a.Ktot < 256)) return launch_igemm_dma<64, 128, 2, 5>(a, st);
     if (a.Cin % 64 != 0 && a.Cin % 32 == 0 && a.Ktot >= 32) return launch_igemm_dma<64, 128, 2, 5, 32>(a, st);
     return pick_depth<64, 128, 2>(a, st);
+  }
+  // Long contractions whose 128x128 tiles would leave at most one and a half workgroups per CU (4x4 and 7x7 maps at
+  // small batch): the single-stage kernel hides its load latency only behind other resident workgroups, so 32-channel
+  // tiles -- four times the workgroups -- finish sooner although each fetches the activation tile again.  (Two and
+  // a half workgroups per CU are enough: the 640-channel layers of the wide ResNets lose 12 % this way.)
+  if (a.stat_mode != 3 && a.Cin % 64 == 0 && a.Ktot >= 1024 && g_narrow_underfilled.load(std::memory_order_relaxed)) {
+    const int64_t wgs128 = (int64_t)((a.M + 127) / 128) * ((a.Cout + 127) / 128);
+    if (2 * wgs128 <= 3 * (int64_t)compute_units()) return launch_igemm_dma<32, 128, 1, 6>(a, st);
   }
   return pick_depth_wide(a, st);
 }
@@ -1562,6 +1571,7 @@ extern "C" dat_status dat_set_kernel_option(dat_kernel_option opt, int value) {
     case DAT_KOPT_RING_KERNEL: g_ring_enabled.store(value != 0, std::memory_order_relaxed); return DAT_OK;
     case DAT_KOPT_STEM_PAIRS: g_stem_pairs.store(value != 0, std::memory_order_relaxed); return DAT_OK;
     case DAT_KOPT_TILE_160: g_tile160.store(value != 0, std::memory_order_relaxed); return DAT_OK;
+    case DAT_KOPT_NARROW_UNDERFILLED: g_narrow_underfilled.store(value != 0, std::memory_order_relaxed); return DAT_OK;
   }
   return DAT_ERR_ARG;
 }

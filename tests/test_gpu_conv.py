@@ -44,6 +44,8 @@ SHAPES = [
     (5, 9, 11, 160, 160, 3, 1, 1),     # 160-channel tiles with a ragged pixel tail
     (2, 8, 8, 96, 160, 3, 1, 1),       # k-tiles of 64 over 96-channel taps: a tile ends two thirds into a tap
     (2, 9, 9, 32, 160, 5, 1, 2),       # ... and two taps per k-tile (5x5 window)
+    (8, 4, 4, 512, 512, 3, 1, 1),      # last stage of the CIFAR ResNets: few tiles, long contraction
+    (2, 8, 8, 1024, 256, 1, 1, 0),     # reducing 1x1 layer with a long contraction
 ]
 WIDE_NET_SHAPES = [s for s in SHAPES if s[4] in (160, 320) or s[3] in (160, 320)]
 
@@ -89,11 +91,11 @@ def test_conv_forward_backward_parity(dat, shape):
 
 
 
-@pytest.mark.parametrize("shape", WIDE_NET_SHAPES)
-def test_160_channel_tiles_give_the_bits_of_128_channel_tiles(dat, shape):
-    """Layers 160 or 320 channels wide run in 160-channel tiles (no partly empty last tile).  Every output element is
-    the same chain of MFMA accumulations over the same k order under either tiling, so forward and backward-data
-    results must not differ by a bit; the 128-channel launches stay covered by this test."""
+# long contractions into more than 64 channels: at these sizes they have few tiles and run in 32-channel tiles
+FEW_TILE_SHAPES = [s for s in SHAPES if s[3] % 64 == 0 and s[4] > 64 and s[5] * s[5] * s[3] >= 1024]
+
+
+def _ab(dat, shape, option, what):
     B, H, W, Ci, Co, k, st, pad = shape
     rng = np.random.default_rng(hash(shape) % (2 ** 31) + 1)
     x = _bf16_values(rng, (B, H, W, Ci)).cuda()
@@ -102,13 +104,32 @@ def test_160_channel_tiles_give_the_bits_of_128_channel_tiles(dat, shape):
     dy = _bf16_values(rng, (B, Ho, Wo, Co)).cuda()
     res = []
     try:
-        for wide in (1, 0):
-            dat.set_kernel_option(dat.KOPT_TILE_160, wide)
+        for on in (1, 0):
+            dat.set_kernel_option(option, on)
             y = dat.conv_forward(x, w, st, pad)
             dx = dat.conv_backward_data(dy, w, (H, W), st, pad)
             torch.cuda.synchronize()
             res.append((y.view(torch.int16).cpu().numpy(), dx.view(torch.int16).cpu().numpy()))
     finally:
-        dat.set_kernel_option(dat.KOPT_TILE_160, 1)
-    _check(y, oracle.conv_forward(x.double().cpu().numpy(), w.double().cpu().numpy(), st, pad), "forward, 128-channel tiles")
+        dat.set_kernel_option(option, 1)
+    _check(y, oracle.conv_forward(x.double().cpu().numpy(), w.double().cpu().numpy(), st, pad), "forward, " + what)
+    _check(dx, oracle.conv_backward(x.double().cpu().numpy(), w.double().cpu().numpy(), dy.double().cpu().numpy(), st, pad)[0],
+           "backward_data, " + what)
     assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
+
+
+@pytest.mark.parametrize("shape", WIDE_NET_SHAPES)
+def test_160_channel_tiles_give_the_bits_of_128_channel_tiles(dat, shape):
+    """Layers 160 or 320 channels wide run in 160-channel tiles (no partly empty last tile).  Every output element is
+    the same chain of MFMA accumulations over the same k order under either tiling, so forward and backward-data
+    results must not differ by a bit; the 128-channel launches stay covered by this test."""
+    _ab(dat, shape, dat.KOPT_TILE_160, "128-channel tiles")
+
+
+@pytest.mark.parametrize("shape", FEW_TILE_SHAPES)
+def test_32_channel_tiles_of_underfilled_layers_give_the_bits_of_128_channel_tiles(dat, shape):
+    """A long contraction with too few 128x128 tiles to keep the compute units busy runs in 32-channel tiles.  Same k order
+    per accumulator, so the same bits; with the switch off these shapes go through the 128-channel kernels, which this
+    test thereby keeps covered at small sizes."""
+    assert len(FEW_TILE_SHAPES) >= 6
+    _ab(dat, shape, dat.KOPT_NARROW_UNDERFILLED, "128-channel tiles")
