@@ -332,15 +332,12 @@ dat_status dat_model_set_option(dat_model* m, dat_option opt, int value);
  * model and of the dat_conv_* entry points).  DAT_KOPT_RING_KERNEL (default 1): layers that run as one round of
  * 256-channel tiles go through the multi-stage kernel; 0: through the 128x128 kernels.  The convolution outputs
  * are bit-identical, the grouping of the batch-norm partial sums differs (256 instead of 128 pixels per slab).
- * DAT_KOPT_STEM_PAIRS (default 1): the input gradient of a 7x7/2 stem stored as 2x2 pixel blocks is computed for
- * two neighbouring blocks per matrix column where a row holds an even number of blocks; 0: one block per column.
- * Bit-identical results.  DAT_KOPT_TILE_160 (default 1): layers with 160 or 320 output channels (the wide ResNets)
+ * DAT_KOPT_TILE_160 (default 1): layers with 160 or 320 output channels (the wide ResNets)
  * run in 160-channel tiles; 0: in 128-channel tiles, the last one partly empty.  Bit-identical outputs.
  * DAT_KOPT_NARROW_UNDERFILLED (default 1): a layer with a contraction >= 1024 whose 128x128 tiles would number at
  * most 1.5 per compute unit runs in 32-channel tiles; 0: in 128-channel tiles.  Bit-identical outputs (the partial
  * sums of the batch statistics are grouped differently). */
-typedef enum { DAT_KOPT_RING_KERNEL = 0, DAT_KOPT_STEM_PAIRS = 1, DAT_KOPT_TILE_160 = 2,
-               DAT_KOPT_NARROW_UNDERFILLED = 3 } dat_kernel_option;
+typedef enum { DAT_KOPT_RING_KERNEL = 0, DAT_KOPT_TILE_160 = 1, DAT_KOPT_NARROW_UNDERFILLED = 2 } dat_kernel_option;
 dat_status dat_set_kernel_option(dat_kernel_option opt, int value);
 
 /* ---- introspection for parity tests (not part of the paper's method) --------------------------------

@@ -99,9 +99,8 @@ OPT_ABSORB_SHORTCUT_BN = 5
 OPT_FUSE_STEM_POOL = 6
 OPT_GRADIENT_SCALES = 7
 KOPT_RING_KERNEL = 0
-KOPT_STEM_PAIRS = 1
-KOPT_TILE_160 = 2
-KOPT_NARROW_UNDERFILLED = 3
+KOPT_TILE_160 = 1
+KOPT_NARROW_UNDERFILLED = 2
 _lib.dat_set_kernel_option.argtypes = [_i, _i]
 _lib.dat_profile_read.argtypes = [_vp, _i, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]
 PROF_CLASSES = ("conv_fwd", "conv_bwd_data", "conv_wgrad", "bn", "pgd", "conv_bwd_data_bn")

@@ -76,7 +76,6 @@ struct IgemmArgs {
   bf16_t* out;          // [M][Cout], M = B*Hout*Wout
   int B, Hin, Win, Cin, Hout, Wout, Cout;   // Hout x Wout = grid of output pixels this launch computes
   int KH, KW, ostride, pad_h, pad_w;
-  int ostride_w = 0;    // step between output columns in input pixels when it differs from the rows' (0: ostride)
   // Elements between neighbouring input pixels of a row (0: Cin, the ordinary case).  With 0 < xstride < Cin the
   // "Cin channels" of pixel w are the stored values of the pixels w .. w + Cin/xstride - 1, i.e. a filter row of
   // Cin/xstride taps read as one contiguous vector (igemm_dma_kernel with Cin equal to its k-tile only); a 16-byte
@@ -356,7 +355,7 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_kernel(IgemmArgs a) {
     const int mm = mv[i] ? m : 0;
     const int n = mm / HW, rem = mm - n * HW;
     const int ho = rem / a.Wout, wo = rem - ho * a.Wout;
-    hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * (a.ostride_w ? a.ostride_w : a.ostride) - a.pad_w;
+    hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * a.ostride - a.pad_w;
     nb[i] = n * a.Hin * a.Win;
   }
   const int ntiles = (a.Ktot + BKT - 1) / BKT;
@@ -595,7 +594,7 @@ __global__ __launch_bounds__(kThreads, OCC) void igemm_dma_kernel(IgemmArgs a) {
     const int mm = mv[i] ? m : 0;
     const int n = mm / HW, rem = mm - n * HW;
     const int ho = rem / a.Wout, wo = rem - ho * a.Wout;
-    hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * (a.ostride_w ? a.ostride_w : a.ostride) - a.pad_w;
+    hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * a.ostride - a.pad_w;
     nb[i] = n * a.Hin * a.Win;
   }
   const int ntiles = ANYC ? (a.Ktot + BKT - 1) / BKT : a.Ktot / BKT;
@@ -760,7 +759,7 @@ __global__ __launch_bounds__(512) void igemm_ring_kernel(IgemmArgs a) {
     const int mm = mv[i] ? m : 0;
     const int n = mm / HW, rem = mm - n * HW;
     const int ho = rem / a.Wout, wo = rem - ho * a.Wout;
-    hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * (a.ostride_w ? a.ostride_w : a.ostride) - a.pad_w;
+    hb[i] = ho * a.ostride - a.pad_h; wb[i] = wo * a.ostride - a.pad_w;
     nb[i] = n * a.Hin * a.Win;
   }
   const int ntiles = a.Ktot / BKT;
@@ -969,7 +968,6 @@ int compute_units() {
 // and 2048->512 44 -> 37 us with 256x128; slower than the 128x128 kernel wherever several rounds are needed or the
 // contraction is short).
 std::atomic<bool> g_ring_enabled{true};
-std::atomic<bool> g_stem_pairs{true};
 std::atomic<bool> g_tile160{true};
 std::atomic<bool> g_narrow_underfilled{true};
 
@@ -1100,16 +1098,6 @@ constexpr int kStemV = 16;     // values per 2x2 block: 4 positions x 4 channels
 __global__ void stem_weight_transform_kernel(const float* __restrict__ master, bf16_t* __restrict__ vf, bf16_t* __restrict__ vb,
                                              int Cout, int cin_real) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < Cout * 32 * 20) {   // vb2[h*16 + v][a][s][co] behind vb: block 2j'+h of a pair sees window column s as its tap b = s - h
-    const int co = i % Cout; int t = i / Cout;
-    const int s = t % 5; t /= 5;
-    const int a = t & 3, row = t >> 2;
-    const int h = row >> 4, v = row & 15, b = s - h;
-    const int ph = v >> 3, pw = (v >> 2) & 1, c = v & 3;
-    const int r = 5 + ph - 2 * a, q = 5 + pw - 2 * b;
-    const bool ok = c < cin_real && b >= 0 && b < 4 && r >= 0 && r < 7 && q >= 0 && q < 7;
-    vb[Cout * 16 * kStemV + i] = ok ? f2bf(master[((co * 7 + r) * 7 + q) * cin_real + c]) : (bf16_t)0;
-  }
   if (i >= Cout * 16 * kStemV) return;
   {   // vf[co][a][b][v]
     const int v = i & 15, b = (i >> 4) & 3, a = (i >> 6) & 3, co = i >> 8;
@@ -1482,7 +1470,7 @@ ConvGeom conv_mfma_stem_blocked_geom(const ConvGeom& g) {
 }
 
 dat_status launch_stem_weight_transform(const float* master, bf16_t* vf, bf16_t* vb, int Cout, int cin_real, hipStream_t st) {
-  const int n = Cout * 32 * 20;
+  const int n = Cout * 16 * kStemV;
   hipLaunchKernelGGL(stem_weight_transform_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, master, vf, vb, Cout, cin_real);
   DAT_LAUNCH_CHECK();
   return DAT_OK;
@@ -1510,13 +1498,8 @@ dat_status conv_mfma_stem_backward_data(const bf16_t* dy, const bf16_t* vb, bf16
   a.in = dy; a.wt = vb; a.res = accumulate ? dx2 : nullptr; a.res_mask = nullptr; a.res_even_only = 0; a.out = dx2;
   a.B = g.B; a.Hin = g.Ho; a.Win = g.Wo; a.Cin = g.Cout; a.Hout = g.H / 2; a.Wout = g.W / 2; a.Cout = kStemV;
   a.KH = a.KW = 4; a.ostride = 1; a.pad_h = a.pad_w = 1;
-  if (a.Wout % 2 == 0 && g_stem_pairs.load(std::memory_order_relaxed)) {
-    // two neighbouring blocks of a row per MFMA column (32 result rows instead of 16 of 32 used): their windows
-    // are one column apart, so the pair contracts a 4 x 5 window and steps two columns per output "pixel"
-    a.wt = vb + (size_t)g.Cout * 16 * kStemV; a.Wout /= 2; a.Cout = 2 * kStemV; a.KW = 5; a.ostride_w = 2;
-  }
   a.outH = a.Hout; a.outW = a.Wout; a.ostep = 1; a.oh0 = a.ow0 = 0;
-  a.M = g.B * a.Hout * a.Wout; a.Ktot = a.KH * a.KW * g.Cout; a.nct = a.npt = 0;
+  a.M = g.B * a.Hout * a.Wout; a.Ktot = 16 * g.Cout; a.nct = a.npt = 0;
   set_stats(a, nullptr, 0);
   return run_igemm(a, st);
 }
@@ -1569,7 +1552,6 @@ using namespace dat;
 extern "C" dat_status dat_set_kernel_option(dat_kernel_option opt, int value) {
   switch (opt) {
     case DAT_KOPT_RING_KERNEL: g_ring_enabled.store(value != 0, std::memory_order_relaxed); return DAT_OK;
-    case DAT_KOPT_STEM_PAIRS: g_stem_pairs.store(value != 0, std::memory_order_relaxed); return DAT_OK;
     case DAT_KOPT_TILE_160: g_tile160.store(value != 0, std::memory_order_relaxed); return DAT_OK;
     case DAT_KOPT_NARROW_UNDERFILLED: g_narrow_underfilled.store(value != 0, std::memory_order_relaxed); return DAT_OK;
   }

@@ -448,7 +448,7 @@ dat_status allocate(dat_model& m) {
     if (op.kind == OP_CONV && m.dtype == DAT_BF16) {
       const size_t n = op.blocked ? (size_t)m.tens[op.out].C * 16 * 16 : (size_t)m.tens[op.out].C * op.k * op.k * m.tens[op.in].C;   // blocked: [Cout][4][4][16]
       DAT_TRY(dev_alloc(m, &op.w16, n * 2));
-      DAT_TRY(dev_alloc(m, &op.w16T, (op.blocked ? n + (size_t)m.tens[op.out].C * 32 * 20 : n) * 2));   // blocked: [16][4][4][Cout], then [32][4][5][Cout]
+      DAT_TRY(dev_alloc(m, &op.w16T, n * 2));
       if (op.blocked) DAT_TRY(dev_alloc(m, &op.dv, n * 4));
       const ConvGeom gmax = geom_of(m, op, m.maxB);
       const size_t need = conv_mfma_wgrad_workspace(op.blocked ? conv_mfma_stem_blocked_geom(gmax) : gmax);

@@ -404,30 +404,6 @@ def test_weight_gradients_on_the_side_stream_give_the_same_bits(dat, arch, B, H,
                 assert np.array_equal(a, b)
 
 
-@pytest.mark.parametrize("B,H,W", [(5, 64, 64), (3, 72, 100), (2, 224, 224)])
-def test_stem_input_gradient_two_blocks_per_column_gives_the_same_bits(dat, B, H, W):
-    """The 7x7/2 stem's input gradient on 2x2 pixel blocks: with an even number of blocks per row two neighbouring
-    blocks share one matrix column (a 4 x 5 window, zero weights where a block does not see a column).  The non-zero
-    products and their order are those of the one-block launch, so pixel gradient and attack must not change by a bit."""
-    classes = 12
-    gpu = dat.Model(3, dat.BF16, B, H, W, classes, MEAN, STD)
-    gpu.set_params(syn.perturbed_params(91, gpu.offsets, gpu.fan_in, gpu.kind))
-    xd, yd = _cuda(syn.images(91, B, H, W)), _cuda(syn.labels(91, B, classes))
-    res = []
-    try:
-        for pairs in (1, 0):
-            dat.set_kernel_option(dat.KOPT_STEM_PAIRS, pairs)
-            gx, logits, loss = gpu.input_grad(xd, yd)
-            delta = gpu.attack(xd, yd, 8 / 255, 2 / 255, 3, init=dat.INIT_UNIFORM, seed=7)
-            res.append((gx.cpu().numpy(), logits.cpu().numpy(), delta.cpu().numpy()))
-    finally:
-        dat.set_kernel_option(dat.KOPT_STEM_PAIRS, 1)
-    assert np.abs(res[0][0]).max() > 0 and np.abs(res[0][2]).max() > 0
-    for a, b in zip(*res):
-        assert np.array_equal(a, b)
-    gpu.close()
-
-
 @pytest.mark.parametrize("arch,B,H,W,classes", [(100, 8, 16, 16, 5), (1, 16, 16, 16, 10), (2, 4, 8, 8, 10), (3, 5, 64, 96, 12)])
 def test_scales_from_the_gradient_writers_are_the_quantizers_own(dat, arch, B, H, W, classes):
     """bf16 models: every kernel that writes a parameter gradient also raises that tensor's abs-max
