@@ -74,7 +74,7 @@ def _pair(dat, arch, dtype, B, H, W, classes, cfg, norm=False, perturbed=True):
 
 
 def test_config1_tiny_cnn_fp32_full_step(dat):
-    """BASELINE config 1: FGSM eps=8/255 from zero init, one SGD step (lr 0.1), 8-bit quantizer."""
+    """Configuration 1 (tiny CNN, fp32): FGSM eps=8/255 from zero init, one SGD step (lr 0.1), 8-bit quantizer."""
     ref, gpu, x, y = _pair(dat, dat.ARCH_TINYCNN, dat.F32, 32, 32, 32, 10, cfg=1, perturbed=False)
     xd, yd = _cuda(x), _cuda(y)
     # attack
