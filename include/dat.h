@@ -323,10 +323,15 @@ dat_status dat_profile_read(dat_model* m, int cls, double* ms_total, int64_t* la
  * DAT_OPT_GRADIENT_SCALES (default 1, bf16 models): the kernels that write parameter gradients in dat_step also
  * maintain the per-tensor abs-max that dat_model_grad_scales returns.  0: they do not (dat_model_grad_scales then
  * refuses).  The gradients are the same bits either way.
+ * DAT_OPT_KEEP_BOTH_PASSES (default 1): dat_step_reg with the KL regulariser keeps the clean pass's activations,
+ * batch statistics and masks in a second set of buffers (allocated on the first such call: as much device memory
+ * again as the model's activations) while the perturbed pass runs, so each branch of the gradient finds its own
+ * pass; 0, or when that allocation fails: one set, the clean pass is run a second time.  Identical bits either way.
  * Options may be changed between calls, not while a call on the model is in flight. */
 typedef enum { DAT_OPT_FUSE_BN_INPUT_GRAD = 0, DAT_OPT_FUSE_BN_SUMS = 1, DAT_OPT_FUSE_PGD_GRADIENT = 2,
                DAT_OPT_SPARSE_SHORTCUT_GRADIENT = 3, DAT_OPT_OVERLAP_WEIGHT_GRADIENTS = 4,
-               DAT_OPT_ABSORB_SHORTCUT_BN = 5, DAT_OPT_FUSE_STEM_POOL = 6, DAT_OPT_GRADIENT_SCALES = 7 } dat_option;
+               DAT_OPT_ABSORB_SHORTCUT_BN = 5, DAT_OPT_FUSE_STEM_POOL = 6, DAT_OPT_GRADIENT_SCALES = 7,
+               DAT_OPT_KEEP_BOTH_PASSES = 8 } dat_option;
 dat_status dat_model_set_option(dat_model* m, dat_option opt, int value);
 /* Process-wide kernel selection (ablations and tests; an atomic flag, read at every convolution launch of every
  * model and of the dat_conv_* entry points).  DAT_KOPT_RING_KERNEL (default 1): layers that run as one round of

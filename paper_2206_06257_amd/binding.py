@@ -98,6 +98,7 @@ OPT_OVERLAP_WEIGHT_GRADIENTS = 4
 OPT_ABSORB_SHORTCUT_BN = 5
 OPT_FUSE_STEM_POOL = 6
 OPT_GRADIENT_SCALES = 7
+OPT_KEEP_BOTH_PASSES = 8
 KOPT_RING_KERNEL = 0
 KOPT_TILE_160 = 1
 KOPT_NARROW_UNDERFILLED = 2

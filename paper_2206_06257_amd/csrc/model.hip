@@ -101,6 +101,12 @@ struct dat_model {
   uint32_t* gscale = nullptr;        // per parameter tensor: bit pattern of max |gradient| written by the last dat_step (bf16 models)
   bool gscale_valid = false;         //   ... and whether that call produced all of them
   float* g_tmp = nullptr;            // second gradient vector of a two-pass objective (allocated on first use)
+  // A second set of everything a forward pass leaves for its backward pass (activations, batch statistics, ReLU masks,
+  // pool positions; allocated on first use): the KL objective keeps the clean pass there while the perturbed pass runs,
+  // instead of running the clean pass a second time for its branch of the gradient (dat_model_set_option(
+  // DAT_OPT_KEEP_BOTH_PASSES)).  swap_bank exchanges the two sets; gradients and scratch buffers are shared.
+  struct PassBank { std::vector<void*> act; std::vector<float*> mean, rstd; std::vector<uint8_t*> mask, argmax; bool ready = false; } bank2;
+  bool keep_both_passes = true;
   float* opt_m = nullptr; float* opt_v = nullptr; float* opt_u = nullptr; double* opt_norms = nullptr;   // LAMB state
   // optional per-launch timing (dat_profile_*): one event pair per launch group
   bool prof = false;
@@ -939,6 +945,35 @@ dat_status kl_grad(dat_model& m, const float* z_clean, const float* z_adv, const
   return DAT_OK;
 }
 
+dat_status ensure_bank(dat_model& m) {
+  dat_model::PassBank& b = m.bank2;
+  if (b.ready) return DAT_OK;
+  const int es = m.esize();
+  b.act.assign(m.tens.size(), nullptr);
+  b.mean.assign(m.ops.size(), nullptr); b.rstd.assign(m.ops.size(), nullptr);
+  b.mask.assign(m.ops.size(), nullptr); b.argmax.assign(m.ops.size(), nullptr);
+  for (size_t t = 0; t < m.tens.size(); ++t)
+    DAT_TRY(dev_alloc(m, &b.act[t], (size_t)m.maxB * m.tens[t].numel() * (m.is_f32[t] ? 4 : es)));
+  for (size_t i = 0; i < m.ops.size(); ++i) {
+    const Op& op = m.ops[i];
+    if (op.mean) DAT_TRY(dev_alloc(m, &b.mean[i], (size_t)m.tens[op.in].C * 4));
+    if (op.rstd) DAT_TRY(dev_alloc(m, &b.rstd[i], (size_t)m.tens[op.in].C * 4));
+    if (op.mask) DAT_TRY(dev_alloc(m, &b.mask[i], (size_t)m.maxB * m.tens[op.in].numel() / 8));
+    if (op.argmax) DAT_TRY(dev_alloc(m, &b.argmax[i], (size_t)m.maxB * m.tens[op.out].numel()));
+  }
+  b.ready = true;
+  return DAT_OK;
+}
+
+void swap_bank(dat_model& m) {
+  dat_model::PassBank& b = m.bank2;
+  for (size_t t = 0; t < m.tens.size(); ++t) std::swap(m.act[t], b.act[t]);
+  for (size_t i = 0; i < m.ops.size(); ++i) {
+    Op& op = m.ops[i];
+    std::swap(op.mean, b.mean[i]); std::swap(op.rstd, b.rstd[i]); std::swap(op.mask, b.mask[i]); std::swap(op.argmax, b.argmax[i]);
+  }
+}
+
 dat_status keep_logits(dat_model& m, float* dst, int B, hipStream_t st) {
   DAT_HIP(hipMemcpyAsync(dst, m.act[m.ops.back().out], (size_t)B * m.classes * 4, hipMemcpyDeviceToDevice, st));
   return DAT_OK;
@@ -1001,6 +1036,23 @@ extern "C" dat_status dat_step_reg(dat_model* m, const float* x, const float* x_
     DAT_TRY(forward(*m, B, st));
     DAT_TRY(loss_grad(*m, y, B, inv, 1, st));
     DAT_TRY(backward(*m, B, grads, false, st));
+  } else if (m->keep_both_passes && ensure_bank(*m) == DAT_OK) {
+    // the clean pass stays in one set of buffers while the perturbed pass runs in the other; each branch's backward
+    // sweep then finds its own activations (a failed allocation of the second set falls through to the path below)
+    const int tz = m->ops.back().out;
+    DAT_TRY(launch_make_input(x, nullptr, npix, in, st));
+    DAT_TRY(forward(*m, B, st));
+    const float* z_clean = (const float*)m->act[tz];
+    swap_bank(*m);
+    dat_status s = launch_make_input(x_adv, nullptr, npix, input_desc(*m), st);   // (the network input is one of the exchanged buffers)
+    if (s == DAT_OK) s = forward(*m, B, st);
+    const float* z_adv = (const float*)m->act[tz];
+    if (s == DAT_OK) s = kl_grad(*m, z_clean, z_adv, y, 0, lambda, B, inv, 1, st);
+    if (s == DAT_OK) s = backward(*m, B, grads, false, st);
+    swap_bank(*m);                        // the clean pass is the model's current one again, also after an error
+    DAT_TRY(s);
+    DAT_TRY(kl_grad(*m, z_clean, z_adv, y, 1, lambda, B, inv, 0, st));
+    DAT_TRY(backward(*m, B, m->g_tmp, false, st));
   } else {
     const float* z_here = (const float*)m->act[m->ops.back().out];
     // clean logits, then the perturbed pass and its branch of the gradient
@@ -1071,6 +1123,7 @@ extern "C" dat_status dat_model_set_option(dat_model* m, dat_option opt, int val
     case DAT_OPT_ABSORB_SHORTCUT_BN: m->absorb_shortcut_bn = value != 0; link_fusions(*m); return DAT_OK;
     case DAT_OPT_FUSE_STEM_POOL: m->fuse_pool = value != 0; return DAT_OK;
     case DAT_OPT_GRADIENT_SCALES: m->grad_scales = value != 0; return DAT_OK;
+    case DAT_OPT_KEEP_BOTH_PASSES: m->keep_both_passes = value != 0; return DAT_OK;
   }
   return DAT_ERR_ARG;
 }

@@ -138,6 +138,26 @@ def test_trades_step_clean_branch_op_by_op(dat, arch, bf16, B, H, classes, norm,
 
 
 @pytest.mark.parametrize("arch,bf16,B,H,classes,norm", REPLAY_CASES)
+def test_kl_step_with_both_passes_resident_gives_the_same_bits(dat, arch, bf16, B, H, classes, norm):
+    """The KL step keeps the clean pass in a second set of buffers while the perturbed pass runs (default), or runs the
+    clean pass again (option off): the same launches on the same data, so gradients and losses are bit-identical; a
+    plain step before and after is unaffected by the exchange of the buffer sets."""
+    ref, gpu, x, xadv, y = _pair(dat, arch, dat.BF16 if bf16 else dat.F32, B, H, classes, cfg=47, norm=norm)
+    xd, xad, yd = _cuda(x), _cuda(xadv), _cuda(y)
+    g_plain = gpu.step(xd, yd).clone()
+    res = []
+    for keep in (1, 0, 1):
+        gpu.set_option(dat.OPT_KEEP_BOTH_PASSES, keep)
+        g, l = gpu.step_reg(xd, xad, yd, 1.5, dat.PHI_TRADES_KL, want_losses=True)
+        res.append((g.clone(), np.array(l)))
+        assert torch.equal(gpu.step(xd, yd), g_plain)
+    assert float(res[0][0].abs().max()) > 0
+    for g, l in res[1:]:
+        assert torch.equal(g, res[0][0]) and np.array_equal(l, res[0][1])
+    gpu.close()
+
+
+@pytest.mark.parametrize("arch,bf16,B,H,classes,norm", REPLAY_CASES)
 def test_kl_attack_perturbed_pass_op_by_op(dat, arch, bf16, B, H, classes, norm):
     """One step of dat_attack_kl from a given start: the perturbed pass and its backward-to-input sweep op by op (logit
     gradient q - p at the GPU's logits, summed over the batch), and the projected sign step against the reference's
