@@ -27,8 +27,18 @@
 // Parity pins (tests/test_oracle_*.py): central finite differences, adjoint identities,
 // closed-form softmax-CE gradient, published parameter counts of the three ResNets,
 // Philox4x32-10 known answers, quantizer mean/variance closed forms, attack invariants,
-// brute-force inner maximum of a linear model.  Nothing here is "parity unpinned" except
-// trained-model accuracies, which need data that does not exist in this build.
+// brute-force inner maximum of a linear model, an autograd mirror of every architecture and of
+// the general objective.  Parity unpinned: (1) trained-model accuracies, which need data that does
+// not exist in this build; (2) the PLACEMENT of the bf16 rounding points in bf16-storage mode --
+// which tensors are rounded, and that a gradient with several contributions is stored after the
+// first and re-rounded after each later one.  That placement mirrors the GPU library's storage
+// schedule on purpose (it is a definition both sides share, the paper fixes no precision); the
+// arithmetic between the rounding points is the fp64 mode's, which the pins above cover.
+//
+// Besides the whole-network entry points there is a stepping interface (orc_begin, orc_forward_op,
+// orc_loss_backward_begin, orc_backward_op, orc_get/set/compare_tensor): one op at a time, with
+// any stored tensor replaceable from outside, for teacher-forced comparisons; the tests show that
+// stepping reproduces the whole-network results bit for bit.
 
 #include <algorithm>
 #include <cmath>
