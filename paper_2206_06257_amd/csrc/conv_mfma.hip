@@ -298,11 +298,16 @@ __device__ __forceinline__ void igemm_epilogue(const IgemmArgs& a, f32x16 (&acc)
     __syncthreads();
     const int ns = a.stat_mode == 3 ? 3 : 2;        // sums per channel
     float* red = reinterpret_cast<float*>(lds);     // [RPP][ns][TC]
-    if (EXACT || pr0 < RPP)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      red[(pr0 * ns + 0) * TC + cv * 8 + j] = s1[j]; red[(pr0 * ns + 1) * TC + cv * 8 + j] = s2[j];
-      if (ns == 3) red[(pr0 * ns + 2) * TC + cv * 8 + j] = s3[j];
+    if (EXACT || pr0 < RPP) {
+      // 16-byte stores: as single floats the lanes of a wave (8 floats apart, rows a multiple of 64 floats apart) would
+      // land eight to a bank
+      auto put = [&](int which, const float (&v)[8]) {
+        float4* dst = reinterpret_cast<float4*>(red + (pr0 * ns + which) * TC + cv * 8);
+        dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+        dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+      };
+      put(0, s1); put(1, s2);
+      if (ns == 3) put(2, s3);
     }
     __syncthreads();
     for (int q = tid; q < ns * TC; q += NT) {
